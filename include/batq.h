@@ -1,0 +1,156 @@
+/*
+ * libbatq - W4A4 MXFP4 linear layer with block-wise affine transforms (BATQuant)
+ * for AMD MI355X (gfx950).  C ABI.
+ *
+ * The layer computes  Y = Q(X P) * Q(P^-1 W)  (Sec. 3.1 of the paper, where it is
+ * written with W stored out x in):
+ *   - P = diag(T_0 .. T_{K/32-1}) is block-diagonal with one 32x32 block per MXFP
+ *     block of the reduction dimension (Eq. 1);
+ *   - each block is a Kronecker product of a factor shared by all blocks and a
+ *     factor private to the block (Eq. 2, "Global and Private Kronecker");
+ *   - after the transform each 32-block is clipped at a learned fraction of its
+ *     own absolute maximum (Eq. 3-4, symmetric form) and quantised to MXFP4:
+ *     E2M1 elements {0,.5,1,1.5,2,3,4,6} with sign, one UE8M0 power-of-two scale
+ *     per 32 elements (Sec. 2, MXFP definition);
+ *   - the weight side P^-1 W is computed and quantised once, offline (Alg. 2,
+ *     "Offline Fusion"); the activation side runs online, fused with the quantiser.
+ *
+ * Notation used here: X is M x K (tokens x in-features), W is K x N (in x out),
+ * Y is M x N.  Block k covers columns 32k .. 32k+31 of X (rows of W).
+ *   T_k = G (x) P_k,  T_k[a*gi + c, a2*gi + c2] = G[a][a2] * P_k[c][c2],
+ *   G: g_outer x g_outer shared ("global"), P_k: g_inner x g_inner ("private"),
+ *   g_outer * g_inner = 32.  A row vector x_k is mapped to x_k T_k.
+ *
+ * Quantised tensor layout (both activations and exported weights):
+ *   codes  [rows][K/2]  uint8, element 2j in bits 3:0 and 2j+1 in bits 7:4 of byte j;
+ *                       a 4-bit code is S|E1 E0|M (bit 3 = sign);
+ *   scales [rows][K/32] uint8, E8M0: value 2^(s-127); 255 is never produced.
+ * Quantiser definition: bound = fl32(clip_k * max_j |y_j|); elements beyond +-bound
+ * are replaced by +-bound; E = clamp(floor(log2 bound) - 2, -127, 127) (E = -127 for
+ * a zero block); code = round-to-nearest on the E2M1 grid of y * 2^-E, ties to the
+ * code with even mantissa bit, saturating at 6; the sign bit is always the sign bit
+ * of the input element (also for results that round to zero).
+ *
+ * Conventions
+ *   - Every function returns a batq_status; nothing throws, aborts or prints.
+ *   - Pointers documented HOST are read on the host during the call; pointers
+ *     documented DEVICE must be device memory on the current HIP device and stay
+ *     valid until the stream has passed the call.  The caller owns every tensor it
+ *     passes; the library owns only what is inside its handles.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Online calls (batq_quantize_act, batq_gemm_mxfp4, batq_linear) only enqueue
+ *     work: no host synchronisation and no allocation.
+ *   - Argument errors are detected on the host before anything is launched and
+ *     leave all outputs untouched.  Non-finite inputs are outside the contract.
+ *   - Calls on distinct handles are thread-safe.
+ */
+#ifndef BATQ_H
+#define BATQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BATQ_OK = 0,
+    BATQ_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    BATQ_ERR_SHAPE = 2,       /* K % 32 != 0, a size <= 0, or a leading dimension too small  */
+    BATQ_ERR_DTYPE = 3,       /* unknown batq_dtype                                          */
+    BATQ_ERR_UNSUPPORTED = 4, /* (g_outer, g_inner) not one of (4,8), (8,4)                   */
+    BATQ_ERR_SINGULAR = 5,    /* G or some P_k is not invertible                             */
+    BATQ_ERR_CLIP_RANGE = 6,  /* a clip ratio is not in (0, 1]                               */
+    BATQ_ERR_WORKSPACE = 7,   /* workspace smaller than batq_linear_workspace()              */
+    BATQ_ERR_ALLOC = 8,       /* host or device allocation failed                            */
+    BATQ_ERR_DEVICE = 9,      /* a HIP call failed, or the device is not gfx950              */
+    BATQ_ERR_MISMATCH = 10    /* transform and weight were built for different K             */
+} batq_status;
+
+typedef enum { BATQ_F32 = 0, BATQ_BF16 = 1 } batq_dtype;
+
+/* Static, NUL-terminated description of a status code. */
+const char* batq_status_string(batq_status s);
+
+/* Library version, "major.minor". Static storage. */
+const char* batq_version(void);
+
+/* ------------------------------------------------------------------------------------
+ * Transform object: the learned parameters of one transform set (Alg. 2's Theta):
+ * the shared factor, the private factors and the activation clip ratios.
+ *   K        in-features, multiple of 32
+ *   g_outer  size of the shared factor G, g_inner size of each private factor P_k;
+ *            (4,8) or (8,4)
+ *   G        HOST [g_outer*g_outer] row-major fp32; NULL = no transform (T_k = I),
+ *            in which case P must be NULL too
+ *   P        HOST [K/32][g_inner*g_inner] row-major fp32
+ *   clip_a   HOST [K/32] clip ratios in (0,1] applied to the block amax of the
+ *            transformed activations; NULL = 1.0 (no clipping)
+ * The library copies everything (to the device too); the caller may free its arrays
+ * on return.  The factors are inverted on the host in fp64; a pivot below
+ * 1e-12 * max|entry| gives BATQ_ERR_SINGULAR.  Synchronises with the device.
+ */
+typedef struct batq_transform batq_transform;
+batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int g_inner,
+                                  const float* G, const float* P, const float* clip_a);
+batq_status batq_transform_destroy(batq_transform* t);
+
+/* ------------------------------------------------------------------------------------
+ * Offline weight preparation (Alg. 2, "Offline Fusion for Deployment"):
+ * W~ = P^-1 W (each 32-row K-slab of W multiplied from the left by T_k^-1, fp64
+ * accumulation, rounded once to fp32), optional block clip, MXFP4 along K.
+ *   t        transform the weights pair with (its K must equal K)
+ *   W        DEVICE, read-only; w_is_KxN != 0: row-major K x N with row stride ldw
+ *            (>= N); w_is_KxN == 0: row-major N x K (the paper's out x in) with row
+ *            stride ldw (>= K).  ldw counts elements.
+ *   clip_w   HOST [K/32] ratios in (0,1] or NULL (= 1.0)
+ * The result is an opaque handle owning device memory in the GEMM's internal layout.
+ * Synchronises `stream` before returning (offline call).
+ */
+typedef struct batq_weight batq_weight;
+batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t,
+                                const void* W, batq_dtype wdtype, int K, int N, int64_t ldw,
+                                int w_is_KxN, const float* clip_w, void* stream);
+/* Copy the prepared weights out in the canonical layout: codes DEVICE [N][K/2],
+ * scales DEVICE [N][K/32].  Enqueued on `stream`. */
+batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream);
+/* Build a weight handle from canonical codes/scales (DEVICE), e.g. a stored checkpoint. */
+batq_status batq_weight_import(batq_weight** out, const uint8_t* codes, const uint8_t* scales,
+                               int K, int N, void* stream);
+batq_status batq_weight_shape(const batq_weight* w, int* K, int* N);
+batq_status batq_weight_destroy(batq_weight* w);
+
+/* ------------------------------------------------------------------------------------
+ * Online step 1: fused transform (Eq. 1-2) + block clip (Eq. 3-4) + MXFP4 (Sec. 2).
+ *   X       DEVICE M x K row-major, row stride ldx elements (>= K), fp32 or bf16;
+ *           the products and sums of the transform are carried in fp32 (bf16 is
+ *           storage only; nothing is rounded to bf16 before the quantiser)
+ *   codes   DEVICE [M][K/2]   out
+ *   scales  DEVICE [M][K/32]  out
+ * M == 0 is a no-op.  A transform created with G == NULL quantises X as is.
+ */
+batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype,
+                              int M, int K, int64_t ldx,
+                              uint8_t* codes, uint8_t* scales, void* stream);
+
+/* Online step 2 alone: MXFP4 x MXFP4 GEMM on canonical activation codes/scales.
+ *   Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} val(xq[m][32k+j]) val(wq[n][32k+j])
+ * with fp32 accumulation; Y DEVICE M x N row-major, row stride ldy (>= N), fp32 or
+ * bf16 (round-to-nearest-even). */
+batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
+                            int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+
+/* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
+ * `workspace` is DEVICE memory of at least batq_linear_workspace(M, K) bytes that
+ * holds the activation codes and scales between the two kernels. */
+size_t batq_linear_workspace(int M, int K);
+batq_status batq_linear(const batq_transform* t, const batq_weight* w,
+                        const void* X, batq_dtype xdtype, int M, int64_t ldx,
+                        void* Y, batq_dtype ydtype, int64_t ldy,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BATQ_H */

@@ -1,0 +1,9 @@
+"""libbatq: MI355X-native W4A4 MXFP4 linear layer with block-wise affine transforms.
+
+The product is the C-ABI shared library built from ``csrc/`` (see include/batq.h);
+this package is its thin ctypes binding.
+"""
+from .binding import (  # noqa: F401
+    BatqError, Transform, Weight, batq_prepare_weight, batq_weight_import, batq_quantize_act,
+    batq_gemm_mxfp4, batq_linear, batq_linear_workspace, lib, LIB_PATH, SYMBOLS, STATUS_NAMES, F32, BF16,
+)

@@ -1,0 +1,226 @@
+"""ctypes binding of libbatq's C ABI (include/batq.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP
+kernels.  PyTorch tensors are used as device memory; the current torch stream is
+passed as the hipStream_t.  There is no CPU fallback: if the library has not
+been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbatq.so")
+
+F32, BF16 = 0, 1
+
+STATUS_NAMES = {
+    0: "BATQ_OK", 1: "BATQ_ERR_NULL", 2: "BATQ_ERR_SHAPE", 3: "BATQ_ERR_DTYPE", 4: "BATQ_ERR_UNSUPPORTED",
+    5: "BATQ_ERR_SINGULAR", 6: "BATQ_ERR_CLIP_RANGE", 7: "BATQ_ERR_WORKSPACE", 8: "BATQ_ERR_ALLOC",
+    9: "BATQ_ERR_DEVICE", 10: "BATQ_ERR_MISMATCH",
+}
+
+# every symbol include/batq.h declares: (restype, argtypes)
+_vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+_fp = C.POINTER(C.c_float)
+SYMBOLS = {
+    "batq_status_string": (C.c_char_p, [_i]),
+    "batq_version": (C.c_char_p, []),
+    "batq_transform_create": (_i, [C.POINTER(_vp), _i, _i, _i, _fp, _fp, _fp]),
+    "batq_transform_destroy": (_i, [_vp]),
+    "batq_prepare_weight": (_i, [C.POINTER(_vp), _vp, _vp, _i, _i, _i, _i64, _i, _fp, _vp]),
+    "batq_weight_export": (_i, [_vp, _vp, _vp, _vp]),
+    "batq_weight_import": (_i, [C.POINTER(_vp), _vp, _vp, _i, _i, _vp]),
+    "batq_weight_shape": (_i, [_vp, C.POINTER(_i), C.POINTER(_i)]),
+    "batq_weight_destroy": (_i, [_vp]),
+    "batq_quantize_act": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp]),
+    "batq_gemm_mxfp4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
+    "batq_linear_workspace": (_sz, [_i, _i]),
+    "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
+}
+
+
+class BatqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.batq_status_string(status).decode() if lib is not None else "?"
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({msg})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_16590_amd.build` "
+            "(there is no fallback path)")
+    l = C.CDLL(LIB_PATH)
+    for name, (res, args) in SYMBOLS.items():
+        fn = getattr(l, name)            # AttributeError if the library does not export it
+        fn.restype = res
+        fn.argtypes = args
+    return l
+
+
+lib: Optional[C.CDLL] = None
+lib = _load()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise BatqError(status, where)
+
+
+def _fptr(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_fp)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+class Transform:
+    """Owns a batq_transform handle (shared factor G, private factors P, clip ratios)."""
+
+    def __init__(self, K: int, G: Optional[np.ndarray], P: Optional[np.ndarray], clip: Optional[np.ndarray],
+                 g_outer: int = 4, g_inner: int = 8):
+        self.K, self.g_outer, self.g_inner = K, g_outer, g_inner
+        self._h = _vp()
+        G = None if G is None else np.ascontiguousarray(G, dtype=np.float32)
+        P = None if P is None else np.ascontiguousarray(P, dtype=np.float32)
+        clip = None if clip is None else np.ascontiguousarray(clip, dtype=np.float32)
+        if G is not None:
+            assert G.shape == (g_outer, g_outer) and P.shape == (K // 32, g_inner, g_inner)
+        if clip is not None:
+            assert clip.shape == (K // 32,)
+        _check(lib.batq_transform_create(C.byref(self._h), K, g_outer, g_inner, _fptr(G), _fptr(P), _fptr(clip)),
+               "batq_transform_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if self._h:
+            lib.batq_transform_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Weight:
+    """Owns a batq_weight handle (prepared MXFP4 weights on the device)."""
+
+    def __init__(self, handle: _vp):
+        self._h = handle
+        k, n = _i(), _i()
+        _check(lib.batq_weight_shape(self._h, C.byref(k), C.byref(n)), "batq_weight_shape")
+        self.K, self.N = k.value, n.value
+
+    @property
+    def handle(self):
+        return self._h
+
+    def export(self):
+        """Canonical (codes [N, K/2], scales [N, K/32]) as uint8 device tensors."""
+        import torch
+        codes = torch.empty((self.N, self.K // 2), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((self.N, self.K // 32), dtype=torch.uint8, device="cuda")
+        _check(lib.batq_weight_export(self._h, codes.data_ptr(), scales.data_ptr(), _stream()), "batq_weight_export")
+        return codes, scales
+
+    def close(self):
+        if self._h:
+            lib.batq_weight_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def batq_prepare_weight(t: Transform, W, w_is_KxN: bool = True, clip_w: Optional[np.ndarray] = None) -> Weight:
+    """W: 2-D device tensor (fp32 or bf16), K x N if ``w_is_KxN`` else N x K; rows may be strided."""
+    assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1
+    K, N = (W.shape[0], W.shape[1]) if w_is_KxN else (W.shape[1], W.shape[0])
+    clip_w = None if clip_w is None else np.ascontiguousarray(clip_w, dtype=np.float32)
+    h = _vp()
+    _check(lib.batq_prepare_weight(C.byref(h), t.handle, W.data_ptr(), _dtype_code(W), K, N, W.stride(0),
+                                   1 if w_is_KxN else 0, _fptr(clip_w), _stream()), "batq_prepare_weight")
+    return Weight(h)
+
+
+def batq_weight_import(codes, scales, K: int, N: int) -> Weight:
+    assert codes.is_cuda and scales.is_cuda and codes.is_contiguous() and scales.is_contiguous()
+    h = _vp()
+    _check(lib.batq_weight_import(C.byref(h), codes.data_ptr(), scales.data_ptr(), K, N, _stream()),
+           "batq_weight_import")
+    return Weight(h)
+
+
+def batq_quantize_act(t: Transform, X, codes=None, scales=None):
+    """X: M x K device tensor (fp32 or bf16, unit column stride). Returns (codes, scales) uint8 tensors."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if codes is None:
+        codes = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device)
+    if scales is None:
+        scales = torch.empty((M, K // 32), dtype=torch.uint8, device=X.device)
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib.batq_quantize_act(t.handle, X.data_ptr(), _dtype_code(X), M, K, ldx, codes.data_ptr(),
+                                 scales.data_ptr(), _stream()), "batq_quantize_act")
+    return codes, scales
+
+
+def batq_gemm_mxfp4(xcodes, xscales, w: Weight, out_dtype=None, Y=None):
+    """GEMM on canonical activation codes/scales. Returns Y (M x N, fp32 or bf16)."""
+    import torch
+    M = xcodes.shape[0]
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes.device)
+    _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                               Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_mxfp4")
+    return Y
+
+
+def batq_linear_workspace(M: int, K: int) -> int:
+    return int(lib.batq_linear_workspace(M, K))
+
+
+def batq_linear(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspace=None):
+    """Y = Q(X P) Q(P^-1 W): fused transform+quantise kernel, then the MXFP4 GEMM."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
+    need = batq_linear_workspace(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+    _check(lib.batq_linear(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
+                           X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
+                           Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
+                           workspace.numel(), _stream()), "batq_linear")
+    return Y

@@ -1,0 +1,347 @@
+// C ABI of libbatq: argument validation, handle management, host-side fp64 inversion of
+// the Kronecker factors (Alg. 2 uses A^-1 and B_i^-1 for the weight side).
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "batq_internal.h"
+
+namespace {
+
+#define BATQ_HIP(expr)                                   \
+    do {                                                 \
+        if ((expr) != hipSuccess) {                      \
+            (void)hipGetLastError();                     \
+            return BATQ_ERR_DEVICE;                      \
+        }                                                \
+    } while (0)
+
+// In-place fp64 Gauss-Jordan inverse with partial pivoting of an n x n row-major matrix.
+bool invert_small(const double* A, int n, double* inv) {
+    std::vector<double> a(A, A + n * n);
+    double amax = 0.0;
+    for (double v : a) amax = std::fmax(amax, std::fabs(v));
+    if (!(amax > 0.0) || !std::isfinite(amax)) return false;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) inv[i * n + j] = (i == j) ? 1.0 : 0.0;
+    for (int col = 0; col < n; ++col) {
+        int piv = col;
+        for (int r = col + 1; r < n; ++r)
+            if (std::fabs(a[r * n + col]) > std::fabs(a[piv * n + col])) piv = r;
+        if (!(std::fabs(a[piv * n + col]) >= 1e-12 * amax)) return false;
+        if (piv != col)
+            for (int j = 0; j < n; ++j) {
+                std::swap(a[piv * n + j], a[col * n + j]);
+                std::swap(inv[piv * n + j], inv[col * n + j]);
+            }
+        const double d = 1.0 / a[col * n + col];
+        for (int j = 0; j < n; ++j) {
+            a[col * n + j] *= d;
+            inv[col * n + j] *= d;
+        }
+        for (int r = 0; r < n; ++r) {
+            if (r == col) continue;
+            const double f = a[r * n + col];
+            if (f == 0.0) continue;
+            for (int j = 0; j < n; ++j) {
+                a[r * n + j] -= f * a[col * n + j];
+                inv[r * n + j] -= f * inv[col * n + j];
+            }
+        }
+    }
+    return true;
+}
+
+bool clip_ok(const float* c, int n) {
+    for (int i = 0; i < n; ++i)
+        if (!(c[i] > 0.0f && c[i] <= 1.0f)) return false;
+    return true;
+}
+
+bool dtype_ok(batq_dtype d) { return d == BATQ_F32 || d == BATQ_BF16; }
+size_t dtype_size(batq_dtype d) { return d == BATQ_BF16 ? 2 : 4; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+batq_status check_device() {
+    static int state = 0;   // 0 unknown, 1 ok, 2 bad
+    if (state == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return BATQ_ERR_DEVICE;
+        }
+        state = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
+    }
+    return state == 1 ? BATQ_OK : BATQ_ERR_DEVICE;
+}
+
+template <typename T>
+batq_status upload(T** dst, const T* src, size_t count) {
+    if (hipMalloc(reinterpret_cast<void**>(dst), count * sizeof(T)) != hipSuccess) {
+        (void)hipGetLastError();
+        *dst = nullptr;
+        return BATQ_ERR_ALLOC;
+    }
+    BATQ_HIP(hipMemcpy(*dst, src, count * sizeof(T), hipMemcpyHostToDevice));
+    return BATQ_OK;
+}
+
+void free_transform(batq_transform* t) {
+    if (!t) return;
+    if (t->d_G) (void)hipFree(t->d_G);
+    if (t->d_P) (void)hipFree(t->d_P);
+    if (t->d_clip) (void)hipFree(t->d_clip);
+    if (t->d_Tinv) (void)hipFree(t->d_Tinv);
+    if (t->d_Tsplit) (void)hipFree(t->d_Tsplit);
+    delete t;
+}
+
+void free_weight(batq_weight* w) {
+    if (!w) return;
+    if (w->d_codes) (void)hipFree(w->d_codes);
+    if (w->d_scales) (void)hipFree(w->d_scales);
+    delete w;
+}
+
+batq_status alloc_weight(batq_weight** out, int K, int N) {
+    batq_weight* w = new (std::nothrow) batq_weight;
+    if (!w) return BATQ_ERR_ALLOC;
+    w->K = K;
+    w->N = N;
+    w->nb = K / 32;
+    if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), (size_t)N * (K / 2)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void**>(&w->d_scales), (size_t)N * (K / 32)) != hipSuccess) {
+        (void)hipGetLastError();
+        free_weight(w);
+        return BATQ_ERR_ALLOC;
+    }
+    *out = w;
+    return BATQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* batq_status_string(batq_status s) {
+    switch (s) {
+        case BATQ_OK: return "ok";
+        case BATQ_ERR_NULL: return "null pointer";
+        case BATQ_ERR_SHAPE: return "bad shape, stride or alignment";
+        case BATQ_ERR_DTYPE: return "unknown dtype";
+        case BATQ_ERR_UNSUPPORTED: return "unsupported Kronecker split";
+        case BATQ_ERR_SINGULAR: return "transform factor is singular";
+        case BATQ_ERR_CLIP_RANGE: return "clip ratio outside (0, 1]";
+        case BATQ_ERR_WORKSPACE: return "workspace too small";
+        case BATQ_ERR_ALLOC: return "allocation failed";
+        case BATQ_ERR_DEVICE: return "HIP error or device is not gfx950";
+        case BATQ_ERR_MISMATCH: return "transform and weight disagree on K";
+    }
+    return "unknown status";
+}
+
+const char* batq_version(void) { return "0.1"; }
+
+batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int g_inner, const float* G,
+                                  const float* P, const float* clip_a) {
+    if (!out) return BATQ_ERR_NULL;
+    if (K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (!((g_outer == 4 && g_inner == 8) || (g_outer == 8 && g_inner == 4))) return BATQ_ERR_UNSUPPORTED;
+    if ((G == nullptr) != (P == nullptr)) return BATQ_ERR_NULL;
+    const int nb = K / 32;
+    if (clip_a && !clip_ok(clip_a, nb)) return BATQ_ERR_CLIP_RANGE;
+
+    // host fp64: G^-1, P_k^-1 and the dense inverse blocks T_k^-1 = G^-1 (x) P_k^-1
+    std::vector<double> Tinv;
+    if (G) {
+        const int go = g_outer, gi = g_inner;
+        std::vector<double> Gd(go * go), Ginv(go * go), Pd(gi * gi), Pinv(gi * gi);
+        for (int i = 0; i < go * go; ++i) Gd[i] = G[i];
+        if (!invert_small(Gd.data(), go, Ginv.data())) return BATQ_ERR_SINGULAR;
+        Tinv.resize((size_t)nb * 1024);
+        for (int k = 0; k < nb; ++k) {
+            for (int i = 0; i < gi * gi; ++i) Pd[i] = P[(size_t)k * gi * gi + i];
+            if (!invert_small(Pd.data(), gi, Pinv.data())) return BATQ_ERR_SINGULAR;
+            double* Tk = Tinv.data() + (size_t)k * 1024;
+            for (int a = 0; a < go; ++a)
+                for (int c = 0; c < gi; ++c)
+                    for (int a2 = 0; a2 < go; ++a2)
+                        for (int c2 = 0; c2 < gi; ++c2)
+                            Tk[(a * gi + c) * 32 + a2 * gi + c2] = Ginv[a * go + a2] * Pinv[c * gi + c2];
+        }
+    }
+
+    batq_status st = check_device();
+    if (st != BATQ_OK) return st;
+    batq_transform* t = new (std::nothrow) batq_transform;
+    if (!t) return BATQ_ERR_ALLOC;
+    t->K = K;
+    t->nb = nb;
+    t->g_outer = g_outer;
+    t->g_inner = g_inner;
+    t->has_transform = G != nullptr;
+    t->has_clip = clip_a != nullptr;
+    std::vector<float> clip(nb, 1.0f);
+    if (clip_a) std::memcpy(clip.data(), clip_a, sizeof(float) * nb);
+    st = upload(&t->d_clip, clip.data(), (size_t)nb);
+    if (st == BATQ_OK && G) {
+        st = upload(&t->d_G, G, (size_t)g_outer * g_outer);
+        if (st == BATQ_OK) st = upload(&t->d_P, P, (size_t)nb * g_inner * g_inner);
+        if (st == BATQ_OK) st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
+    }
+    if (st != BATQ_OK) {
+        free_transform(t);
+        return st;
+    }
+    *out = t;
+    return BATQ_OK;
+}
+
+batq_status batq_transform_destroy(batq_transform* t) {
+    if (!t) return BATQ_ERR_NULL;
+    free_transform(t);
+    return BATQ_OK;
+}
+
+batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
+                                int K, int N, int64_t ldw, int w_is_KxN, const float* clip_w, void* stream) {
+    if (!out || !t || !W) return BATQ_ERR_NULL;
+    if (!dtype_ok(wdtype)) return BATQ_ERR_DTYPE;
+    if (K <= 0 || N <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (ldw < (w_is_KxN ? N : K)) return BATQ_ERR_SHAPE;
+    if (t->K != K) return BATQ_ERR_MISMATCH;
+    const int nb = K / 32;
+    if (clip_w && !clip_ok(clip_w, nb)) return BATQ_ERR_CLIP_RANGE;
+    batq_status st = check_device();
+    if (st != BATQ_OK) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    batq_weight* w = nullptr;
+    st = alloc_weight(&w, K, N);
+    if (st != BATQ_OK) return st;
+    float* d_clip_w = nullptr;
+    if (clip_w) {
+        st = upload(&d_clip_w, clip_w, (size_t)nb);
+        if (st != BATQ_OK) {
+            free_weight(w);
+            return st;
+        }
+    }
+    hipError_t e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_w, w->d_codes,
+                                               w->d_scales, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (d_clip_w) (void)hipFree(d_clip_w);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_weight(w);
+        return BATQ_ERR_DEVICE;
+    }
+    *out = w;
+    return BATQ_OK;
+}
+
+batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream) {
+    if (!w || !codes || !scales) return BATQ_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    BATQ_HIP(hipMemcpyAsync(codes, w->d_codes, (size_t)w->N * (w->K / 2), hipMemcpyDeviceToDevice, s));
+    BATQ_HIP(hipMemcpyAsync(scales, w->d_scales, (size_t)w->N * w->nb, hipMemcpyDeviceToDevice, s));
+    return BATQ_OK;
+}
+
+batq_status batq_weight_import(batq_weight** out, const uint8_t* codes, const uint8_t* scales, int K, int N,
+                               void* stream) {
+    if (!out || !codes || !scales) return BATQ_ERR_NULL;
+    if (K <= 0 || N <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    batq_status st = check_device();
+    if (st != BATQ_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    batq_weight* w = nullptr;
+    st = alloc_weight(&w, K, N);
+    if (st != BATQ_OK) return st;
+    hipError_t e = hipMemcpyAsync(w->d_codes, codes, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(w->d_scales, scales, (size_t)N * (K / 32), hipMemcpyDeviceToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_weight(w);
+        return BATQ_ERR_DEVICE;
+    }
+    *out = w;
+    return BATQ_OK;
+}
+
+batq_status batq_weight_shape(const batq_weight* w, int* K, int* N) {
+    if (!w || !K || !N) return BATQ_ERR_NULL;
+    *K = w->K;
+    *N = w->N;
+    return BATQ_OK;
+}
+
+batq_status batq_weight_destroy(batq_weight* w) {
+    if (!w) return BATQ_ERR_NULL;
+    free_weight(w);
+    return BATQ_OK;
+}
+
+batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                              int64_t ldx, uint8_t* codes, uint8_t* scales, void* stream) {
+    if (!t) return BATQ_ERR_NULL;
+    if (!dtype_ok(xdtype)) return BATQ_ERR_DTYPE;
+    if (M < 0 || K <= 0 || K % 32 != 0 || ldx < K) return BATQ_ERR_SHAPE;
+    if (t->K != K) return BATQ_ERR_MISMATCH;
+    if (M == 0) return BATQ_OK;          // nothing to do; empty tensors may carry null pointers
+    if (!X || !codes || !scales) return BATQ_ERR_NULL;
+    // rows are read with 128-bit loads and codes written as dwords
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes)) return BATQ_ERR_SHAPE;
+    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return BATQ_OK;
+}
+
+batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
+                            batq_dtype ydtype, int64_t ldy, void* stream) {
+    if (!w) return BATQ_ERR_NULL;
+    if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
+    if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M == 0) return BATQ_OK;
+    if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
+    if (!aligned16(xcodes)) return BATQ_ERR_SHAPE;
+    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return BATQ_OK;
+}
+
+size_t batq_linear_workspace(int M, int K) {
+    if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
+    // codes [M][K/2] followed by scales [M][K/32]; codes size is a multiple of 16 bytes
+    return (size_t)M * (K / 2) + (size_t)M * (K / 32);
+}
+
+batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
+                        int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    if (!t || !w) return BATQ_ERR_NULL;
+    if (!dtype_ok(xdtype) || !dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
+    if (t->K != w->K) return BATQ_ERR_MISMATCH;
+    if (M < 0 || ldx < t->K || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M == 0) return BATQ_OK;
+    if (!X || !Y || !workspace) return BATQ_ERR_NULL;
+    if (workspace_bytes < batq_linear_workspace(M, t->K)) return BATQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return BATQ_ERR_SHAPE;
+    uint8_t* codes = static_cast<uint8_t*>(workspace);
+    uint8_t* scales = codes + (size_t)M * (t->K / 2);
+    batq_status st = batq_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, stream);
+    if (st != BATQ_OK) return st;
+    return batq_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Internal declarations of libbatq: handle layouts and kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/batq.h"
+
+namespace batq {
+
+constexpr int kBlock = 32;   // MXFP block size (Sec. 2, MXFP definition)
+
+}  // namespace batq
+
+// Learned parameters of one transform set, host-validated and resident on the device.
+struct batq_transform {
+    int K = 0, nb = 0;
+    int g_outer = 4, g_inner = 8;
+    bool has_transform = false;   // false: T_k = I
+    bool has_clip = false;
+    float* d_G = nullptr;         // [g_outer*g_outer]            (null when !has_transform)
+    float* d_P = nullptr;         // [nb][g_inner*g_inner]        (null when !has_transform)
+    float* d_clip = nullptr;      // [nb], 1.0 when no clipping
+    double* d_Tinv = nullptr;     // [nb][32][32] fp64 T_k^-1     (null when !has_transform)
+    uint16_t* d_Tsplit = nullptr; // [nb][3][2][64][8] bf16 three-term split of T_k in MFMA operand order
+};
+
+// Prepared (inverse-transformed, quantised) weights.
+struct batq_weight {
+    int K = 0, N = 0, nb = 0;
+    uint8_t* d_codes = nullptr;   // canonical [N][K/2]
+    uint8_t* d_scales = nullptr;  // canonical [N][K/32]
+};
+
+namespace batq {
+
+// Each launcher validates nothing: callers (the C ABI) have checked shapes already.
+hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
+                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
+                                 uint8_t* scales, hipStream_t stream);
+hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M,
+                             void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream);
+
+}  // namespace batq

@@ -1,0 +1,48 @@
+// Device-side MXFP4 encoding helpers (Sec. 2 of the paper: E2M1 elements, one UE8M0
+// scale per 32 elements), written for gfx950's scaled fp32->fp4 convert instruction.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace batq {
+
+// E8M0 byte of a block whose clipped bound is `bound` (>= 0, finite):
+// E = floor(log2 bound) - 2 clamped below at -127, byte = E + 127.  For a normal fp32
+// bound floor(log2) is the exponent field minus 127; zero and subnormal bounds have
+// field 0 and clamp to byte 0.
+__device__ __forceinline__ uint32_t e8m0_of_bound(float bound) {
+    uint32_t field = __float_as_uint(bound) >> 23;
+    return field > 2u ? field - 2u : 0u;
+}
+
+// The scale operand of the convert instruction is an fp32 whose exponent field is the
+// E8M0 byte (a field of 0 is read as 2^-127).
+__device__ __forceinline__ float scale_operand(uint32_t e8m0) { return __uint_as_float(e8m0 << 23); }
+
+// Clamp to [-bound, bound] keeping the element's own sign bit (also for zeros).
+__device__ __forceinline__ float clamp_keep_sign(float y, float bound) {
+    float m = __builtin_fminf(__builtin_fabsf(y), bound);
+    return __builtin_copysignf(m, y);
+}
+
+// Eight fp32 values -> eight E2M1 codes in one dword, element 0 in bits 3:0.
+// The hardware convert rounds to nearest even on the E2M1 grid, saturates at 6 and
+// keeps the sign bit of results that round to zero.
+__device__ __forceinline__ uint32_t encode8(const float* y, float bound, float sc) {
+    uint32_t r = 0;
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[0], bound), clamp_keep_sign(y[1], bound), sc, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[2], bound), clamp_keep_sign(y[3], bound), sc, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[4], bound), clamp_keep_sign(y[5], bound), sc, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[6], bound), clamp_keep_sign(y[7], bound), sc, 3);
+    return r;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+}  // namespace batq

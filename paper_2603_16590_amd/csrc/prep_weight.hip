@@ -1,0 +1,94 @@
+// Offline weight preparation (Alg. 2, "Offline Fusion for Deployment"):
+// W~ = P^-1 W per 32-row K-slab, optional block clip (Eq. 3-4), MXFP4 along K (Sec. 2).
+// Not on the timed path: written for accuracy (fp64 products with the host-inverted
+// fp64 blocks, one rounding to fp32) rather than speed.  gfx950 only.
+#include "batq_internal.h"
+#include "mxfp4_device.h"
+
+namespace batq {
+namespace {
+
+template <typename WT>
+__device__ __forceinline__ double load_w(const WT* p);
+template <>
+__device__ __forceinline__ double load_w<float>(const float* p) { return (double)*p; }
+template <>
+__device__ __forceinline__ double load_w<uint16_t>(const uint16_t* p) { return (double)bf16_bits_to_float(*p); }
+
+// One thread per (K-block k, output column n).  blockIdx.y = k, blockIdx.x tiles N by 256.
+template <typename WT, bool TRANSFORM>
+__global__ void __launch_bounds__(256)
+prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, int nb,
+                   const double* __restrict__ Tinv, const float* __restrict__ clip_w,
+                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    __shared__ double sT[TRANSFORM ? 32 * 32 : 1];
+    const int k = blockIdx.y;
+    if constexpr (TRANSFORM) {
+        for (int i = threadIdx.x; i < 32 * 32; i += 256) sT[i] = Tinv[(size_t)k * 1024 + i];
+        __syncthreads();
+    }
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+
+    double w[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const size_t idx = w_is_KxN ? (size_t)(32 * k + j) * ldw + n : (size_t)n * ldw + 32 * k + j;
+        w[j] = load_w<WT>(W + idx);
+    }
+    float y[32];
+    if constexpr (TRANSFORM) {
+#pragma unroll 4
+        for (int j2 = 0; j2 < 32; ++j2) {
+            double acc = 0.0;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) acc = __builtin_fma(sT[j2 * 32 + j], w[j], acc);
+            y[j2] = (float)acc;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 32; ++j) y[j] = (float)w[j];
+    }
+    float m = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[j]));
+    const float bound = clip_w ? clip_w[k] * m : m;
+    const uint32_t s = e8m0_of_bound(bound);
+    const float sc = scale_operand(s);
+    uint4 out;
+    out.x = encode8(y, bound, sc);
+    out.y = encode8(y + 8, bound, sc);
+    out.z = encode8(y + 16, bound, sc);
+    out.w = encode8(y + 24, bound, sc);
+    *reinterpret_cast<uint4*>(codes + (size_t)n * nb * 16 + (size_t)k * 16) = out;
+    scales[(size_t)n * nb + k] = (uint8_t)s;
+}
+
+}  // namespace
+
+hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
+                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
+                                 uint8_t* scales, hipStream_t stream) {
+    const int nb = K / 32;
+    const dim3 grid((N + 255) / 256, nb), block(256);
+    if (wdtype == BATQ_BF16) {
+        auto Wp = static_cast<const uint16_t*>(W);
+        if (t->has_transform)
+            prep_weight_kernel<uint16_t, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
+                                                                           d_clip_w, codes, scales);
+        else
+            prep_weight_kernel<uint16_t, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
+                                                                            d_clip_w, codes, scales);
+    } else {
+        auto Wp = static_cast<const float*>(W);
+        if (t->has_transform)
+            prep_weight_kernel<float, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
+                                                                        d_clip_w, codes, scales);
+        else
+            prep_weight_kernel<float, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
+                                                                         d_clip_w, codes, scales);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace batq

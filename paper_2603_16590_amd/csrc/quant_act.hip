@@ -1,0 +1,181 @@
+// Fused online activation path: block-wise affine transform (Eq. 1-2, Global-and-Private
+// Kronecker factors), block clipping (Eq. 3-4, symmetric form) and MXFP4 quantisation
+// (Sec. 2: E2M1 elements, one UE8M0 scale per 32).  gfx950 only.
+//
+// Register-level kernel (`quant_act_quad`).  One quad of lanes owns one 32-element block
+// of one row: lane q of the quad holds the 8 contiguous elements 8q..8q+7 (one 128-bit load
+// for bf16).  The Kronecker structure T_k = G (x) P_k splits the 32x32 block product into
+//   - a product with the factor that acts on the contiguous index, done in the lane's own
+//     registers, and
+//   - a mix across the four lanes of the quad with the other factor, done with DPP
+//     quad broadcasts,
+// which is the vec identity of Sec. 3.1.1 (12 multiply-adds per element instead of 32).
+// The block amax is a two-step DPP reduction inside the quad.  Every lane then emits its
+// 8 codes as one dword; lane 0 of the quad stores the scale byte.
+#include "batq_internal.h"
+#include "mxfp4_device.h"
+
+namespace batq {
+namespace {
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_quad(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+__device__ __forceinline__ void load8(const float* p, float (&x)[8]) {
+    const float4 a = reinterpret_cast<const float4*>(p)[0];
+    const float4 b = reinterpret_cast<const float4*>(p)[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+__device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xFFFF0000u);
+}
+
+// Mix across the quad: out = sum over source lanes s of coef[s] * (value held by lane s).
+#define BATQ_QUAD_MIX(out, v, c0, c1, c2, c3)            \
+    do {                                                  \
+        out = (c0) * dpp_quad<0x00>(v);                   \
+        out = __builtin_fmaf((c1), dpp_quad<0x55>(v), out); \
+        out = __builtin_fmaf((c2), dpp_quad<0xAA>(v), out); \
+        out = __builtin_fmaf((c3), dpp_quad<0xFF>(v), out); \
+    } while (0)
+
+// GO = size of the shared factor G (4 or 8); the private factor is (32/GO) x (32/GO).
+// MODE 0: no transform; 1: transform.
+template <typename XT, int GO, bool TRANSFORM>
+__global__ void __launch_bounds__(256)
+quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
+               const float* __restrict__ G, const float* __restrict__ P, const float* __restrict__ clip,
+               uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    constexpr int GI = 32 / GO;
+    const int q = threadIdx.x & 3;
+    int k = blockIdx.x * 64 + (threadIdx.x >> 2);
+    const bool live = k < nb;
+    if (!live) k = nb - 1;               // keep the whole quad running for the DPP exchanges
+
+    // factors, held in registers across the row loop
+    float Pr[GI * GI];
+    float Gc[GO == 4 ? 4 : 16];
+    if constexpr (TRANSFORM) {
+#pragma unroll
+        for (int i = 0; i < GI * GI; ++i) Pr[i] = P[(size_t)k * GI * GI + i];
+        if constexpr (GO == 4) {
+            // lane q produces row a' = q of the mixed result: needs G[a][q], a = 0..3
+#pragma unroll
+            for (int a = 0; a < 4; ++a) Gc[a] = G[a * 4 + q];
+        } else {
+            // lane q produces rows a' = 2q + h': needs G[2s+h][2q+h'], index (s, h, h')
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) Gc[s * 4 + h * 2 + h2] = G[(2 * s + h) * 8 + 2 * q + h2];
+        }
+    }
+    const float ck = clip[k];
+
+    const int row0 = blockIdx.y * rows_per_wg;
+    const int row1 = min(M, row0 + rows_per_wg);
+    const size_t Kh = (size_t)nb * 16;   // bytes of codes per row
+    for (int row = row0; row < row1; ++row) {
+        float x[8], y[8];
+        load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, x);
+        if constexpr (TRANSFORM) {
+            float v[8];
+            if constexpr (GO == 4) {
+                // private 8x8 factor on the contiguous index, in registers
+#pragma unroll
+                for (int c2 = 0; c2 < 8; ++c2) {
+                    float acc = x[0] * Pr[c2];
+#pragma unroll
+                    for (int c = 1; c < 8; ++c) acc = __builtin_fmaf(x[c], Pr[c * 8 + c2], acc);
+                    v[c2] = acc;
+                }
+                // shared 4x4 factor across the quad
+#pragma unroll
+                for (int c2 = 0; c2 < 8; ++c2) BATQ_QUAD_MIX(y[c2], v[c2], Gc[0], Gc[1], Gc[2], Gc[3]);
+            } else {
+                // private 4x4 factor on each of the lane's two rows
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int c2 = 0; c2 < 4; ++c2) {
+                        float acc = x[4 * h] * Pr[c2];
+#pragma unroll
+                        for (int c = 1; c < 4; ++c) acc = __builtin_fmaf(x[4 * h + c], Pr[c * 4 + c2], acc);
+                        v[4 * h + c2] = acc;
+                    }
+                // shared 8x8 factor: 8 source rows live in 4 lanes x 2 registers
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                    for (int c2 = 0; c2 < 4; ++c2) {
+                        float lo, hi;
+                        BATQ_QUAD_MIX(lo, v[c2], Gc[0 + h2], Gc[4 + h2], Gc[8 + h2], Gc[12 + h2]);
+                        BATQ_QUAD_MIX(hi, v[4 + c2], Gc[2 + h2], Gc[6 + h2], Gc[10 + h2], Gc[14 + h2]);
+                        y[4 * h2 + c2] = lo + hi;
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) y[i] = x[i];
+        }
+
+        // block amax over the quad's 32 values
+        float m = __builtin_fabsf(y[0]);
+#pragma unroll
+        for (int i = 1; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(y[i]));
+        m = __builtin_fmaxf(m, dpp_quad<0xB1>(m));
+        m = __builtin_fmaxf(m, dpp_quad<0x4E>(m));
+
+        const float bound = ck * m;                     // one fp32 multiply
+        const uint32_t s = e8m0_of_bound(bound);
+        const uint32_t packed = encode8(y, bound, scale_operand(s));
+        if (live) {
+            *reinterpret_cast<uint32_t*>(codes + (size_t)row * Kh + (size_t)k * 16 + q * 4) = packed;
+            if (q == 0) scales[(size_t)row * nb + k] = (uint8_t)s;
+        }
+    }
+}
+
+template <typename XT>
+hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes,
+                       uint8_t* scales, hipStream_t stream) {
+    const int nb = t->nb;
+    const int gx = (nb + 63) / 64;
+    // aim at >= 4 workgroups per CU while keeping the per-lane factor loads amortised
+    int rows_per_wg = 16;
+    while (rows_per_wg > 1 && (long)gx * ((M + rows_per_wg - 1) / rows_per_wg) < 2048) rows_per_wg >>= 1;
+    const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
+    if (!t->has_transform)
+        quant_act_quad<XT, 4, false><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, nullptr,
+                                                                  t->d_clip, codes, scales);
+    else if (t->g_outer == 4)
+        quant_act_quad<XT, 4, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
+                                                                 t->d_clip, codes, scales);
+    else
+        quant_act_quad<XT, 8, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
+                                                                 t->d_clip, codes, scales);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+    (void)K;
+    if (M == 0) return hipSuccess;
+    if (xdtype == BATQ_BF16)
+        return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+    return launch_quad(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
+}
+
+}  // namespace batq

@@ -1,0 +1,166 @@
+"""GPU parity: MXFP4 x MXFP4 GEMM and the whole batq_linear path against the fp64 oracle.
+
+Bar: relative Frobenius error <= 1e-3 against the oracle's fp64 product of the same
+dequantised operands (the codes and scales the GPU itself produced).  A bf16 output is
+compared with the oracle's result rounded to bf16 (bf16 rounding alone is ~1.7e-3 relative,
+so the unrounded fp64 result cannot be the reference for it) and may differ by one bf16 ulp
+where the fp32 accumulation order moves a value across a rounding boundary.
+"""
+import numpy as np
+import pytest
+
+import batq_inputs as bi
+from oracle import batq_oracle as o
+from gpu_util import require_gpu, to_dev, y_to_f32, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    require_gpu()
+    import paper_2603_16590_amd as b
+    return b
+
+
+def _relfro(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def _rand_q(rng, R, K, lo=118, hi=136):
+    import torch
+    codes = rng.integers(0, 256, size=(R, K // 2), dtype=np.uint8)
+    scales = rng.integers(lo, hi, size=(R, K // 32), dtype=np.uint8)
+    return codes, scales, torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda()
+
+
+def test_single_block_is_exact(B):
+    # K = 32: every product and the 32-term sum are exact in fp32, so the result equals the oracle's
+    import torch
+    rng = np.random.default_rng(0)
+    xc, xs, dxc, dxs = _rand_q(rng, 40, 32)
+    wc, ws, dwc, dws = _rand_q(rng, 50, 32)
+    wh = B.batq_weight_import(dwc, dws, 32, 50)
+    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    torch.cuda.synchronize()
+    ref = o.gemm(xc, xs, wc, ws)
+    assert np.array_equal(y_to_f32(Y).astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 64, 1), (37, 96, 70), (64, 128, 64), (65, 160, 129), (130, 1024, 96),
+                                   (16, 4096, 256), (300, 2048 + 64, 520)])
+def test_small_shapes_random_codes(B, M, K, N):
+    import torch
+    rng = np.random.default_rng(M * 7 + K + N)
+    xc, xs, dxc, dxs = _rand_q(rng, M, K)
+    wc, ws, dwc, dws = _rand_q(rng, N, K)
+    wh = B.batq_weight_import(dwc, dws, K, N)
+    ref = o.gemm(xc, xs, wc, ws)
+    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    torch.cuda.synchronize()
+    assert _relfro(y_to_f32(Y), ref) <= 1e-5
+    # element-wise: fp32 accumulation of nb exact block terms
+    tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
+    assert np.all(np.abs(y_to_f32(Y) - ref) <= tol + 1e-30)
+    Yb = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.bfloat16)
+    torch.cuda.synchronize()
+    refb = o.bf16_round(ref).astype(np.float64)
+    got = y_to_f32(Yb).astype(np.float64)
+    assert _relfro(got, refb) <= 1e-3
+    # one bf16 ulp, plus the fp32 accumulation error where the sum cancels
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+    assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol)
+
+
+def test_extreme_scales(B):
+    import torch
+    rng = np.random.default_rng(5)
+    xc, xs, dxc, dxs = _rand_q(rng, 33, 64, lo=0, hi=40)
+    wc, ws, dwc, dws = _rand_q(rng, 34, 64, lo=200, hi=255)
+    wh = B.batq_weight_import(dwc, dws, 64, 34)
+    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    torch.cuda.synchronize()
+    ref = o.gemm(xc, xs, wc, ws)
+    assert _relfro(y_to_f32(Y), ref) <= 1e-5
+
+
+def test_strided_output_and_empty(B):
+    import torch
+    rng = np.random.default_rng(6)
+    xc, xs, dxc, dxs = _rand_q(rng, 20, 64)
+    wc, ws, dwc, dws = _rand_q(rng, 24, 64)
+    wh = B.batq_weight_import(dwc, dws, 64, 24)
+    wide = torch.full((20, 40), 7.0, device="cuda")
+    B.batq_gemm_mxfp4(dxc, dxs, wh, Y=wide[:, :24])
+    torch.cuda.synchronize()
+    assert _relfro(wide[:, :24].cpu().numpy(), o.gemm(xc, xs, wc, ws)) <= 1e-5
+    assert bool((wide[:, 24:] == 7.0).all())
+    Y0 = B.batq_gemm_mxfp4(dxc[:0], dxs[:0], wh, torch.float32)
+    assert Y0.shape == (0, 24)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_linear_all_configs(B, cfg):
+    """batq_linear at full size; checked on sampled rows x sampled columns against the oracle GEMM
+    of the operands the GPU produced, and end to end against the pure-oracle layer."""
+    import torch
+    w = bi.make_workload(cfg)
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    wh = B.batq_prepare_weight(t, to_dev(w.W, w.dtype))
+    X = to_dev(w.X, w.dtype)
+    ws_bytes = B.batq_linear_workspace(w.M, w.K)
+    assert ws_bytes == w.M * w.K // 2 + w.M * w.K // 32
+    work = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out_dtype = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
+    Y = B.batq_linear(t, wh, X, out_dtype, workspace=work)
+    Y32 = B.batq_linear(t, wh, X, torch.float32, workspace=work)
+    torch.cuda.synchronize()
+    rows = sample_rows(w.M, 96, seed=cfg)
+    cols = sample_rows(w.N, 768, seed=cfg + 10)
+    xcodes = work[: w.M * w.K // 2].view(w.M, w.K // 2)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    xscales = work[w.M * w.K // 2:].view(w.M, w.K // 32)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    wc, wsc = wh.export()
+    torch.cuda.synchronize()
+    wc, wsc = wc[torch.from_numpy(cols).cuda()].cpu().numpy(), wsc[torch.from_numpy(cols).cuda()].cpu().numpy()
+    ref = o.gemm(xcodes, xscales, wc, wsc)
+    sub = lambda T: T[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].float().cpu().numpy()
+    e32 = _relfro(sub(Y32), ref)
+    assert e32 <= 1e-3 and e32 <= 1e-5, e32
+    if w.out_dtype == "bf16":
+        refb = o.bf16_round(ref).astype(np.float64)
+        got = sub(Y).astype(np.float64)
+        eb = _relfro(got, refb)
+        assert eb <= 1e-3, eb
+        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+        tol = 1e-6 * (np.abs(o.dequantize(xcodes, xscales)) @ np.abs(o.dequantize(wc, wsc)).T)
+        assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol)
+    # end to end: the oracle quantises the same rows itself; only tie-level code differences remain
+    oxc, oxs = o.quantize_act(w.X_f32()[rows], w.G, w.P, w.clip)
+    owc, ows = o.prepare_weight(w.W_f32()[:, cols], w.G, w.P)
+    ref_e2e = o.gemm(oxc, oxs, owc, ows)
+    e2e = _relfro(sub(Y32), ref_e2e)
+    print(f"cfg {cfg}: fp32-out err {e32:.2e}, end-to-end err {e2e:.2e}")
+    assert e2e <= 2e-3, e2e
+
+
+def test_linear_argument_errors(B):
+    import torch
+    w = bi.make_small(8, 64, 16, seed=1, dtype="bf16")
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    wh = B.batq_prepare_weight(t, to_dev(w.W, "bf16"))
+    X = to_dev(w.X, "bf16")
+    Y = torch.zeros((8, 16), device="cuda")
+    work = torch.empty(B.batq_linear_workspace(8, 64), dtype=torch.uint8, device="cuda")
+    lib = B.lib
+    args = lambda **kw: None
+    assert lib.batq_linear(t.handle, wh.handle, X.data_ptr(), 1, 8, 64, Y.data_ptr(), 0, 16, work.data_ptr(),
+                           work.numel() - 1, None) == 7
+    assert lib.batq_linear(t.handle, wh.handle, X.data_ptr(), 1, 8, 64, Y.data_ptr(), 0, 8, work.data_ptr(),
+                           work.numel(), None) == 2
+    assert lib.batq_linear(t.handle, wh.handle, X.data_ptr(), 1, 8, 64, Y.data_ptr(), 0, 16, None,
+                           work.numel(), None) == 1
+    t2 = B.Transform(96, None, None, None)
+    assert lib.batq_linear(t2.handle, wh.handle, X.data_ptr(), 1, 8, 96, Y.data_ptr(), 0, 16, work.data_ptr(),
+                           work.numel(), None) == 10
+    torch.cuda.synchronize()
+    assert bool((Y == 0).all())

@@ -1,0 +1,216 @@
+"""GPU parity: batq_quantize_act (fused transform + clip + MXFP4) against the CPU oracle.
+
+Bars: codes and scales bit-exact when the GPU quantiser is fed the oracle's
+transformed fp32 tensor; end to end at most 0.1% of codes differ in value and
+every difference sits at a rounding tie.
+"""
+import numpy as np
+import pytest
+
+import batq_inputs as bi
+from oracle import batq_oracle as o
+from gpu_util import require_gpu, to_dev, unpack, code_value_mismatch, sample_rows, TIE_POINTS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    require_gpu()
+    import paper_2603_16590_amd as b
+    return b
+
+
+def _run(B, t, Xdev):
+    import torch
+    c, s = B.batq_quantize_act(t, Xdev)
+    torch.cuda.synchronize()
+    return c.cpu().numpy(), s.cpu().numpy()
+
+
+# ------------------------------------------------------------------ T1: quantiser alone, bit-exact
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_quantiser_bit_exact_on_oracle_transformed_input(B, cfg):
+    rows = {0: None, 1: None, 2: 512, 3: 256, 4: 512}[cfg]
+    w = bi.make_workload(cfg, rows=rows, with_weight=False)
+    Xt = o.transform(w.X_f32(), w.G, w.P)                       # oracle's fp32 transformed tensor
+    t = B.Transform(w.K, None, None, w.clip)
+    gc, gs = _run(B, t, to_dev(Xt, "f32"))
+    oc, os_ = o.mxfp4_quantize(Xt, w.clip)
+    assert np.array_equal(gs, os_)
+    assert np.array_equal(gc, oc)
+
+
+def test_exhaustive_bf16_patterns_bit_exact(B):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    f = bi.bf16_bits_to_f32(bits)
+    bits = bits[np.isfinite(f)]
+    rng = np.random.default_rng(7)
+    variants = [np.sort(bits), bits.copy(), rng.permutation(bits)]
+    # group by exponent so that every mantissa/sign pattern meets a block scale close to it
+    f_ok = bi.bf16_bits_to_f32(bits)
+    order = np.lexsort((rng.random(bits.size), np.abs(f_ok)))
+    variants.append(bits[order])
+    t = B.Transform(32 * 8, None, None, None)
+    for v in variants:
+        n = (v.size // 256) * 256
+        Xb = v[:n].reshape(-1, 256)
+        gc, gs = _run(B, t, to_dev(Xb, "bf16"))
+        oc, os_ = o.mxfp4_quantize(bi.bf16_bits_to_f32(Xb), None)
+        assert np.array_equal(gs, os_)
+        assert np.array_equal(gc, oc)
+
+
+def test_edge_blocks_bit_exact(B):
+    K = 64
+    rows = []
+    z = np.zeros(K, np.float32); rows.append(z)                                    # all-zero blocks
+    nz = np.zeros(K, np.float32); nz[::3] = -0.0; rows.append(nz)                  # signed zeros only
+    d = np.zeros(K, np.float32); d[:8] = np.float32(1e-41) * np.arange(1, 9); d[9] = -1e-42; rows.append(d)   # subnormal block
+    e = np.zeros(K, np.float32); e[0] = 2.0 ** -126; e[1] = -(2.0 ** -127); e[2] = 1.5 * 2.0 ** -125; rows.append(e)
+    h = np.zeros(K, np.float32); h[0] = 3.0e38; h[1] = -1.7e38; h[2] = 1e30; h[40] = -3.4e38; rows.append(h)  # near fp32 max
+    p = np.zeros(K, np.float32); p[:7] = TIE_POINTS * 4; p[7] = 24.0; p[32:39] = -TIE_POINTS / 8; p[39] = 0.75; rows.append(p)
+    X = np.stack(rows)
+    for clip in (None, np.array([0.6, 1.0], np.float32), np.array([1.0, 0.33], np.float32)):
+        t = B.Transform(K, None, None, clip)
+        gc, gs = _run(B, t, to_dev(X, "f32"))
+        oc, os_ = o.mxfp4_quantize(X, clip)
+        assert np.array_equal(gs, os_), clip
+        assert np.array_equal(gc, oc), clip
+
+
+# ------------------------------------------------------------------ T2: end to end with the transform
+def _check_end_to_end(w, gc, gs, rows_idx, g_outer=4, g_inner=8):
+    Xs = w.X_f32()[rows_idx]
+    T = o.kron_blocks(w.G, w.P)
+    Yt = o.apply_blocks(Xs, T)                                   # fp64, before the fp32 rounding
+    oc, os_ = o.mxfp4_quantize(Yt.astype(np.float32), w.clip)
+    gc, gs = gc[rows_idx], gs[rows_idx]
+    R, nb = os_.shape
+    scale_bad = gs != os_
+    mism = code_value_mismatch(gc, oc)
+    mism_blocks = mism.reshape(R, nb, 32)
+    # a block whose scale differs counts all 32 elements as mismatched
+    n_bad = int(np.where(scale_bad, 32, mism_blocks.sum(axis=2)).sum())
+    frac = n_bad / mism.size
+    assert frac <= 1e-3, f"{frac:.2e} of codes differ"
+    # every differing element (in blocks with equal scale) sits at a rounding tie:
+    # its exact scaled magnitude is within a few fp32 ulps (relative to the block range) of a tie point
+    Xc, bound = o.clip_blocks(Yt.astype(np.float32), w.clip)
+    E = os_.astype(np.int64) - 127
+    v = np.abs(np.minimum(np.abs(Yt.reshape(R, nb, 32)), bound[:, :, None].astype(np.float64))) / np.exp2(E)[:, :, None]
+    dist = np.abs(v[..., None] - TIE_POINTS).min(axis=-1)
+    sel = mism_blocks & ~scale_bad[:, :, None]
+    assert np.all(dist[sel] < 1e-4), dist[sel].max() if sel.any() else 0
+    # and the two codes are neighbours
+    g, oo = unpack(gc).reshape(R, nb, 32), unpack(oc).reshape(R, nb, 32)
+    assert np.all(np.abs((g & 7).astype(int) - (oo & 7).astype(int))[sel] <= 1)
+    # a scale difference can only come from a bound within rounding of a power of two (or of 5/4 of one)
+    if scale_bad.any():
+        b = bound[scale_bad].astype(np.float64)
+        m, _ = np.frexp(b)
+        assert np.all(np.minimum(np.abs(m - 0.5), np.abs(m - 1.0)) < 1e-5)
+    return frac
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_fused_transform_quantise_full_configs(B, cfg):
+    w = bi.make_workload(cfg, with_weight=False)
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    gc, gs = _run(B, t, to_dev(w.X, w.dtype))
+    assert gc.shape == (w.M, w.K // 2) and gs.shape == (w.M, w.K // 32)
+    idx = sample_rows(w.M, 192, seed=cfg)
+    frac = _check_end_to_end(w, gc, gs, idx)
+    print(f"cfg {cfg}: code mismatch fraction {frac:.2e} on {len(idx)} sampled rows")
+
+
+@pytest.mark.parametrize("M,K", [(1, 32), (3, 64), (37, 96), (65, 2080), (130, 4096 + 32), (17, 6144)])
+def test_ragged_shapes_and_both_dtypes(B, M, K):
+    for dtype in ("bf16", "f32"):
+        w = bi.make_small(M, K, 8, seed=M + K, dtype=dtype)
+        t = B.Transform(K, w.G, w.P, w.clip)
+        gc, gs = _run(B, t, to_dev(w.X, dtype))
+        _check_end_to_end(w, gc, gs, np.arange(M))
+
+
+def test_empty_input_is_a_noop(B):
+    import torch
+    t = B.Transform(64, None, None, None)
+    X = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    c, s = B.batq_quantize_act(t, X)
+    assert c.shape == (0, 32) and s.shape == (0, 2)
+
+
+def test_strided_rows(B):
+    import torch
+    w = bi.make_small(33, 128, 8, seed=5, dtype="bf16")
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    wide = torch.zeros((33, 256), dtype=torch.bfloat16, device="cuda")
+    wide[:, :128] = to_dev(w.X, "bf16")
+    gc, gs = _run(B, t, wide[:, :128])
+    gc2, gs2 = _run(B, t, to_dev(w.X, "bf16"))
+    assert np.array_equal(gc, gc2) and np.array_equal(gs, gs2)
+
+
+def test_global8_private4_split(B):
+    w = bi.make_small(48, 256, 8, seed=9, dtype="bf16", g_outer=8, g_inner=4)
+    assert w.G.shape == (8, 8) and w.P.shape == (8, 4, 4)
+    t = B.Transform(w.K, w.G, w.P, w.clip, g_outer=8, g_inner=4)
+    gc, gs = _run(B, t, to_dev(w.X, "bf16"))
+    _check_end_to_end(w, gc, gs, np.arange(w.M))
+
+
+def test_special_transforms_are_bit_exact(B):
+    w = bi.make_workload(0)
+    nb = w.nb
+    rng = np.random.default_rng(17)
+    I8 = np.tile(np.eye(8, dtype=np.float32), (nb, 1, 1))
+    # identity == plain RTN
+    t = B.Transform(w.K, np.eye(4, dtype=np.float32), I8, w.clip)
+    gc, gs = _run(B, t, to_dev(w.X, "f32"))
+    oc, os_ = o.mxfp4_quantize(w.X, w.clip)
+    assert np.array_equal(gc, oc) and np.array_equal(gs, os_)
+    # permutations (exact arithmetic: one non-zero product per output)
+    G = np.eye(4, dtype=np.float32)[rng.permutation(4)]
+    P = np.stack([np.eye(8, dtype=np.float32)[rng.permutation(8)] for _ in range(nb)])
+    t = B.Transform(w.K, G, P, w.clip)
+    gc, gs = _run(B, t, to_dev(w.X, "f32"))
+    oc, os_ = o.quantize_act(w.X, G, P, w.clip)
+    assert np.array_equal(gc, oc) and np.array_equal(gs, os_)
+    # power-of-two scaling moves only the scale byte
+    t = B.Transform(w.K, np.eye(4, dtype=np.float32) * 8, I8, w.clip)
+    gc2, gs2 = _run(B, t, to_dev(w.X, "f32"))
+    oc0, os0 = o.mxfp4_quantize(w.X, w.clip)
+    assert np.array_equal(gc2, oc0) and np.array_equal(gs2.astype(int), os0.astype(int) + 3)
+    # block Hadamard (the block-rotation baseline as a special case): end-to-end bar
+    H2 = np.array([[1.0, 1.0], [1.0, -1.0]])
+    w.G = (np.kron(H2, H2) / 2).astype(np.float32)
+    w.P = np.tile((np.kron(H2, np.kron(H2, H2)) / np.sqrt(8.0)).astype(np.float32), (nb, 1, 1))
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    gc, gs = _run(B, t, to_dev(w.X, "f32"))
+    _check_end_to_end(w, gc, gs, np.arange(w.M))
+
+
+def test_deterministic(B):
+    w = bi.make_workload(1, with_weight=False)
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    X = to_dev(w.X, "bf16")
+    a = _run(B, t, X)
+    b = _run(B, t, X)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_argument_errors_leave_outputs_untouched(B):
+    import torch
+    t = B.Transform(64, None, None, None)
+    X = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    codes = torch.full((4, 32), 0xAB, dtype=torch.uint8, device="cuda")
+    scales = torch.full((4, 2), 0xCD, dtype=torch.uint8, device="cuda")
+    lib = B.lib
+    assert lib.batq_quantize_act(t.handle, X.data_ptr(), 1, 4, 96, 96, codes.data_ptr(), scales.data_ptr(), None) == 10
+    assert lib.batq_quantize_act(t.handle, X.data_ptr(), 1, 4, 64, 32, codes.data_ptr(), scales.data_ptr(), None) == 2
+    assert lib.batq_quantize_act(t.handle, X.data_ptr(), 7, 4, 64, 64, codes.data_ptr(), scales.data_ptr(), None) == 3
+    assert lib.batq_quantize_act(t.handle, X.data_ptr() + 2, 1, 4, 64, 64, codes.data_ptr(), scales.data_ptr(), None) == 2
+    assert lib.batq_quantize_act(t.handle, None, 1, 4, 64, 64, codes.data_ptr(), scales.data_ptr(), None) == 1
+    torch.cuda.synchronize()
+    assert bool((codes == 0xAB).all()) and bool((scales == 0xCD).all())

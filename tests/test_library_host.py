@@ -1,0 +1,105 @@
+"""CPU-side tests of libbatq: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2603_16590_amd as b
+    return b
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "batq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(batq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = _header_functions()
+    assert "batq_quantize_act" in names and "batq_linear" in names and "batq_prepare_weight" in names
+    raw = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"libbatq.so does not export {n}"
+    assert set(names) == set(B.SYMBOLS), "binding and header disagree on the entry points"
+
+
+def test_status_strings(B):
+    for code in range(11):
+        s = B.lib.batq_status_string(code)
+        assert s and s != b"unknown status"
+    assert B.lib.batq_status_string(99) == b"unknown status"
+    assert re.match(rb"\d+\.\d+", B.lib.batq_version())
+
+
+def _fp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def test_transform_argument_validation_happens_on_the_host(B):
+    lib = B.lib
+    h = C.c_void_p()
+    G = np.eye(4, dtype=np.float32)
+    P = np.tile(np.eye(8, dtype=np.float32), (2, 1, 1))
+    assert lib.batq_transform_create(None, 64, 4, 8, _fp(G), _fp(P), None) == 1
+    assert lib.batq_transform_create(C.byref(h), 60, 4, 8, _fp(G), _fp(P), None) == 2          # K % 32
+    assert lib.batq_transform_create(C.byref(h), 0, 4, 8, _fp(G), _fp(P), None) == 2
+    assert lib.batq_transform_create(C.byref(h), 64, 2, 16, _fp(G), _fp(P), None) == 4         # split
+    assert lib.batq_transform_create(C.byref(h), 64, 4, 8, _fp(G), None, None) == 1            # G without P
+    Ps = P.copy()
+    Ps[1, 3] = Ps[1, 2]                                                                        # two equal rows
+    assert lib.batq_transform_create(C.byref(h), 64, 4, 8, _fp(G), _fp(Ps), None) == 5
+    Gs = G.copy()
+    Gs[2, 2] = 0
+    assert lib.batq_transform_create(C.byref(h), 64, 4, 8, _fp(Gs), _fp(P), None) == 5
+    for bad in ([0.5, 1.5], [0.0, 1.0], [-0.1, 0.9], [float("nan"), 1.0]):
+        c = np.array(bad, np.float32)
+        assert lib.batq_transform_create(C.byref(h), 64, 4, 8, _fp(G), _fp(P), _fp(c)) == 6
+    assert not h.value                                                                         # nothing was created
+
+
+def test_null_handles_are_rejected(B):
+    lib = B.lib
+    assert lib.batq_transform_destroy(None) == 1
+    assert lib.batq_weight_destroy(None) == 1
+    assert lib.batq_quantize_act(None, None, 1, 4, 64, 64, None, None, None) == 1
+    assert lib.batq_gemm_mxfp4(None, None, None, 4, None, 0, 64, None) == 1
+    assert lib.batq_linear(None, None, None, 1, 4, 64, None, 0, 64, None, 0, None) == 1
+    k, n = C.c_int(), C.c_int()
+    assert lib.batq_weight_shape(None, C.byref(k), C.byref(n)) == 1
+
+
+def test_workspace_size(B):
+    assert B.batq_linear_workspace(2048, 4096) == 2048 * 2048 + 2048 * 128
+    assert B.batq_linear_workspace(16, 4096) % 16 == 0
+    assert B.batq_linear_workspace(0, 4096) == 0 and B.batq_linear_workspace(4, 48) == 0
+
+
+def test_no_fallback_when_library_is_missing(tmp_path, monkeypatch):
+    # the binding must fail loudly rather than fall back to another implementation
+    import importlib.util
+    src = open(os.path.join(ROOT, "paper_2603_16590_amd", "binding.py")).read()
+    p = tmp_path / "binding_copy.py"
+    p.write_text(src)
+    spec = importlib.util.spec_from_file_location("binding_copy", p)
+    mod = importlib.util.module_from_spec(spec)
+    with pytest.raises(ImportError):
+        spec.loader.exec_module(mod)
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_16590_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, f"{f} mentions the oracle"
+    otext = open(os.path.join(ROOT, "oracle", "batq_oracle.py")).read()
+    assert "paper_2603_16590_amd" not in otext and "ctypes" not in otext
