@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 MXFP4 linear hot path on one MI355X.
+
+One "step" is one pass of the whole online path, batq_linear = fused transform + clip +
+MXFP4 quantise of the activations followed by the MXFP4 x MXFP4 GEMM, over one batch of
+synthetic activations that is already resident in HBM.  Prints ONE JSON line.
+
+The timed loop rotates over enough distinct (X, workspace, Y) buffer sets that the
+footprint exceeds twice the 256 MB last-level cache, so the activation kernel is
+measured against HBM and not against the cache.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP4_TFLOPS = 10100.0    # MI355X dense MXFP4 MFMA
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+
+
+def _die(msg: str, code: int = 2):
+    print(msg, file=sys.stderr)
+    sys.exit(code)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, choices=[0, 1, 2, 3, 4],
+                    help="which synthetic configuration is the timed workload (default: 8B-class prefill up/gate)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        _die("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import batq_inputs as bi
+    import paper_2603_16590_amd as B
+
+    if not torch.cuda.is_available():
+        _die("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    torch.cuda.set_device(0)
+
+    def to_dev(a, dtype):
+        if dtype == "bf16":
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+    def run_config(cfg: int, steps: int, warmup: int):
+        w = bi.make_workload(cfg)
+        t = B.Transform(w.K, w.G, w.P, w.clip)
+        wh = B.batq_prepare_weight(t, to_dev(w.W, w.dtype))
+        ydt = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
+        xbytes = 2 if w.dtype == "bf16" else 4
+        ybytes = 2 if w.out_dtype == "bf16" else 4
+        wsz = B.batq_linear_workspace(w.M, w.K)
+        per_set = w.M * w.K * xbytes + wsz + w.M * w.N * ybytes
+        nsets = max(2, min(64, -(-(600 << 20) // per_set)))
+        X0 = to_dev(w.X, w.dtype)
+        Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
+        Ws = [torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+        Ys = [torch.empty((w.M, w.N), dtype=ydt, device="cuda") for _ in range(nsets)]
+        codes = [wk[: w.M * w.K // 2].view(w.M, w.K // 2) for wk in Ws]
+        scales = [wk[w.M * w.K // 2: wsz].view(w.M, w.K // 32) for wk in Ws]
+
+        def step(i):
+            j = i % nsets
+            B.batq_linear(t, wh, Xs[j], Y=Ys[j], workspace=Ws[j])
+
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_step = (t1 - t0) * 1e3 / steps
+
+        # per-kernel durations: HIP events on the stream the kernels are launched on
+        def timed(fn, n):
+            for i in range(min(warmup, 10)):
+                fn(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(n):
+                fn(i)
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        ms_quant = timed(lambda i: B.batq_quantize_act(t, Xs[i % nsets], codes[i % nsets], scales[i % nsets]), steps)
+        ms_gemm = timed(lambda i: B.batq_gemm_mxfp4(codes[i % nsets], scales[i % nsets], wh, Y=Ys[i % nsets]), steps)
+        ms_quant_warm = timed(lambda i: B.batq_quantize_act(t, Xs[0], codes[0], scales[0]), steps)
+
+        flops = 2.0 * w.M * w.K * w.N
+        qbytes = w.M * w.K * (xbytes + 0.5 + 1.0 / 32)
+        res = {
+            "workload": f"cfg{cfg}:{w.name} M={w.M} K={w.K} N={w.N} x={w.dtype} y={w.out_dtype}",
+            "ms_per_step": ms_step,
+            "linear_tflops": flops / ms_step / 1e9,
+            "quant_ms": ms_quant, "quant_gbs": qbytes / ms_quant / 1e6,
+            "quant_gbs_cache_warm": qbytes / ms_quant_warm / 1e6,
+            "gemm_ms": ms_gemm, "gemm_tflops": flops / ms_gemm / 1e9,
+            "buffer_sets": nsets,
+        }
+        return w, t, wh, res, flops, qbytes
+
+    w, t, wh, res, flops, qbytes = run_config(args.workload, args.steps, args.warmup)
+
+    # the dominant kernel of the step decides which roofline is reported first
+    gemm_dominant = res["gemm_ms"] >= res["quant_ms"]
+    roof_gemm = {"kernel": "gemm_mxfp4", "bound": "mfma", "achieved": res["gemm_tflops"], "peak": PEAK_FP4_TFLOPS,
+                 "unit": "TFLOP/s", "frac": res["gemm_tflops"] / PEAK_FP4_TFLOPS, "traffic": None}
+    roof_quant = {"kernel": "quant_act", "bound": "hbm", "achieved": res["quant_gbs"], "peak": PEAK_HBM_GBS,
+                  "unit": "GB/s", "frac": res["quant_gbs"] / PEAK_HBM_GBS, "traffic": None}
+    traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            tr = json.load(open(traffic_file)).get(f"cfg{args.workload}", {})
+            roof_gemm["traffic"] = tr.get("gemm_mxfp4")
+            roof_quant["traffic"] = tr.get("quant_act")
+        except Exception:
+            pass
+
+    also = {}
+    for c in [int(x) for x in args.also.split(",") if x.strip() != ""]:
+        if c == args.workload:
+            continue
+        _, _, _, r, _, _ = run_config(c, max(10, args.steps // 4), max(3, args.warmup // 4))
+        also[f"cfg{c}"] = r
+        torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import batq_oracle as o
+        # bounded sample sized for roughly 10-30 s of oracle work on the host cores
+        ms_rows = min(w.M, 2048)
+        ns_cols = min(w.N, 8192)
+        Xs_ = w.X_f32()[:ms_rows]
+        Wc, Wsc = o.prepare_weight(w.W_f32()[:, :ns_cols], w.G, w.P)          # offline, not timed
+        c0 = time.perf_counter()
+        xc, xs = o.quantize_act(Xs_, w.G, w.P, w.clip)
+        c1 = time.perf_counter()
+        o.gemm(xc, xs, Wc, Wsc)
+        c2 = time.perf_counter()
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            blas_threads = len(os.sched_getaffinity(0))
+        cpu = {
+            "value": 2.0 * ms_rows * w.K * ns_cols / (c2 - c0) / 1e12, "unit": "TFLOP/s",
+            "cores": int(min(blas_threads, len(os.sched_getaffinity(0)))), "kind": "oracle",
+            "sample": f"{ms_rows} rows x {ns_cols} output columns of the same workload "
+                      f"(oracle quantize_act + fp64 dequantise/matmul; weights prepared beforehand)",
+            "quant_gbs": ms_rows * w.K * ((2 if w.dtype == 'bf16' else 4) + 0.5 + 1 / 32) / (c1 - c0) / 1e9,
+            "seconds": c2 - c0,
+        }
+
+    line = {
+        "metric": "W4A4 MXFP4 linear TFLOP/s incl. online transform+quantize",
+        "value": res["linear_tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "mxfp4 (e2m1 x e8m0), fp32 accumulate", "data": "synthetic",
+        "config": {"workload": res["workload"], "block": 32, "gpk": "G4x4 (x) P8x8", "buffer_sets": res["buffer_sets"]},
+        "quantize_gbs": res["quant_gbs"], "quantize_gbs_cache_warm": res["quant_gbs_cache_warm"],
+        "gemm_tflops": res["gemm_tflops"], "quant_ms": res["quant_ms"], "gemm_ms": res["gemm_ms"],
+        "roofline": roof_gemm if gemm_dominant else roof_quant,
+        "roofline_other": roof_quant if gemm_dominant else roof_gemm,
+        "cpu_baseline": cpu,
+        "also": also,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,22 +128,28 @@ batq_status batq_weight_destroy(batq_weight* w);
  *           storage only; nothing is rounded to bf16 before the quantiser)
  *   codes   DEVICE [M][K/2]   out
  *   scales  DEVICE [M][K/32]  out
+ * X and codes must be 16-byte aligned and ldx * sizeof(element) a multiple of 16.
  * M == 0 is a no-op.  A transform created with G == NULL quantises X as is.
  */
 batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype,
                               int M, int K, int64_t ldx,
                               uint8_t* codes, uint8_t* scales, void* stream);
 
-/* Online step 2 alone: MXFP4 x MXFP4 GEMM on canonical activation codes/scales.
+/* Online step 2 alone: MXFP4 x MXFP4 GEMM on activation codes/scales in the layout
+ * batq_quantize_act writes.
  *   Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} val(xq[m][32k+j]) val(wq[n][32k+j])
  * with fp32 accumulation; Y DEVICE M x N row-major, row stride ldy (>= N), fp32 or
- * bf16 (round-to-nearest-even). */
+ * bf16 (round-to-nearest-even).  `workspace` is DEVICE memory (16-byte aligned) of at
+ * least batq_gemm_workspace(M, K) bytes; the scales are re-ordered into it for the kernel. */
+size_t batq_gemm_workspace(int M, int K);
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
-                            int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+                            int M, void* Y, batq_dtype ydtype, int64_t ldy,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
- * `workspace` is DEVICE memory of at least batq_linear_workspace(M, K) bytes that
- * holds the activation codes and scales between the two kernels. */
+ * `workspace` is DEVICE memory (16-byte aligned) of at least batq_linear_workspace(M, K)
+ * bytes.  It holds the activation codes ([M][K/2], at offset 0) and their scales (in the
+ * GEMM's own order) between the two kernels; its contents are otherwise unspecified. */
 size_t batq_linear_workspace(int M, int K);
 batq_status batq_linear(const batq_transform* t, const batq_weight* w,
                         const void* X, batq_dtype xdtype, int M, int64_t ldx,

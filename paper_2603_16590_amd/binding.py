@@ -38,7 +38,8 @@ SYMBOLS = {
     "batq_weight_shape": (_i, [_vp, C.POINTER(_i), C.POINTER(_i)]),
     "batq_weight_destroy": (_i, [_vp]),
     "batq_quantize_act": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp]),
-    "batq_gemm_mxfp4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
+    "batq_gemm_workspace": (_sz, [_i, _i]),
+    "batq_gemm_mxfp4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_linear_workspace": (_sz, [_i, _i]),
     "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
 }
@@ -194,14 +195,21 @@ def batq_quantize_act(t: Transform, X, codes=None, scales=None):
     return codes, scales
 
 
-def batq_gemm_mxfp4(xcodes, xscales, w: Weight, out_dtype=None, Y=None):
-    """GEMM on canonical activation codes/scales. Returns Y (M x N, fp32 or bf16)."""
+def batq_gemm_workspace(M: int, K: int) -> int:
+    return int(lib.batq_gemm_workspace(M, K))
+
+
+def batq_gemm_mxfp4(xcodes, xscales, w: Weight, out_dtype=None, Y=None, workspace=None):
+    """GEMM on activation codes/scales as batq_quantize_act writes them. Returns Y (M x N, fp32 or bf16)."""
     import torch
     M = xcodes.shape[0]
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes.device)
+    if workspace is None:
+        workspace = torch.empty((max(batq_gemm_workspace(M, w.K), 16),), dtype=torch.uint8, device=xcodes.device)
     _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
-                               Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_mxfp4")
+                               Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
+                               workspace.numel(), _stream()), "batq_gemm_mxfp4")
     return Y
 
 

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "batq_internal.h"
+#include "scale_layout.h"
 
 namespace {
 
@@ -113,7 +114,7 @@ batq_status alloc_weight(batq_weight** out, int K, int N) {
     w->N = N;
     w->nb = K / 32;
     if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), (size_t)N * (K / 2)) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void**>(&w->d_scales), (size_t)N * (K / 32)) != hipSuccess) {
+        hipMalloc(reinterpret_cast<void**>(&w->d_scales), batq::scale_bytes_internal(N, K / 32)) != hipSuccess) {
         (void)hipGetLastError();
         free_weight(w);
         return BATQ_ERR_ALLOC;
@@ -230,8 +231,10 @@ batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, cons
             return st;
         }
     }
-    hipError_t e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_w, w->d_codes,
-                                               w->d_scales, s);
+    // padding blocks of the last scale group carry the neutral scale
+    hipError_t e = hipMemsetAsync(w->d_scales, 127, batq::scale_bytes_internal(N, nb), s);
+    if (e == hipSuccess)
+        e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_w, w->d_codes, w->d_scales, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (d_clip_w) (void)hipFree(d_clip_w);
     if (e != hipSuccess) {
@@ -247,7 +250,7 @@ batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* sc
     if (!w || !codes || !scales) return BATQ_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     BATQ_HIP(hipMemcpyAsync(codes, w->d_codes, (size_t)w->N * (w->K / 2), hipMemcpyDeviceToDevice, s));
-    BATQ_HIP(hipMemcpyAsync(scales, w->d_scales, (size_t)w->N * w->nb, hipMemcpyDeviceToDevice, s));
+    BATQ_HIP(batq::launch_scales_to_canonical(w->d_scales, scales, w->N, w->nb, s));
     return BATQ_OK;
 }
 
@@ -262,7 +265,7 @@ batq_status batq_weight_import(batq_weight** out, const uint8_t* codes, const ui
     st = alloc_weight(&w, K, N);
     if (st != BATQ_OK) return st;
     hipError_t e = hipMemcpyAsync(w->d_codes, codes, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, s);
-    if (e == hipSuccess) e = hipMemcpyAsync(w->d_scales, scales, (size_t)N * (K / 32), hipMemcpyDeviceToDevice, s);
+    if (e == hipSuccess) e = batq::launch_scales_to_internal(scales, w->d_scales, N, K / 32, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -296,24 +299,34 @@ batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype
     if (!X || !codes || !scales) return BATQ_ERR_NULL;
     // rows are read with 128-bit loads and codes written as dwords
     if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes)) return BATQ_ERR_SHAPE;
-    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, static_cast<hipStream_t>(stream)) !=
-        hipSuccess) {
+    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, false,
+                                  static_cast<hipStream_t>(stream)) != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
     return BATQ_OK;
 }
 
+size_t batq_gemm_workspace(int M, int K) {
+    if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
+    return batq::scale_bytes_internal(M, K / 32);
+}
+
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
-                            batq_dtype ydtype, int64_t ldy, void* stream) {
+                            batq_dtype ydtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                            void* stream) {
     if (!w) return BATQ_ERR_NULL;
     if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
     if (M == 0) return BATQ_OK;
-    if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
-    if (!aligned16(xcodes)) return BATQ_ERR_SHAPE;
-    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, static_cast<hipStream_t>(stream)) !=
-        hipSuccess) {
+    if (!xcodes || !xscales || !Y || !workspace) return BATQ_ERR_NULL;
+    if (workspace_bytes < batq_gemm_workspace(M, w->K)) return BATQ_ERR_WORKSPACE;
+    if (!aligned16(xcodes) || !aligned16(workspace)) return BATQ_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* xs_int = static_cast<uint8_t*>(workspace);
+    hipError_t e = batq::launch_scales_to_internal(xscales, xs_int, M, w->nb, s);
+    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(xcodes, xs_int, w, M, Y, ydtype, ldy, s);
+    if (e != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
@@ -322,8 +335,8 @@ batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const
 
 size_t batq_linear_workspace(int M, int K) {
     if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
-    // codes [M][K/2] followed by scales [M][K/32]; codes size is a multiple of 16 bytes
-    return (size_t)M * (K / 2) + (size_t)M * (K / 32);
+    // activation codes [M][K/2] (a multiple of 16 bytes) followed by their scales in the GEMM's layout
+    return (size_t)M * (K / 2) + batq::scale_bytes_internal(M, K / 32);
 }
 
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
@@ -336,12 +349,17 @@ batq_status batq_linear(const batq_transform* t, const batq_weight* w, const voi
     if (M == 0) return BATQ_OK;
     if (!X || !Y || !workspace) return BATQ_ERR_NULL;
     if (workspace_bytes < batq_linear_workspace(M, t->K)) return BATQ_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return BATQ_ERR_SHAPE;
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace)) return BATQ_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* codes = static_cast<uint8_t*>(workspace);
     uint8_t* scales = codes + (size_t)M * (t->K / 2);
-    batq_status st = batq_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, stream);
-    if (st != BATQ_OK) return st;
-    return batq_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, stream);
+    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, true, s);
+    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, s);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return BATQ_OK;
 }
 
 }  // extern "C"

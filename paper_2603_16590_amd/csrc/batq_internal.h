@@ -26,19 +26,25 @@ struct batq_transform {
 // Prepared (inverse-transformed, quantised) weights.
 struct batq_weight {
     int K = 0, N = 0, nb = 0;
-    uint8_t* d_codes = nullptr;   // canonical [N][K/2]
-    uint8_t* d_scales = nullptr;  // canonical [N][K/32]
+    uint8_t* d_codes = nullptr;   // [N][K/2], K contiguous: one 16-byte chunk per MX block
+    uint8_t* d_scales = nullptr;  // internal group-major layout (scale_layout.h), padded groups
 };
 
 namespace batq {
 
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
+// scales_internal: write the scales in the GEMM's group-major layout instead of [M][K/32].
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool scales_internal,
+                               hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
                                  int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
                                  uint8_t* scales, hipStream_t stream);
-hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M,
+// Weight scales are written in the internal layout (pad bytes must have been set to 127).
+// xscales_internal: activation scales in the internal layout.
+hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
                              void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream);
+hipError_t launch_scales_to_internal(const uint8_t* canon, uint8_t* internal, int rows, int nb, hipStream_t stream);
+hipError_t launch_scales_to_canonical(const uint8_t* internal, uint8_t* canon, int rows, int nb, hipStream_t stream);
 
 }  // namespace batq
