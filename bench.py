@@ -73,7 +73,7 @@ def main():
         Ws = [torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
         Ys = [torch.empty((w.M, w.N), dtype=ydt, device="cuda") for _ in range(nsets)]
         codes = [wk[: w.M * w.K // 2].view(w.M, w.K // 2) for wk in Ws]
-        scales = [wk[w.M * w.K // 2: wsz].view(w.M, w.K // 32) for wk in Ws]
+        scales = [wk[w.M * w.K // 2: wsz] for wk in Ws]
 
         def step(i):
             j = i % nsets

@@ -21,10 +21,19 @@
  *   G: g_outer x g_outer shared ("global"), P_k: g_inner x g_inner ("private"),
  *   g_outer * g_inner = 32.  A row vector x_k is mapped to x_k T_k.
  *
- * Quantised tensor layout (both activations and exported weights):
+ * Quantised tensor layout:
  *   codes  [rows][K/2]  uint8, element 2j in bits 3:0 and 2j+1 in bits 7:4 of byte j;
  *                       a 4-bit code is S|E1 E0|M (bit 3 = sign);
- *   scales [rows][K/32] uint8, E8M0: value 2^(s-127); 255 is never produced.
+ *   scales uint8, E8M0: value 2^(s-127); 255 is never produced.  Two orders are used:
+ *     row-major  [rows][K/32]                      (weight export / import);
+ *     grouped    byte batq_scale_index(row, k, rows) of batq_scale_bytes(rows, K) bytes
+ *                (activations: written by batq_quantize_act, read by batq_gemm_mxfp4).
+ *                Blocks are grouped by 8 along K, group-major, 8 bytes per (group, row),
+ *                the even blocks of a group before the odd ones:
+ *                  index = ((k/8)*rows + row)*8 + (k%8)/2 + 4*(k%2);
+ *                a last partial group is padded with the neutral scale 127.  This is the
+ *                order in which the matrix instruction consumes scales (one dword per lane
+ *                per 256 K elements), so the GEMM reads them with contiguous loads.
  * Quantiser definition: bound = fl32(clip_k * max_j |y_j|); elements beyond +-bound
  * are replaced by +-bound; E = clamp(floor(log2 bound) - 2, -127, 127) (E = -127 for
  * a zero block); code = round-to-nearest on the E2M1 grid of y * 2^-E, ties to the
@@ -127,29 +136,35 @@ batq_status batq_weight_destroy(batq_weight* w);
  *           the products and sums of the transform are carried in fp32 (bf16 is
  *           storage only; nothing is rounded to bf16 before the quantiser)
  *   codes   DEVICE [M][K/2]   out
- *   scales  DEVICE [M][K/32]  out
- * X and codes must be 16-byte aligned and ldx * sizeof(element) a multiple of 16.
- * M == 0 is a no-op.  A transform created with G == NULL quantises X as is.
+ *   scales  DEVICE, batq_scale_bytes(M, K) bytes, grouped order, out
+ * X and codes must be 16-byte aligned, scales 8-byte aligned, and ldx * sizeof(element) a
+ * multiple of 16.  M == 0 is a no-op.  A transform created with G == NULL quantises X as is.
  */
 batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype,
                               int M, int K, int64_t ldx,
                               uint8_t* codes, uint8_t* scales, void* stream);
 
-/* Online step 2 alone: MXFP4 x MXFP4 GEMM on activation codes/scales in the layout
- * batq_quantize_act writes.
+/* Scale-order helpers (Sec. 2: one UE8M0 scale per 32 elements; the order is this library's).
+ * batq_scale_bytes: size of a grouped scale array (0 for invalid arguments).
+ * batq_scale_index: byte offset of block k of `row` in a grouped array of `rows` rows.
+ * The two conversions run on the device (both pointers DEVICE), enqueued on `stream`. */
+size_t batq_scale_bytes(int rows, int K);
+size_t batq_scale_index(int row, int k, int rows);
+batq_status batq_scales_to_rowmajor(const uint8_t* grouped, uint8_t* rowmajor, int rows, int K, void* stream);
+batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped, int rows, int K, void* stream);
+
+/* Online step 2 alone: MXFP4 x MXFP4 GEMM on activation codes and grouped scales as
+ * batq_quantize_act writes them.
  *   Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} val(xq[m][32k+j]) val(wq[n][32k+j])
  * with fp32 accumulation; Y DEVICE M x N row-major, row stride ldy (>= N), fp32 or
- * bf16 (round-to-nearest-even).  `workspace` is DEVICE memory (16-byte aligned) of at
- * least batq_gemm_workspace(M, K) bytes; the scales are re-ordered into it for the kernel. */
-size_t batq_gemm_workspace(int M, int K);
+ * bf16 (round-to-nearest-even). */
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
-                            int M, void* Y, batq_dtype ydtype, int64_t ldy,
-                            void* workspace, size_t workspace_bytes, void* stream);
+                            int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
 
 /* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
  * `workspace` is DEVICE memory (16-byte aligned) of at least batq_linear_workspace(M, K)
- * bytes.  It holds the activation codes ([M][K/2], at offset 0) and their scales (in the
- * GEMM's own order) between the two kernels; its contents are otherwise unspecified. */
+ * bytes (= M*K/2 + batq_scale_bytes(M, K)).  It holds the activation codes ([M][K/2], at
+ * offset 0) followed by their grouped scales between the two kernels. */
 size_t batq_linear_workspace(int M, int K);
 batq_status batq_linear(const batq_transform* t, const batq_weight* w,
                         const void* X, batq_dtype xdtype, int M, int64_t ldx,

@@ -298,35 +298,50 @@ batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype
     if (M == 0) return BATQ_OK;          // nothing to do; empty tensors may carry null pointers
     if (!X || !codes || !scales) return BATQ_ERR_NULL;
     // rows are read with 128-bit loads and codes written as dwords
-    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes)) return BATQ_ERR_SHAPE;
-    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, false,
-                                  static_cast<hipStream_t>(stream)) != hipSuccess) {
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes) ||
+        (reinterpret_cast<uintptr_t>(scales) & 7u) != 0)
+        return BATQ_ERR_SHAPE;
+    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
     return BATQ_OK;
 }
 
-size_t batq_gemm_workspace(int M, int K) {
-    if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
-    return batq::scale_bytes_internal(M, K / 32);
+size_t batq_scale_bytes(int rows, int K) {
+    if (rows <= 0 || K <= 0 || K % 32 != 0) return 0;
+    return batq::scale_bytes_internal(rows, K / 32);
+}
+
+size_t batq_scale_index(int row, int k, int rows) { return batq::scale_index_internal(row, k, rows); }
+
+batq_status batq_scales_to_rowmajor(const uint8_t* grouped, uint8_t* rowmajor, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!grouped || !rowmajor) return BATQ_ERR_NULL;
+    BATQ_HIP(batq::launch_scales_to_canonical(grouped, rowmajor, rows, K / 32, static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
+}
+
+batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!grouped || !rowmajor) return BATQ_ERR_NULL;
+    BATQ_HIP(batq::launch_scales_to_internal(rowmajor, grouped, rows, K / 32, static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
 }
 
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
-                            batq_dtype ydtype, int64_t ldy, void* workspace, size_t workspace_bytes,
-                            void* stream) {
+                            batq_dtype ydtype, int64_t ldy, void* stream) {
     if (!w) return BATQ_ERR_NULL;
     if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
     if (M == 0) return BATQ_OK;
-    if (!xcodes || !xscales || !Y || !workspace) return BATQ_ERR_NULL;
-    if (workspace_bytes < batq_gemm_workspace(M, w->K)) return BATQ_ERR_WORKSPACE;
-    if (!aligned16(xcodes) || !aligned16(workspace)) return BATQ_ERR_SHAPE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    uint8_t* xs_int = static_cast<uint8_t*>(workspace);
-    hipError_t e = batq::launch_scales_to_internal(xscales, xs_int, M, w->nb, s);
-    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(xcodes, xs_int, w, M, Y, ydtype, ldy, s);
-    if (e != hipSuccess) {
+    if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
+    if (!aligned16(xcodes) || (reinterpret_cast<uintptr_t>(xscales) & 7u) != 0) return BATQ_ERR_SHAPE;
+    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
@@ -353,7 +368,7 @@ batq_status batq_linear(const batq_transform* t, const batq_weight* w, const voi
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* codes = static_cast<uint8_t*>(workspace);
     uint8_t* scales = codes + (size_t)M * (t->K / 2);
-    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, true, s);
+    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, s);
     if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, s);
     if (e != hipSuccess) {
         (void)hipGetLastError();

@@ -33,15 +33,14 @@ struct batq_weight {
 namespace batq {
 
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
-// scales_internal: write the scales in the GEMM's group-major layout instead of [M][K/32].
+// Scales are written in the grouped layout of scale_layout.h (padding blocks included).
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool scales_internal,
-                               hipStream_t stream);
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
                                  int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
                                  uint8_t* scales, hipStream_t stream);
 // Weight scales are written in the internal layout (pad bytes must have been set to 127).
-// xscales_internal: activation scales in the internal layout.
+// xscales_internal: activation scales in the grouped layout.
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
                              void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream);
 hipError_t launch_scales_to_internal(const uint8_t* canon, uint8_t* internal, int rows, int nb, hipStream_t stream);

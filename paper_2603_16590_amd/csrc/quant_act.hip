@@ -11,7 +11,7 @@
 //     quad broadcasts,
 // which is the vec identity of Sec. 3.1.1 (12 multiply-adds per element instead of 32).
 // The block amax is a two-step DPP reduction inside the quad.  Every lane then emits its
-// 8 codes as one dword; lane 0 of the quad stores the scale byte.
+// 8 codes as one dword; lane 0 of the quad stores the scale byte (grouped scale layout).
 #include "batq_internal.h"
 #include "mxfp4_device.h"
 #include "scale_layout.h"
@@ -50,7 +50,7 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
 
 // GO = size of the shared factor G (4 or 8); the private factor is (32/GO) x (32/GO).
 // MODE 0: no transform; 1: transform.
-template <typename XT, int GO, bool TRANSFORM, bool SCALES_INTERNAL>
+template <typename XT, int GO, bool TRANSFORM>
 __global__ void __launch_bounds__(256)
 quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
                const float* __restrict__ G, const float* __restrict__ P, const float* __restrict__ clip,
@@ -59,8 +59,8 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
     const int q = threadIdx.x & 3;
     int k = blockIdx.x * 64 + (threadIdx.x >> 2);
     const bool live = k < nb;
-    // padding blocks of the last 8-block scale group get the neutral scale (internal layout only)
-    const bool pad = SCALES_INTERNAL && !live && k < scale_groups(nb) * 8 && q == 0;
+    // padding blocks of the last 8-block scale group get the neutral scale
+    const bool pad = !live && k < scale_groups(nb) * 8 && q == 0;
     const int kpad = k;
     if (!live) k = nb - 1;               // keep the whole quad running for the DPP exchanges
 
@@ -145,17 +145,14 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
         const uint32_t packed = encode8(y, bound, scale_operand(s));
         if (live) {
             *reinterpret_cast<uint32_t*>(codes + (size_t)row * Kh + (size_t)k * 16 + q * 4) = packed;
-            if (q == 0) {
-                if constexpr (SCALES_INTERNAL) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
-                else scales[(size_t)row * nb + k] = (uint8_t)s;
-            }
+            if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
         } else if (pad) {
             scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
         }
     }
 }
 
-template <typename XT, bool SI>
+template <typename XT>
 hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes,
                        uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
@@ -166,13 +163,13 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     while ((M + rows_per_wg - 1) / rows_per_wg > 65535) rows_per_wg <<= 1;      // grid.y limit
     const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
     if (!t->has_transform)
-        quant_act_quad<XT, 4, false, SI><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, nullptr,
+        quant_act_quad<XT, 4, false><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, nullptr,
                                                                   t->d_clip, codes, scales);
     else if (t->g_outer == 4)
-        quant_act_quad<XT, 4, true, SI><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
+        quant_act_quad<XT, 4, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
                                                                  t->d_clip, codes, scales);
     else
-        quant_act_quad<XT, 8, true, SI><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
+        quant_act_quad<XT, 8, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
                                                                  t->d_clip, codes, scales);
     return hipGetLastError();
 }
@@ -180,18 +177,11 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
 }  // namespace
 
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool scales_internal,
-                               hipStream_t stream) {
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    if (xdtype == BATQ_BF16) {
-        auto Xp = static_cast<const uint16_t*>(X);
-        return scales_internal ? launch_quad<uint16_t, true>(t, Xp, M, ldx, codes, scales, stream)
-                               : launch_quad<uint16_t, false>(t, Xp, M, ldx, codes, scales, stream);
-    }
-    auto Xp = static_cast<const float*>(X);
-    return scales_internal ? launch_quad<float, true>(t, Xp, M, ldx, codes, scales, stream)
-                           : launch_quad<float, false>(t, Xp, M, ldx, codes, scales, stream);
+    if (xdtype == BATQ_BF16) return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+    return launch_quad(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
 }
 
 }  // namespace batq

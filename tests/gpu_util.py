@@ -48,3 +48,25 @@ def sample_rows(M: int, n: int, seed: int = 0) -> np.ndarray:
     rng = np.random.default_rng(seed)
     r = rng.choice(np.arange(1, M - 1), size=n - 2, replace=False)
     return np.sort(np.concatenate([[0, M - 1], r]))
+
+
+def grouped_to_rowmajor(grouped: np.ndarray, rows: int, nb: int) -> np.ndarray:
+    """De-interleave the library's grouped scale order, from the formula the header documents:
+    index(row, k) = ((k // 8) * rows + row) * 8 + (k % 8) // 2 + 4 * (k % 2); pad bytes must be 127."""
+    groups = (nb + 7) // 8
+    assert grouped.size == groups * rows * 8
+    k = np.arange(groups * 8)
+    idx = ((k // 8)[None, :] * rows + np.arange(rows)[:, None]) * 8 + (k % 8)[None, :] // 2 + 4 * (k % 2)[None, :]
+    full = grouped.reshape(-1)[idx]
+    assert np.all(full[:, nb:] == 127), "padding scale bytes must be the neutral scale"
+    return np.ascontiguousarray(full[:, :nb])
+
+
+def rowmajor_to_grouped(rm: np.ndarray) -> np.ndarray:
+    rows, nb = rm.shape
+    groups = (nb + 7) // 8
+    out = np.full(groups * rows * 8, 127, dtype=np.uint8)
+    k = np.arange(nb)
+    idx = ((k // 8)[None, :] * rows + np.arange(rows)[:, None]) * 8 + (k % 8)[None, :] // 2 + 4 * (k % 2)[None, :]
+    out[idx] = rm
+    return out

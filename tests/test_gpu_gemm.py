@@ -11,7 +11,7 @@ import pytest
 
 import batq_inputs as bi
 from oracle import batq_oracle as o
-from gpu_util import require_gpu, to_dev, y_to_f32, sample_rows
+from gpu_util import require_gpu, to_dev, y_to_f32, sample_rows, grouped_to_rowmajor, rowmajor_to_grouped
 
 pytestmark = pytest.mark.gpu
 
@@ -31,7 +31,13 @@ def _rand_q(rng, R, K, lo=118, hi=136):
     import torch
     codes = rng.integers(0, 256, size=(R, K // 2), dtype=np.uint8)
     scales = rng.integers(lo, hi, size=(R, K // 32), dtype=np.uint8)
+    # device side: activation scales travel in the grouped order, weight import takes row-major
     return codes, scales, torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda()
+
+
+def _xs(scales):
+    import torch
+    return torch.from_numpy(rowmajor_to_grouped(scales)).cuda()
 
 
 def test_single_block_is_exact(B):
@@ -41,7 +47,7 @@ def test_single_block_is_exact(B):
     xc, xs, dxc, dxs = _rand_q(rng, 40, 32)
     wc, ws, dwc, dws = _rand_q(rng, 50, 32)
     wh = B.batq_weight_import(dwc, dws, 32, 50)
-    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
     torch.cuda.synchronize()
     ref = o.gemm(xc, xs, wc, ws)
     assert np.array_equal(y_to_f32(Y).astype(np.float64), ref)
@@ -56,13 +62,13 @@ def test_small_shapes_random_codes(B, M, K, N):
     wc, ws, dwc, dws = _rand_q(rng, N, K)
     wh = B.batq_weight_import(dwc, dws, K, N)
     ref = o.gemm(xc, xs, wc, ws)
-    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
     torch.cuda.synchronize()
     assert _relfro(y_to_f32(Y), ref) <= 1e-5
     # element-wise: fp32 accumulation of nb exact block terms
     tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
     assert np.all(np.abs(y_to_f32(Y) - ref) <= tol + 1e-30)
-    Yb = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.bfloat16)
+    Yb = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.bfloat16)
     torch.cuda.synchronize()
     refb = o.bf16_round(ref).astype(np.float64)
     got = y_to_f32(Yb).astype(np.float64)
@@ -78,7 +84,7 @@ def test_extreme_scales(B):
     xc, xs, dxc, dxs = _rand_q(rng, 33, 64, lo=0, hi=40)
     wc, ws, dwc, dws = _rand_q(rng, 34, 64, lo=200, hi=255)
     wh = B.batq_weight_import(dwc, dws, 64, 34)
-    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
     torch.cuda.synchronize()
     ref = o.gemm(xc, xs, wc, ws)
     assert _relfro(y_to_f32(Y), ref) <= 1e-5
@@ -91,11 +97,11 @@ def test_strided_output_and_empty(B):
     wc, ws, dwc, dws = _rand_q(rng, 24, 64)
     wh = B.batq_weight_import(dwc, dws, 64, 24)
     wide = torch.full((20, 40), 7.0, device="cuda")
-    B.batq_gemm_mxfp4(dxc, dxs, wh, Y=wide[:, :24])
+    B.batq_gemm_mxfp4(dxc, _xs(xs), wh, Y=wide[:, :24])
     torch.cuda.synchronize()
     assert _relfro(wide[:, :24].cpu().numpy(), o.gemm(xc, xs, wc, ws)) <= 1e-5
     assert bool((wide[:, 24:] == 7.0).all())
-    Y0 = B.batq_gemm_mxfp4(dxc[:0], dxs[:0], wh, torch.float32)
+    Y0 = B.batq_gemm_mxfp4(dxc[:0], _xs(xs)[:0], wh, torch.float32)
     assert Y0.shape == (0, 24)
 
 
@@ -123,7 +129,7 @@ def test_linear_all_configs(B, cfg):
     rows = sample_rows(w.M, 96, seed=cfg)
     cols = sample_rows(w.N, 768, seed=cfg + 10)
     xcodes = xc_d[torch.from_numpy(rows).cuda()].cpu().numpy()
-    xscales = xs_d[torch.from_numpy(rows).cuda()].cpu().numpy()
+    xscales = grouped_to_rowmajor(xs_d.cpu().numpy(), w.M, w.K // 32)[rows]
     wc, wsc = wh.export()
     torch.cuda.synchronize()
     wc, wsc = wc[torch.from_numpy(cols).cuda()].cpu().numpy(), wsc[torch.from_numpy(cols).cuda()].cpu().numpy()
@@ -167,8 +173,8 @@ def test_linear_argument_errors(B):
     assert lib.batq_linear(t2.handle, wh.handle, X.data_ptr(), 1, 8, 96, Y.data_ptr(), 0, 16, work.data_ptr(),
                            work.numel(), None) == 10
     xc, xs = B.batq_quantize_act(t, X)
-    assert lib.batq_gemm_mxfp4(xc.data_ptr(), xs.data_ptr(), wh.handle, 8, Y.data_ptr(), 0, 16, work.data_ptr(),
-                               B.batq_gemm_workspace(8, 64) - 1, None) == 7
-    assert lib.batq_gemm_mxfp4(xc.data_ptr(), xs.data_ptr(), wh.handle, 8, Y.data_ptr(), 0, 16, None, 1024, None) == 1
+    assert lib.batq_gemm_mxfp4(xc.data_ptr(), xs.data_ptr(), wh.handle, 8, Y.data_ptr(), 0, 8, None) == 2
+    assert lib.batq_gemm_mxfp4(xc.data_ptr(), None, wh.handle, 8, Y.data_ptr(), 0, 16, None) == 1
+    assert lib.batq_gemm_mxfp4(xc.data_ptr(), xs.data_ptr(), wh.handle, 8, Y.data_ptr(), 5, 16, None) == 3
     torch.cuda.synchronize()
     assert bool((Y == 0).all())

@@ -9,7 +9,7 @@ import pytest
 
 import batq_inputs as bi
 from oracle import batq_oracle as o
-from gpu_util import require_gpu, to_dev, unpack, code_value_mismatch, sample_rows, TIE_POINTS
+from gpu_util import require_gpu, to_dev, unpack, code_value_mismatch, sample_rows, TIE_POINTS, grouped_to_rowmajor
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,9 @@ def _run(B, t, Xdev):
     import torch
     c, s = B.batq_quantize_act(t, Xdev)
     torch.cuda.synchronize()
-    return c.cpu().numpy(), s.cpu().numpy()
+    M, K = Xdev.shape
+    assert s.numel() == B.batq_scale_bytes(M, K) == ((K // 32 + 7) // 8) * 8 * M
+    return c.cpu().numpy(), grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
 
 
 # ------------------------------------------------------------------ T1: quantiser alone, bit-exact
@@ -138,7 +140,7 @@ def test_empty_input_is_a_noop(B):
     t = B.Transform(64, None, None, None)
     X = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     c, s = B.batq_quantize_act(t, X)
-    assert c.shape == (0, 32) and s.shape == (0, 2)
+    assert c.shape == (0, 32) and s.numel() == 0
 
 
 def test_strided_rows(B):
@@ -191,6 +193,21 @@ def test_special_transforms_are_bit_exact(B):
     _check_end_to_end(w, gc, gs, np.arange(w.M))
 
 
+def test_scale_order_helpers(B):
+    import torch
+    rng = np.random.default_rng(2)
+    for rows, nb in ((5, 3), (64, 8), (33, 21)):
+        rm = rng.integers(0, 255, size=(rows, nb), dtype=np.uint8)
+        g = B.batq_scales_from_rowmajor(torch.from_numpy(rm).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(grouped_to_rowmajor(g.cpu().numpy(), rows, nb), rm)
+        back = B.batq_scales_to_rowmajor(g, rows, nb * 32)
+        torch.cuda.synchronize()
+        assert np.array_equal(back.cpu().numpy(), rm)
+        for (r, k) in ((0, 0), (rows - 1, nb - 1), (rows // 2, nb // 2)):
+            assert B.lib.batq_scale_index(r, k, rows) == ((k // 8) * rows + r) * 8 + (k % 8) // 2 + 4 * (k % 2)
+
+
 def test_deterministic(B):
     w = bi.make_workload(1, with_weight=False)
     t = B.Transform(w.K, w.G, w.P, w.clip)
@@ -205,7 +222,7 @@ def test_argument_errors_leave_outputs_untouched(B):
     t = B.Transform(64, None, None, None)
     X = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
     codes = torch.full((4, 32), 0xAB, dtype=torch.uint8, device="cuda")
-    scales = torch.full((4, 2), 0xCD, dtype=torch.uint8, device="cuda")
+    scales = torch.full((4 * 8,), 0xCD, dtype=torch.uint8, device="cuda")
     lib = B.lib
     assert lib.batq_quantize_act(t.handle, X.data_ptr(), 1, 4, 96, 96, codes.data_ptr(), scales.data_ptr(), None) == 10
     assert lib.batq_quantize_act(t.handle, X.data_ptr(), 1, 4, 64, 32, codes.data_ptr(), scales.data_ptr(), None) == 2

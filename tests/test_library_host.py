@@ -70,7 +70,7 @@ def test_null_handles_are_rejected(B):
     assert lib.batq_transform_destroy(None) == 1
     assert lib.batq_weight_destroy(None) == 1
     assert lib.batq_quantize_act(None, None, 1, 4, 64, 64, None, None, None) == 1
-    assert lib.batq_gemm_mxfp4(None, None, None, 4, None, 0, 64, None, 0, None) == 1
+    assert lib.batq_gemm_mxfp4(None, None, None, 4, None, 0, 64, None) == 1
     assert lib.batq_linear(None, None, None, 1, 4, 64, None, 0, 64, None, 0, None) == 1
     k, n = C.c_int(), C.c_int()
     assert lib.batq_weight_shape(None, C.byref(k), C.byref(n)) == 1
@@ -81,8 +81,13 @@ def test_workspace_size(B):
     assert B.batq_linear_workspace(16, 4096) % 16 == 0
     assert B.batq_linear_workspace(0, 4096) == 0 and B.batq_linear_workspace(4, 48) == 0
     # scales are kept in groups of 8 blocks: K = 96 (3 blocks) pads to one group
-    assert B.batq_gemm_workspace(5, 96) == 5 * 8 and B.batq_linear_workspace(5, 96) == 5 * 48 + 5 * 8
-    assert B.batq_gemm_workspace(2048, 4096) == 2048 * 128
+    assert B.batq_scale_bytes(5, 96) == 5 * 8 and B.batq_linear_workspace(5, 96) == 5 * 48 + 5 * 8
+    assert B.batq_scale_bytes(2048, 4096) == 2048 * 128 and B.batq_scale_bytes(4, 48) == 0
+    seen = set()
+    for k in range(16):
+        for r in range(3):
+            seen.add(B.lib.batq_scale_index(r, k, 3))
+    assert seen == set(range(48))                       # a bijection onto the grouped array
 
 
 def test_no_fallback_when_library_is_missing(tmp_path, monkeypatch):
