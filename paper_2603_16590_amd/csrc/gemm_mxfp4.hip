@@ -9,12 +9,12 @@
 //
 // Two kernels:
 //   gemm_tiled  - 256x256 output tile per workgroup (4 waves, each 128x128 = 4x4 matrix
-//                 tiles held in 256 accumulator registers), K stage of 256 elements,
-//                 operands staged through LDS (double buffered, XOR-swizzled 16-byte slots),
-//                 scales read straight from the group-major internal layout, workgroup ->
-//                 tile mapping grouped per XCD so that an XCD's L2 sees a compact sub-grid.
+//                 tiles held in 256 accumulator registers); codes and scales stream
+//                 global -> LDS with LDS-direct loads through a 4-stage ring (XOR-swizzled
+//                 16-byte slots); workgroup -> tile mapping grouped per XCD so that an XCD's
+//                 L2 sees a compact sub-grid.  Needs K % 256 == 0.
 //   gemm_direct - one wave per 32x32 tile with operands straight from global memory, for
-//                 problems too small to fill 256x256 tiles.
+//                 small M and for K that is not a multiple of 256.
 #include <algorithm>
 
 #include "batq_internal.h"
@@ -26,6 +26,8 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <typename YT>
 __device__ __forceinline__ void store_y(YT* p, float v);
@@ -106,14 +108,22 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 }
 
 // ------------------------------------------------------------------------------------------
-constexpr int kTile = 256;            // output tile edge
-constexpr int kStageBytes = 128;      // code bytes per row per K stage (256 elements, 8 MX blocks)
-constexpr int kOperandStage = kTile * kStageBytes;   // 32 KiB per operand per stage
-constexpr int kTiledLds = 4 * kOperandStage;         // A and B, double buffered
+// Tiled kernel.  256x256 output tile per workgroup of 4 waves (2x2, each wave 128x128 = 4x4
+// matrix tiles in 256 accumulator registers).  K advances in stages of 128 elements (64 code
+// bytes per row).  Codes and scales go global -> LDS with LDS-direct loads (no VGPR staging,
+// no ds_write): a ring of 4 stage buffers keeps three stages in flight.  Scales of a whole
+// 256-element K group (two stages) are fetched once per group into a 2-deep ring.
+constexpr int kTile = 256;                 // output tile edge
+constexpr int kStageBytes = 64;            // code bytes per row per stage (128 elements, 4 MX blocks)
+constexpr int kOperandStage = kTile * kStageBytes;        // 16 KiB per operand per stage
+constexpr int kStageLds = 2 * kOperandStage;               // A then B
+constexpr int kRing = 4;                   // stage buffers
+constexpr int kScaleGroupLds = 2 * kTile * 8;              // A then B scale bytes of one K group (4 KiB)
+constexpr int kTiledLds = kRing * kStageLds + 2 * kScaleGroupLds;   // 136 KiB
 
-// 16-byte slot swizzle inside a 128-byte LDS row: conflict-free for both the row-strided
-// fragment reads (32 rows, one slot) and the row-contiguous staging writes.
-__device__ __forceinline__ int slot_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// 16-byte slot swizzle inside a 64-byte LDS row: the 32 rows a fragment read touches, and the
+// 16 rows x 4 slots an LDS-direct load writes, both spread over all banks.
+__device__ __forceinline__ int slot_swizzle(int row) { return (row >> 2) & 3; }
 
 // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of tile
 // ids, and order tile ids in bands of kBand tile-rows so that the range is a compact sub-grid.
@@ -132,119 +142,266 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tile
     tn = id / rows_in_band;
 }
 
+// LDS-direct loads: lane i of the wave writes its 16 (4) bytes at LDS address m0 + 16 i (4 i).
+// `gbase` and `lds_addr` are wave-uniform.  Completion is tracked by vmcnt, in issue order.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+}
+// s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at their maxima), gfx9 encoding.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// One matrix instruction of the 4x4 grid of 32x32 tiles a wave owns.
 template <int KK>
-__device__ __forceinline__ void mfma_kstep(v16f (&acc)[4][4], const uint4 (&a)[4], const uint4 (&b)[4],
-                                           const int (&sa)[4], const int (&sb)[4]) {
+__device__ __forceinline__ void mfma_one(v16f& acc, const uint4& a, const uint4& b, int sa, int sb) {
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, KK, sa, KK, sb);
+}
+
+// Scheduling hints: keep the instruction order written below (the wave runs alone on its
+// SIMD, so LDS latency is hidden only by what the wave itself has queued on the matrix pipe).
+#define BATQ_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, (n), 0)
+#define BATQ_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, (n), 0)
+
+struct TiledCtx {
+    // global -> LDS
+    const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
+    uint32_t aoff[4], boff[4], sao[2], sbo[2];
+    uint32_t lds0, lds_sc;
+    int M, N, wave;
+    // LDS -> registers
+    const uint8_t* smem;
+    int a_rd, b_rd, sc_a_rd, sc_b_rd, kg, fsw;
+
+    __device__ __forceinline__ void issue_stage(int s) const {
+        const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds + (uint32_t)wave * 4096;
+        const uint8_t* ag = xc + (size_t)s * kStageBytes;
+        const uint8_t* bg = wc + (size_t)s * kStageBytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma16(ag, aoff[j], buf + j * 1024);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma16(bg, boff[j], buf + kOperandStage + j * 1024);
+        if ((s & 1) == 0) {     // scales of the K group this even stage opens
+            const int g = s >> 1;
+            const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
+            const uint8_t* sag = xs + (size_t)g * M * 8;
+            const uint8_t* sbg = ws + (size_t)g * N * 8;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
+        }
+    }
+    __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[4], uint4 (&fb)[4]) const {
+        const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
+            fb[i] = *reinterpret_cast<const uint4*>(base + b_rd + i * 32 * kStageBytes);
+        }
+    }
+    __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[4]) const {
+        const uint8_t* sp = smem + kRing * kStageLds + (g & 1) * kScaleGroupLds;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
+            sb[i] = *reinterpret_cast<const int*>(sp + sc_b_rd + i * 256);
+        }
+    }
+};
+
+// One K stage (two matrix-instruction K steps) of the software pipeline.
+//   PAR    parity of the stage inside its K group (selects the scale bytes: op_sel 2 PAR, 2 PAR + 1)
+//   WAIT   loads that may stay in flight once stage s+1 has landed (-1: there is no stage s+1)
+//   ISSUE  start the loads of stage s+4 into the ring slot this stage frees
+// On entry f0 holds the fragments of (s, first half); on exit those of (s+1, first half).
+template <int PAR, int WAIT, bool ISSUE>
+__device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc)[4][4], uint4 (&a0)[4],
+                                            uint4 (&b0)[4], int (&sa)[4], int (&sb)[4]) {
+    uint4 a1[4], b1[4];
+    // first half: fetch the second half's fragments underneath the 16 matrix instructions
+    c.read_frags(s, 1, a1, b1);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[i]), frag(b[j]), acc[i][j], 4, 4, KK,
-                                                                        sa[i], KK, sb[j]);
+        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR>(acc[i][j], a0[i], b0[j], sa[i], sb[j]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        BATQ_SCHED_DSRD(1);
+        BATQ_SCHED_MFMA(2);
+    }
+    // second half, part one
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+    BATQ_SCHED_MFMA(8);
+    __builtin_amdgcn_sched_barrier(0);
+    int sna[4], snb[4];
+    if constexpr (WAIT >= 0) {
+        // every wave has read stage s completely (its last fragments are in registers); once all
+        // have also seen stage s+1 land, the slot of stage s can be refilled
+        wait_vmcnt<WAIT>();
+        __syncthreads();
+        if constexpr (ISSUE) c.issue_stage(s + 4);
+        c.read_frags(s + 1, 0, a0, b0);
+        if constexpr (PAR == 1) c.read_scales((s + 1) >> 1, sna, snb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // second half, part two: covers the latency of the reads just issued
+#pragma unroll
+    for (int i = 2; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+    if constexpr (WAIT >= 0 && PAR == 1) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sa[i] = sna[i];
+            sb[i] = snb[i];
+        }
+    }
 }
 
+// Requires nb % 8 == 0 (K a multiple of 256) and operand arrays below 2 GiB.
 template <typename YT>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
            const uint8_t* __restrict__ ws, int M, int N, int nb, int tiles_m, int tiles_n,
            YT* __restrict__ Y, int64_t ldy) {
     extern __shared__ __align__(16) uint8_t smem[];
-    uint8_t* const As = smem;
-    uint8_t* const Bs = smem + 2 * kOperandStage;
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
     int tm, tn;
     tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * kTile, n0 = tn * kTile;
 
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
     const uint32_t Kh = (uint32_t)nb * 16;
-    const int stages = (nb + 7) >> 3;
+    const int T = nb >> 2;                  // stages of 128 K elements
+    const int G = nb >> 3;                  // K groups of 256 (= T / 2)
 
-    // ---- global -> LDS staging: thread t copies 16-byte chunk (t & 7) of rows (t >> 3) + 32 j
-    const int lrow = t >> 3, lcc = t & 7;
-    const int lds_w = lrow * kStageBytes + ((lcc ^ slot_swizzle(lrow)) << 4);
-    uint32_t aoff[8], boff[8];
+    TiledCtx c;
+    c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
+    c.M = M; c.N = N; c.wave = wave; c.smem = smem;
+    c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;            // LDS byte address of the stage ring
+    c.lds_sc = c.lds0 + kRing * kStageLds;                    // scale ring
+    {
+        // LDS-direct tile loads: wave w, load j (0..3) fills LDS rows 16 (4 w + j) .. + 15 of a stage
+        // buffer; lane i supplies row (i >> 2), slot (i & 3) of that 1 KiB piece, and slot s of row r
+        // holds K chunk s ^ f(r).
+        const int r_in = lane >> 2;
+        const int chunk = (lane & 3) ^ slot_swizzle(r_in);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        aoff[j] = (uint32_t)min(m0 + lrow + 32 * j, M - 1) * Kh + lcc * 16;
-        boff[j] = (uint32_t)min(n0 + lrow + 32 * j, N - 1) * Kh + lcc * 16;
-    }
-    uint4 ra[8], rb[8];
-    auto load_stage = [&](int s) {
-        const bool valid = s * 8 + lcc < nb;            // K tail: chunks past the last block are zero
-        const uint32_t ko = (uint32_t)s * kStageBytes;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            ra[j] = valid ? *reinterpret_cast<const uint4*>(xc + aoff[j] + ko) : uint4{0, 0, 0, 0};
-            rb[j] = valid ? *reinterpret_cast<const uint4*>(wc + boff[j] + ko) : uint4{0, 0, 0, 0};
+        for (int j = 0; j < 4; ++j) {
+            const int row = 16 * (4 * wave + j) + r_in;
+            c.aoff[j] = (uint32_t)min(m0 + row, M - 1) * Kh + chunk * 16;
+            c.boff[j] = (uint32_t)min(n0 + row, N - 1) * Kh + chunk * 16;
         }
-    };
-    auto store_stage = [&](int buf) {
+        // LDS-direct scale loads: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords
+        // 128 w .. 128 w + 127 of each (two pieces of 64).
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            *reinterpret_cast<uint4*>(As + buf * kOperandStage + lds_w + j * 32 * kStageBytes) = ra[j];
-            *reinterpret_cast<uint4*>(Bs + buf * kOperandStage + lds_w + j * 32 * kStageBytes) = rb[j];
+        for (int j = 0; j < 2; ++j) {
+            const int d = 128 * wave + 64 * j + lane;
+            c.sao[j] = ((uint32_t)min(m0 + (d >> 1), M - 1) * 2 + (d & 1)) * 4;
+            c.sbo[j] = ((uint32_t)min(n0 + (d >> 1), N - 1) * 2 + (d & 1)) * 4;
         }
-    };
-
-    // ---- fragment reads: lane reads slot (2 kk + kg) of row (wave row base + 32 i + l32)
-    const int fsw = slot_swizzle(l32);
-    const int a_rd = (wm * 128 + l32) * kStageBytes;
-    const int b_rd = (wn * 128 + l32) * kStageBytes;
-    // ---- scales: one dword per fragment per stage (four K steps, selected by op_sel)
-    uint32_t sa_idx[4], sb_idx[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        sa_idx[i] = (uint32_t)min(m0 + wm * 128 + 32 * i + l32, M - 1) * 2 + kg;
-        sb_idx[i] = (uint32_t)min(n0 + wn * 128 + 32 * i + l32, N - 1) * 2 + kg;
     }
-    const uint32_t* xs32 = reinterpret_cast<const uint32_t*>(xs);
-    const uint32_t* ws32 = reinterpret_cast<const uint32_t*>(ws);
+    // fragment reads: lane reads slot ((2 half + kg) ^ f(row)) of row (wave row base + 32 i + l32)
+    c.kg = kg;
+    c.fsw = slot_swizzle(l32);
+    c.a_rd = (wm * 128 + l32) * kStageBytes;
+    c.b_rd = kOperandStage + (wn * 128 + l32) * kStageBytes;
+    c.sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
+    c.sc_b_rd = kTile * 8 + ((wn * 128 + l32) * 2 + kg) * 4;
 
     v16f acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v16f{};
+    uint4 fa[4], fb[4];
+    int sa[4], sb[4];
 
-    load_stage(0);
-    store_stage(0);
+    // Loads per thread: 8 per stage, plus 4 for the scales of a K group issued right after the
+    // group's even stage; they complete in issue order.  In steady state stages s+2 and s+3
+    // (8 + 8 + 4 = 20 loads) stay in flight while stage s+1 is awaited.
+    c.issue_stage(0);
+    c.issue_stage(1);
+    if (T >= 4) {
+        c.issue_stage(2);
+        c.issue_stage(3);
+        wait_vmcnt<28>();
+    } else {
+        wait_vmcnt<8>();
+    }
     __syncthreads();
+    c.read_scales(0, sa, sb);
+    c.read_frags(0, 0, fa, fb);
 
-    for (int s = 0; s < stages; ++s) {
-        const int buf = s & 1;
-        const bool more = s + 1 < stages;
-        if (more) load_stage(s + 1);
-        int sa[4], sb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sa[i] = (int)xs32[(size_t)s * M * 2 + sa_idx[i]];
-            sb[i] = (int)ws32[(size_t)s * N * 2 + sb_idx[i]];
-        }
-        const uint8_t* Ab = As + buf * kOperandStage + a_rd;
-        const uint8_t* Bb = Bs + buf * kOperandStage + b_rd;
-        uint4 fa[4], fb[4];
-#define BATQ_LOAD_FRAGS(KK)                                                                                  \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                          \
-        fa[i] = *reinterpret_cast<const uint4*>(Ab + i * 32 * kStageBytes + (((2 * (KK) + kg) ^ fsw) << 4)); \
-        fb[i] = *reinterpret_cast<const uint4*>(Bb + i * 32 * kStageBytes + (((2 * (KK) + kg) ^ fsw) << 4)); \
+    for (int g = 0; g + 2 < G; ++g) {
+        tiled_stage<0, 20, true>(c, 2 * g, acc, fa, fb, sa, sb);
+        tiled_stage<1, 20, true>(c, 2 * g + 1, acc, fa, fb, sa, sb);
     }
-        BATQ_LOAD_FRAGS(0)
-        mfma_kstep<0>(acc, fa, fb, sa, sb);
-        BATQ_LOAD_FRAGS(1)
-        mfma_kstep<1>(acc, fa, fb, sa, sb);
-        BATQ_LOAD_FRAGS(2)
-        mfma_kstep<2>(acc, fa, fb, sa, sb);
-        BATQ_LOAD_FRAGS(3)
-        mfma_kstep<3>(acc, fa, fb, sa, sb);
-#undef BATQ_LOAD_FRAGS
-        if (more) store_stage(buf ^ 1);
-        __syncthreads();
+    if (G >= 2) {
+        tiled_stage<0, 20, false>(c, T - 4, acc, fa, fb, sa, sb);
+        tiled_stage<1, 8, false>(c, T - 3, acc, fa, fb, sa, sb);
     }
+    tiled_stage<0, 0, false>(c, T - 2, acc, fa, fb, sa, sb);
+    tiled_stage<1, -1, false>(c, T - 1, acc, fa, fb, sa, sb);
 
     // ---- epilogue: accumulators -> Y
+    if constexpr (sizeof(YT) == 2) {
+        // bf16: transpose through LDS so that every lane stores 16 contiguous bytes.
+        // Needs the whole 256-column span inside N and 16-byte aligned rows (workgroup-uniform).
+        const bool fast = n0 + kTile <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+        if (fast) {
+            __syncthreads();                                  // every wave is done with the stage ring
+            uint8_t* ep = smem + wave * 32768;                // wave-private [128 rows][256 bytes]
+            const int odd = lane & 1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int rr = 0; rr < 8; ++rr) {
+                        // lanes pair up: the even lane keeps row r0 and both columns, the odd lane row r0 + 1
+                        const float v0 = acc[i][j][2 * rr], v1 = acc[i][j][2 * rr + 1];
+                        const float send = odd ? v0 : v1;
+                        const float recv = __builtin_bit_cast(
+                            float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                        f32x2 pr;
+                        pr.x = odd ? recv : v0;
+                        pr.y = odd ? v1 : recv;
+                        const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                        const int R = 32 * i + 8 * (rr >> 1) + 4 * kg + 2 * (rr & 1) + odd;
+                        int chunk = 4 * j + (l32 >> 3);
+                        chunk ^= ((R & 1) << 2) | (((R >> 2) & 1) << 3);      // spread the four row groups over the banks
+                        *reinterpret_cast<uint32_t*>(ep + R * 256 + chunk * 16 + ((l32 >> 1) & 3) * 4) = packed;
+                    }
+            // wave-private region: the wave's own LDS operations complete in order
+            const int rsub = lane >> 4, c16 = lane & 15;
+#pragma unroll 4
+            for (int it = 0; it < 32; ++it) {
+                const int R = 4 * it + rsub;
+                const int chunk = c16 ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
+                const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
+                const int row = m0 + wm * 128 + R;
+                if (row < M)
+                    *reinterpret_cast<uint4*>(Y + (size_t)row * ldy + n0 + wn * 128 + c16 * 8) = v;
+            }
+            return;
+        }
+    }
     const int col0 = n0 + wn * 128 + l32;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -268,7 +425,7 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
                         hipStream_t stream) {
     const int N = w->N, nb = w->nb;
     const bool fits32 = (size_t)M * nb * 16 < (1ull << 31) && (size_t)N * nb * 16 < (1ull << 31);
-    if (M > 64 && fits32) {
+    if (M > 64 && fits32 && nb % 8 == 0) {
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
