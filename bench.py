@@ -72,8 +72,9 @@ def main():
         Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
         Ws = [torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
         Ys = [torch.empty((w.M, w.N), dtype=ydt, device="cuda") for _ in range(nsets)]
-        codes = [wk[: w.M * w.K // 2].view(w.M, w.K // 2) for wk in Ws]
-        scales = [wk[w.M * w.K // 2: wsz] for wk in Ws]
+        cb = B.batq_code_bytes(w.M, w.K)
+        codes = [wk[:cb] for wk in Ws]
+        scales = [wk[cb: wsz] for wk in Ws]
 
         def step(i):
             j = i % nsets
@@ -103,7 +104,7 @@ def main():
             return e0.elapsed_time(e1) / n
 
         ms_quant = timed(lambda i: B.batq_quantize_act(t, Xs[i % nsets], codes[i % nsets], scales[i % nsets]), steps)
-        ms_gemm = timed(lambda i: B.batq_gemm_mxfp4(codes[i % nsets], scales[i % nsets], wh, Y=Ys[i % nsets]), steps)
+        ms_gemm = timed(lambda i: B.batq_gemm_mxfp4(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets]), steps)
         ms_quant_warm = timed(lambda i: B.batq_quantize_act(t, Xs[0], codes[0], scales[0]), steps)
 
         flops = 2.0 * w.M * w.K * w.N

@@ -21,19 +21,23 @@
  *   G: g_outer x g_outer shared ("global"), P_k: g_inner x g_inner ("private"),
  *   g_outer * g_inner = 32.  A row vector x_k is mapped to x_k T_k.
  *
- * Quantised tensor layout:
- *   codes  [rows][K/2]  uint8, element 2j in bits 3:0 and 2j+1 in bits 7:4 of byte j;
- *                       a 4-bit code is S|E1 E0|M (bit 3 = sign);
- *   scales uint8, E8M0: value 2^(s-127); 255 is never produced.  Two orders are used:
- *     row-major  [rows][K/32]                      (weight export / import);
- *     grouped    byte batq_scale_index(row, k, rows) of batq_scale_bytes(rows, K) bytes
- *                (activations: written by batq_quantize_act, read by batq_gemm_mxfp4).
- *                Blocks are grouped by 8 along K, group-major, 8 bytes per (group, row),
- *                the even blocks of a group before the odd ones:
- *                  index = ((k/8)*rows + row)*8 + (k%8)/2 + 4*(k%2);
- *                a last partial group is padded with the neutral scale 127.  This is the
- *                order in which the matrix instruction consumes scales (one dword per lane
- *                per 256 K elements), so the GEMM reads them with contiguous loads.
+ * Quantised tensors.  A 4-bit code is S|E1 E0|M (bit 3 = sign); a scale byte is E8M0,
+ * value 2^(s-127), and 255 is never produced.  The 32 codes of one MX block form a 16-byte
+ * chunk: element j of the block in byte j/2, even j in bits 3:0, odd j in bits 7:4.
+ * Row-major order (weight export / import, and the conversion helpers):
+ *     codes [rows][K/2], scales [rows][K/32].
+ * Device order (what batq_quantize_act writes and batq_gemm_mxfp4 reads), chosen so that
+ * the GEMM moves operands with contiguous 1 KiB loads that already are its LDS image, and
+ * reads scales as the matrix instruction consumes them:
+ *     codes   batq_code_bytes(rows, K) bytes; the chunk of block k of `row` starts at
+ *             batq_code_chunk_offset(row, k, K)
+ *               = ((row/16) * S + k/4) * 1024 + (row%16) * 64 + (((k%4) ^ ((row%16)/4)) * 16),
+ *             S = 2 * ceil(K/256); rows are padded to a multiple of 16 (pad rows hold
+ *             unspecified bytes) and K to a multiple of 256 with zero codes;
+ *     scales  batq_scale_bytes(rows, K) bytes; block k of `row` at batq_scale_index(row, k, rows)
+ *               = ((k/8) * rows + row) * 8 + (k%8)/2 + 4 * (k%2)
+ *             (groups of 8 blocks, group-major, even blocks of a group first); a last
+ *             partial group is padded with the neutral scale 127.
  * Quantiser definition: bound = fl32(clip_k * max_j |y_j|); elements beyond +-bound
  * are replaced by +-bound; E = clamp(floor(log2 bound) - 2, -127, 127) (E = -127 for
  * a zero block); code = round-to-nearest on the E2M1 grid of y * 2^-E, ties to the
@@ -135,8 +139,8 @@ batq_status batq_weight_destroy(batq_weight* w);
  *   X       DEVICE M x K row-major, row stride ldx elements (>= K), fp32 or bf16;
  *           the products and sums of the transform are carried in fp32 (bf16 is
  *           storage only; nothing is rounded to bf16 before the quantiser)
- *   codes   DEVICE [M][K/2]   out
- *   scales  DEVICE, batq_scale_bytes(M, K) bytes, grouped order, out
+ *   codes   DEVICE, batq_code_bytes(M, K) bytes, device order, out
+ *   scales  DEVICE, batq_scale_bytes(M, K) bytes, device order, out
  * X and codes must be 16-byte aligned, scales 8-byte aligned, and ldx * sizeof(element) a
  * multiple of 16.  M == 0 is a no-op.  A transform created with G == NULL quantises X as is.
  */
@@ -144,17 +148,21 @@ batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype
                               int M, int K, int64_t ldx,
                               uint8_t* codes, uint8_t* scales, void* stream);
 
-/* Scale-order helpers (Sec. 2: one UE8M0 scale per 32 elements; the order is this library's).
- * batq_scale_bytes: size of a grouped scale array (0 for invalid arguments).
- * batq_scale_index: byte offset of block k of `row` in a grouped array of `rows` rows.
- * The two conversions run on the device (both pointers DEVICE), enqueued on `stream`. */
+/* Layout helpers (Sec. 2: 32-element blocks with one UE8M0 scale; the orders are this library's).
+ * Sizes return 0 for invalid arguments.  The four conversions run on the device (both
+ * pointers DEVICE, 16-byte aligned for codes), enqueued on `stream`; converting to device
+ * order also writes the zero / neutral padding of K. */
+size_t batq_code_bytes(int rows, int K);
+size_t batq_code_chunk_offset(int row, int k, int K);
 size_t batq_scale_bytes(int rows, int K);
 size_t batq_scale_index(int row, int k, int rows);
-batq_status batq_scales_to_rowmajor(const uint8_t* grouped, uint8_t* rowmajor, int rows, int K, void* stream);
-batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped, int rows, int K, void* stream);
+batq_status batq_codes_to_rowmajor(const uint8_t* device_order, uint8_t* rowmajor, int rows, int K, void* stream);
+batq_status batq_codes_from_rowmajor(const uint8_t* rowmajor, uint8_t* device_order, int rows, int K, void* stream);
+batq_status batq_scales_to_rowmajor(const uint8_t* device_order, uint8_t* rowmajor, int rows, int K, void* stream);
+batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* device_order, int rows, int K, void* stream);
 
-/* Online step 2 alone: MXFP4 x MXFP4 GEMM on activation codes and grouped scales as
- * batq_quantize_act writes them.
+/* Online step 2 alone: MXFP4 x MXFP4 GEMM on activation codes and scales in device order,
+ * as batq_quantize_act writes them.
  *   Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} val(xq[m][32k+j]) val(wq[n][32k+j])
  * with fp32 accumulation; Y DEVICE M x N row-major, row stride ldy (>= N), fp32 or
  * bf16 (round-to-nearest-even). */
@@ -163,8 +171,8 @@ batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const
 
 /* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
  * `workspace` is DEVICE memory (16-byte aligned) of at least batq_linear_workspace(M, K)
- * bytes (= M*K/2 + batq_scale_bytes(M, K)).  It holds the activation codes ([M][K/2], at
- * offset 0) followed by their grouped scales between the two kernels. */
+ * bytes (= batq_code_bytes(M, K) + batq_scale_bytes(M, K)).  It holds the activation codes
+ * (at offset 0) followed by their scales, both in device order, between the two kernels. */
 size_t batq_linear_workspace(int M, int K);
 batq_status batq_linear(const batq_transform* t, const batq_weight* w,
                         const void* X, batq_dtype xdtype, int M, int64_t ldx,

@@ -38,6 +38,10 @@ SYMBOLS = {
     "batq_weight_shape": (_i, [_vp, C.POINTER(_i), C.POINTER(_i)]),
     "batq_weight_destroy": (_i, [_vp]),
     "batq_quantize_act": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp]),
+    "batq_code_bytes": (_sz, [_i, _i]),
+    "batq_code_chunk_offset": (_sz, [_i, _i, _i]),
+    "batq_codes_to_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
+    "batq_codes_from_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
     "batq_scale_bytes": (_sz, [_i, _i]),
     "batq_scale_index": (_sz, [_i, _i, _i]),
     "batq_scales_to_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
@@ -183,6 +187,10 @@ def batq_weight_import(codes, scales, K: int, N: int) -> Weight:
     return Weight(h)
 
 
+def batq_code_bytes(rows: int, K: int) -> int:
+    return int(lib.batq_code_bytes(rows, K))
+
+
 def batq_scale_bytes(rows: int, K: int) -> int:
     return int(lib.batq_scale_bytes(rows, K))
 
@@ -190,18 +198,37 @@ def batq_scale_bytes(rows: int, K: int) -> int:
 def batq_quantize_act(t: Transform, X, codes=None, scales=None):
     """X: M x K device tensor (fp32 or bf16, unit column stride).
 
-    Returns (codes [M, K/2], scales) uint8 tensors; scales is a flat tensor in the grouped order."""
+    Returns (codes, scales): flat uint8 tensors in the library's device order."""
     import torch
     assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
     M, K = X.shape
     if codes is None:
-        codes = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device)
+        codes = torch.empty((batq_code_bytes(M, K),), dtype=torch.uint8, device=X.device)
     if scales is None:
         scales = torch.empty((batq_scale_bytes(M, K),), dtype=torch.uint8, device=X.device)
     ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
     _check(lib.batq_quantize_act(t.handle, X.data_ptr(), _dtype_code(X), M, K, ldx, codes.data_ptr(),
                                  scales.data_ptr(), _stream()), "batq_quantize_act")
     return codes, scales
+
+
+def batq_codes_to_rowmajor(codes, rows: int, K: int):
+    """Device-order codes -> [rows, K/2] uint8 tensor."""
+    import torch
+    out = torch.empty((rows, K // 2), dtype=torch.uint8, device=codes.device)
+    _check(lib.batq_codes_to_rowmajor(codes.data_ptr(), out.data_ptr(), rows, K, _stream()), "batq_codes_to_rowmajor")
+    return out
+
+
+def batq_codes_from_rowmajor(rowmajor):
+    """[rows, K/2] uint8 tensor -> flat device-order codes (K padding zeroed)."""
+    import torch
+    assert rowmajor.is_contiguous()
+    rows, kh = rowmajor.shape
+    out = torch.empty((batq_code_bytes(rows, kh * 2),), dtype=torch.uint8, device=rowmajor.device)
+    _check(lib.batq_codes_from_rowmajor(rowmajor.data_ptr(), out.data_ptr(), rows, kh * 2, _stream()),
+           "batq_codes_from_rowmajor")
+    return out
 
 
 def batq_scales_to_rowmajor(grouped, rows: int, K: int):
@@ -224,10 +251,9 @@ def batq_scales_from_rowmajor(rowmajor):
     return out
 
 
-def batq_gemm_mxfp4(xcodes, xscales, w: Weight, out_dtype=None, Y=None):
-    """GEMM on activation codes and grouped scales as batq_quantize_act writes them. Returns Y (M x N)."""
+def batq_gemm_mxfp4(xcodes, xscales, w: Weight, M: int, out_dtype=None, Y=None):
+    """GEMM on device-order activation codes and scales of M rows. Returns Y (M x N)."""
     import torch
-    M = xcodes.shape[0]
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes.device)
     _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),

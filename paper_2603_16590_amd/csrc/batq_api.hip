@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "batq_internal.h"
+#include "code_layout.h"
 #include "scale_layout.h"
 
 namespace {
@@ -113,7 +114,7 @@ batq_status alloc_weight(batq_weight** out, int K, int N) {
     w->K = K;
     w->N = N;
     w->nb = K / 32;
-    if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), (size_t)N * (K / 2)) != hipSuccess ||
+    if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), batq::code_bytes_blocked(N, K / 32)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void**>(&w->d_scales), batq::scale_bytes_internal(N, K / 32)) != hipSuccess) {
         (void)hipGetLastError();
         free_weight(w);
@@ -231,8 +232,9 @@ batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, cons
             return st;
         }
     }
-    // padding blocks of the last scale group carry the neutral scale
+    // padding: zero codes (rows up to a multiple of 16, K up to a multiple of 256), neutral scales
     hipError_t e = hipMemsetAsync(w->d_scales, 127, batq::scale_bytes_internal(N, nb), s);
+    if (e == hipSuccess) e = hipMemsetAsync(w->d_codes, 0, batq::code_bytes_blocked(N, nb), s);
     if (e == hipSuccess)
         e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_w, w->d_codes, w->d_scales, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
@@ -249,7 +251,7 @@ batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, cons
 batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream) {
     if (!w || !codes || !scales) return BATQ_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    BATQ_HIP(hipMemcpyAsync(codes, w->d_codes, (size_t)w->N * (w->K / 2), hipMemcpyDeviceToDevice, s));
+    BATQ_HIP(batq::launch_codes_to_rowmajor(w->d_codes, codes, w->N, w->nb, s));
     BATQ_HIP(batq::launch_scales_to_canonical(w->d_scales, scales, w->N, w->nb, s));
     return BATQ_OK;
 }
@@ -264,7 +266,8 @@ batq_status batq_weight_import(batq_weight** out, const uint8_t* codes, const ui
     batq_weight* w = nullptr;
     st = alloc_weight(&w, K, N);
     if (st != BATQ_OK) return st;
-    hipError_t e = hipMemcpyAsync(w->d_codes, codes, (size_t)N * (K / 2), hipMemcpyDeviceToDevice, s);
+    hipError_t e = hipMemsetAsync(w->d_codes, 0, batq::code_bytes_blocked(N, K / 32), s);
+    if (e == hipSuccess) e = batq::launch_codes_to_blocked(codes, w->d_codes, N, K / 32, s);
     if (e == hipSuccess) e = batq::launch_scales_to_internal(scales, w->d_scales, N, K / 32, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
@@ -309,6 +312,31 @@ batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype
     return BATQ_OK;
 }
 
+size_t batq_code_bytes(int rows, int K) {
+    if (rows <= 0 || K <= 0 || K % 32 != 0) return 0;
+    return batq::code_bytes_blocked(rows, K / 32);
+}
+
+size_t batq_code_chunk_offset(int row, int k, int K) { return batq::code_chunk_offset(row, k, K / 32); }
+
+batq_status batq_codes_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!blocked || !rowmajor) return BATQ_ERR_NULL;
+    if (!aligned16(blocked) || !aligned16(rowmajor)) return BATQ_ERR_SHAPE;
+    BATQ_HIP(batq::launch_codes_to_rowmajor(blocked, rowmajor, rows, K / 32, static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
+}
+
+batq_status batq_codes_from_rowmajor(const uint8_t* rowmajor, uint8_t* blocked, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!blocked || !rowmajor) return BATQ_ERR_NULL;
+    if (!aligned16(blocked) || !aligned16(rowmajor)) return BATQ_ERR_SHAPE;
+    BATQ_HIP(batq::launch_codes_to_blocked(rowmajor, blocked, rows, K / 32, static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
+}
+
 size_t batq_scale_bytes(int rows, int K) {
     if (rows <= 0 || K <= 0 || K % 32 != 0) return 0;
     return batq::scale_bytes_internal(rows, K / 32);
@@ -350,8 +378,8 @@ batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const
 
 size_t batq_linear_workspace(int M, int K) {
     if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
-    // activation codes [M][K/2] (a multiple of 16 bytes) followed by their scales in the GEMM's layout
-    return (size_t)M * (K / 2) + batq::scale_bytes_internal(M, K / 32);
+    // activation codes (blocked layout, a multiple of 1 KiB) followed by their grouped scales
+    return batq::code_bytes_blocked(M, K / 32) + batq::scale_bytes_internal(M, K / 32);
 }
 
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
@@ -367,7 +395,7 @@ batq_status batq_linear(const batq_transform* t, const batq_weight* w, const voi
     if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace)) return BATQ_ERR_SHAPE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* codes = static_cast<uint8_t*>(workspace);
-    uint8_t* scales = codes + (size_t)M * (t->K / 2);
+    uint8_t* scales = codes + batq::code_bytes_blocked(M, t->nb);
     hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, s);
     if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, s);
     if (e != hipSuccess) {

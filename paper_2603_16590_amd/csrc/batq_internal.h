@@ -26,14 +26,15 @@ struct batq_transform {
 // Prepared (inverse-transformed, quantised) weights.
 struct batq_weight {
     int K = 0, N = 0, nb = 0;
-    uint8_t* d_codes = nullptr;   // [N][K/2], K contiguous: one 16-byte chunk per MX block
+    uint8_t* d_codes = nullptr;   // blocked code layout (code_layout.h), rows and K zero-padded
     uint8_t* d_scales = nullptr;  // internal group-major layout (scale_layout.h), padded groups
 };
 
 namespace batq {
 
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
-// Scales are written in the grouped layout of scale_layout.h (padding blocks included).
+// Codes are written in the blocked layout of code_layout.h, scales in the grouped layout of
+// scale_layout.h (padding blocks of the last K group included).
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
@@ -43,6 +44,8 @@ hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dt
 // xscales_internal: activation scales in the grouped layout.
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
                              void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream);
+hipError_t launch_codes_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);
+hipError_t launch_codes_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream);
 hipError_t launch_scales_to_internal(const uint8_t* canon, uint8_t* internal, int rows, int nb, hipStream_t stream);
 hipError_t launch_scales_to_canonical(const uint8_t* internal, uint8_t* canon, int rows, int nb, hipStream_t stream);
 

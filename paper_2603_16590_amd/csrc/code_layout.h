@@ -1,0 +1,33 @@
+// Layout of packed E2M1 codes shared by the quantiser, the weight preparation and the GEMM.
+//
+// The GEMM streams operands global -> LDS in pieces of 1 KiB = 16 rows x 128 K elements
+// (64 code bytes per row, one 16-byte chunk per MX block), one piece per wave-level
+// LDS-direct load.  Codes are stored so that such a piece is contiguous in memory and is
+// already the LDS image the matrix-instruction fragment reads expect:
+//   piece(rg, ks)   rg = row / 16, ks = k / 128 (k = K element index), at byte
+//                   (rg * stages + ks) * 1024, stages = Kp / 128, Kp = K rounded up to 256
+//   inside a piece  row r = row % 16 at byte 64 r; MX block c = (k / 32) % 4 in 16-byte
+//                   slot c ^ ((r / 4) % 4) (bank swizzle); element j = k % 32 in byte j / 2,
+//                   even j in the low nibble.
+// Rows are padded to a multiple of 16 (pad rows are never read into results) and K to a
+// multiple of 256 with zero codes (and neutral scales), which contribute nothing.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace batq {
+
+__host__ __device__ inline int code_stages(int nb) { return ((nb + 7) >> 3) << 1; }      // Kp / 128
+
+__host__ __device__ inline size_t code_bytes_blocked(int rows, int nb) {
+    return (size_t)((rows + 15) >> 4) * (size_t)code_stages(nb) * 1024;
+}
+
+// Byte offset of the 16-byte chunk holding MX block k of `row`.
+__host__ __device__ inline size_t code_chunk_offset(int row, int k, int nb) {
+    const int r = row & 15;
+    return ((size_t)(row >> 4) * (size_t)code_stages(nb) + (size_t)(k >> 2)) * 1024 + (size_t)r * 64 +
+           (size_t)(((k & 3) ^ ((r >> 2) & 3)) << 4);
+}
+
+}  // namespace batq

@@ -3,8 +3,8 @@
 //
 // v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in FP4: lane l supplies, for matrix
 // row (l % 32), the 32 consecutive K elements of MX block (l / 32) as 16 packed bytes, plus
-// that block's E8M0 scale; so one 128-bit read of the [rows][K/2] code layout is exactly one
-// operand fragment.  Accumulator register r of lane l is element
+// that block's E8M0 scale; so one 16-byte chunk of the code layout (code_layout.h) is exactly
+// one operand fragment.  Accumulator register r of lane l is element
 // (8*(r/4) + 4*(l/32) + r%4, l % 32) of the 32x32 tile.
 //
 // Two kernels:
@@ -12,12 +12,13 @@
 //                 tiles held in 256 accumulator registers); codes and scales stream
 //                 global -> LDS with LDS-direct loads through a 4-stage ring (XOR-swizzled
 //                 16-byte slots); workgroup -> tile mapping grouped per XCD so that an XCD's
-//                 L2 sees a compact sub-grid.  Needs K % 256 == 0.
+//                 L2 sees a compact sub-grid.
 //   gemm_direct - one wave per 32x32 tile with operands straight from global memory, for
-//                 small M and for K that is not a multiple of 256.
+//                 small M.
 #include <algorithm>
 
 #include "batq_internal.h"
+#include "code_layout.h"
 #include "mxfp4_device.h"
 #include "scale_layout.h"
 
@@ -61,6 +62,29 @@ scales_to_canonical(const uint8_t* __restrict__ internal, uint8_t* __restrict__ 
     }
 }
 
+// row-major [rows][nb*16]  <->  blocked code layout (one thread per 16-byte chunk)
+__global__ void __launch_bounds__(256)
+codes_to_blocked(const uint8_t* __restrict__ rowmajor, uint8_t* __restrict__ blocked, int rows, int nb) {
+    const int nbp = scale_groups(nb) * 8;
+    const size_t total = (size_t)rows * nbp;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int row = (int)(i / nbp), k = (int)(i % nbp);
+        uint4 v = {0, 0, 0, 0};
+        if (k < nb) v = *reinterpret_cast<const uint4*>(rowmajor + ((size_t)row * nb + k) * 16);
+        *reinterpret_cast<uint4*>(blocked + code_chunk_offset(row, k, nb)) = v;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+codes_to_rowmajor(const uint8_t* __restrict__ blocked, uint8_t* __restrict__ rowmajor, int rows, int nb) {
+    const size_t total = (size_t)rows * nb;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int row = (int)(i / nb), k = (int)(i % nb);
+        *reinterpret_cast<uint4*>(rowmajor + i * 16) =
+            *reinterpret_cast<const uint4*>(blocked + code_chunk_offset(row, k, nb));
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 template <typename YT>
 __global__ void __launch_bounds__(256)
@@ -72,14 +96,11 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
     if (m0 >= M || n0 >= N) return;                       // wave-uniform
     const int i = lane & 31, kg = lane >> 5;
     const int am = min(m0 + i, M - 1), bn = min(n0 + i, N - 1);   // rows past the edge are computed, not stored
-    const size_t Kh = (size_t)nb * 16;
-    const uint8_t* ap = xc + (size_t)am * Kh + kg * 16;
-    const uint8_t* bp = wc + (size_t)bn * Kh + kg * 16;
     v16f acc = {};
     const int steps = nb >> 1;
     for (int s = 0; s < steps; ++s) {
-        const uint4 a = *reinterpret_cast<const uint4*>(ap + (size_t)s * 32);
-        const uint4 b = *reinterpret_cast<const uint4*>(bp + (size_t)s * 32);
+        const uint4 a = *reinterpret_cast<const uint4*>(xc + code_chunk_offset(am, 2 * s + kg, nb));
+        const uint4 b = *reinterpret_cast<const uint4*>(wc + code_chunk_offset(bn, 2 * s + kg, nb));
         const int sa = xs[scale_index_internal(am, 2 * s + kg, M)];
         const int sb = ws[scale_index_internal(bn, 2 * s + kg, N)];
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, 0, sa, 0, sb);
@@ -90,8 +111,8 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
         uint4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
         int sa = 127, sb = 127;
         if (kg == 0) {
-            a = *reinterpret_cast<const uint4*>(ap + (size_t)s * 32);
-            b = *reinterpret_cast<const uint4*>(bp + (size_t)s * 32);
+            a = *reinterpret_cast<const uint4*>(xc + code_chunk_offset(am, 2 * s, nb));
+            b = *reinterpret_cast<const uint4*>(wc + code_chunk_offset(bn, 2 * s, nb));
             sa = xs[scale_index_internal(am, 2 * s, M)];
             sb = ws[scale_index_internal(bn, 2 * s, N)];
         }
@@ -181,8 +202,8 @@ struct TiledCtx {
 
     __device__ __forceinline__ void issue_stage(int s) const {
         const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds + (uint32_t)wave * 4096;
-        const uint8_t* ag = xc + (size_t)s * kStageBytes;
-        const uint8_t* bg = wc + (size_t)s * kStageBytes;
+        const uint8_t* ag = xc + (size_t)s * 1024;          // one 1 KiB piece per 16 rows and stage
+        const uint8_t* bg = wc + (size_t)s * 1024;
 #pragma unroll
         for (int j = 0; j < 4; ++j) dma16(ag, aoff[j], buf + j * 1024);
 #pragma unroll
@@ -269,7 +290,7 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
     }
 }
 
-// Requires nb % 8 == 0 (K a multiple of 256) and operand arrays below 2 GiB.
+// Requires operand code arrays below 2 GiB (32-bit load offsets).
 template <typename YT>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
@@ -286,9 +307,8 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
-    const uint32_t Kh = (uint32_t)nb * 16;
-    const int T = nb >> 2;                  // stages of 128 K elements
-    const int G = nb >> 3;                  // K groups of 256 (= T / 2)
+    const int G = (nb + 7) >> 3;            // K groups of 256 elements (K is zero-padded to them)
+    const int T = 2 * G;                    // stages of 128 K elements
 
     TiledCtx c;
     c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
@@ -296,16 +316,15 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;            // LDS byte address of the stage ring
     c.lds_sc = c.lds0 + kRing * kStageLds;                    // scale ring
     {
-        // LDS-direct tile loads: wave w, load j (0..3) fills LDS rows 16 (4 w + j) .. + 15 of a stage
-        // buffer; lane i supplies row (i >> 2), slot (i & 3) of that 1 KiB piece, and slot s of row r
-        // holds K chunk s ^ f(r).
-        const int r_in = lane >> 2;
-        const int chunk = (lane & 3) ^ slot_swizzle(r_in);
+        // LDS-direct tile loads: wave w, load j (0..3) copies the 1 KiB piece of row group
+        // (tile row / 16 + 4 w + j) into LDS rows 16 (4 w + j) .. + 15 of a stage buffer; the blocked
+        // code layout already is the swizzled LDS image, so lane i just moves bytes 16 i .. 16 i + 15.
+        const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int row = 16 * (4 * wave + j) + r_in;
-            c.aoff[j] = (uint32_t)min(m0 + row, M - 1) * Kh + chunk * 16;
-            c.boff[j] = (uint32_t)min(n0 + row, N - 1) * Kh + chunk * 16;
+            const int rg = 4 * wave + j;
+            c.aoff[j] = (uint32_t)min((m0 >> 4) + rg, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
+            c.boff[j] = (uint32_t)min((n0 >> 4) + rg, rgB - 1) * (uint32_t)(T * 1024) + lane * 16;
         }
         // LDS-direct scale loads: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords
         // 128 w .. 128 w + 127 of each (two pieces of 64).
@@ -424,8 +443,8 @@ template <typename YT>
 hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight* w, int M, YT* Y, int64_t ldy,
                         hipStream_t stream) {
     const int N = w->N, nb = w->nb;
-    const bool fits32 = (size_t)M * nb * 16 < (1ull << 31) && (size_t)N * nb * 16 < (1ull << 31);
-    if (M > 64 && fits32 && nb % 8 == 0) {
+    const bool fits32 = code_bytes_blocked(M, nb) < (1ull << 31) && code_bytes_blocked(N, nb) < (1ull << 31);
+    if (M > 64 && fits32) {
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
@@ -456,6 +475,20 @@ hipError_t launch_scales_to_canonical(const uint8_t* internal, uint8_t* canon, i
     const size_t total = (size_t)rows * nb;
     const int grid = (int)std::min<size_t>((total + 255) / 256, 4096);
     scales_to_canonical<<<grid, 256, 0, stream>>>(internal, canon, rows, nb);
+    return hipGetLastError();
+}
+
+hipError_t launch_codes_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream) {
+    const size_t total = (size_t)rows * scale_groups(nb) * 8;
+    const int grid = (int)std::min<size_t>((total + 255) / 256, 8192);
+    codes_to_blocked<<<grid, 256, 0, stream>>>(rowmajor, blocked, rows, nb);
+    return hipGetLastError();
+}
+
+hipError_t launch_codes_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream) {
+    const size_t total = (size_t)rows * nb;
+    const int grid = (int)std::min<size_t>((total + 255) / 256, 8192);
+    codes_to_rowmajor<<<grid, 256, 0, stream>>>(blocked, rowmajor, rows, nb);
     return hipGetLastError();
 }
 

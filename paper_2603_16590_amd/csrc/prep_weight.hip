@@ -4,6 +4,7 @@
 // fp64 blocks, one rounding to fp32) rather than speed.  gfx950 only.
 #include "batq_internal.h"
 #include "mxfp4_device.h"
+#include "code_layout.h"
 #include "scale_layout.h"
 
 namespace batq {
@@ -17,7 +18,8 @@ template <>
 __device__ __forceinline__ double load_w<uint16_t>(const uint16_t* p) { return (double)bf16_bits_to_float(*p); }
 
 // One thread per (K-block k, output column n).  blockIdx.y = k, blockIdx.x tiles N by 256.
-// Codes go to [N][K/2]; scales to the GEMM's group-major layout (pad bytes are set by the caller).
+// Codes go to the blocked code layout, scales to the grouped layout (padding of both is
+// initialised by the caller).
 template <typename WT, bool TRANSFORM>
 __global__ void __launch_bounds__(256)
 prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, int nb,
@@ -62,7 +64,7 @@ prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, i
     out.y = encode8(y + 8, bound, sc);
     out.z = encode8(y + 16, bound, sc);
     out.w = encode8(y + 24, bound, sc);
-    *reinterpret_cast<uint4*>(codes + (size_t)n * nb * 16 + (size_t)k * 16) = out;
+    *reinterpret_cast<uint4*>(codes + code_chunk_offset(n, k, nb)) = out;
     scales[scale_index_internal(n, k, N)] = (uint8_t)s;
 }
 

@@ -11,9 +11,11 @@
 //     quad broadcasts,
 // which is the vec identity of Sec. 3.1.1 (12 multiply-adds per element instead of 32).
 // The block amax is a two-step DPP reduction inside the quad.  Every lane then emits its
-// 8 codes as one dword; lane 0 of the quad stores the scale byte (grouped scale layout).
+// 8 codes as one dword into the GEMM's blocked code layout; lane 0 of the quad stores the
+// scale byte (grouped scale layout).
 #include "batq_internal.h"
 #include "mxfp4_device.h"
+#include "code_layout.h"
 #include "scale_layout.h"
 
 namespace batq {
@@ -60,7 +62,7 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
     int k = blockIdx.x * 64 + (threadIdx.x >> 2);
     const bool live = k < nb;
     // padding blocks of the last 8-block scale group get the neutral scale
-    const bool pad = !live && k < scale_groups(nb) * 8 && q == 0;
+    const bool pad = !live && k < scale_groups(nb) * 8;
     const int kpad = k;
     if (!live) k = nb - 1;               // keep the whole quad running for the DPP exchanges
 
@@ -88,7 +90,6 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
 
     const int row0 = blockIdx.y * rows_per_wg;
     const int row1 = min(M, row0 + rows_per_wg);
-    const size_t Kh = (size_t)nb * 16;   // bytes of codes per row
     for (int row = row0; row < row1; ++row) {
         float x[8], y[8];
         load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, x);
@@ -144,10 +145,12 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
         const uint32_t s = e8m0_of_bound(bound);
         const uint32_t packed = encode8(y, bound, scale_operand(s));
         if (live) {
-            *reinterpret_cast<uint32_t*>(codes + (size_t)row * Kh + (size_t)k * 16 + q * 4) = packed;
+            *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, k, nb) + q * 4) = packed;
             if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
         } else if (pad) {
-            scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+            // padding blocks up to the next multiple of 8: zero codes, neutral scale
+            *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, kpad, nb) + q * 4) = 0u;
+            if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
         }
     }
 }

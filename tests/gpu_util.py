@@ -70,3 +70,46 @@ def rowmajor_to_grouped(rm: np.ndarray) -> np.ndarray:
     idx = ((k // 8)[None, :] * rows + np.arange(rows)[:, None]) * 8 + (k % 8)[None, :] // 2 + 4 * (k % 2)[None, :]
     out[idx] = rm
     return out
+
+
+def _chunk_offsets(rows: int, nb: int) -> np.ndarray:
+    """Byte offset of the 16-byte chunk of block k of each row in the library's device code order
+    (formula from the header): ((row//16)*S + k//4)*1024 + (row%16)*64 + (((k%4) ^ ((row%16)//4))*16)."""
+    S = 2 * ((nb + 7) // 8)
+    row = np.arange(rows)[:, None]
+    k = np.arange(nb)[None, :]
+    r = row % 16
+    return ((row // 16) * S + k // 4) * 1024 + r * 64 + (((k % 4) ^ ((r // 4) % 4)) * 16)
+
+
+def blocked_to_rowmajor(blocked: np.ndarray, rows: int, nb: int) -> np.ndarray:
+    S = 2 * ((nb + 7) // 8)
+    assert blocked.size == ((rows + 15) // 16) * S * 1024
+    off = _chunk_offsets(rows, nb)
+    idx = off[:, :, None] + np.arange(16)[None, None, :]
+    out = blocked.reshape(-1)[idx].reshape(rows, nb * 16)
+    # K padding up to a multiple of 8 blocks must hold zero codes
+    nbp = ((nb + 7) // 8) * 8
+    if nbp > nb:
+        offp = _chunk_offsets_range(rows, nb, nbp)
+        assert np.all(blocked.reshape(-1)[offp[:, :, None] + np.arange(16)[None, None, :]] == 0)
+    return np.ascontiguousarray(out)
+
+
+def _chunk_offsets_range(rows, k0, k1):
+    S = 2 * ((k1 + 7) // 8)
+    row = np.arange(rows)[:, None]
+    k = np.arange(k0, k1)[None, :]
+    r = row % 16
+    return ((row // 16) * S + k // 4) * 1024 + r * 64 + (((k % 4) ^ ((r // 4) % 4)) * 16)
+
+
+def rowmajor_to_blocked(rm: np.ndarray) -> np.ndarray:
+    rows, kh = rm.shape
+    nb = kh // 16
+    S = 2 * ((nb + 7) // 8)
+    out = np.zeros(((rows + 15) // 16) * S * 1024, dtype=np.uint8)
+    off = _chunk_offsets(rows, nb)
+    idx = off[:, :, None] + np.arange(16)[None, None, :]
+    out[idx.reshape(-1)] = rm.reshape(-1)
+    return out

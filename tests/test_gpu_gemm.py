@@ -11,7 +11,7 @@ import pytest
 
 import batq_inputs as bi
 from oracle import batq_oracle as o
-from gpu_util import require_gpu, to_dev, y_to_f32, sample_rows, grouped_to_rowmajor, rowmajor_to_grouped
+from gpu_util import require_gpu, to_dev, y_to_f32, sample_rows, grouped_to_rowmajor, rowmajor_to_grouped, blocked_to_rowmajor, rowmajor_to_blocked
 
 pytestmark = pytest.mark.gpu
 
@@ -40,6 +40,11 @@ def _xs(scales):
     return torch.from_numpy(rowmajor_to_grouped(scales)).cuda()
 
 
+def _xc(codes):
+    import torch
+    return torch.from_numpy(rowmajor_to_blocked(codes)).cuda()
+
+
 def test_single_block_is_exact(B):
     # K = 32: every product and the 32-term sum are exact in fp32, so the result equals the oracle's
     import torch
@@ -47,7 +52,7 @@ def test_single_block_is_exact(B):
     xc, xs, dxc, dxs = _rand_q(rng, 40, 32)
     wc, ws, dwc, dws = _rand_q(rng, 50, 32)
     wh = B.batq_weight_import(dwc, dws, 32, 50)
-    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, xc.shape[0], torch.float32)
     torch.cuda.synchronize()
     ref = o.gemm(xc, xs, wc, ws)
     assert np.array_equal(y_to_f32(Y).astype(np.float64), ref)
@@ -62,13 +67,13 @@ def test_small_shapes_random_codes(B, M, K, N):
     wc, ws, dwc, dws = _rand_q(rng, N, K)
     wh = B.batq_weight_import(dwc, dws, K, N)
     ref = o.gemm(xc, xs, wc, ws)
-    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, xc.shape[0], torch.float32)
     torch.cuda.synchronize()
     assert _relfro(y_to_f32(Y), ref) <= 1e-5
     # element-wise: fp32 accumulation of nb exact block terms
     tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
     assert np.all(np.abs(y_to_f32(Y) - ref) <= tol + 1e-30)
-    Yb = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.bfloat16)
+    Yb = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, xc.shape[0], torch.bfloat16)
     torch.cuda.synchronize()
     refb = o.bf16_round(ref).astype(np.float64)
     got = y_to_f32(Yb).astype(np.float64)
@@ -84,7 +89,7 @@ def test_extreme_scales(B):
     xc, xs, dxc, dxs = _rand_q(rng, 33, 64, lo=0, hi=40)
     wc, ws, dwc, dws = _rand_q(rng, 34, 64, lo=200, hi=255)
     wh = B.batq_weight_import(dwc, dws, 64, 34)
-    Y = B.batq_gemm_mxfp4(dxc, _xs(xs), wh, torch.float32)
+    Y = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, xc.shape[0], torch.float32)
     torch.cuda.synchronize()
     ref = o.gemm(xc, xs, wc, ws)
     assert _relfro(y_to_f32(Y), ref) <= 1e-5
@@ -97,11 +102,11 @@ def test_strided_output_and_empty(B):
     wc, ws, dwc, dws = _rand_q(rng, 24, 64)
     wh = B.batq_weight_import(dwc, dws, 64, 24)
     wide = torch.full((20, 40), 7.0, device="cuda")
-    B.batq_gemm_mxfp4(dxc, _xs(xs), wh, Y=wide[:, :24])
+    B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, 20, Y=wide[:, :24])
     torch.cuda.synchronize()
     assert _relfro(wide[:, :24].cpu().numpy(), o.gemm(xc, xs, wc, ws)) <= 1e-5
     assert bool((wide[:, 24:] == 7.0).all())
-    Y0 = B.batq_gemm_mxfp4(dxc[:0], _xs(xs)[:0], wh, torch.float32)
+    Y0 = B.batq_gemm_mxfp4(_xc(xc)[:0], _xs(xs)[:0], wh, 0, torch.float32)
     assert Y0.shape == (0, 24)
 
 
@@ -115,20 +120,20 @@ def test_linear_all_configs(B, cfg):
     wh = B.batq_prepare_weight(t, to_dev(w.W, w.dtype))
     X = to_dev(w.X, w.dtype)
     ws_bytes = B.batq_linear_workspace(w.M, w.K)
-    assert ws_bytes >= w.M * w.K // 2 + w.M * w.K // 32
+    assert ws_bytes == B.batq_code_bytes(w.M, w.K) + B.batq_scale_bytes(w.M, w.K)
     work = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     out_dtype = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
     Y = B.batq_linear(t, wh, X, out_dtype, workspace=work)
     Y32 = B.batq_linear(t, wh, X, torch.float32, workspace=work)
     # the two-call route (quantise, then GEMM on the codes it wrote) is the same arithmetic
     xc_d, xs_d = B.batq_quantize_act(t, X)
-    Y32b = B.batq_gemm_mxfp4(xc_d, xs_d, wh, torch.float32)
+    Y32b = B.batq_gemm_mxfp4(xc_d, xs_d, wh, w.M, torch.float32)
     torch.cuda.synchronize()
     assert torch.equal(Y32, Y32b)
-    assert torch.equal(work[: w.M * w.K // 2].view(w.M, w.K // 2), xc_d)
+    assert torch.equal(work[: xc_d.numel()], xc_d)
     rows = sample_rows(w.M, 96, seed=cfg)
     cols = sample_rows(w.N, 768, seed=cfg + 10)
-    xcodes = xc_d[torch.from_numpy(rows).cuda()].cpu().numpy()
+    xcodes = blocked_to_rowmajor(xc_d.cpu().numpy(), w.M, w.K // 32)[rows]
     xscales = grouped_to_rowmajor(xs_d.cpu().numpy(), w.M, w.K // 32)[rows]
     wc, wsc = wh.export()
     torch.cuda.synchronize()

@@ -9,7 +9,7 @@ import pytest
 
 import batq_inputs as bi
 from oracle import batq_oracle as o
-from gpu_util import require_gpu, to_dev, unpack, code_value_mismatch, sample_rows, TIE_POINTS, grouped_to_rowmajor
+from gpu_util import require_gpu, to_dev, unpack, code_value_mismatch, sample_rows, TIE_POINTS, grouped_to_rowmajor, blocked_to_rowmajor
 
 pytestmark = pytest.mark.gpu
 
@@ -27,7 +27,8 @@ def _run(B, t, Xdev):
     torch.cuda.synchronize()
     M, K = Xdev.shape
     assert s.numel() == B.batq_scale_bytes(M, K) == ((K // 32 + 7) // 8) * 8 * M
-    return c.cpu().numpy(), grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
+    assert c.numel() == B.batq_code_bytes(M, K) == ((M + 15) // 16) * 16 * ((K + 255) // 256) * 128
+    return blocked_to_rowmajor(c.cpu().numpy(), M, K // 32), grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
 
 
 # ------------------------------------------------------------------ T1: quantiser alone, bit-exact
@@ -140,7 +141,7 @@ def test_empty_input_is_a_noop(B):
     t = B.Transform(64, None, None, None)
     X = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     c, s = B.batq_quantize_act(t, X)
-    assert c.shape == (0, 32) and s.numel() == 0
+    assert c.numel() == 0 and s.numel() == 0
 
 
 def test_strided_rows(B):
@@ -208,6 +209,24 @@ def test_scale_order_helpers(B):
             assert B.lib.batq_scale_index(r, k, rows) == ((k // 8) * rows + r) * 8 + (k % 8) // 2 + 4 * (k % 2)
 
 
+def test_code_order_helpers(B):
+    import torch
+    from gpu_util import rowmajor_to_blocked
+    rng = np.random.default_rng(4)
+    for rows, nb in ((5, 3), (64, 8), (33, 21), (16, 4)):
+        rm = rng.integers(0, 256, size=(rows, nb * 16), dtype=np.uint8)
+        d = B.batq_codes_from_rowmajor(torch.from_numpy(rm).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(blocked_to_rowmajor(d.cpu().numpy(), rows, nb), rm)
+        back = B.batq_codes_to_rowmajor(d, rows, nb * 32)
+        torch.cuda.synchronize()
+        assert np.array_equal(back.cpu().numpy(), rm)
+        S = 2 * ((nb + 7) // 8)
+        for (r, k) in ((0, 0), (rows - 1, nb - 1), (rows // 2, nb // 2)):
+            exp = ((r // 16) * S + k // 4) * 1024 + (r % 16) * 64 + (((k % 4) ^ ((r % 16) // 4)) * 16)
+            assert B.lib.batq_code_chunk_offset(r, k, nb * 32) == exp
+
+
 def test_deterministic(B):
     w = bi.make_workload(1, with_weight=False)
     t = B.Transform(w.K, w.G, w.P, w.clip)
@@ -221,7 +240,7 @@ def test_argument_errors_leave_outputs_untouched(B):
     import torch
     t = B.Transform(64, None, None, None)
     X = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
-    codes = torch.full((4, 32), 0xAB, dtype=torch.uint8, device="cuda")
+    codes = torch.full((B.batq_code_bytes(4, 64),), 0xAB, dtype=torch.uint8, device="cuda")
     scales = torch.full((4 * 8,), 0xCD, dtype=torch.uint8, device="cuda")
     lib = B.lib
     assert lib.batq_quantize_act(t.handle, X.data_ptr(), 1, 4, 96, 96, codes.data_ptr(), scales.data_ptr(), None) == 10
