@@ -55,6 +55,19 @@ bool invert_small(const double* A, int n, double* inv) {
     return true;
 }
 
+uint16_t bf16_rne(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+float bf16_value(uint16_t b) {
+    const uint32_t u = (uint32_t)b << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
 bool clip_ok(const float* c, int n) {
     for (int i = 0; i < n; ++i)
         if (!(c[i] > 0.0f && c[i] <= 1.0f)) return false;
@@ -156,8 +169,11 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
     const int nb = K / 32;
     if (clip_a && !clip_ok(clip_a, nb)) return BATQ_ERR_CLIP_RANGE;
 
-    // host fp64: G^-1, P_k^-1 and the dense inverse blocks T_k^-1 = G^-1 (x) P_k^-1
+    // host fp64: G^-1, P_k^-1 and the dense inverse blocks T_k^-1 = G^-1 (x) P_k^-1;
+    // and the forward blocks T_k = G (x) P_k split into three bf16 terms in the lane order of
+    // the activation kernel's matrix-instruction operand
     std::vector<double> Tinv;
+    std::vector<uint16_t> Tsplit;
     if (G) {
         const int go = g_outer, gi = g_inner;
         std::vector<double> Gd(go * go), Ginv(go * go), Pd(gi * gi), Pinv(gi * gi);
@@ -174,6 +190,23 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
                         for (int c2 = 0; c2 < gi; ++c2)
                             Tk[(a * gi + c) * 32 + a2 * gi + c2] = Ginv[a * go + a2] * Pinv[c * gi + c2];
         }
+        Tsplit.resize((size_t)nb * 3 * 2 * 64 * 8);
+        for (int k = 0; k < nb; ++k)
+            for (int half = 0; half < 2; ++half)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e) {
+                        const int m = lane & 31;
+                        const int out_col = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
+                        const int in_col = 16 * (lane >> 5) + 8 * half + e;
+                        const double tv = (double)G[(in_col / gi) * go + out_col / gi] *
+                                          (double)P[(size_t)k * gi * gi + (in_col % gi) * gi + out_col % gi];
+                        double rest = tv;
+                        for (int term = 0; term < 3; ++term) {
+                            const uint16_t b = bf16_rne((float)rest);
+                            rest -= (double)bf16_value(b);
+                            Tsplit[((((size_t)k * 3 + term) * 2 + half) * 64 + lane) * 8 + e] = b;
+                        }
+                    }
     }
 
     batq_status st = check_device();
@@ -193,6 +226,7 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
         st = upload(&t->d_G, G, (size_t)g_outer * g_outer);
         if (st == BATQ_OK) st = upload(&t->d_P, P, (size_t)nb * g_inner * g_inner);
         if (st == BATQ_OK) st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
+        if (st == BATQ_OK) st = upload(&t->d_Tsplit, Tsplit.data(), Tsplit.size());
     }
     if (st != BATQ_OK) {
         free_transform(t);

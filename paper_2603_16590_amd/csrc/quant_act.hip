@@ -2,9 +2,26 @@
 // Kronecker factors), block clipping (Eq. 3-4, symmetric form) and MXFP4 quantisation
 // (Sec. 2: E2M1 elements, one UE8M0 scale per 32).  gfx950 only.
 //
-// Register-level kernel (`quant_act_quad`).  One quad of lanes owns one 32-element block
-// of one row: lane q of the quad holds the 8 contiguous elements 8q..8q+7 (one 128-bit load
-// for bf16).  The Kronecker structure T_k = G (x) P_k splits the 32x32 block product into
+// Two kernels.
+//
+// Matrix-core kernel (`quant_act_mfma`, bf16 input with a transform).  The 12 multiply-adds
+// per element of the Kronecker route would make the kernel VALU-bound on this chip (packed
+// fp32 arithmetic is not used), so the 32x32 block product runs on the matrix pipe instead,
+// at fp32 accuracy: bf16 inputs are exact, and the fp32 entries of T_k are split on the host
+// into three bf16 terms (hi + mid + lo = 24 significant bits), so every product is exact in
+// the fp32 accumulator.  A wave owns one MX block k and walks down 32-row tiles:
+//   D (32 out-cols x 32 rows) = T_k^T (32 x 32) * X_tile^T (32 x 32), six 32x32x16 bf16
+//   matrix instructions (3 terms x 2 K-halves).  The K order of the instruction is mapped
+//   to input columns so that a lane's operand is 32 contiguous bytes of one row of X, and
+//   the output rows of T_k^T are permuted so that a lane ends with 16 consecutive output
+//   columns of one row: amax needs one cross-lane exchange, and the 16 codes are 8 bytes of
+//   the block's 16-byte chunk.  The four waves of a workgroup own the four blocks of one
+//   128-element K stage and assemble whole 1 KiB pieces of the code layout in LDS, so that
+//   global stores are contiguous full cache lines.
+//
+// Register-level kernel (`quant_act_quad`; fp32 input, or no transform).  One quad of lanes
+// owns one 32-element block
+// of one row: lane q of the quad holds the 8 contiguous elements 8q..8q+7.  The Kronecker structure T_k = G (x) P_k splits the 32x32 block product into
 //   - a product with the factor that acts on the contiguous index, done in the lane's own
 //     registers, and
 //   - a mix across the four lanes of the quad with the other factor, done with DPP
@@ -13,6 +30,8 @@
 // The block amax is a two-step DPP reduction inside the quad.  Every lane then emits its
 // 8 codes as one dword into the GEMM's blocked code layout; lane 0 of the quad stores the
 // scale byte (grouped scale layout).
+#include <algorithm>
+
 #include "batq_internal.h"
 #include "mxfp4_device.h"
 #include "code_layout.h"
@@ -155,6 +174,111 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
     }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// Lane layout of the pre-split transform operand (built by the host, see batq_api.hip):
+//   Tsplit[k][term][half][lane] = 8 bf16: T_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)], e = 0..7,
+//   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3); terms 0, 1, 2 = hi, mid, lo.
+__global__ void __launch_bounds__(256)
+quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
+               const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
+               uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    // The four waves of a workgroup own the four MX blocks of one 128-element K stage, i.e. one
+    // 1 KiB piece column of the blocked code layout.  Per 32-row tile they assemble two complete
+    // pieces in LDS and store them with contiguous 512-byte wave stores (full cache lines).
+    __shared__ __align__(16) uint8_t stage[2][2048];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int k = blockIdx.x * 4 + wave;
+    const bool live = k < nb;                               // else: zero padding of the last K group
+    const int kc = live ? k : nb - 1;
+    const int tile0 = blockIdx.y * tiles_per_wg;
+    const int row_groups = (M + 15) >> 4;
+    const size_t piece_stride = (size_t)code_stages(nb) * 1024;
+
+    uint4 tf[3][2];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) tf[t][h] = Tsplit[((size_t)(kc * 3 + t) * 2 + h) * 64 + lane];
+    const float ck = clip[kc];
+    // this lane's 8 bytes inside the two-piece staging buffer
+    const int r16 = l32 & 15;
+    const int st_off = (l32 >> 4) * 1024 + r16 * 64 + ((wave ^ ((r16 >> 2) & 3)) << 4) + 8 * kg;
+
+    auto load_tile = [&](int tile, uint4& x0, uint4& x1) {
+        const int rowc = min(tile * 32 + l32, M - 1);       // rows past the end are computed, not stored
+        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)kc * 32 + 16 * kg);
+        x0 = xp[0];
+        x1 = xp[1];
+    };
+    uint4 x0 = {}, x1 = {};
+    if (live && tile0 * 32 < M) load_tile(tile0, x0, x1);
+
+    for (int it = 0; it < tiles_per_wg; ++it) {
+        const int tile = tile0 + it;
+        if (tile * 32 >= M) break;                          // workgroup-uniform
+        const int row = tile * 32 + l32;
+        uint2 out = {0u, 0u};
+        uint32_t s = 127;
+        if (live) {
+            const uint4 c0 = x0, c1 = x1;
+            if (it + 1 < tiles_per_wg && (tile + 1) * 32 < M) load_tile(tile + 1, x0, x1);   // prefetch
+            v16f acc = {};
+            // smallest terms first
+#pragma unroll
+            for (int t = 2; t >= 0; --t) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][0]),
+                                                              __builtin_bit_cast(bf16x8, c0), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][1]),
+                                                              __builtin_bit_cast(bf16x8, c1), acc, 0, 0, 0);
+            }
+            // acc[r] = transformed element 16 kg + r of this lane's row
+            float y[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) y[r] = acc[r];
+            float m = __builtin_fabsf(y[0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
+            // the other half of the block lives in lane ^ 32
+            const float mo = __builtin_bit_cast(
+                float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
+            m = __builtin_fmaxf(m, mo);
+            const float bound = ck * m;                     // one fp32 multiply
+            s = e8m0_of_bound(bound);
+            const float sc = scale_operand(s);
+            out.x = encode8(y, bound, sc);
+            out.y = encode8(y + 8, bound, sc);
+        }
+        uint8_t* sb = stage[it & 1];
+        *reinterpret_cast<uint2*>(sb + st_off) = out;
+        if (kg == 0 && row < M) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+        __syncthreads();
+        // waves 0,1 store the piece of row group 2 tile, waves 2,3 that of row group 2 tile + 1
+        const int rg = 2 * tile + (tid >> 7);
+        if (rg < row_groups) {
+            const uint2 v = *reinterpret_cast<const uint2*>(sb + tid * 8);
+            *reinterpret_cast<uint2*>(codes + (size_t)rg * piece_stride + (size_t)blockIdx.x * 1024 + (tid & 127) * 8) = v;
+        }
+    }
+}
+
+hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
+                       uint8_t* scales, hipStream_t stream) {
+    const int nb = t->nb;
+    const int nbp = scale_groups(nb) * 8;
+    const int row_tiles = (M + 31) / 32;
+    // enough waves to fill the chip several times over, otherwise as many row tiles per wave as
+    // possible so that the transform operand is fetched rarely
+    int tiles_per_wave = (int)std::min<long>(8, std::max<long>(1, (long)row_tiles * nb / 6144));
+    while ((row_tiles + tiles_per_wave - 1) / tiles_per_wave > 65535) tiles_per_wave <<= 1;
+    const dim3 grid(nbp / 4, (row_tiles + tiles_per_wave - 1) / tiles_per_wave), block(256);
+    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wave,
+                                               reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
+    return hipGetLastError();
+}
+
 template <typename XT>
 hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes,
                        uint8_t* scales, hipStream_t stream) {
@@ -183,7 +307,11 @@ hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtyp
                                int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    if (xdtype == BATQ_BF16) return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+    if (xdtype == BATQ_BF16) {
+        if (t->has_transform && t->d_Tsplit)
+            return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+        return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+    }
     return launch_quad(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
 }
 
