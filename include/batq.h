@@ -32,7 +32,7 @@
  *     codes   batq_code_bytes(rows, K) bytes; the chunk of block k of `row` starts at
  *             batq_code_chunk_offset(row, k, K)
  *               = ((row/16) * S + k/4) * 1024 + (row%16) * 64 + (((k%4) ^ ((row%16)/4)) * 16),
- *             S = 2 * ceil(K/256); rows are padded to a multiple of 16 (pad rows hold
+ *             S = 2 * ceil(K/256); rows are padded to a multiple of 32 (pad rows hold
  *             unspecified bytes) and K to a multiple of 256 with zero codes;
  *     scales  batq_scale_bytes(rows, K) bytes; block k of `row` at batq_scale_index(row, k, rows)
  *               = ((k/8) * rows + row) * 8 + (k%8)/2 + 4 * (k%2)

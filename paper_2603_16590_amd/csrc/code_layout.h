@@ -9,7 +9,7 @@
 //   inside a piece  row r = row % 16 at byte 64 r; MX block c = (k / 32) % 4 in 16-byte
 //                   slot c ^ ((r / 4) % 4) (bank swizzle); element j = k % 32 in byte j / 2,
 //                   even j in the low nibble.
-// Rows are padded to a multiple of 16 (pad rows are never read into results) and K to a
+// Rows are padded to a multiple of 32 (pad rows are never read into results) and K to a
 // multiple of 256 with zero codes (and neutral scales), which contribute nothing.
 #pragma once
 #include <stddef.h>
@@ -19,8 +19,10 @@ namespace batq {
 
 __host__ __device__ inline int code_stages(int nb) { return ((nb + 7) >> 3) << 1; }      // Kp / 128
 
+// Rows are padded to a multiple of 32 so that a 32-row tile of the quantiser always stores two
+// whole pieces.
 __host__ __device__ inline size_t code_bytes_blocked(int rows, int nb) {
-    return (size_t)((rows + 15) >> 4) * (size_t)code_stages(nb) * 1024;
+    return (size_t)(((rows + 31) >> 5) << 1) * (size_t)code_stages(nb) * 1024;
 }
 
 // Byte offset of the 16-byte chunk holding MX block k of `row`.

@@ -180,32 +180,66 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // Lane layout of the pre-split transform operand (built by the host, see batq_api.hip):
 //   Tsplit[k][term][half][lane] = 8 bf16: T_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)], e = 0..7,
 //   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3); terms 0, 1, 2 = hi, mid, lo.
-__global__ void __launch_bounds__(256)
+constexpr int kQuantThreads = 576;      // 8 compute waves + 1 store wave
+
+__global__ void __launch_bounds__(kQuantThreads)
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
-    // The four waves of a workgroup own the four MX blocks of one 128-element K stage, i.e. one
-    // 1 KiB piece column of the blocked code layout.  Per 32-row tile they assemble two complete
-    // pieces in LDS and store them with contiguous 512-byte wave stores (full cache lines).
-    __shared__ __align__(16) uint8_t stage[2][2048];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Waves 0-7 own the eight MX blocks of one 256-element K group: two 1 KiB piece columns of
+    // the blocked code layout and one 8-byte word of the grouped scale layout per row.  Per
+    // 32-row tile they leave four complete pieces and 32 scale words in LDS; wave 8 does nothing
+    // but copy those to global memory with contiguous full-cache-line stores.  Loads and stores
+    // are kept in different waves on purpose: a wave that has stores in flight cannot wait for
+    // its loads alone (the memory counter is shared and the two complete out of order), which
+    // would serialise the prefetch of the next tile behind the write acknowledgements.
+    __shared__ __align__(16) uint8_t cstage[2][4096];
+    __shared__ __align__(16) uint8_t sstage[2][256];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile0 = blockIdx.y * tiles_per_wg;
+    const int row_tiles = (M + 31) >> 5;
+    const int ntiles = min(tiles_per_wg, row_tiles - tile0);            // >= 1 by construction of the grid
+
+    if (wave == 8) {
+        // ---- store wave
+        const size_t piece_stride = (size_t)code_stages(nb) * 1024;
+        for (int it = 0; it < ntiles; ++it) {
+            const int tile = tile0 + it;
+            __syncthreads();
+            const uint8_t* cb = cstage[it & 1];
+            const uint8_t* sb = sstage[it & 1];
+            // staging order: pieces (column 0, rows 0-15), (0, 16-31), (1, 0-15), (1, 16-31);
+            // the code array is padded to whole 32-row tiles, so all four always exist
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint4 v = *reinterpret_cast<const uint4*>(cb + p * 1024 + lane * 16);
+                *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + (p & 1)) * piece_stride +
+                                          (size_t)(2 * blockIdx.x + (p >> 1)) * 1024 + lane * 16) = v;
+            }
+            const int row = tile * 32 + lane;
+            if (lane < 32 && row < M)
+                *reinterpret_cast<uint2*>(scales + ((size_t)blockIdx.x * M + row) * 8) =
+                    *reinterpret_cast<const uint2*>(sb + lane * 8);
+        }
+        return;
+    }
+
+    // ---- compute waves
     const int l32 = lane & 31, kg = lane >> 5;
-    const int k = blockIdx.x * 4 + wave;
+    const int k = blockIdx.x * 8 + wave;
     const bool live = k < nb;                               // else: zero padding of the last K group
     const int kc = live ? k : nb - 1;
-    const int tile0 = blockIdx.y * tiles_per_wg;
-    const int row_groups = (M + 15) >> 4;
-    const size_t piece_stride = (size_t)code_stages(nb) * 1024;
-
     uint4 tf[3][2];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
         for (int h = 0; h < 2; ++h) tf[t][h] = Tsplit[((size_t)(kc * 3 + t) * 2 + h) * 64 + lane];
     const float ck = clip[kc];
-    // this lane's 8 bytes inside the two-piece staging buffer
+    // this lane's 8 code bytes inside the staging buffer [piece column][row group][1 KiB]
     const int r16 = l32 & 15;
-    const int st_off = (l32 >> 4) * 1024 + r16 * 64 + ((wave ^ ((r16 >> 2) & 3)) << 4) + 8 * kg;
+    const int st_off = (wave >> 2) * 2048 + (l32 >> 4) * 1024 + r16 * 64 + (((wave & 3) ^ ((r16 >> 2) & 3)) << 4) + 8 * kg;
+    const int sc_off = l32 * 8 + ((wave >> 1) | ((wave & 1) << 2));      // byte order inside a scale word
 
     auto load_tile = [&](int tile, uint4& x0, uint4& x1) {
         const int rowc = min(tile * 32 + l32, M - 1);       // rows past the end are computed, not stored
@@ -213,68 +247,55 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int t
         x0 = xp[0];
         x1 = xp[1];
     };
-    uint4 x0 = {}, x1 = {};
-    if (live && tile0 * 32 < M) load_tile(tile0, x0, x1);
+    uint4 x0, x1;
+    load_tile(tile0, x0, x1);
 
-    for (int it = 0; it < tiles_per_wg; ++it) {
+    for (int it = 0; it < ntiles; ++it) {
         const int tile = tile0 + it;
-        if (tile * 32 >= M) break;                          // workgroup-uniform
-        const int row = tile * 32 + l32;
-        uint2 out = {0u, 0u};
-        uint32_t s = 127;
-        if (live) {
-            const uint4 c0 = x0, c1 = x1;
-            if (it + 1 < tiles_per_wg && (tile + 1) * 32 < M) load_tile(tile + 1, x0, x1);   // prefetch
-            v16f acc = {};
-            // smallest terms first
+        const uint4 c0 = x0, c1 = x1;
+        load_tile(min(tile + 1, row_tiles - 1), x0, x1);    // prefetch (the last one re-reads a valid tile)
+        v16f acc = {};
+        // smallest terms first
 #pragma unroll
-            for (int t = 2; t >= 0; --t) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][0]),
-                                                              __builtin_bit_cast(bf16x8, c0), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][1]),
-                                                              __builtin_bit_cast(bf16x8, c1), acc, 0, 0, 0);
-            }
-            // acc[r] = transformed element 16 kg + r of this lane's row
-            float y[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) y[r] = acc[r];
-            float m = __builtin_fabsf(y[0]);
-#pragma unroll
-            for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
-            // the other half of the block lives in lane ^ 32
-            const float mo = __builtin_bit_cast(
-                float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
-            m = __builtin_fmaxf(m, mo);
-            const float bound = ck * m;                     // one fp32 multiply
-            s = e8m0_of_bound(bound);
-            const float sc = scale_operand(s);
-            out.x = encode8(y, bound, sc);
-            out.y = encode8(y + 8, bound, sc);
+        for (int t = 2; t >= 0; --t) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][0]),
+                                                          __builtin_bit_cast(bf16x8, c0), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][1]),
+                                                          __builtin_bit_cast(bf16x8, c1), acc, 0, 0, 0);
         }
-        uint8_t* sb = stage[it & 1];
-        *reinterpret_cast<uint2*>(sb + st_off) = out;
-        if (kg == 0 && row < M) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+        // acc[r] = transformed element 16 kg + r of this lane's row
+        float y[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] = acc[r];
+        float m = __builtin_fabsf(y[0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
+        // the other half of the block lives in lane ^ 32
+        const float mo = __builtin_bit_cast(
+            float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
+        m = __builtin_fmaxf(m, mo);
+        const float bound = ck * m;                         // one fp32 multiply
+        const uint32_t s = live ? e8m0_of_bound(bound) : 127u;
+        const float sc = scale_operand(s);
+        uint2 out;
+        out.x = live ? encode8(y, bound, sc) : 0u;          // padding blocks: zero codes, neutral scale
+        out.y = live ? encode8(y + 8, bound, sc) : 0u;
+        *reinterpret_cast<uint2*>(cstage[it & 1] + st_off) = out;
+        if (kg == 0) sstage[it & 1][sc_off] = (uint8_t)s;
         __syncthreads();
-        // waves 0,1 store the piece of row group 2 tile, waves 2,3 that of row group 2 tile + 1
-        const int rg = 2 * tile + (tid >> 7);
-        if (rg < row_groups) {
-            const uint2 v = *reinterpret_cast<const uint2*>(sb + tid * 8);
-            *reinterpret_cast<uint2*>(codes + (size_t)rg * piece_stride + (size_t)blockIdx.x * 1024 + (tid & 127) * 8) = v;
-        }
     }
 }
 
 hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
                        uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
-    const int nbp = scale_groups(nb) * 8;
+    const int groups = scale_groups(nb);
     const int row_tiles = (M + 31) / 32;
-    // enough waves to fill the chip several times over, otherwise as many row tiles per wave as
-    // possible so that the transform operand is fetched rarely
-    int tiles_per_wave = (int)std::min<long>(8, std::max<long>(1, (long)row_tiles * nb / 6144));
-    while ((row_tiles + tiles_per_wave - 1) / tiles_per_wave > 65535) tiles_per_wave <<= 1;
-    const dim3 grid(nbp / 4, (row_tiles + tiles_per_wave - 1) / tiles_per_wave), block(256);
-    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wave,
+    // few row tiles per workgroup: many short workgroups keep more loads in flight than few long ones
+    int tiles_per_wg = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / 2048));
+    while ((row_tiles + tiles_per_wg - 1) / tiles_per_wg > 65535) tiles_per_wg <<= 1;
+    const dim3 grid(groups, (row_tiles + tiles_per_wg - 1) / tiles_per_wg), block(kQuantThreads);
+    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wg,
                                                reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
     return hipGetLastError();
 }

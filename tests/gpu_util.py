@@ -84,7 +84,7 @@ def _chunk_offsets(rows: int, nb: int) -> np.ndarray:
 
 def blocked_to_rowmajor(blocked: np.ndarray, rows: int, nb: int) -> np.ndarray:
     S = 2 * ((nb + 7) // 8)
-    assert blocked.size == ((rows + 15) // 16) * S * 1024
+    assert blocked.size == ((rows + 31) // 32) * 2 * S * 1024
     off = _chunk_offsets(rows, nb)
     idx = off[:, :, None] + np.arange(16)[None, None, :]
     out = blocked.reshape(-1)[idx].reshape(rows, nb * 16)
@@ -108,7 +108,7 @@ def rowmajor_to_blocked(rm: np.ndarray) -> np.ndarray:
     rows, kh = rm.shape
     nb = kh // 16
     S = 2 * ((nb + 7) // 8)
-    out = np.zeros(((rows + 15) // 16) * S * 1024, dtype=np.uint8)
+    out = np.zeros(((rows + 31) // 32) * 2 * S * 1024, dtype=np.uint8)
     off = _chunk_offsets(rows, nb)
     idx = off[:, :, None] + np.arange(16)[None, None, :]
     out[idx.reshape(-1)] = rm.reshape(-1)

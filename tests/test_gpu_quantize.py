@@ -27,7 +27,7 @@ def _run(B, t, Xdev):
     torch.cuda.synchronize()
     M, K = Xdev.shape
     assert s.numel() == B.batq_scale_bytes(M, K) == ((K // 32 + 7) // 8) * 8 * M
-    assert c.numel() == B.batq_code_bytes(M, K) == ((M + 15) // 16) * 16 * ((K + 255) // 256) * 128
+    assert c.numel() == B.batq_code_bytes(M, K) == ((M + 31) // 32) * 32 * ((K + 255) // 256) * 128
     return blocked_to_rowmajor(c.cpu().numpy(), M, K // 32), grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
 
 

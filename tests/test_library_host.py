@@ -80,9 +80,9 @@ def test_workspace_size(B):
     assert B.batq_linear_workspace(2048, 4096) == 2048 * 2048 + 2048 * 128
     assert B.batq_linear_workspace(16, 4096) % 16 == 0
     assert B.batq_linear_workspace(0, 4096) == 0 and B.batq_linear_workspace(4, 48) == 0
-    # codes: rows padded to 16, K to 256; scales are kept in groups of 8 blocks
-    assert B.batq_code_bytes(5, 96) == 16 * 128 and B.batq_code_bytes(2048, 4096) == 2048 * 2048
-    assert B.batq_scale_bytes(5, 96) == 5 * 8 and B.batq_linear_workspace(5, 96) == 16 * 128 + 5 * 8
+    # codes: rows padded to 32, K to 256; scales are kept in groups of 8 blocks
+    assert B.batq_code_bytes(5, 96) == 32 * 128 and B.batq_code_bytes(2048, 4096) == 2048 * 2048
+    assert B.batq_scale_bytes(5, 96) == 5 * 8 and B.batq_linear_workspace(5, 96) == 32 * 128 + 5 * 8
     chunks = {B.lib.batq_code_chunk_offset(r, k, 256) for r in range(32) for k in range(8)}
     assert chunks == set(range(0, 32 * 128, 16))        # a bijection onto 16-byte chunks
     assert B.batq_scale_bytes(2048, 4096) == 2048 * 128 and B.batq_scale_bytes(4, 48) == 0
