@@ -39,6 +39,8 @@ def main():
                     help="which synthetic configuration is the timed workload (default: 8B-class prefill up/gate)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
+                    "loop, streaming HBM kernels)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         _die("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1")
@@ -124,16 +126,16 @@ def main():
 
     # the dominant kernel of the step decides which roofline is reported first
     gemm_dominant = res["gemm_ms"] >= res["quant_ms"]
-    roof_gemm = {"kernel": "gemm_mxfp4", "bound": "mfma", "achieved": res["gemm_tflops"], "peak": PEAK_FP4_TFLOPS,
+    roof_gemm = {"kernel": "gemm_tiled", "bound": "mfma", "achieved": res["gemm_tflops"], "peak": PEAK_FP4_TFLOPS,
                  "unit": "TFLOP/s", "frac": res["gemm_tflops"] / PEAK_FP4_TFLOPS, "traffic": None}
-    roof_quant = {"kernel": "quant_act", "bound": "hbm", "achieved": res["quant_gbs"], "peak": PEAK_HBM_GBS,
+    roof_quant = {"kernel": "quant_act_mfma", "bound": "hbm", "achieved": res["quant_gbs"], "peak": PEAK_HBM_GBS,
                   "unit": "GB/s", "frac": res["quant_gbs"] / PEAK_HBM_GBS, "traffic": None}
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(traffic_file):
         try:
             tr = json.load(open(traffic_file)).get(f"cfg{args.workload}", {})
-            roof_gemm["traffic"] = tr.get("gemm_mxfp4")
-            roof_quant["traffic"] = tr.get("quant_act")
+            roof_gemm["traffic"] = tr.get("gemm_tiled")
+            roof_quant["traffic"] = tr.get("quant_act_mfma")
         except Exception:
             pass
 
@@ -144,6 +146,17 @@ def main():
         _, _, _, r, _, _ = run_config(c, max(10, args.steps // 4), max(3, args.warmup // 4))
         also[f"cfg{c}"] = r
         torch.cuda.empty_cache()
+
+    ceilings = None
+    tool = os.path.join(ROOT, "paper_2603_16590_amd", "batq_ceilings")
+    if not args.no_ceilings and os.path.exists(tool):
+        import subprocess
+        torch.cuda.synchronize()
+        try:
+            out = subprocess.run([tool], capture_output=True, text=True, timeout=120)
+            ceilings = json.loads(out.stdout.strip().splitlines()[-1])
+        except Exception as e:  # the headline numbers do not depend on it
+            ceilings = {"error": str(e)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -183,6 +196,7 @@ def main():
         "gemm_tflops": res["gemm_tflops"], "quant_ms": res["quant_ms"], "gemm_ms": res["gemm_ms"],
         "roofline": roof_gemm if gemm_dominant else roof_quant,
         "roofline_other": roof_quant if gemm_dominant else roof_gemm,
+        "measured_ceilings": ceilings,
         "cpu_baseline": cpu,
         "also": also,
     }

@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbatq.so")
+CEILINGS = os.path.join(HERE, "batq_ceilings")     # standalone tool: measured chip ceilings
 SOURCES = ["batq_api.hip", "quant_act.hip", "prep_weight.hip", "gemm_mxfp4.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -28,7 +29,8 @@ def _run(cmd):
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source and link libbatq.so next to this file. Always recompiles."""
+    """Compile every HIP source, link libbatq.so and the batq_ceilings tool next to this file.
+    Always recompiles."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
@@ -40,6 +42,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     with ThreadPoolExecutor(max_workers=4) as ex:
         outs = list(ex.map(compile_one, zip(SOURCES, objs)))
     outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
+    outs.append(_run([HIPCC, *FLAGS, *extra_flags, os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS]))
     if verbose:
         for o in outs:
             if o.strip():
