@@ -161,9 +161,10 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import batq_oracle as o
-        # bounded sample sized for roughly 10-30 s of oracle work on the host cores
+        # bounded sample: at most 2048 rows x 16384 output columns (the whole of cfg2), a few
+        # seconds to tens of seconds of oracle work on the host cores
         ms_rows = min(w.M, 2048)
-        ns_cols = min(w.N, 8192)
+        ns_cols = min(w.N, 16384)
         Xs_ = w.X_f32()[:ms_rows]
         Wc, Wsc = o.prepare_weight(w.W_f32()[:, :ns_cols], w.G, w.P)          # offline, not timed
         c0 = time.perf_counter()

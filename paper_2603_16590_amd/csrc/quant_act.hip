@@ -9,15 +9,16 @@
 // fp32 arithmetic is not used), so the 32x32 block product runs on the matrix pipe instead,
 // at fp32 accuracy: bf16 inputs are exact, and the fp32 entries of T_k are split on the host
 // into three bf16 terms (hi + mid + lo = 24 significant bits), so every product is exact in
-// the fp32 accumulator.  A wave owns one MX block k and walks down 32-row tiles:
+// the fp32 accumulator.  Per 32-row tile and MX block:
 //   D (32 out-cols x 32 rows) = T_k^T (32 x 32) * X_tile^T (32 x 32), six 32x32x16 bf16
 //   matrix instructions (3 terms x 2 K-halves).  The K order of the instruction is mapped
 //   to input columns so that a lane's operand is 32 contiguous bytes of one row of X, and
 //   the output rows of T_k^T are permuted so that a lane ends with 16 consecutive output
 //   columns of one row: amax needs one cross-lane exchange, and the 16 codes are 8 bytes of
-//   the block's 16-byte chunk.  The four waves of a workgroup own the four blocks of one
-//   128-element K stage and assemble whole 1 KiB pieces of the code layout in LDS, so that
-//   global stores are contiguous full cache lines.
+//   the block's 16-byte chunk.
+// A workgroup owns one 256-element K group and keeps its transform operands in LDS; each wave
+// owns whole 32-row tiles (512 contiguous bytes per row), so there are no barriers in the
+// steady state, and code pieces and scale words leave as whole cache lines.
 //
 // Register-level kernel (`quant_act_quad`; fp32 input, or no transform).  One quad of lanes
 // owns one 32-element block
@@ -180,109 +181,106 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // Lane layout of the pre-split transform operand (built by the host, see batq_api.hip):
 //   Tsplit[k][term][half][lane] = 8 bf16: T_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)], e = 0..7,
 //   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3); terms 0, 1, 2 = hi, mid, lo.
-constexpr int kQuantThreads = 576;      // 8 compute waves + 1 store wave
+constexpr int kQuantWaves = 8;          // waves per workgroup, each owning whole 32-row tiles
+constexpr int kTsplitBlock = 3 * 2 * 64 * 16;               // bytes of pre-split transform operand per MX block
 
-__global__ void __launch_bounds__(kQuantThreads)
-quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
+__global__ void __launch_bounds__(kQuantWaves * 64)
+quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wave,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
-    // Waves 0-7 own the eight MX blocks of one 256-element K group: two 1 KiB piece columns of
-    // the blocked code layout and one 8-byte word of the grouped scale layout per row.  Per
-    // 32-row tile they leave four complete pieces and 32 scale words in LDS; wave 8 does nothing
-    // but copy those to global memory with contiguous full-cache-line stores.  Loads and stores
-    // are kept in different waves on purpose: a wave that has stores in flight cannot wait for
-    // its loads alone (the memory counter is shared and the two complete out of order), which
-    // would serialise the prefetch of the next tile behind the write acknowledgements.
-    __shared__ __align__(16) uint8_t cstage[2][4096];
-    __shared__ __align__(16) uint8_t sstage[2][256];
+    // A workgroup owns one 256-element K group (8 MX blocks = two 1 KiB piece columns of the code
+    // layout and one 8-byte scale word per row).  Its transform operands (48 KiB) are fetched once
+    // into LDS; after that every wave works alone, without workgroup barriers: it reads 32 rows x
+    // 512 contiguous bytes of X, runs the 8 blocks through the matrix pipe one after the other,
+    // collects its four finished code pieces in a private 4 KiB LDS area and writes them, and the
+    // 32 scale words, as whole cache lines.
+    __shared__ __align__(16) uint8_t tlds[8 * kTsplitBlock];
+    __shared__ __align__(16) uint8_t cstage[kQuantWaves][4096];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile0 = blockIdx.y * tiles_per_wg;
-    const int row_tiles = (M + 31) >> 5;
-    const int ntiles = min(tiles_per_wg, row_tiles - tile0);            // >= 1 by construction of the grid
-
-    if (wave == 8) {
-        // ---- store wave
-        const size_t piece_stride = (size_t)code_stages(nb) * 1024;
-        for (int it = 0; it < ntiles; ++it) {
-            const int tile = tile0 + it;
-            __syncthreads();
-            const uint8_t* cb = cstage[it & 1];
-            const uint8_t* sb = sstage[it & 1];
-            // staging order: pieces (column 0, rows 0-15), (0, 16-31), (1, 0-15), (1, 16-31);
-            // the code array is padded to whole 32-row tiles, so all four always exist
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint4 v = *reinterpret_cast<const uint4*>(cb + p * 1024 + lane * 16);
-                *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + (p & 1)) * piece_stride +
-                                          (size_t)(2 * blockIdx.x + (p >> 1)) * 1024 + lane * 16) = v;
-            }
-            const int row = tile * 32 + lane;
-            if (lane < 32 && row < M)
-                *reinterpret_cast<uint2*>(scales + ((size_t)blockIdx.x * M + row) * 8) =
-                    *reinterpret_cast<const uint2*>(sb + lane * 8);
-        }
-        return;
+    const int g = blockIdx.x;                               // K group
+    const int k0 = g * 8;
+    const int nblk = min(8, nb - k0);                       // real blocks in this group (rest is padding)
+    {
+        const uint4* src = Tsplit + (size_t)k0 * (kTsplitBlock / 16);
+        uint4* dst = reinterpret_cast<uint4*>(tlds);
+        for (int i = tid; i < nblk * (kTsplitBlock / 16); i += kQuantWaves * 64) dst[i] = src[i];
     }
+    __syncthreads();
 
-    // ---- compute waves
     const int l32 = lane & 31, kg = lane >> 5;
-    const int k = blockIdx.x * 8 + wave;
-    const bool live = k < nb;                               // else: zero padding of the last K group
-    const int kc = live ? k : nb - 1;
-    uint4 tf[3][2];
-#pragma unroll
-    for (int t = 0; t < 3; ++t)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) tf[t][h] = Tsplit[((size_t)(kc * 3 + t) * 2 + h) * 64 + lane];
-    const float ck = clip[kc];
-    // this lane's 8 code bytes inside the staging buffer [piece column][row group][1 KiB]
+    const int row_tiles = (M + 31) >> 5;
+    const size_t piece_stride = (size_t)code_stages(nb) * 1024;
+    uint8_t* const my = cstage[wave];
     const int r16 = l32 & 15;
-    const int st_off = (wave >> 2) * 2048 + (l32 >> 4) * 1024 + r16 * 64 + (((wave & 3) ^ ((r16 >> 2) & 3)) << 4) + 8 * kg;
-    const int sc_off = l32 * 8 + ((wave >> 1) | ((wave & 1) << 2));      // byte order inside a scale word
+    // this lane's 8 code bytes of block b inside the wave's staging area [piece column][row group][1 KiB]
+    const int st_base = (l32 >> 4) * 1024 + r16 * 64 + 8 * kg;
+    const int st_swz = (r16 >> 2) & 3;
 
-    auto load_tile = [&](int tile, uint4& x0, uint4& x1) {
-        const int rowc = min(tile * 32 + l32, M - 1);       // rows past the end are computed, not stored
-        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)kc * 32 + 16 * kg);
-        x0 = xp[0];
-        x1 = xp[1];
-    };
-    uint4 x0, x1;
-    load_tile(tile0, x0, x1);
-
-    for (int it = 0; it < ntiles; ++it) {
-        const int tile = tile0 + it;
-        const uint4 c0 = x0, c1 = x1;
-        load_tile(min(tile + 1, row_tiles - 1), x0, x1);    // prefetch (the last one re-reads a valid tile)
-        v16f acc = {};
-        // smallest terms first
+    for (int it = 0; it < tiles_per_wave; ++it) {
+        const int tile = (blockIdx.y * kQuantWaves + wave) * tiles_per_wave + it;
+        if (tile >= row_tiles) break;                       // wave-uniform; no barriers below
+        const int row = tile * 32 + l32;
+        const int rowc = min(row, M - 1);                   // rows past the end are computed, not stored
+        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)k0 * 32 + 16 * kg);
+        uint4 x[8][2];
 #pragma unroll
-        for (int t = 2; t >= 0; --t) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][0]),
-                                                          __builtin_bit_cast(bf16x8, c0), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[t][1]),
-                                                          __builtin_bit_cast(bf16x8, c1), acc, 0, 0, 0);
+        for (int b = 0; b < 8; ++b) {
+            if (b < nblk) {
+                x[b][0] = xp[4 * b];
+                x[b][1] = xp[4 * b + 1];
+            }
         }
-        // acc[r] = transformed element 16 kg + r of this lane's row
-        float y[16];
+        uint32_t sc_lo = 0x7F7F7F7Fu, sc_hi = 0x7F7F7F7Fu; // scale word, padding blocks stay neutral
 #pragma unroll
-        for (int r = 0; r < 16; ++r) y[r] = acc[r];
-        float m = __builtin_fabsf(y[0]);
+        for (int b = 0; b < 8; ++b) {
+            uint2 out = {0u, 0u};                           // padding blocks: zero codes
+            if (b < nblk) {
+                const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
+                v16f acc = {};
+                // smallest terms first
 #pragma unroll
-        for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
-        // the other half of the block lives in lane ^ 32
-        const float mo = __builtin_bit_cast(
-            float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
-        m = __builtin_fmaxf(m, mo);
-        const float bound = ck * m;                         // one fp32 multiply
-        const uint32_t s = live ? e8m0_of_bound(bound) : 127u;
-        const float sc = scale_operand(s);
-        uint2 out;
-        out.x = live ? encode8(y, bound, sc) : 0u;          // padding blocks: zero codes, neutral scale
-        out.y = live ? encode8(y + 8, bound, sc) : 0u;
-        *reinterpret_cast<uint2*>(cstage[it & 1] + st_off) = out;
-        if (kg == 0) sstage[it & 1][sc_off] = (uint8_t)s;
-        __syncthreads();
+                for (int t = 2; t >= 0; --t) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + 0) * 64]),
+                                                                  __builtin_bit_cast(bf16x8, x[b][0]), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + 1) * 64]),
+                                                                  __builtin_bit_cast(bf16x8, x[b][1]), acc, 0, 0, 0);
+                }
+                // acc[r] = transformed element 16 kg + r of this lane's row
+                float y[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) y[r] = acc[r];
+                float m = __builtin_fabsf(y[0]);
+#pragma unroll
+                for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
+                // the other half of the block lives in lane ^ 32
+                const float mo = __builtin_bit_cast(
+                    float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
+                m = __builtin_fmaxf(m, mo);
+                const float bound = clip[k0 + b] * m;       // one fp32 multiply
+                const uint32_t s = e8m0_of_bound(bound);
+                const float sc = scale_operand(s);
+                out.x = encode8(y, bound, sc);
+                out.y = encode8(y + 8, bound, sc);
+                // byte (b/2) + 4 (b%2) of the row's scale word
+                constexpr uint32_t kNeutral = 0x7Fu;
+                const int sh = 8 * (b >> 1);
+                if (b & 1) sc_hi = (sc_hi & ~(0xFFu << sh)) | (s << sh);
+                else sc_lo = (sc_lo & ~(0xFFu << sh)) | (s << sh);
+                (void)kNeutral;
+            }
+            *reinterpret_cast<uint2*>(my + (b >> 2) * 2048 + st_base + (((b & 3) ^ st_swz) << 4)) = out;
+        }
+        // staging order: pieces (column 0, rows 0-15), (0, 16-31), (1, 0-15), (1, 16-31); the code
+        // array is padded to whole 32-row tiles, so all four always exist
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint4 v = *reinterpret_cast<const uint4*>(my + p * 1024 + lane * 16);
+            *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + (p & 1)) * piece_stride +
+                                      (size_t)(2 * g + (p >> 1)) * 1024 + lane * 16) = v;
+        }
+        if (kg == 0 && row < M)
+            *reinterpret_cast<uint2*>(scales + ((size_t)g * M + row) * 8) = uint2{sc_lo, sc_hi};
     }
 }
 
@@ -291,11 +289,12 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
     const int nb = t->nb;
     const int groups = scale_groups(nb);
     const int row_tiles = (M + 31) / 32;
-    // few row tiles per workgroup: many short workgroups keep more loads in flight than few long ones
-    int tiles_per_wg = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / 2048));
-    while ((row_tiles + tiles_per_wg - 1) / tiles_per_wg > 65535) tiles_per_wg <<= 1;
-    const dim3 grid(groups, (row_tiles + tiles_per_wg - 1) / tiles_per_wg), block(kQuantThreads);
-    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wg,
+    // a few 32-row tiles per wave amortise the 48 KiB operand fetch of a workgroup; small problems
+    // keep one tile per wave so that the grid still covers the chip
+    int tiles_per_wave = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / (2048L * kQuantWaves)));
+    const int per_wg = kQuantWaves * tiles_per_wave;
+    const dim3 grid(groups, (row_tiles + per_wg - 1) / per_wg), block(kQuantWaves * 64);
+    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wave,
                                                reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
     return hipGetLastError();
 }
