@@ -201,55 +201,74 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int t
     const int g = blockIdx.x;                               // K group
     const int k0 = g * 8;
     const int nblk = min(8, nb - k0);                       // real blocks in this group (rest is padding)
-    {
-        const uint4* src = Tsplit + (size_t)k0 * (kTsplitBlock / 16);
-        uint4* dst = reinterpret_cast<uint4*>(tlds);
-        for (int i = tid; i < nblk * (kTsplitBlock / 16); i += kQuantWaves * 64) dst[i] = src[i];
-    }
-    __syncthreads();
-
     const int l32 = lane & 31, kg = lane >> 5;
     const int row_tiles = (M + 31) >> 5;
     const size_t piece_stride = (size_t)code_stages(nb) * 1024;
     uint8_t* const my = cstage[wave];
     const int r16 = l32 & 15;
-    // this lane's 8 code bytes of block b inside the wave's staging area [piece column][row group][1 KiB]
+    // this lane's 8 code bytes of a block inside the wave's staging area [piece column][row group][1 KiB]
     const int st_base = (l32 >> 4) * 1024 + r16 * 64 + 8 * kg;
     const int st_swz = (r16 >> 2) & 3;
 
-    for (int it = 0; it < tiles_per_wave; ++it) {
-        const int tile = (blockIdx.y * kQuantWaves + wave) * tiles_per_wave + it;
-        if (tile >= row_tiles) break;                       // wave-uniform; no barriers below
-        const int row = tile * 32 + l32;
-        const int rowc = min(row, M - 1);                   // rows past the end are computed, not stored
-        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)k0 * 32 + 16 * kg);
-        uint4 x[8][2];
+    // ---- per-wave work: units of (32-row tile, half K group = 4 blocks = 256 bytes per row); the
+    // next unit is loaded into a second register set while the current one is processed
+    const int wave_tile0 = (blockIdx.y * kQuantWaves + wave) * tiles_per_wave;
+    const int ntiles = max(0, min(tiles_per_wave, row_tiles - wave_tile0));
+    const int nunits = 2 * ntiles;
+    auto load_unit = [&](int u, uint4 (&x)[4][2]) {
+        const int rowc = min((wave_tile0 + (u >> 1)) * 32 + l32, M - 1);   // rows past the end: computed, not stored
+        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)(k0 + 4 * (u & 1)) * 32 + 16 * kg);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            if (b < nblk) {
+        for (int b = 0; b < 4; ++b) {
+            if (4 * (u & 1) + b < nblk) {                   // uniform
                 x[b][0] = xp[4 * b];
                 x[b][1] = xp[4 * b + 1];
             }
         }
-        uint32_t sc_lo = 0x7F7F7F7Fu, sc_hi = 0x7F7F7F7Fu; // scale word, padding blocks stay neutral
+    };
+    uint4 xc[4][2], xn[4][2];
+    if (nunits > 0) load_unit(0, xc);                       // in flight while the operands go to LDS
+    {
+        // the group's transform operands go global -> LDS with LDS-direct loads (1 KiB per wave
+        // instruction, lane i -> LDS base + 16 i), all issued back to back
+        typedef __attribute__((address_space(3))) uint8_t lds_byte;
+        const uint32_t lds_t = (uint32_t)(uintptr_t)(lds_byte*)tlds;
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(Tsplit) + (size_t)k0 * kTsplitBlock;
+        const int pieces = nblk * (kTsplitBlock / 1024);   // 6 per block
+        for (int p = wave; p < pieces; p += kQuantWaves)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :: "v"((uint32_t)(p * 1024 + lane * 16)), "s"(src), "s"(lds_t + (uint32_t)p * 1024) : "memory");
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): operands (and the first X unit) have landed
+    }
+    __syncthreads();
+
+    uint32_t sc_lo = 0x7F7F7F7Fu, sc_hi = 0x7F7F7F7Fu;     // scale word of the row; padding blocks stay neutral
+    for (int u = 0; u < nunits; ++u) {
+        const int tile = wave_tile0 + (u >> 1);
+        const int half = u & 1;
+        if (u + 1 < nunits) load_unit(u + 1, xn);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
+        for (int bb = 0; bb < 4; ++bb) {
+            const int b = 4 * half + bb;                    // block inside the K group
             uint2 out = {0u, 0u};                           // padding blocks: zero codes
             if (b < nblk) {
                 const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
-                v16f acc = {};
-                // smallest terms first
+                uint4 tfr[6];
+#pragma unroll
+                for (int i = 0; i < 6; ++i) tfr[i] = tf[i * 64];
+                // two independent accumulation chains (one per K half), smallest terms first
+                v16f acc0 = {}, acc1 = {};
 #pragma unroll
                 for (int t = 2; t >= 0; --t) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + 0) * 64]),
-                                                                  __builtin_bit_cast(bf16x8, x[b][0]), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + 1) * 64]),
-                                                                  __builtin_bit_cast(bf16x8, x[b][1]), acc, 0, 0, 0);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 0]),
+                                                                   __builtin_bit_cast(bf16x8, xc[bb][0]), acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 1]),
+                                                                   __builtin_bit_cast(bf16x8, xc[bb][1]), acc1, 0, 0, 0);
                 }
-                // acc[r] = transformed element 16 kg + r of this lane's row
+                // y[r] = transformed element 16 kg + r of this lane's row
                 float y[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) y[r] = acc[r];
+                for (int r = 0; r < 16; ++r) y[r] = acc0[r] + acc1[r];
                 float m = __builtin_fabsf(y[0]);
 #pragma unroll
                 for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
@@ -263,24 +282,32 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int t
                 out.x = encode8(y, bound, sc);
                 out.y = encode8(y + 8, bound, sc);
                 // byte (b/2) + 4 (b%2) of the row's scale word
-                constexpr uint32_t kNeutral = 0x7Fu;
                 const int sh = 8 * (b >> 1);
                 if (b & 1) sc_hi = (sc_hi & ~(0xFFu << sh)) | (s << sh);
                 else sc_lo = (sc_lo & ~(0xFFu << sh)) | (s << sh);
-                (void)kNeutral;
             }
-            *reinterpret_cast<uint2*>(my + (b >> 2) * 2048 + st_base + (((b & 3) ^ st_swz) << 4)) = out;
+            *reinterpret_cast<uint2*>(my + half * 2048 + st_base + ((bb ^ st_swz) << 4)) = out;
         }
-        // staging order: pieces (column 0, rows 0-15), (0, 16-31), (1, 0-15), (1, 16-31); the code
-        // array is padded to whole 32-row tiles, so all four always exist
+        // the two finished pieces of this half: (column `half`, rows 0-15) and (column `half`, rows 16-31);
+        // the code array is padded to whole 32-row tiles, so both always exist
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(my + p * 1024 + lane * 16);
-            *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + (p & 1)) * piece_stride +
-                                      (size_t)(2 * g + (p >> 1)) * 1024 + lane * 16) = v;
+        for (int p = 0; p < 2; ++p) {
+            const uint4 v = *reinterpret_cast<const uint4*>(my + half * 2048 + p * 1024 + lane * 16);
+            *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + p) * piece_stride + (size_t)(2 * g + half) * 1024 +
+                                      lane * 16) = v;
         }
-        if (kg == 0 && row < M)
-            *reinterpret_cast<uint2*>(scales + ((size_t)g * M + row) * 8) = uint2{sc_lo, sc_hi};
+        if (half == 1) {
+            const int row = tile * 32 + l32;
+            if (kg == 0 && row < M)
+                *reinterpret_cast<uint2*>(scales + ((size_t)g * M + row) * 8) = uint2{sc_lo, sc_hi};
+            sc_lo = 0x7F7F7F7Fu;
+            sc_hi = 0x7F7F7F7Fu;
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            xc[b][0] = xn[b][0];
+            xc[b][1] = xn[b][1];
+        }
     }
 }
 
@@ -291,7 +318,7 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
     const int row_tiles = (M + 31) / 32;
     // a few 32-row tiles per wave amortise the 48 KiB operand fetch of a workgroup; small problems
     // keep one tile per wave so that the grid still covers the chip
-    int tiles_per_wave = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / (2048L * kQuantWaves)));
+    int tiles_per_wave = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / (512L * kQuantWaves)));
     const int per_wg = kQuantWaves * tiles_per_wave;
     const dim3 grid(groups, (row_tiles + per_wg - 1) / per_wg), block(kQuantWaves * 64);
     quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wave,
