@@ -200,15 +200,16 @@ struct TiledCtx {
     const uint8_t* smem;
     int a_rd, b_rd, sc_a_rd, sc_b_rd, kg, fsw;
 
-    __device__ __forceinline__ void issue_stage(int s) const {
+    // The loads of one stage, in a fixed order: part 0..7 = the 8 code pieces of this wave (A then B),
+    // part 8 = the scales of the K group an even stage opens (4 dword loads).  Completion is counted
+    // per thread in this order.
+    __device__ __forceinline__ void issue_part(int s, int part) const {
         const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds + (uint32_t)wave * 4096;
-        const uint8_t* ag = xc + (size_t)s * 1024;          // one 1 KiB piece per 16 rows and stage
-        const uint8_t* bg = wc + (size_t)s * 1024;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dma16(ag, aoff[j], buf + j * 1024);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dma16(bg, boff[j], buf + kOperandStage + j * 1024);
-        if ((s & 1) == 0) {     // scales of the K group this even stage opens
+        if (part < 4) {
+            dma16(xc + (size_t)s * 1024, aoff[part], buf + part * 1024);        // one 1 KiB piece per 16 rows and stage
+        } else if (part < 8) {
+            dma16(wc + (size_t)s * 1024, boff[part - 4], buf + kOperandStage + (part - 4) * 1024);
+        } else if ((s & 1) == 0) {
             const int g = s >> 1;
             const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
             const uint8_t* sag = xs + (size_t)g * M * 8;
@@ -219,13 +220,18 @@ struct TiledCtx {
             for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
         }
     }
+    __device__ __forceinline__ void issue_stage(int s) const {
+#pragma unroll
+        for (int part = 0; part < 9; ++part) issue_part(s, part);
+    }
     __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[4], uint4 (&fb)[4]) const {
         const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
+        // in the order the matrix instructions consume them: a0, b0..b3, a1..a3
+        fa[0] = *reinterpret_cast<const uint4*>(base + a_rd);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
-            fb[i] = *reinterpret_cast<const uint4*>(base + b_rd + i * 32 * kStageBytes);
-        }
+        for (int i = 0; i < 4; ++i) fb[i] = *reinterpret_cast<const uint4*>(base + b_rd + i * 32 * kStageBytes);
+#pragma unroll
+        for (int i = 1; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
     }
     __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[4]) const {
         const uint8_t* sp = smem + kRing * kStageLds + (g & 1) * kScaleGroupLds;
@@ -270,16 +276,24 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
         // have also seen stage s+1 land, the slot of stage s can be refilled
         wait_vmcnt<WAIT>();
         __syncthreads();
-        if constexpr (ISSUE) c.issue_stage(s + 4);
         c.read_frags(s + 1, 0, a0, b0);
         if constexpr (PAR == 1) c.read_scales((s + 1) >> 1, sna, snb);
     }
     __builtin_amdgcn_sched_barrier(0);
-    // second half, part two: covers the latency of the reads just issued
+    // second half, part two: covers the latency of the reads just issued; the loads of stage s+4
+    // are issued one between every two matrix instructions, so the matrix pipe never waits for them
 #pragma unroll
     for (int i = 2; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+        for (int j = 0; j < 4; ++j) {
+            mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+            if constexpr (WAIT >= 0 && ISSUE) {
+                __builtin_amdgcn_sched_barrier(0);
+                c.issue_part(s + 4, (i - 2) * 4 + j);
+                if (i == 3 && j == 3) c.issue_part(s + 4, 8);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     if constexpr (WAIT >= 0 && PAR == 1) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -387,6 +401,14 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
             __syncthreads();                                  // every wave is done with the stage ring
             uint8_t* ep = smem + wave * 32768;                // wave-private [128 rows][256 bytes]
             const int odd = lane & 1;
+            // Element (i, j, rr) of this lane goes to row R = 32 i + 8 (rr / 2) + 2 (rr % 2) + (4 kg + odd)
+            // and 16-byte chunk (4 j + l32 / 8) ^ swizzle(R); the swizzle only depends on the lane
+            // (R & 1 = odd, (R >> 2) & 1 = kg), so it folds into four per-lane base pointers, one per j,
+            // and everything else is an immediate offset.
+            uint8_t* pj[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pj[j] = ep + (4 * kg + odd) * 256 + ((4 * (j ^ (odd | (kg << 1))) + (l32 >> 3)) << 4) + ((l32 >> 1) & 3) * 4;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -402,10 +424,7 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
                         pr.x = odd ? recv : v0;
                         pr.y = odd ? v1 : recv;
                         const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-                        const int R = 32 * i + 8 * (rr >> 1) + 4 * kg + 2 * (rr & 1) + odd;
-                        int chunk = 4 * j + (l32 >> 3);
-                        chunk ^= ((R & 1) << 2) | (((R >> 2) & 1) << 3);      // spread the four row groups over the banks
-                        *reinterpret_cast<uint32_t*>(ep + R * 256 + chunk * 16 + ((l32 >> 1) & 3) * 4) = packed;
+                        *reinterpret_cast<uint32_t*>(pj[j] + (32 * i + 8 * (rr >> 1) + 2 * (rr & 1)) * 256) = packed;
                     }
             // wave-private region: the wave's own LDS operations complete in order
             const int rsub = lane >> 4, c16 = lane & 15;
