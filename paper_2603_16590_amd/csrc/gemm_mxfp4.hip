@@ -129,38 +129,61 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 }
 
 // ------------------------------------------------------------------------------------------
-// Tiled kernel.  256x256 output tile per workgroup of 4 waves (2x2, each wave 128x128 = 4x4
-// matrix tiles in 256 accumulator registers).  K advances in stages of 128 elements (64 code
-// bytes per row).  Codes and scales go global -> LDS with LDS-direct loads (no VGPR staging,
-// no ds_write): a ring of 4 stage buffers keeps three stages in flight.  Scales of a whole
-// 256-element K group (two stages) are fetched once per group into a 2-deep ring.
-constexpr int kTile = 256;                 // output tile edge
+// Tiled kernel.  Persistent workgroups of 4 waves, one per compute unit.  An output tile is
+// 256 rows by 64 NJ columns (NJ = 1..4 "strips" of 64 columns); the waves sit 2x2 on it, each
+// holding 4 x NJ matrix tiles (128 x 32 NJ outputs) in up to 256 accumulator registers.
+// K advances in stages of 128 elements (64 code bytes per row).  Codes and scales go
+// global -> LDS with LDS-direct loads (no VGPR staging, no ds_write): a ring of 4 stage
+// buffers keeps three stages in flight.  Scales of a whole 256-element K group (two stages)
+// are fetched once per group into a 2-deep ring.
+//
+// Work split: the strips of all row panels are put in one linear order (column bands, inside
+// a band row panel by row panel) and every workgroup takes an equal contiguous share of it,
+// which it cuts into tiles of at most 4 strips.  Workgroups go to the 8 XCDs round-robin, so
+// workgroup b works on share (b % 8) * (workgroups / 8) + b / 8: the shares of one XCD are
+// contiguous and its L2 sees a compact block of the output.
+constexpr int kTile = 256;                 // tile rows
+constexpr int kStrip = 64;                 // tile columns come in strips of 64
 constexpr int kStageBytes = 64;            // code bytes per row per stage (128 elements, 4 MX blocks)
 constexpr int kOperandStage = kTile * kStageBytes;        // 16 KiB per operand per stage
 constexpr int kStageLds = 2 * kOperandStage;               // A then B
 constexpr int kRing = 4;                   // stage buffers
 constexpr int kScaleGroupLds = 2 * kTile * 8;              // A then B scale bytes of one K group (4 KiB)
-constexpr int kTiledLds = kRing * kStageLds + 2 * kScaleGroupLds;   // 136 KiB
+constexpr int kEpilogueWaveLds = 16 * 256;                 // per wave: 16 output rows x 256 bytes
+constexpr int kEpilogueLds0 = kRing * kStageLds + 2 * kScaleGroupLds;
+constexpr int kTiledLds = kEpilogueLds0 + 4 * kEpilogueWaveLds;     // 152 KiB
 
 // 16-byte slot swizzle inside a 64-byte LDS row: the 32 rows a fragment read touches, and the
 // 16 rows x 4 slots an LDS-direct load writes, both spread over all banks.
 __device__ __forceinline__ int slot_swizzle(int row) { return (row >> 2) & 3; }
 
-// Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of tile
-// ids, and order tile ids in bands of kBand tile-rows so that the range is a compact sub-grid.
-__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
-    const int T = tiles_m * tiles_n;
-    const int q = T >> 3, rem = T & 7;
-    const int xcd = pid & 7, local = pid >> 3;
-    int id = xcd * q + min(xcd, rem) + local;
-    constexpr int kBand = 4;
-    const int per_band = kBand * tiles_n;
-    const int band = id / per_band;
-    const int first_m = band * kBand;
-    const int rows_in_band = min(kBand, tiles_m - first_m);
-    id -= band * per_band;
-    tm = first_m + id % rows_in_band;
-    tn = id / rows_in_band;
+struct TilePlan {
+    int tiles_m;      // row panels of 256
+    int strips_n;     // column strips of 64
+    int bands;        // column bands (1, 2, 4 or 8)
+    int workers;      // workgroups launched, a multiple of 8
+};
+
+struct Tile {
+    int m0, n0, nj;
+};
+
+// Takes the next tile off the share [cur, end) of the linear strip order.
+__device__ __forceinline__ bool next_tile(const TilePlan& pl, int& cur, int end, Tile& t) {
+    if (cur >= end) return false;
+    int b = 0;
+    while (b + 1 < pl.bands && cur >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
+    const int bs = b * pl.strips_n / pl.bands, be = (b + 1) * pl.strips_n / pl.bands;
+    const int width = be - bs;
+    const int local = cur - pl.tiles_m * bs;
+    const int p = local / width, sl = local - p * width;
+    const int run = min(end - cur, width - sl);          // strips left in this row panel of the band
+    const int nt = (run + 3) >> 2;                        // tiles the run is cut into, near-equal widths
+    t.nj = (run + nt - 1) / nt;
+    t.m0 = p * kTile;
+    t.n0 = (bs + sl) * kStrip;
+    cur += t.nj;
+    return true;
 }
 
 // LDS-direct loads: lane i of the wave writes its 16 (4) bytes at LDS address m0 + 16 i (4 i).
@@ -176,13 +199,17 @@ __device__ __forceinline__ void dma4(const void* gbase, uint32_t voff, uint32_t 
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at their maxima), gfx9 encoding.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// One matrix instruction of the 4x4 grid of 32x32 tiles a wave owns.
-template <int KK>
+// One matrix instruction of the grid of 32x32 tiles a wave owns; ZERO starts the accumulation.
+template <int KK, bool ZERO>
 __device__ __forceinline__ void mfma_one(v16f& acc, const uint4& a, const uint4& b, int sa, int sb) {
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, KK, sa, KK, sb);
+    if constexpr (ZERO)
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), v16f{}, 4, 4, KK, sa, KK, sb);
+    else
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, KK, sa, KK, sb);
 }
 
 // Scheduling hints: keep the instruction order written below (the wave runs alone on its
@@ -195,267 +222,381 @@ struct TiledCtx {
     const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
     uint32_t aoff[4], boff[4], sao[2], sbo[2];
     uint32_t lds0, lds_sc;
-    int M, N, wave;
+    int M, N, T, wave, lane;
     // LDS -> registers
     const uint8_t* smem;
     int a_rd, b_rd, sc_a_rd, sc_b_rd, kg, fsw;
 
-    // The loads of one stage, in a fixed order: part 0..7 = the 8 code pieces of this wave (A then B),
-    // part 8 = the scales of the K group an even stage opens (4 dword loads).  Completion is counted
-    // per thread in this order.
-    __device__ __forceinline__ void issue_part(int s, int part) const {
-        const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds + (uint32_t)wave * 4096;
-        if (part < 4) {
-            dma16(xc + (size_t)s * 1024, aoff[part], buf + part * 1024);        // one 1 KiB piece per 16 rows and stage
-        } else if (part < 8) {
-            dma16(wc + (size_t)s * 1024, boff[part - 4], buf + kOperandStage + (part - 4) * 1024);
-        } else if ((s & 1) == 0) {
-            const int g = s >> 1;
-            const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
-            const uint8_t* sag = xs + (size_t)g * M * 8;
-            const uint8_t* sbg = ws + (size_t)g * N * 8;
+    // Per-lane load offsets of a tile.  Wave w, load j copies the 1 KiB piece of row group
+    // (tile row / 16 + 4 w + j) of A, and (tile column / 16 + nj w + j) of B, into LDS rows
+    // 16 (4 w + j) .. + 15 (16 (nj w + j) ..) of a stage buffer; the blocked code layout already is
+    // the swizzled LDS image, so lane i just moves bytes 16 i .. 16 i + 15.  Row groups past the
+    // edge are clamped to the last one (their results are never stored).
+    __device__ __forceinline__ void aim(const Tile& t) {
+        const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
+        for (int j = 0; j < 4; ++j) {
+            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
+            boff[j] = (uint32_t)min((t.n0 >> 4) + t.nj * wave + j, rgB - 1) * (uint32_t)(T * 1024) + lane * 16;
+        }
+        // scales: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords 128 w .. 128 w + 127
+        // of each (two pieces of 64).  B rows beyond the tile's 64 nj are fetched and not used.
 #pragma unroll
-            for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
+        for (int j = 0; j < 2; ++j) {
+            const int d = 128 * wave + 64 * j + lane;
+            sao[j] = ((uint32_t)min(t.m0 + (d >> 1), M - 1) * 2 + (d & 1)) * 4;
+            sbo[j] = ((uint32_t)min(t.n0 + (d >> 1), N - 1) * 2 + (d & 1)) * 4;
         }
     }
-    __device__ __forceinline__ void issue_stage(int s) const {
+    // The loads of one stage, in a fixed order: parts 0..3 = this wave's 4 A pieces, parts 4..4+nj-1
+    // its nj B pieces, part 4+nj = the scales of the K group an even stage opens (4 dword loads).
+    // Completion is counted per thread in this order.
+    __device__ __forceinline__ void issue_scales(int s) const {
+        const int g = s >> 1;
+        const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
+        const uint8_t* sag = xs + (size_t)g * M * 8;
+        const uint8_t* sbg = ws + (size_t)g * N * 8;
 #pragma unroll
-        for (int part = 0; part < 9; ++part) issue_part(s, part);
+        for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
     }
-    __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[4], uint4 (&fb)[4]) const {
+    template <int PART>
+    __device__ __forceinline__ void issue_part(int s, int nj, bool even) const {
+        const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds;
+        if constexpr (PART < 4) {
+            dma16(xc + (size_t)s * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
+        } else {
+            if (PART < 4 + nj)
+                dma16(wc + (size_t)s * 1024, boff[(PART - 4) & 3], buf + kOperandStage + (uint32_t)(nj * wave + PART - 4) * 1024);
+            else if (PART == 4 + nj && even)
+                issue_scales(s);
+        }
+    }
+    // First stages of a tile (all ring slots must be free): 4 + nj loads each, 4 more on even stages.
+    __device__ __forceinline__ void issue_prologue(int nj) const {
+        const int n = T < kRing ? T : kRing;
+        for (int s = 0; s < n; ++s) {
+            issue_part<0>(s, nj, false);
+            issue_part<1>(s, nj, false);
+            issue_part<2>(s, nj, false);
+            issue_part<3>(s, nj, false);
+            issue_part<4>(s, nj, false);
+            if (nj > 1) issue_part<5>(s, nj, false);
+            if (nj > 2) issue_part<6>(s, nj, false);
+            if (nj > 3) issue_part<7>(s, nj, false);
+            if ((s & 1) == 0) issue_scales(s);
+        }
+    }
+    // Where this lane reads its fragments and scales from: row (wave row base + 32 i + l32),
+    // slot ((2 half + kg) ^ f(row)).
+    __device__ __forceinline__ void aim_reads(int nj, int wm, int wn, int l32) {
+        a_rd = (wm * 128 + l32) * kStageBytes;
+        b_rd = kOperandStage + (wn * 32 * nj + l32) * kStageBytes;
+        sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
+        sc_b_rd = kTile * 8 + ((wn * 32 * nj + l32) * 2 + kg) * 4;
+    }
+    // in the order the matrix instructions consume them: a0, b0.., a1..a3
+    template <int NJ>
+    __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[4], uint4 (&fb)[NJ]) const {
         const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
-        // in the order the matrix instructions consume them: a0, b0..b3, a1..a3
         fa[0] = *reinterpret_cast<const uint4*>(base + a_rd);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fb[i] = *reinterpret_cast<const uint4*>(base + b_rd + i * 32 * kStageBytes);
+        for (int j = 0; j < NJ; ++j) fb[j] = *reinterpret_cast<const uint4*>(base + b_rd + j * 32 * kStageBytes);
 #pragma unroll
         for (int i = 1; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
     }
-    __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[4]) const {
+    template <int NJ>
+    __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[NJ]) const {
         const uint8_t* sp = smem + kRing * kStageLds + (g & 1) * kScaleGroupLds;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
-            sb[i] = *reinterpret_cast<const int*>(sp + sc_b_rd + i * 256);
-        }
+        for (int i = 0; i < 4; ++i) sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sb[j] = *reinterpret_cast<const int*>(sp + sc_b_rd + j * 256);
     }
 };
 
+// Loads [P0, P1) of stage s, in the fixed order (NJ static).
+template <int NJ, bool EVEN, int P0, int P1>
+__device__ __forceinline__ void issue_range(const TiledCtx& c, int s) {
+    if constexpr (P0 < P1) {
+        if constexpr (P0 < 4 + NJ) c.issue_part<P0>(s, NJ, false);
+        else if constexpr (EVEN) c.issue_scales(s);
+        issue_range<NJ, EVEN, P0 + 1, P1>(c, s);
+    }
+}
+
+// Matrix instructions Q .. 2 NJ - 1 of the last quarter of a stage (tile rows 2 and 3 of the second
+// K step), each followed by its share of the 5 + NJ load parts of stage s+4.
+template <int NJ, int PAR, bool DO_ISSUE, int Q>
+__device__ __forceinline__ void stage_part_two(const TiledCtx& c, int s, v16f (&acc)[4][NJ], const uint4 (&a1)[4],
+                                               const uint4 (&b1)[NJ], const int (&sa)[4], const int (&sb)[NJ]) {
+    if constexpr (Q < 2 * NJ) {
+        constexpr int i = 2 + Q / NJ, j = Q % NJ;
+        constexpr int kParts = 5 + NJ, kSlots = 2 * NJ;
+        mfma_one<2 * PAR + 1, false>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+        if constexpr (DO_ISSUE) {
+            __builtin_amdgcn_sched_barrier(0);
+            issue_range<NJ, PAR == 0, Q * kParts / kSlots, (Q + 1) * kParts / kSlots>(c, s + 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage_part_two<NJ, PAR, DO_ISSUE, Q + 1>(c, s, acc, a1, b1, sa, sb);
+    }
+}
+
 // One K stage (two matrix-instruction K steps) of the software pipeline.
+//   NJ     32-column matrix tiles per wave
 //   PAR    parity of the stage inside its K group (selects the scale bytes: op_sel 2 PAR, 2 PAR + 1)
 //   WAIT   loads that may stay in flight once stage s+1 has landed (-1: there is no stage s+1)
 //   ISSUE  start the loads of stage s+4 into the ring slot this stage frees
-// On entry f0 holds the fragments of (s, first half); on exit those of (s+1, first half).
-template <int PAR, int WAIT, bool ISSUE>
-__device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc)[4][4], uint4 (&a0)[4],
-                                            uint4 (&b0)[4], int (&sa)[4], int (&sb)[4]) {
-    uint4 a1[4], b1[4];
-    // first half: fetch the second half's fragments underneath the 16 matrix instructions
-    c.read_frags(s, 1, a1, b1);
+//   FIRST  first stage of a tile: its first K step starts the accumulators from zero
+// On entry a0/b0 hold the fragments of (s, first half); on exit those of (s+1, first half).
+template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+__device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a0)[4],
+                                            uint4 (&b0)[NJ], int (&sa)[4], int (&sb)[NJ]) {
+    uint4 a1[4], b1[NJ];
+    // first half: fetch the second half's fragments underneath its matrix instructions
+    c.read_frags<NJ>(s, 1, a1, b1);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR>(acc[i][j], a0[i], b0[j], sa[i], sb[j]);
+        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR, FIRST>(acc[i][j], a0[i], b0[j], sa[i], sb[j]);
+    if constexpr (NJ == 4) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        BATQ_SCHED_DSRD(1);
-        BATQ_SCHED_MFMA(2);
+        for (int i = 0; i < 8; ++i) {
+            BATQ_SCHED_DSRD(1);
+            BATQ_SCHED_MFMA(2);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4 + NJ; ++i) {
+            BATQ_SCHED_DSRD(1);
+            BATQ_SCHED_MFMA(1);
+        }
+        if constexpr (4 * NJ > 4 + NJ) BATQ_SCHED_MFMA(4 * NJ - (4 + NJ));
     }
     // second half, part one
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
-    BATQ_SCHED_MFMA(8);
+        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR + 1, false>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
+    BATQ_SCHED_MFMA(2 * NJ);
     __builtin_amdgcn_sched_barrier(0);
-    int sna[4], snb[4];
+    int sna[4], snb[NJ];
     if constexpr (WAIT >= 0) {
         // every wave has read stage s completely (its last fragments are in registers); once all
         // have also seen stage s+1 land, the slot of stage s can be refilled
         wait_vmcnt<WAIT>();
         __syncthreads();
-        c.read_frags(s + 1, 0, a0, b0);
-        if constexpr (PAR == 1) c.read_scales((s + 1) >> 1, sna, snb);
+        c.read_frags<NJ>(s + 1, 0, a0, b0);
+        if constexpr (PAR == 1) c.read_scales<NJ>((s + 1) >> 1, sna, snb);
     }
     __builtin_amdgcn_sched_barrier(0);
     // second half, part two: covers the latency of the reads just issued; the loads of stage s+4
-    // are issued one between every two matrix instructions, so the matrix pipe never waits for them
-#pragma unroll
-    for (int i = 2; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            mfma_one<2 * PAR + 1>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
-            if constexpr (WAIT >= 0 && ISSUE) {
-                __builtin_amdgcn_sched_barrier(0);
-                c.issue_part(s + 4, (i - 2) * 4 + j);
-                if (i == 3 && j == 3) c.issue_part(s + 4, 8);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+    // are issued between the matrix instructions, so the matrix pipe never waits for them
+    stage_part_two<NJ, PAR, (WAIT >= 0 && ISSUE), 0>(c, s, acc, a1, b1, sa, sb);
     if constexpr (WAIT >= 0 && PAR == 1) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sa[i] = sna[i];
-            sb[i] = snb[i];
-        }
+        for (int i = 0; i < 4; ++i) sa[i] = sna[i];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sb[j] = snb[j];
     }
 }
 
-// Requires operand code arrays below 2 GiB (32-bit load offsets).
-template <typename YT>
-__global__ void __launch_bounds__(256, 1)
-gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
-           const uint8_t* __restrict__ ws, int M, int N, int nb, int tiles_m, int tiles_n,
-           YT* __restrict__ Y, int64_t ldy) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    typedef __attribute__((address_space(3))) uint8_t lds_byte;
-
-    int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int m0 = tm * kTile, n0 = tn * kTile;
-
-    const int t = threadIdx.x, lane = t & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+// One output tile: on entry the loads of its first stages are in flight (issue_prologue); before
+// the epilogue the loads of the next tile's first stages are started, so they run underneath it.
+template <int NJ, typename YT>
+__device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_next, const Tile& next,
+                                         YT* __restrict__ Y, int64_t ldy) {
+    const int lane = c.lane, wave = c.wave;
     const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, kg = lane >> 5;
-    const int G = (nb + 7) >> 3;            // K groups of 256 elements (K is zero-padded to them)
-    const int T = 2 * G;                    // stages of 128 K elements
+    const int T = c.T, G = T >> 1;
+    c.aim_reads(NJ, wm, wn, lane & 31);
 
-    TiledCtx c;
-    c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
-    c.M = M; c.N = N; c.wave = wave; c.smem = smem;
-    c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;            // LDS byte address of the stage ring
-    c.lds_sc = c.lds0 + kRing * kStageLds;                    // scale ring
-    {
-        // LDS-direct tile loads: wave w, load j (0..3) copies the 1 KiB piece of row group
-        // (tile row / 16 + 4 w + j) into LDS rows 16 (4 w + j) .. + 15 of a stage buffer; the blocked
-        // code layout already is the swizzled LDS image, so lane i just moves bytes 16 i .. 16 i + 15.
-        const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int rg = 4 * wave + j;
-            c.aoff[j] = (uint32_t)min((m0 >> 4) + rg, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
-            c.boff[j] = (uint32_t)min((n0 >> 4) + rg, rgB - 1) * (uint32_t)(T * 1024) + lane * 16;
-        }
-        // LDS-direct scale loads: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords
-        // 128 w .. 128 w + 127 of each (two pieces of 64).
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int d = 128 * wave + 64 * j + lane;
-            c.sao[j] = ((uint32_t)min(m0 + (d >> 1), M - 1) * 2 + (d & 1)) * 4;
-            c.sbo[j] = ((uint32_t)min(n0 + (d >> 1), N - 1) * 2 + (d & 1)) * 4;
-        }
-    }
-    // fragment reads: lane reads slot ((2 half + kg) ^ f(row)) of row (wave row base + 32 i + l32)
-    c.kg = kg;
-    c.fsw = slot_swizzle(l32);
-    c.a_rd = (wm * 128 + l32) * kStageBytes;
-    c.b_rd = kOperandStage + (wn * 128 + l32) * kStageBytes;
-    c.sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
-    c.sc_b_rd = kTile * 8 + ((wn * 128 + l32) * 2 + kg) * 4;
+    v16f acc[4][NJ];
+    uint4 fa[4], fb[NJ];
+    int sa[4], sb[NJ];
 
-    v16f acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = v16f{};
-    uint4 fa[4], fb[4];
-    int sa[4], sb[4];
-
-    // Loads per thread: 8 per stage, plus 4 for the scales of a K group issued right after the
+    // Loads per thread: 4 + NJ per stage, plus 4 for the scales of a K group issued with the
     // group's even stage; they complete in issue order.  In steady state stages s+2 and s+3
-    // (8 + 8 + 4 = 20 loads) stay in flight while stage s+1 is awaited.
-    c.issue_stage(0);
-    c.issue_stage(1);
-    if (T >= 4) {
-        c.issue_stage(2);
-        c.issue_stage(3);
-        wait_vmcnt<28>();
-    } else {
-        wait_vmcnt<8>();
-    }
+    // (12 + 2 NJ loads) stay in flight while stage s+1 is awaited.  Stores of the previous tile
+    // that are still pending only make a wait longer than needed.
+    constexpr int kOdd = 4 + NJ, kSteady = 12 + 2 * NJ;
+    if (T >= 4) wait_vmcnt<kSteady + kOdd>();
+    else wait_vmcnt<kOdd>();
     __syncthreads();
-    c.read_scales(0, sa, sb);
-    c.read_frags(0, 0, fa, fb);
+    c.read_scales<NJ>(0, sa, sb);
+    c.read_frags<NJ>(0, 0, fa, fb);
 
-    for (int g = 0; g + 2 < G; ++g) {
-        tiled_stage<0, 20, true>(c, 2 * g, acc, fa, fb, sa, sb);
-        tiled_stage<1, 20, true>(c, 2 * g + 1, acc, fa, fb, sa, sb);
+    if (G >= 3) {
+        tiled_stage<NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
+        for (int g = 1; g + 2 < G; ++g) {
+            tiled_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
+            tiled_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = v16f{};
     }
     if (G >= 2) {
-        tiled_stage<0, 20, false>(c, T - 4, acc, fa, fb, sa, sb);
-        tiled_stage<1, 8, false>(c, T - 3, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 1, kOdd, false, false>(c, T - 3, acc, fa, fb, sa, sb);
     }
-    tiled_stage<0, 0, false>(c, T - 2, acc, fa, fb, sa, sb);
-    tiled_stage<1, -1, false>(c, T - 1, acc, fa, fb, sa, sb);
+    tiled_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
+    tiled_stage<NJ, 1, -1, false, false>(c, T - 1, acc, fa, fb, sa, sb);
+
+    __syncthreads();                                      // every wave is done with the stage ring
+    if (has_next) {
+        c.aim(next);
+        c.issue_prologue(next.nj);
+    }
 
     // ---- epilogue: accumulators -> Y
+    // (lane-derived addresses are recomputed per tile rather than kept in registers across the main loop)
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int m0 = t.m0, n0 = t.n0;
     if constexpr (sizeof(YT) == 2) {
-        // bf16: transpose through LDS so that every lane stores 16 contiguous bytes.
-        // Needs the whole 256-column span inside N and 16-byte aligned rows (workgroup-uniform).
-        const bool fast = n0 + kTile <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+        // bf16: transpose through a wave-private LDS buffer so that every lane stores 16 contiguous
+        // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
+        const bool fast = n0 + kStrip * NJ <= c.N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
         if (fast) {
-            __syncthreads();                                  // every wave is done with the stage ring
-            uint8_t* ep = smem + wave * 32768;                // wave-private [128 rows][256 bytes]
-            const int odd = lane & 1;
-            // Element (i, j, rr) of this lane goes to row R = 32 i + 8 (rr / 2) + 2 (rr % 2) + (4 kg + odd)
-            // and 16-byte chunk (4 j + l32 / 8) ^ swizzle(R); the swizzle only depends on the lane
-            // (R & 1 = odd, (R >> 2) & 1 = kg), so it folds into four per-lane base pointers, one per j,
-            // and everything else is an immediate offset.
-            uint8_t* pj[4];
+            uint8_t* ep = const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds;   // [16 rows][256 bytes]
+            const int odd = lane_e & 1, l32 = lane_e & 31, kg = lane_e >> 5;
+            // Lanes pair up: from its two packed values (rows r, r+1 of its column) and the neighbour's,
+            // the even lane assembles row r and the odd lane row r+1 of the column pair.
+            const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+            // Value pair (j, u) of a 16-row block goes to block row 8 (u / 2) + 2 (u % 2) + (4 kg + odd) and
+            // 16-byte chunk (4 j + l32 / 8) ^ swizzle(row); the swizzle only depends on the lane
+            // (row & 1 = odd, (row >> 2) & 1 = kg), so it folds into per-lane base pointers, one per j.
+            uint8_t* pj[NJ];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
                 pj[j] = ep + (4 * kg + odd) * 256 + ((4 * (j ^ (odd | (kg << 1))) + (l32 >> 3)) << 4) + ((l32 >> 1) & 3) * 4;
+            // read-back: one instruction covers kRows rows of 4 NJ 16-byte units (NJ = 3 leaves lanes
+            // 48..63 idle); row pointers advance by additions only
+            constexpr int kUnits = 4 * NJ, kRows = NJ == 3 ? 4 : 64 / kUnits;
+            const int rl = lane_e / kUnits, unit = lane_e % kUnits;
+            const bool lane_on = NJ != 3 || lane_e < 48;
+            int row = m0 + wm * 128 + rl;
+            YT* yrow = Y + (size_t)row * ldy + n0 + wn * 32 * NJ + unit * 8;
+            const int64_t ystep = (int64_t)kRows * ldy;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int h = 0; h < 2; ++h) {
 #pragma unroll
-                    for (int rr = 0; rr < 8; ++rr) {
-                        // lanes pair up: the even lane keeps row r0 and both columns, the odd lane row r0 + 1
-                        const float v0 = acc[i][j][2 * rr], v1 = acc[i][j][2 * rr + 1];
-                        const float send = odd ? v0 : v1;
-                        const float recv = __builtin_bit_cast(
-                            float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
-                        f32x2 pr;
-                        pr.x = odd ? recv : v0;
-                        pr.y = odd ? v1 : recv;
-                        const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-                        *reinterpret_cast<uint32_t*>(pj[j] + (32 * i + 8 * (rr >> 1) + 2 * (rr & 1)) * 256) = packed;
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            f32x2 pr;
+                            pr.x = acc[i][j][8 * h + 2 * u];
+                            pr.y = acc[i][j][8 * h + 2 * u + 1];
+                            const int mine = __builtin_bit_cast(int, __builtin_convertvector(pr, bf16x2));
+                            const int theirs = __builtin_amdgcn_mov_dpp(mine, 0xB1, 0xF, 0xF, true);
+                            *reinterpret_cast<uint32_t*>(pj[j] + (8 * (u >> 1) + 2 * (u & 1)) * 256) =
+                                __builtin_amdgcn_perm((uint32_t)theirs, (uint32_t)mine, sel);
+                        }
+                    // wave-private buffer: the wave's own LDS operations complete in order
+#pragma unroll
+                    for (int it = 0; it < 16 / kRows; ++it) {
+                        const int R = it * kRows + rl;
+                        const int chunk = unit ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
+                        const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
+                        if (lane_on && row < c.M) *reinterpret_cast<uint4*>(yrow) = v;
+                        row += kRows;
+                        yrow += ystep;
                     }
-            // wave-private region: the wave's own LDS operations complete in order
-            const int rsub = lane >> 4, c16 = lane & 15;
-#pragma unroll 4
-            for (int it = 0; it < 32; ++it) {
-                const int R = 4 * it + rsub;
-                const int chunk = c16 ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
-                const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
-                const int row = m0 + wm * 128 + R;
-                if (row < M)
-                    *reinterpret_cast<uint4*>(Y + (size_t)row * ldy + n0 + wn * 128 + c16 * 8) = v;
-            }
+                }
             return;
         }
     }
-    const int col0 = n0 + wn * 128 + l32;
+    // general path: element-wise stores with edge checks; rows visited in increasing order per lane
+    const int col0 = n0 + wn * 32 * NJ + (lane_e & 31);
+    int row = m0 + wm * 128 + 4 * (lane_e >> 5);
+    YT* yp = Y + (size_t)row * ldy + col0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 128 + 32 * i + 8 * (r >> 2) + 4 * kg + (r & 3);
-            if (row < M) {
-                YT* yp = Y + (size_t)row * ldy;
+        for (int q = 0; q < 4; ++q) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int col = col0 + 32 * j;
-                    if (col < N) store_y<YT>(yp + col, acc[i][j][r]);
+            for (int r = 0; r < 4; ++r) {
+                if (row < c.M) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        if (col0 + 32 * j < c.N) store_y<YT>(yp + 32 * j, acc[i][j][4 * q + r]);
                 }
+                ++row;
+                yp += ldy;
             }
+            row += 4;
+            yp += 4 * ldy;
+        }
+}
+
+// Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
+template <typename YT>
+__global__ void __launch_bounds__(256, 1)
+gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
+           const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    // this workgroup's share of the linear strip order
+    const int per_xcd = pl.workers >> 3;
+    const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n;
+    int cur = (int)(total * share / pl.workers);
+    const int end = (int)(total * (share + 1) / pl.workers);
+
+    Tile t, next;
+    if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
+
+    const int lane = threadIdx.x & 63;
+    TiledCtx c;
+    c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
+    c.M = M; c.N = N; c.smem = smem;
+    c.T = 2 * ((nb + 7) >> 3);                                // stages of 128 K elements (K zero-padded to 256)
+    c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    c.lane = lane;
+    c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;            // LDS byte address of the stage ring
+    c.lds_sc = c.lds0 + kRing * kStageLds;                    // scale ring
+    c.kg = lane >> 5;
+    c.fsw = slot_swizzle(lane & 31);
+
+    c.aim(t);
+    c.issue_prologue(t.nj);
+    for (;;) {
+        const bool has_next = next_tile(pl, cur, end, next);
+        switch (t.nj) {
+            case 4: run_tile<4, YT>(c, t, has_next, next, Y, ldy); break;
+            case 3: run_tile<3, YT>(c, t, has_next, next, Y, ldy); break;
+            case 2: run_tile<2, YT>(c, t, has_next, next, Y, ldy); break;
+            default: run_tile<1, YT>(c, t, has_next, next, Y, ldy); break;
+        }
+        if (!has_next) break;
+        t = next;
+    }
+}
+
+// Column bands: with b bands an XCD's block spans 1/b of N and b/8 of M, so the bytes all XCDs
+// pull through their L2s are proportional to b M + (8 / b) N; take the b that minimises it.
+int choose_bands(int M, int N, int strips_n) {
+    int best = 1;
+    double best_cost = 1e300;
+    for (int b = 1; b <= 8; b *= 2) {
+        if (b > strips_n) break;
+        const double cost = (double)b * M + (8.0 / b) * N;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = b;
         }
     }
+    return best;
 }
 
 template <typename YT>
@@ -471,9 +612,17 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        const int tiles_m = (M + kTile - 1) / kTile, tiles_n = (N + kTile - 1) / kTile;
-        gemm_tiled<YT><<<dim3(tiles_m * tiles_n), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
-                                                                                   N, nb, tiles_m, tiles_n, Y, ldy);
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        TilePlan pl;
+        pl.tiles_m = (M + kTile - 1) / kTile;
+        pl.strips_n = (N + kStrip - 1) / kStrip;
+        pl.bands = choose_bands(M, N, pl.strips_n);
+        pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
+        gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb,
+                                                                            pl, Y, ldy);
     } else {
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
         gemm_direct<YT><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);

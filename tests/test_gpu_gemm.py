@@ -83,6 +83,33 @@ def test_small_shapes_random_codes(B, M, K, N):
     assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol)
 
 
+@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
+def test_tile_schedule_shapes(B, M, K, N):
+    """Shapes that give the persistent workgroups of the tiled kernel several tiles each, of every
+    width (64 .. 256 columns), with ragged last row panels and column strips, 2 to 10 K stages and
+    every column-band count; every output element is checked."""
+    import torch
+    rng = np.random.default_rng(M + K + N)
+    xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
+    wc, ws, dwc, dws = _rand_q(rng, N, K, lo=122, hi=132)
+    wh = B.batq_weight_import(dwc, dws, K, N)
+    ref = o.gemm(xc, xs, wc, ws)
+    dxc_b, dxs_g = _xc(xc), _xs(xs)
+    Y = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
+    torch.cuda.synchronize()
+    got = y_to_f32(Y)
+    tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
+    bad = np.argwhere(np.abs(got - ref) > tol + 1e-30)
+    assert bad.size == 0, f"{len(bad)} wrong elements, first at {bad[0]}"
+    Yb = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.bfloat16)
+    torch.cuda.synchronize()
+    refb = o.bf16_round(ref).astype(np.float64)
+    gotb = y_to_f32(Yb).astype(np.float64)
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+    bad = np.argwhere(np.abs(gotb - refb) > ulp * 1.0001 + tol)
+    assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
+
+
 def test_extreme_scales(B):
     import torch
     rng = np.random.default_rng(5)
