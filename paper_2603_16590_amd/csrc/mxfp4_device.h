@@ -19,21 +19,24 @@ __device__ __forceinline__ uint32_t e8m0_of_bound(float bound) {
 // E8M0 byte (a field of 0 is read as 2^-127).
 __device__ __forceinline__ float scale_operand(uint32_t e8m0) { return __uint_as_float(e8m0 << 23); }
 
-// Clamp to [-bound, bound] keeping the element's own sign bit (also for zeros).
-__device__ __forceinline__ float clamp_keep_sign(float y, float bound) {
-    float m = __builtin_fminf(__builtin_fabsf(y), bound);
-    return __builtin_copysignf(m, y);
+// Clamp to [-bound, bound] keeping the element's own sign bit (also for zeros): the median of
+// (y, -b, b).  `b` must be positive for a zero to keep its sign, so a zero bound (an all-zero
+// block, where nothing is clamped anyway) is replaced by the smallest positive fp32.
+__device__ __forceinline__ float clamp_limit(float bound) {
+    return __uint_as_float(max(__float_as_uint(bound), 1u));
 }
+__device__ __forceinline__ float clamp_keep_sign(float y, float b) { return __builtin_amdgcn_fmed3f(y, -b, b); }
 
 // Eight fp32 values -> eight E2M1 codes in one dword, element 0 in bits 3:0.
 // The hardware convert rounds to nearest even on the E2M1 grid, saturates at 6 and
 // keeps the sign bit of results that round to zero.
 __device__ __forceinline__ uint32_t encode8(const float* y, float bound, float sc) {
+    const float b = clamp_limit(bound);
     uint32_t r = 0;
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[0], bound), clamp_keep_sign(y[1], bound), sc, 0);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[2], bound), clamp_keep_sign(y[3], bound), sc, 1);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[4], bound), clamp_keep_sign(y[5], bound), sc, 2);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[6], bound), clamp_keep_sign(y[7], bound), sc, 3);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[0], b), clamp_keep_sign(y[1], b), sc, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[2], b), clamp_keep_sign(y[3], b), sc, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[4], b), clamp_keep_sign(y[5], b), sc, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[6], b), clamp_keep_sign(y[7], b), sc, 3);
     return r;
 }
 

@@ -177,152 +177,223 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Lane layout of the pre-split transform operand (built by the host, see batq_api.hip):
 //   Tsplit[k][term][half][lane] = 8 bf16: T_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)], e = 0..7,
 //   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3); terms 0, 1, 2 = hi, mid, lo.
-constexpr int kQuantWaves = 8;          // waves per workgroup, each owning whole 32-row tiles
+constexpr int kQuantWaves = 10;         // waves of the persistent workgroup (one workgroup per compute unit)
 constexpr int kTsplitBlock = 3 * 2 * 64 * 16;               // bytes of pre-split transform operand per MX block
+constexpr int kXSlot = 32 * 256;        // one unit of X: 32 rows x 128 bf16
+constexpr int kCodeStage = 2048;        // the two 1 KiB code pieces a unit produces
+constexpr int kQuantLdsT = 8 * kTsplitBlock;
+constexpr int kQuantLdsX = kQuantLdsT;
+constexpr int kQuantLdsStage = kQuantLdsX + kQuantWaves * kXSlot;
+constexpr int kQuantLdsCounter = kQuantLdsStage + kQuantWaves * kCodeStage;
+constexpr int kQuantLds = kQuantLdsCounter + 16;            // 148 KiB
 
+// Persistent kernel.  Work comes in units of (32-row tile, half K group = 4 MX blocks = 256 bytes per
+// row), numbered K group by K group; a workgroup takes an equal contiguous range of them and its
+// waves draw units from an LDS counter.  The transform operands of the current K group (48 KiB) sit
+// in LDS and are replaced when the range enters the next group.  A wave's unit of X is fetched
+// global -> LDS with LDS-direct loads (no registers are tied up while it is in flight), as rows of 16
+// chunks of 16 bytes, chunk c of row r at position c ^ (r & 7) so that the operand reads (all lanes
+// the same chunk, 32 different rows) spread over the banks.  As soon as the unit is in registers the
+// next one is requested into the same slot; the code pieces and scale bytes of a unit are written
+// out one unit late, so that nothing waits on a store that was just issued (loads and stores share
+// one completion counter).
 __global__ void __launch_bounds__(kQuantWaves * 64)
-quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wave,
+quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int wpg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
-    // A workgroup owns one 256-element K group (8 MX blocks = two 1 KiB piece columns of the code
-    // layout and one 8-byte scale word per row).  Its transform operands (48 KiB) are fetched once
-    // into LDS; after that every wave works alone, without workgroup barriers: it reads 32 rows x
-    // 512 contiguous bytes of X, runs the 8 blocks through the matrix pipe one after the other,
-    // collects its four finished code pieces in a private 4 KiB LDS area and writes them, and the
-    // 32 scale words, as whole cache lines.
-    __shared__ __align__(16) uint8_t tlds[8 * kTsplitBlock];
-    __shared__ __align__(16) uint8_t cstage[kQuantWaves][4096];
+    extern __shared__ __align__(16) uint8_t qlds[];
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = blockIdx.x;                               // K group
-    const int k0 = g * 8;
-    const int nblk = min(8, nb - k0);                       // real blocks in this group (rest is padding)
     const int l32 = lane & 31, kg = lane >> 5;
     const int row_tiles = (M + 31) >> 5;
+    const int groups = scale_groups(nb);
     const size_t piece_stride = (size_t)code_stages(nb) * 1024;
-    uint8_t* const my = cstage[wave];
+
+    uint8_t* const tlds = qlds;
+    uint8_t* const xslot = qlds + kQuantLdsX + wave * kXSlot;
+    uint8_t* const my = qlds + kQuantLdsStage + wave * kCodeStage;
+    uint32_t* const counter = reinterpret_cast<uint32_t*>(qlds + kQuantLdsCounter);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte*)qlds;
+    const uint32_t xslot_lds = lds_base + kQuantLdsX + wave * kXSlot;
+
+    // `wpg` workgroups share a K group, each taking an equal range of its row tiles; with more groups
+    // than workgroups (wpg = 1) a workgroup takes every (gridDim.x)-th group
+    const int part = blockIdx.x % wpg;
+    const int t_begin = (int)((int64_t)row_tiles * part / wpg), t_end = (int)((int64_t)row_tiles * (part + 1) / wpg);
+    const int u_end = 2 * t_end;                            // units of a group: u = 2 tile + half
+    auto grab = [&]() -> int {
+        int v = 0;
+        if (lane == 0) v = (int)__hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+    auto request = [&](int g, int u) {
+        const int tile = u >> 1, half = u & 1;
+        const int kb = 8 * g + 4 * half;                    // first MX block of the unit
+        const int nreal = min(4, nb - kb);                  // blocks that exist (the rest of the group is padding)
+        if (nreal <= 0) return;
+        const uint8_t* base = reinterpret_cast<const uint8_t*>(X) + ((size_t)tile * 32 * ldx + (size_t)kb * 32) * 2;
+        const int rows_left = M - 1 - tile * 32;            // rows past the end repeat the last one: computed, not stored
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = 4 * j + (lane >> 4);
+            int c = (lane & 15) ^ (r & 7);                  // the chunk that belongs at this lane's LDS position
+            if (c >= 4 * nreal) c = 0;                      // never read past the end of the row
+            const uint32_t voff = (uint32_t)min(r, rows_left) * (uint32_t)(ldx * 2) + (uint32_t)c * 16;
+            // X is read exactly once: non-temporal, so it does not push the transform operands or
+            // the pending output lines out of the L2
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                         :: "v"(voff), "s"(base), "s"(xslot_lds + (uint32_t)j * 1024) : "memory");
+        }
+    };
+
     const int r16 = l32 & 15;
-    // this lane's 8 code bytes of a block inside the wave's staging area [piece column][row group][1 KiB]
+    // this lane's 8 code bytes of a block inside the staging area [row group][1 KiB]
     const int st_base = (l32 >> 4) * 1024 + r16 * 64 + 8 * kg;
     const int st_swz = (r16 >> 2) & 3;
 
-    // ---- per-wave work: units of (32-row tile, half K group = 4 blocks = 256 bytes per row); the
-    // next unit is loaded into a second register set while the current one is processed
-    const int wave_tile0 = (blockIdx.y * kQuantWaves + wave) * tiles_per_wave;
-    const int ntiles = max(0, min(tiles_per_wave, row_tiles - wave_tile0));
-    const int nunits = 2 * ntiles;
-    auto load_unit = [&](int u, uint4 (&x)[4][2]) {
-        const int rowc = min((wave_tile0 + (u >> 1)) * 32 + l32, M - 1);   // rows past the end: computed, not stored
-        const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)rowc * ldx + (size_t)(k0 + 4 * (u & 1)) * 32 + 16 * kg);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (4 * (u & 1) + b < nblk) {                   // uniform
-                x[b][0] = xp[4 * b];
-                x[b][1] = xp[4 * b + 1];
-            }
-        }
-    };
-    uint4 xc[4][2], xn[4][2];
-    if (nunits > 0) load_unit(0, xc);                       // in flight while the operands go to LDS
-    {
-        // the group's transform operands go global -> LDS with LDS-direct loads (1 KiB per wave
-        // instruction, lane i -> LDS base + 16 i), all issued back to back
-        typedef __attribute__((address_space(3))) uint8_t lds_byte;
-        const uint32_t lds_t = (uint32_t)(uintptr_t)(lds_byte*)tlds;
-        const uint8_t* src = reinterpret_cast<const uint8_t*>(Tsplit) + (size_t)k0 * kTsplitBlock;
-        const int pieces = nblk * (kTsplitBlock / 1024);   // 6 per block
-        for (int p = wave; p < pieces; p += kQuantWaves)
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                         :: "v"((uint32_t)(p * 1024 + lane * 16)), "s"(src), "s"(lds_t + (uint32_t)p * 1024) : "memory");
-        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): operands (and the first X unit) have landed
-    }
-    __syncthreads();
-
-    uint32_t sc_lo = 0x7F7F7F7Fu, sc_hi = 0x7F7F7F7Fu;     // scale word of the row; padding blocks stay neutral
-    for (int u = 0; u < nunits; ++u) {
-        const int tile = wave_tile0 + (u >> 1);
-        const int half = u & 1;
-        if (u + 1 < nunits) load_unit(u + 1, xn);
-#pragma unroll
-        for (int bb = 0; bb < 4; ++bb) {
-            const int b = 4 * half + bb;                    // block inside the K group
-            uint2 out = {0u, 0u};                           // padding blocks: zero codes
-            if (b < nblk) {
-                const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
-                uint4 tfr[6];
-#pragma unroll
-                for (int i = 0; i < 6; ++i) tfr[i] = tf[i * 64];
-                // two independent accumulation chains (one per K half), smallest terms first
-                v16f acc0 = {}, acc1 = {};
-#pragma unroll
-                for (int t = 2; t >= 0; --t) {
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 0]),
-                                                                   __builtin_bit_cast(bf16x8, xc[bb][0]), acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 1]),
-                                                                   __builtin_bit_cast(bf16x8, xc[bb][1]), acc1, 0, 0, 0);
-                }
-                // y[r] = transformed element 16 kg + r of this lane's row
-                float y[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) y[r] = acc0[r] + acc1[r];
-                float m = __builtin_fabsf(y[0]);
-#pragma unroll
-                for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
-                // the other half of the block lives in lane ^ 32
-                const float mo = __builtin_bit_cast(
-                    float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
-                m = __builtin_fmaxf(m, mo);
-                const float bound = clip[k0 + b] * m;       // one fp32 multiply
-                const uint32_t s = e8m0_of_bound(bound);
-                const float sc = scale_operand(s);
-                out.x = encode8(y, bound, sc);
-                out.y = encode8(y + 8, bound, sc);
-                // byte (b/2) + 4 (b%2) of the row's scale word
-                const int sh = 8 * (b >> 1);
-                if (b & 1) sc_hi = (sc_hi & ~(0xFFu << sh)) | (s << sh);
-                else sc_lo = (sc_lo & ~(0xFFu << sh)) | (s << sh);
-            }
-            *reinterpret_cast<uint2*>(my + half * 2048 + st_base + ((bb ^ st_swz) << 4)) = out;
-        }
-        // the two finished pieces of this half: (column `half`, rows 0-15) and (column `half`, rows 16-31);
-        // the code array is padded to whole 32-row tiles, so both always exist
+    // stores of the unit finished last
+    int pend_u = -1, pend_g = 0;
+    uint32_t pend_sc = 0;
+    auto flush = [&]() {
+        if (pend_u < 0) return;
+        const int tile = pend_u >> 1, half = pend_u & 1;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(my + half * 2048 + p * 1024 + lane * 16);
-            *reinterpret_cast<uint4*>(codes + (size_t)(2 * tile + p) * piece_stride + (size_t)(2 * g + half) * 1024 +
-                                      lane * 16) = v;
+            // (column `half` of the group, rows 0-15) and (rows 16-31); the code array is padded to whole
+            // 32-row tiles, so both pieces always exist
+            // streamed out past the caches' keep-lists: nothing in this kernel reads them again
+            const u32x4 v = *reinterpret_cast<const u32x4*>(my + p * 1024 + lane * 16);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(codes + (size_t)(2 * tile + p) * piece_stride +
+                                                                    (size_t)(2 * pend_g + half) * 1024 + lane * 16));
         }
-        if (half == 1) {
-            const int row = tile * 32 + l32;
-            if (kg == 0 && row < M)
-                *reinterpret_cast<uint2*>(scales + ((size_t)g * M + row) * 8) = uint2{sc_lo, sc_hi};
-            sc_lo = 0x7F7F7F7Fu;
-            sc_hi = 0x7F7F7F7Fu;
+        // the unit's four scale bytes of the row's 8-byte word: even blocks at 2 half, 2 half + 1,
+        // odd blocks at 4 + 2 half, 4 + 2 half + 1; lane kg writes pair kg
+        const int row = tile * 32 + l32;
+        if (row < M)
+            *reinterpret_cast<uint16_t*>(scales + ((size_t)pend_g * M + row) * 8 + 4 * kg + 2 * half) = (uint16_t)pend_sc;
+        pend_u = -1;
+    };
+
+    for (int g = blockIdx.x / wpg; g < groups; g += gridDim.x / wpg) {
+        const int k0 = g * 8;
+        const int nblk = min(8, nb - k0);                   // real blocks in this group
+        __syncthreads();                                    // every wave is done with the previous group's operands
+        if (tid == 0) *counter = (uint32_t)(2 * t_begin);
+        {
+            // the group's transform operands go global -> LDS with LDS-direct loads (1 KiB per wave
+            // instruction, lane i -> LDS base + 16 i)
+            const uint8_t* src = reinterpret_cast<const uint8_t*>(Tsplit) + (size_t)k0 * kTsplitBlock;
+            const int pieces = nblk * (kTsplitBlock / 1024);   // 6 per block
+            for (int p = wave; p < pieces; p += kQuantWaves)
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                             :: "v"((uint32_t)(p * 1024 + lane * 16)), "s"(src), "s"(lds_base + (uint32_t)p * 1024) : "memory");
         }
+        __syncthreads();                                    // the counter is set
+        int my_u = grab();
+        if (my_u < u_end) request(g, my_u);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's share of the operands (and its unit)
+        __syncthreads();                                    // all operands have landed
+
+        while (my_u < u_end) {
+            const int u = my_u;
+            const int half = u & 1;
+            const int nreal = min(4, nb - (k0 + 4 * half));
+            __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): the unit has landed (older stores are long done)
+            u32x4 x[4][2] = {};
+            if (nreal > 0) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            xc[b][0] = xn[b][0];
-            xc[b][1] = xn[b][1];
+                for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int c = 4 * bb + 2 * kg + h;
+                        x[bb][h] = *reinterpret_cast<const u32x4*>(xslot + l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4));
+                    }
+                // the slot is refilled next: its contents must be in registers first
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) asm volatile("" : "+v"(x[bb][h]));
+            }
+            my_u = grab();
+            if (my_u < u_end) request(g, my_u);
+            flush();
+
+            uint32_t sc4[4] = {127u, 127u, 127u, 127u};    // padding blocks keep the neutral scale
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                const int b = 4 * half + bb;                // block inside the K group
+                uint2 out = {0u, 0u};                       // padding blocks: zero codes
+                if (bb < nreal) {
+                    const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
+                    uint4 tfr[6];
+#pragma unroll
+                    for (int i = 0; i < 6; ++i) tfr[i] = tf[i * 64];
+                    // one accumulation chain over 3 terms x 2 K halves, smallest terms first; other waves of the
+                    // SIMD fill the matrix pipe while this chain waits on itself
+                    v16f acc = {};
+#pragma unroll
+                    for (int t = 2; t >= 0; --t) {
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 0]),
+                                                                      __builtin_bit_cast(bf16x8, x[bb][0]), acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 1]),
+                                                                      __builtin_bit_cast(bf16x8, x[bb][1]), acc, 0, 0, 0);
+                    }
+                    // y[r] = transformed element 16 kg + r of this lane's row
+                    float y[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) y[r] = acc[r];
+                    float m = __builtin_fabsf(y[0]);
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
+                    // the other half of the block lives in lane ^ 32
+                    const float mo = __builtin_bit_cast(
+                        float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
+                    m = __builtin_fmaxf(m, mo);
+                    const float bound = clip[k0 + b] * m;   // one fp32 multiply
+                    const uint32_t s = e8m0_of_bound(bound);
+                    const float sc = scale_operand(s);
+                    out.x = encode8(y, bound, sc);
+                    out.y = encode8(y + 8, bound, sc);
+                    sc4[bb] = s;
+                }
+                *reinterpret_cast<uint2*>(my + st_base + ((bb ^ st_swz) << 4)) = out;
+            }
+            pend_u = u;
+            pend_g = g;
+            pend_sc = kg == 0 ? (sc4[0] | (sc4[2] << 8)) : (sc4[1] | (sc4[3] << 8));
         }
     }
+    flush();
 }
 
 hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
                        uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
-    const int groups = scale_groups(nb);
-    const int row_tiles = (M + 31) / 32;
-    // a few 32-row tiles per wave amortise the 48 KiB operand fetch of a workgroup; small problems
-    // keep one tile per wave so that the grid still covers the chip
-    int tiles_per_wave = (int)std::min<long>(4, std::max<long>(1, (long)row_tiles * groups / (512L * kQuantWaves)));
-    const int per_wg = kQuantWaves * tiles_per_wave;
-    const dim3 grid(groups, (row_tiles + per_wg - 1) / per_wg), block(kQuantWaves * 64);
-    quant_act_mfma<<<grid, block, 0, stream>>>(X, ldx, M, nb, tiles_per_wave,
-                                               reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kQuantLds);
+        if (e != hipSuccess) {
+            cus = 0;
+            return e;
+        }
+    }
+    // whole K groups per workgroup set: floor(compute units / groups) workgroups share a group
+    const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
+    const int wpg = std::max(1, std::min(cus / groups, row_tiles));
+    const int wgs = wpg * std::min(groups, cus);
+    quant_act_mfma<<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
+        X, ldx, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
     return hipGetLastError();
 }
 
@@ -355,7 +426,8 @@ hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtyp
     (void)K;
     if (M == 0) return hipSuccess;
     if (xdtype == BATQ_BF16) {
-        if (t->has_transform && t->d_Tsplit)
+        // the matrix-core kernel addresses a 32-row tile with 32-bit byte offsets
+        if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
             return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
         return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
     }
