@@ -234,6 +234,8 @@ struct TiledCtx {
     // edge are clamped to the last one (their results are never stored).
     __device__ __forceinline__ void aim(const Tile& t) {
         const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
+        int lane = this->lane;
+        asm volatile("" : "+v"(lane));      // recompute the lane terms per tile instead of keeping them in registers
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
@@ -429,6 +431,7 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     c.read_scales<NJ>(0, sa, sb);
     c.read_frags<NJ>(0, 0, fa, fb);
 
+    // the first stage of a tile starts the accumulators from zero
     if (G >= 3) {
         tiled_stage<NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
         tiled_stage<NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
@@ -436,17 +439,16 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
             tiled_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
             tiled_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
         }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = v16f{};
-    }
-    if (G >= 2) {
         tiled_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);
         tiled_stage<NJ, 1, kOdd, false, false>(c, T - 3, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
+    } else if (G == 2) {
+        tiled_stage<NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 1, kOdd, false, false>(c, 1, acc, fa, fb, sa, sb);
+        tiled_stage<NJ, 0, 0, false, false>(c, 2, acc, fa, fb, sa, sb);
+    } else {
+        tiled_stage<NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
     }
-    tiled_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
     tiled_stage<NJ, 1, -1, false, false>(c, T - 1, acc, fa, fb, sa, sb);
 
     __syncthreads();                                      // every wave is done with the stage ring
@@ -489,6 +491,7 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
+                    __builtin_amdgcn_sched_barrier(0);      // one 16-row block at a time: keeps register use flat
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -523,6 +526,7 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 if (row < c.M) {
