@@ -7,7 +7,8 @@
 // one operand fragment.  Accumulator register r of lane l is element
 // (8*(r/4) + 4*(l/32) + r%4, l % 32) of the 32x32 tile.
 //
-// Two kernels:
+// Three kernels:
+//   gemm_skinny - M <= 64: one 32x32 tile per workgroup, K split over its 8 waves.
 //   gemm_tiled  - 256x256 output tile per workgroup (4 waves, each 128x128 = 4x4 matrix
 //                 tiles held in 256 accumulator registers); codes and scales stream
 //                 global -> LDS with LDS-direct loads through a 4-stage ring (XOR-swizzled
@@ -124,6 +125,99 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
         for (int r = 0; r < 16; ++r) {
             const int row = m0 + 8 * (r >> 2) + 4 * kg + (r & 3);
             if (row < M) store_y<YT>(Y + (size_t)row * ldy + col, acc[r]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Small M (decode shapes): the time goes into streaming the weight codes once, so the work is
+// split along K as well.  A workgroup of 8 waves owns 32 output columns (all rows); wave w takes an
+// equal share of the K groups (256 elements = 4 matrix instructions, whose 8 scale bytes per row
+// are two dwords), issues all loads of a group before its matrix instructions, and the 8 partial
+// tiles are summed through LDS in a fixed order.  K is zero-padded to whole groups in both
+// operands, so there is no K tail.
+constexpr int kSkinnyWaves = 8;
+
+template <typename YT, int RT>      // RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads
+__global__ void __launch_bounds__(kSkinnyWaves * 64)
+gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
+            const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy) {
+    __shared__ float part[kSkinnyWaves][16][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n0 = blockIdx.x * 32;
+    const int i = lane & 31, kg = lane >> 5;
+    const int bn = min(n0 + i, N - 1);                      // rows and columns past the edge are computed, not stored
+    const int groups = scale_groups(nb);
+    const int g_begin = groups * wave / kSkinnyWaves, g_end = groups * (wave + 1) / kSkinnyWaves;
+    // block k = 8 g + 2 j + kg (j = 0..3): chunk (k / 4, k % 4) = (2 g + j / 2, 2 (j % 2) + kg)
+    const int rb = bn & 15;
+    const uint8_t* pb = wc + (size_t)(bn >> 4) * code_stages(nb) * 1024 + rb * 64;
+    const int swb = (rb >> 2) & 3;
+    int am[RT], swa[RT];
+    const uint8_t* pa[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        am[t] = min(32 * t + i, M - 1);
+        const int ra = am[t] & 15;
+        pa[t] = xc + (size_t)(am[t] >> 4) * code_stages(nb) * 1024 + ra * 64;
+        swa[t] = (ra >> 2) & 3;
+    }
+    v16f acc[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) acc[t] = v16f{};
+    // operands of group g are fetched while group g-1 is multiplied
+    uint4 a[RT][4], b[4], an[RT][4], bn4[4];
+    int sa[RT], sb = 0, san[RT], sbn = 0;
+    auto load_group = [&](int g, uint4 (&ga)[RT][4], uint4 (&gb)[4], int (&gsa)[RT], int& gsb) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int piece = 2 * g + (j >> 1), slot = 2 * (j & 1) + kg;
+            gb[j] = *reinterpret_cast<const uint4*>(pb + (size_t)piece * 1024 + ((slot ^ swb) << 4));
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                ga[t][j] = *reinterpret_cast<const uint4*>(pa[t] + (size_t)piece * 1024 + ((slot ^ swa[t]) << 4));
+        }
+        // byte j of the dword at 4 kg of the row's scale word is the scale of block 8 g + 2 j + kg
+        gsb = *reinterpret_cast<const int*>(ws + ((size_t)g * N + bn) * 8 + 4 * kg);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) gsa[t] = *reinterpret_cast<const int*>(xs + ((size_t)g * M + am[t]) * 8 + 4 * kg);
+    };
+    if (g_begin < g_end) load_group(g_begin, a, b, sa, sb);
+    for (int g = g_begin; g < g_end; ++g) {
+        if (g + 1 < g_end) load_group(g + 1, an, bn4, san, sbn);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][0]), frag(b[0]), acc[t], 4, 4, 0, sa[t], 0, sb);
+            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][1]), frag(b[1]), acc[t], 4, 4, 1, sa[t], 1, sb);
+            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][2]), frag(b[2]), acc[t], 4, 4, 2, sa[t], 2, sb);
+            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][3]), frag(b[3]), acc[t], 4, 4, 3, sa[t], 3, sb);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            b[j] = bn4[j];
+#pragma unroll
+            for (int t = 0; t < RT; ++t) a[t][j] = an[t][j];
+        }
+        sb = sbn;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) sa[t] = san[t];
+    }
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        if (t > 0) __syncthreads();                         // the previous tile's partial sums have been read
+#pragma unroll
+        for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[t][r];
+        __syncthreads();
+        // 1024 outputs, two per thread; element (r, l) of the tile is (8 (r / 4) + 4 (l / 32) + r % 4, l % 32)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int e = threadIdx.x + h * kSkinnyWaves * 64;
+            const int r = e >> 6, l = e & 63;
+            float v = part[0][r][l];
+#pragma unroll
+            for (int w = 1; w < kSkinnyWaves; ++w) v += part[w][r][l];
+            const int row = 32 * t + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), col = n0 + (l & 31);
+            if (row < M && col < N) store_y<YT>(Y + (size_t)row * ldy + col, v);
         }
     }
 }
@@ -627,6 +721,10 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
         gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb,
                                                                             pl, Y, ldy);
+    } else if (M <= 64) {
+        const dim3 grid((N + 31) / 32), block(kSkinnyWaves * 64);
+        if (M <= 32) gemm_skinny<YT, 1><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+        else gemm_skinny<YT, 2><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
     } else {
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
         gemm_direct<YT><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
