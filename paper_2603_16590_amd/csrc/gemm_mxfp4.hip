@@ -8,14 +8,14 @@
 // (8*(r/4) + 4*(l/32) + r%4, l % 32) of the 32x32 tile.
 //
 // Three kernels:
-//   gemm_skinny - M <= 64: one 32x32 tile per workgroup, K split over its 8 waves.
-//   gemm_tiled  - 256x256 output tile per workgroup (4 waves, each 128x128 = 4x4 matrix
-//                 tiles held in 256 accumulator registers); codes and scales stream
-//                 global -> LDS with LDS-direct loads through a 4-stage ring (XOR-swizzled
-//                 16-byte slots); workgroup -> tile mapping grouped per XCD so that an XCD's
-//                 L2 sees a compact sub-grid.
-//   gemm_direct - one wave per 32x32 tile with operands straight from global memory, for
-//                 small M.
+//   gemm_skinny - M <= 64: 32 output columns per workgroup, K split over its 8 waves.
+//   gemm_tiled  - persistent workgroups of 4 waves, output tiles of 256 rows x 64..256 columns
+//                 (each wave 128 x 32..128 = 4 x 1..4 matrix tiles in up to 256 accumulator
+//                 registers); codes and scales stream global -> LDS with LDS-direct loads through
+//                 a 4-stage ring (XOR-swizzled 16-byte slots); every workgroup takes an equal
+//                 share of the output, and the shares of one XCD form a compact block for its L2.
+//   gemm_direct - one wave per 32x32 tile with operands straight from global memory; only for
+//                 operand arrays of 2 GiB or more (the tiled kernel uses 32-bit load offsets).
 #include <algorithm>
 
 #include "batq_internal.h"

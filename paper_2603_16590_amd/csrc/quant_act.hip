@@ -16,9 +16,9 @@
 //   the output rows of T_k^T are permuted so that a lane ends with 16 consecutive output
 //   columns of one row: amax needs one cross-lane exchange, and the 16 codes are 8 bytes of
 //   the block's 16-byte chunk.
-// A workgroup owns one 256-element K group and keeps its transform operands in LDS; each wave
-// owns whole 32-row tiles (512 contiguous bytes per row), so there are no barriers in the
-// steady state, and code pieces and scale words leave as whole cache lines.
+// Persistent workgroups (one per compute unit): the workgroups that share a 256-element K group keep
+// its transform operands in LDS and split its 32-row tiles; X arrives by LDS-direct loads, code
+// pieces and scale bytes leave as whole cache lines (details at the kernel).
 //
 // Register-level kernel (`quant_act_quad`; fp32 input, or no transform).  One quad of lanes
 // owns one 32-element block
