@@ -12,10 +12,15 @@ out x in, Sec. 3.1):
 * ``kron_blocks``      - Eq. 2 (P_i as a Kronecker product of a shared and a
                          private factor), in the factor order T_k = G (x) P_k
                          with G global and P_k private.
+* ``kron_blocks_general`` - the other forms Sec. 3.1.1 discusses: either factor
+                         shared or private (the order Eq. 2 prints, private (x)
+                         global; the naive Kronecker with both private); a dense
+                         P_i is passed to the ``*_blocks`` functions directly.
 * ``transform``        - Eq. 1 (block-diagonal P applied block by block).
 * ``clip_blocks``      - Eq. 3-4 specialised to one symmetric ratio on the
                          block's absolute maximum; ``clip_blocks_minmax`` is
-                         Eq. 3-4 as printed (two ratios on block min and max).
+                         Eq. 3-4 as printed (two ratios on block min and max);
+                         ``mxfp4_quantize_minmax`` quantises what it leaves.
 * ``mxfp4_quantize``   - Sec. 2 "Microscaling Floating-Point Definition":
                          E2M1 elements, 32 per block, one UE8M0 scale; shared
                          exponent floor(log2 amax) - 2, round-to-nearest-even,
@@ -106,6 +111,27 @@ def kron_blocks_private_outer(B: np.ndarray, A: np.ndarray) -> np.ndarray:
             for b2 in range(g2):
                 for a2 in range(g1):
                     T[:, b * g1 + a, b2 * g1 + a2] = B[:, b, b2] * A[a, a2]
+    return T
+
+
+def kron_blocks_general(outer: np.ndarray, inner: np.ndarray, nb: int) -> np.ndarray:
+    """Dense T_k = O_k (x) I_k, fp64 [nb, 32, 32]; a factor given as one matrix is shared by all blocks.
+
+    T_k[a*gi + c, a2*gi + c2] = O_k[a, a2] * I_k[c, c2].  Shared outer + per-block inner is the
+    Global-and-Private form; per-block outer + shared inner is the order Eq. 2 prints; both
+    per-block is the naive Kronecker decomposition of Sec. 3.1.1.
+    """
+    O = np.asarray(outer, dtype=np.float64)
+    I = np.asarray(inner, dtype=np.float64)
+    go, gi = O.shape[-1], I.shape[-1]
+    assert go * gi == BLOCK and O.shape[-2] == go and I.shape[-2] == gi
+    T = np.empty((nb, BLOCK, BLOCK), dtype=np.float64)
+    for k in range(nb):
+        Ok = O if O.ndim == 2 else O[k]
+        Ik = I if I.ndim == 2 else I[k]
+        for a in range(go):
+            for a2 in range(go):
+                T[k, a * gi:(a + 1) * gi, a2 * gi:(a2 + 1) * gi] = Ok[a, a2] * Ik
     return T
 
 
@@ -215,6 +241,34 @@ def mxfp4_quantize(Xt32: np.ndarray, clip=None) -> tuple[np.ndarray, np.ndarray]
     return pack_codes(codes), scales
 
 
+def mxfp4_quantize_minmax(Xt32: np.ndarray, r_min, r_max) -> tuple[np.ndarray, np.ndarray]:
+    """As ``mxfp4_quantize`` with the clipping of Eq. 3-4 as printed: x clamped to
+    [fl32(r_min * min), fl32(r_max * max)] per block; the shared scale comes from the largest
+    magnitude that is left."""
+    Xc = clip_blocks_minmax(Xt32, r_min, r_max)
+    bound = np.max(np.abs(Xc), axis=2).astype(np.float32)
+    codes, scales = quantize_clipped(Xc, bound)
+    return pack_codes(codes), scales
+
+
+def quantize_act_blocks(X: np.ndarray, T, clip=None, clip_min=None, clip_max=None,
+                        chunk: int = 512) -> tuple[np.ndarray, np.ndarray]:
+    """Online activation path for dense blocks T [nb, 32, 32] (None = identity): Eq. 1, then either the
+    symmetric clip (``clip``) or the two-ratio clip of Eq. 3-4 (``clip_min``, ``clip_max``), then MXFP4."""
+    X = np.asarray(X)
+    assert (clip_min is None) == (clip_max is None) and (clip is None or clip_min is None)
+    cs, ss = [], []
+    for r0 in range(0, X.shape[0], chunk):
+        Xr = X[r0:r0 + chunk]
+        Xt = np.asarray(Xr, np.float64).astype(np.float32) if T is None else apply_blocks(Xr, T).astype(np.float32)
+        c, s = mxfp4_quantize(Xt, clip) if clip_min is None else mxfp4_quantize_minmax(Xt, clip_min, clip_max)
+        cs.append(c)
+        ss.append(s)
+    if not cs:
+        return (np.zeros((0, X.shape[1] // 2), np.uint8), np.zeros((0, X.shape[1] // BLOCK), np.uint8))
+    return np.concatenate(cs), np.concatenate(ss)
+
+
 def quantize_act(X: np.ndarray, G, P, clip, chunk: int = 512) -> tuple[np.ndarray, np.ndarray]:
     """Online activation path: transform (Eq. 1-2), clip (Eq. 3-4), MXFP4 (Sec. 2)."""
     X = np.asarray(X)
@@ -280,6 +334,28 @@ def prepare_weight(W: np.ndarray, G, P, clip_w=None, chunk: int = 1024) -> tuple
     cs, ss = [], []
     for n0 in range(0, Wt.shape[1], chunk):
         c, s = mxfp4_quantize(np.ascontiguousarray(Wt[:, n0:n0 + chunk].T), clip_w)
+        cs.append(c)
+        ss.append(s)
+    return np.concatenate(cs), np.concatenate(ss)
+
+
+def prepare_weight_blocks(W: np.ndarray, T, clip_w=None, clip_min=None, clip_max=None,
+                          chunk: int = 1024) -> tuple[np.ndarray, np.ndarray]:
+    """Offline weight path for dense blocks T [nb, 32, 32] (None = identity): each 32-row K-slab of W
+    (K x N) multiplied from the left by T_k^-1 in fp64, one rounding to fp32, clip (symmetric or the two
+    ratios of Eq. 3-4), MXFP4 along K.  Returns canonical (codes [N, K/2], scales [N, K/32])."""
+    W = np.asarray(W, dtype=np.float64)
+    assert (clip_min is None) == (clip_max is None) and (clip_w is None or clip_min is None)
+    if T is None:
+        Wt = W.astype(np.float32)
+    else:
+        Wt = np.empty(W.shape, dtype=np.float32)
+        for k in range(W.shape[0] // BLOCK):
+            Wt[k * BLOCK:(k + 1) * BLOCK] = (invert(T[k]) @ W[k * BLOCK:(k + 1) * BLOCK]).astype(np.float32)
+    cs, ss = [], []
+    for n0 in range(0, Wt.shape[1], chunk):
+        Wn = np.ascontiguousarray(Wt[:, n0:n0 + chunk].T)
+        c, s = mxfp4_quantize(Wn, clip_w) if clip_min is None else mxfp4_quantize_minmax(Wn, clip_min, clip_max)
         cs.append(c)
         ss.append(s)
     return np.concatenate(cs), np.concatenate(ss)
