@@ -38,7 +38,7 @@
  *               = ((k/8) * rows + row) * 8 + (k%8)/2 + 4 * (k%2)
  *             (groups of 8 blocks, group-major, even blocks of a group first); a last
  *             partial group is padded with the neutral scale 127.
- * Quantiser definition: bound = fl32(clip_k * max_j |y_j|); elements beyond +-bound
+ * Quantiser definition (symmetric clip): bound = fl32(clip_k * max_j |y_j|); elements beyond +-bound
  * are replaced by +-bound; E = clamp(floor(log2 bound) - 2, -127, 127) (E = -127 for
  * a zero block); code = round-to-nearest on the E2M1 grid of y * 2^-E, ties to the
  * code with even mantissa bit, saturating at 6; the sign bit is always the sign bit
@@ -72,7 +72,7 @@ typedef enum {
     BATQ_ERR_NULL = 1,        /* a required pointer is NULL                                  */
     BATQ_ERR_SHAPE = 2,       /* K % 32 != 0, a size <= 0, or a leading dimension too small  */
     BATQ_ERR_DTYPE = 3,       /* unknown batq_dtype                                          */
-    BATQ_ERR_UNSUPPORTED = 4, /* (g_outer, g_inner) not one of (4,8), (8,4)                   */
+    BATQ_ERR_UNSUPPORTED = 4, /* (g_outer, g_inner) not one of (4,8), (8,4), or unknown form    */
     BATQ_ERR_SINGULAR = 5,    /* G or some P_k is not invertible                             */
     BATQ_ERR_CLIP_RANGE = 6,  /* a clip ratio is not in (0, 1]                               */
     BATQ_ERR_WORKSPACE = 7,   /* workspace smaller than batq_linear_workspace()              */
@@ -109,6 +109,40 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
                                   const float* G, const float* P, const float* clip_a);
 batq_status batq_transform_destroy(batq_transform* t);
 
+/* General form of the transform set.  Besides the Global-and-Private product above, Sec. 3.1.1
+ * discusses a dense 32x32 matrix per block, the naive Kronecker product with both factors
+ * private, and Eq. 2 prints the product in the order private (x) global; Eq. 3-4 print the
+ * clipping with two ratios, on the block minimum and on the block maximum.
+ *   form      BATQ_FORM_IDENTITY: T_k = I.  BATQ_FORM_KRON: T_k = O_k (x) I_k,
+ *             T_k[a*gi + c, a2*gi + c2] = O_k[a][a2] * I_k[c][c2], (g_outer, g_inner) = (4,8) or (8,4).
+ *             BATQ_FORM_DENSE: T_k given.  A row vector x_k is mapped to x_k T_k in every form.
+ *   outer     HOST row-major fp32: [g_outer^2] if outer_per_block == 0 (one factor shared by all
+ *             blocks), else [K/32][g_outer^2] (one per block)
+ *   inner     likewise with g_inner
+ *   dense     HOST [K/32][32][32] row-major fp32
+ *   clip      HOST [K/32] ratios in (0,1] on the block amax (symmetric form), or NULL
+ *   clip_min, clip_max   HOST [K/32] ratios in (0,1]: the block is clamped to
+ *             [fl32(clip_min_k * min_j y_j), fl32(clip_max_k * max_j y_j)] and the shared scale is taken
+ *             from the largest magnitude that is left.  Both or neither; not together with `clip`.
+ * Everything is copied; blocks (or factors) are inverted on the host in fp64 with the same
+ * singularity rule as batq_transform_create, which is the special case
+ * {KRON, outer = G shared, inner = P per block, clip = clip_a}. */
+typedef enum { BATQ_FORM_IDENTITY = 0, BATQ_FORM_KRON = 1, BATQ_FORM_DENSE = 2 } batq_form;
+typedef struct {
+    int K;
+    int form;
+    int g_outer, g_inner;
+    const float* outer;
+    int outer_per_block;
+    const float* inner;
+    int inner_per_block;
+    const float* dense;
+    const float* clip;
+    const float* clip_min;
+    const float* clip_max;
+} batq_transform_desc;
+batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_desc* desc);
+
 /* ------------------------------------------------------------------------------------
  * Offline weight preparation (Alg. 2, "Offline Fusion for Deployment"):
  * W~ = P^-1 W (each 32-row K-slab of W multiplied from the left by T_k^-1, fp64
@@ -125,6 +159,12 @@ typedef struct batq_weight batq_weight;
 batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t,
                                 const void* W, batq_dtype wdtype, int K, int N, int64_t ldw,
                                 int w_is_KxN, const float* clip_w, void* stream);
+/* The same with the two-ratio clipping of Eq. 3-4 on the weight side: each block of each output
+ * column is clamped to [clip_w_min_k * min, clip_w_max_k * max] before MXFP4.  Both HOST [K/32]. */
+batq_status batq_prepare_weight_minmax(batq_weight** out, const batq_transform* t,
+                                       const void* W, batq_dtype wdtype, int K, int N, int64_t ldw,
+                                       int w_is_KxN, const float* clip_w_min, const float* clip_w_max,
+                                       void* stream);
 /* Copy the prepared weights out in the canonical layout: codes DEVICE [N][K/2],
  * scales DEVICE [N][K/32].  Enqueued on `stream`. */
 batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream);

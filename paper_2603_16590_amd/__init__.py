@@ -4,7 +4,8 @@ The product is the C-ABI shared library built from ``csrc/`` (see include/batq.h
 this package is its thin ctypes binding.
 """
 from .binding import (  # noqa: F401
-    BatqError, Transform, Weight, batq_prepare_weight, batq_weight_import, batq_quantize_act,
+    BatqError, Transform, Weight, batq_prepare_weight, batq_prepare_weight_minmax, batq_weight_import,
+    batq_quantize_act,
     batq_gemm_mxfp4, batq_linear, batq_linear_workspace, batq_scale_bytes, batq_scales_to_rowmajor,
     batq_code_bytes, batq_codes_to_rowmajor, batq_codes_from_rowmajor,
     batq_scales_from_rowmajor, lib, LIB_PATH, SYMBOLS, STATUS_NAMES, F32, BF16,

@@ -31,8 +31,10 @@ SYMBOLS = {
     "batq_status_string": (C.c_char_p, [_i]),
     "batq_version": (C.c_char_p, []),
     "batq_transform_create": (_i, [C.POINTER(_vp), _i, _i, _i, _fp, _fp, _fp]),
+    "batq_transform_create_ex": (_i, [C.POINTER(_vp), _vp]),
     "batq_transform_destroy": (_i, [_vp]),
     "batq_prepare_weight": (_i, [C.POINTER(_vp), _vp, _vp, _i, _i, _i, _i64, _i, _fp, _vp]),
+    "batq_prepare_weight_minmax": (_i, [C.POINTER(_vp), _vp, _vp, _i, _i, _i, _i64, _i, _fp, _fp, _vp]),
     "batq_weight_export": (_i, [_vp, _vp, _vp, _vp]),
     "batq_weight_import": (_i, [C.POINTER(_vp), _vp, _vp, _i, _i, _vp]),
     "batq_weight_shape": (_i, [_vp, C.POINTER(_i), C.POINTER(_i)]),
@@ -50,6 +52,16 @@ SYMBOLS = {
     "batq_linear_workspace": (_sz, [_i, _i]),
     "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
 }
+
+
+FORM_IDENTITY, FORM_KRON, FORM_DENSE = 0, 1, 2
+
+
+class TransformDesc(C.Structure):
+    """batq_transform_desc of include/batq.h."""
+    _fields_ = [("K", _i), ("form", _i), ("g_outer", _i), ("g_inner", _i),
+                ("outer", _fp), ("outer_per_block", _i), ("inner", _fp), ("inner_per_block", _i),
+                ("dense", _fp), ("clip", _fp), ("clip_min", _fp), ("clip_max", _fp)]
 
 
 class BatqError(RuntimeError):
@@ -119,6 +131,35 @@ class Transform:
         _check(lib.batq_transform_create(C.byref(self._h), K, g_outer, g_inner, _fptr(G), _fptr(P), _fptr(clip)),
                "batq_transform_create")
 
+    @classmethod
+    def general(cls, K: int, *, outer=None, inner=None, dense=None, clip=None, clip_min=None, clip_max=None):
+        """batq_transform_create_ex: Kronecker form (``outer`` / ``inner`` 2-D = shared by all blocks,
+        3-D = one per block), dense blocks [K/32, 32, 32], or identity (neither); symmetric ``clip`` or the
+        two ratios ``clip_min`` / ``clip_max``."""
+        self = cls.__new__(cls)
+        self.K = K
+        self._h = _vp()
+        f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+        outer, inner, dense, clip, clip_min, clip_max = map(f32, (outer, inner, dense, clip, clip_min, clip_max))
+        d = TransformDesc()
+        d.K = K
+        keep = [outer, inner, dense, clip, clip_min, clip_max]      # the arrays must outlive the call
+        if dense is not None:
+            assert dense.shape == (K // 32, 32, 32)
+            d.form, d.dense = FORM_DENSE, _fptr(dense)
+        elif outer is not None:
+            d.form = FORM_KRON
+            d.g_outer, d.g_inner = outer.shape[-1], inner.shape[-1]
+            d.outer, d.outer_per_block = _fptr(outer), int(outer.ndim == 3)
+            d.inner, d.inner_per_block = _fptr(inner), int(inner.ndim == 3)
+        else:
+            d.form = FORM_IDENTITY
+        self.g_outer, self.g_inner = d.g_outer, d.g_inner
+        d.clip, d.clip_min, d.clip_max = _fptr(clip), _fptr(clip_min), _fptr(clip_max)
+        _check(lib.batq_transform_create_ex(C.byref(self._h), C.byref(d)), "batq_transform_create_ex")
+        del keep
+        return self
+
     @property
     def handle(self):
         return self._h
@@ -176,6 +217,20 @@ def batq_prepare_weight(t: Transform, W, w_is_KxN: bool = True, clip_w: Optional
     h = _vp()
     _check(lib.batq_prepare_weight(C.byref(h), t.handle, W.data_ptr(), _dtype_code(W), K, N, W.stride(0),
                                    1 if w_is_KxN else 0, _fptr(clip_w), _stream()), "batq_prepare_weight")
+    return Weight(h)
+
+
+def batq_prepare_weight_minmax(t: Transform, W, clip_w_min: np.ndarray, clip_w_max: np.ndarray,
+                               w_is_KxN: bool = True) -> Weight:
+    """As batq_prepare_weight with the two-ratio clipping (ratios on the block minimum and maximum)."""
+    assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1
+    K, N = (W.shape[0], W.shape[1]) if w_is_KxN else (W.shape[1], W.shape[0])
+    cmin = np.ascontiguousarray(clip_w_min, dtype=np.float32)
+    cmax = np.ascontiguousarray(clip_w_max, dtype=np.float32)
+    h = _vp()
+    _check(lib.batq_prepare_weight_minmax(C.byref(h), t.handle, W.data_ptr(), _dtype_code(W), K, N, W.stride(0),
+                                          1 if w_is_KxN else 0, _fptr(cmin), _fptr(cmax), _stream()),
+           "batq_prepare_weight_minmax")
     return Weight(h)
 
 

@@ -106,9 +106,11 @@ batq_status upload(T** dst, const T* src, size_t count) {
 
 void free_transform(batq_transform* t) {
     if (!t) return;
-    if (t->d_G) (void)hipFree(t->d_G);
-    if (t->d_P) (void)hipFree(t->d_P);
+    if (t->d_outer) (void)hipFree(t->d_outer);
+    if (t->d_inner) (void)hipFree(t->d_inner);
+    if (t->d_T) (void)hipFree(t->d_T);
     if (t->d_clip) (void)hipFree(t->d_clip);
+    if (t->d_clip_max) (void)hipFree(t->d_clip_max);
     if (t->d_Tinv) (void)hipFree(t->d_Tinv);
     if (t->d_Tsplit) (void)hipFree(t->d_Tsplit);
     delete t;
@@ -160,35 +162,62 @@ const char* batq_status_string(batq_status s) {
 
 const char* batq_version(void) { return "0.1"; }
 
-batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int g_inner, const float* G,
-                                  const float* P, const float* clip_a) {
-    if (!out) return BATQ_ERR_NULL;
+batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_desc* d) {
+    if (!out || !d) return BATQ_ERR_NULL;
+    const int K = d->K;
     if (K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
-    if (!((g_outer == 4 && g_inner == 8) || (g_outer == 8 && g_inner == 4))) return BATQ_ERR_UNSUPPORTED;
-    if ((G == nullptr) != (P == nullptr)) return BATQ_ERR_NULL;
     const int nb = K / 32;
-    if (clip_a && !clip_ok(clip_a, nb)) return BATQ_ERR_CLIP_RANGE;
+    const int form = d->form;
+    if (form != BATQ_FORM_IDENTITY && form != BATQ_FORM_KRON && form != BATQ_FORM_DENSE) return BATQ_ERR_UNSUPPORTED;
+    const int go = d->g_outer, gi = d->g_inner;
+    if (form == BATQ_FORM_KRON) {
+        if (!((go == 4 && gi == 8) || (go == 8 && gi == 4))) return BATQ_ERR_UNSUPPORTED;
+        if (!d->outer || !d->inner) return BATQ_ERR_NULL;
+    }
+    if (form == BATQ_FORM_DENSE && !d->dense) return BATQ_ERR_NULL;
+    if ((d->clip_min == nullptr) != (d->clip_max == nullptr)) return BATQ_ERR_NULL;
+    if (d->clip && d->clip_min) return BATQ_ERR_UNSUPPORTED;
+    if (d->clip && !clip_ok(d->clip, nb)) return BATQ_ERR_CLIP_RANGE;
+    if (d->clip_min && (!clip_ok(d->clip_min, nb) || !clip_ok(d->clip_max, nb))) return BATQ_ERR_CLIP_RANGE;
 
-    // host fp64: G^-1, P_k^-1 and the dense inverse blocks T_k^-1 = G^-1 (x) P_k^-1;
-    // and the forward blocks T_k = G (x) P_k split into three bf16 terms in the lane order of
-    // the activation kernel's matrix-instruction operand
-    std::vector<double> Tinv;
+    // host fp64: the dense forward blocks T_k, their inverses (from the inverted factors for the
+    // Kronecker forms, T_k^-1 = O_k^-1 (x) I_k^-1), and T_k split into three bf16 terms in the lane
+    // order of the activation kernel's matrix-instruction operand
+    std::vector<double> T, Tinv;
+    std::vector<float> Tf;
     std::vector<uint16_t> Tsplit;
-    if (G) {
-        const int go = g_outer, gi = g_inner;
-        std::vector<double> Gd(go * go), Ginv(go * go), Pd(gi * gi), Pinv(gi * gi);
-        for (int i = 0; i < go * go; ++i) Gd[i] = G[i];
-        if (!invert_small(Gd.data(), go, Ginv.data())) return BATQ_ERR_SINGULAR;
+    if (form != BATQ_FORM_IDENTITY) {
+        T.resize((size_t)nb * 1024);
         Tinv.resize((size_t)nb * 1024);
-        for (int k = 0; k < nb; ++k) {
-            for (int i = 0; i < gi * gi; ++i) Pd[i] = P[(size_t)k * gi * gi + i];
-            if (!invert_small(Pd.data(), gi, Pinv.data())) return BATQ_ERR_SINGULAR;
-            double* Tk = Tinv.data() + (size_t)k * 1024;
-            for (int a = 0; a < go; ++a)
-                for (int c = 0; c < gi; ++c)
-                    for (int a2 = 0; a2 < go; ++a2)
-                        for (int c2 = 0; c2 < gi; ++c2)
-                            Tk[(a * gi + c) * 32 + a2 * gi + c2] = Ginv[a * go + a2] * Pinv[c * gi + c2];
+        if (form == BATQ_FORM_KRON) {
+            std::vector<double> Od(go * go), Oinv(go * go), Id(gi * gi), Iinv(gi * gi);
+            for (int k = 0; k < nb; ++k) {
+                const float* O = d->outer + (d->outer_per_block ? (size_t)k * go * go : 0);
+                const float* I = d->inner + (d->inner_per_block ? (size_t)k * gi * gi : 0);
+                if (k == 0 || d->outer_per_block) {
+                    for (int i = 0; i < go * go; ++i) Od[i] = O[i];
+                    if (!invert_small(Od.data(), go, Oinv.data())) return BATQ_ERR_SINGULAR;
+                }
+                if (k == 0 || d->inner_per_block) {
+                    for (int i = 0; i < gi * gi; ++i) Id[i] = I[i];
+                    if (!invert_small(Id.data(), gi, Iinv.data())) return BATQ_ERR_SINGULAR;
+                }
+                double* Tk = T.data() + (size_t)k * 1024;
+                double* Tik = Tinv.data() + (size_t)k * 1024;
+                for (int a = 0; a < go; ++a)
+                    for (int c = 0; c < gi; ++c)
+                        for (int a2 = 0; a2 < go; ++a2)
+                            for (int c2 = 0; c2 < gi; ++c2) {
+                                Tk[(a * gi + c) * 32 + a2 * gi + c2] = Od[a * go + a2] * Id[c * gi + c2];
+                                Tik[(a * gi + c) * 32 + a2 * gi + c2] = Oinv[a * go + a2] * Iinv[c * gi + c2];
+                            }
+            }
+        } else {
+            Tf.assign(d->dense, d->dense + (size_t)nb * 1024);
+            for (size_t i = 0; i < T.size(); ++i) T[i] = d->dense[i];
+            for (int k = 0; k < nb; ++k)
+                if (!invert_small(T.data() + (size_t)k * 1024, 32, Tinv.data() + (size_t)k * 1024))
+                    return BATQ_ERR_SINGULAR;
         }
         Tsplit.resize((size_t)nb * 3 * 2 * 64 * 8);
         for (int k = 0; k < nb; ++k)
@@ -198,9 +227,7 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
                         const int m = lane & 31;
                         const int out_col = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
                         const int in_col = 16 * (lane >> 5) + 8 * half + e;
-                        const double tv = (double)G[(in_col / gi) * go + out_col / gi] *
-                                          (double)P[(size_t)k * gi * gi + (in_col % gi) * gi + out_col % gi];
-                        double rest = tv;
+                        double rest = T[(size_t)k * 1024 + in_col * 32 + out_col];
                         for (int term = 0; term < 3; ++term) {
                             const uint16_t b = bf16_rne((float)rest);
                             rest -= (double)bf16_value(b);
@@ -215,17 +242,25 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
     if (!t) return BATQ_ERR_ALLOC;
     t->K = K;
     t->nb = nb;
-    t->g_outer = g_outer;
-    t->g_inner = g_inner;
-    t->has_transform = G != nullptr;
-    t->has_clip = clip_a != nullptr;
+    t->form = form;
+    t->has_transform = form != BATQ_FORM_IDENTITY;
+    t->minmax = d->clip_min != nullptr;
     std::vector<float> clip(nb, 1.0f);
-    if (clip_a) std::memcpy(clip.data(), clip_a, sizeof(float) * nb);
+    if (d->clip) std::memcpy(clip.data(), d->clip, sizeof(float) * nb);
+    if (d->clip_min) std::memcpy(clip.data(), d->clip_min, sizeof(float) * nb);
     st = upload(&t->d_clip, clip.data(), (size_t)nb);
-    if (st == BATQ_OK && G) {
-        st = upload(&t->d_G, G, (size_t)g_outer * g_outer);
-        if (st == BATQ_OK) st = upload(&t->d_P, P, (size_t)nb * g_inner * g_inner);
-        if (st == BATQ_OK) st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
+    if (st == BATQ_OK && d->clip_max) st = upload(&t->d_clip_max, d->clip_max, (size_t)nb);
+    if (st == BATQ_OK && form == BATQ_FORM_KRON) {
+        t->g_outer = go;
+        t->g_inner = gi;
+        t->outer_stride = d->outer_per_block ? go * go : 0;
+        t->inner_stride = d->inner_per_block ? gi * gi : 0;
+        st = upload(&t->d_outer, d->outer, (size_t)(d->outer_per_block ? nb : 1) * go * go);
+        if (st == BATQ_OK) st = upload(&t->d_inner, d->inner, (size_t)(d->inner_per_block ? nb : 1) * gi * gi);
+    }
+    if (st == BATQ_OK && form == BATQ_FORM_DENSE) st = upload(&t->d_T, Tf.data(), Tf.size());
+    if (st == BATQ_OK && t->has_transform) {
+        st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
         if (st == BATQ_OK) st = upload(&t->d_Tsplit, Tsplit.data(), Tsplit.size());
     }
     if (st != BATQ_OK) {
@@ -236,21 +271,49 @@ batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int 
     return BATQ_OK;
 }
 
+batq_status batq_transform_create(batq_transform** out, int K, int g_outer, int g_inner, const float* G,
+                                  const float* P, const float* clip_a) {
+    if (!out) return BATQ_ERR_NULL;
+    if (K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (!((g_outer == 4 && g_inner == 8) || (g_outer == 8 && g_inner == 4))) return BATQ_ERR_UNSUPPORTED;
+    if ((G == nullptr) != (P == nullptr)) return BATQ_ERR_NULL;
+    batq_transform_desc d = {};
+    d.K = K;
+    d.form = G ? BATQ_FORM_KRON : BATQ_FORM_IDENTITY;
+    d.g_outer = g_outer;
+    d.g_inner = g_inner;
+    d.outer = G;
+    d.outer_per_block = 0;
+    d.inner = P;
+    d.inner_per_block = 1;
+    d.clip = clip_a;
+    return batq_transform_create_ex(out, &d);
+}
+
 batq_status batq_transform_destroy(batq_transform* t) {
     if (!t) return BATQ_ERR_NULL;
     free_transform(t);
     return BATQ_OK;
 }
 
-batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
-                                int K, int N, int64_t ldw, int w_is_KxN, const float* clip_w, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// clip_a / clip_b: symmetric ratios in clip_a (clip_b null), or the ratios on the block minimum and
+// maximum (two_ratio).
+batq_status prepare_weight_impl(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
+                                int K, int N, int64_t ldw, int w_is_KxN, const float* clip_a, const float* clip_b,
+                                bool two_ratio, void* stream) {
     if (!out || !t || !W) return BATQ_ERR_NULL;
+    if (two_ratio && (!clip_a || !clip_b)) return BATQ_ERR_NULL;
     if (!dtype_ok(wdtype)) return BATQ_ERR_DTYPE;
     if (K <= 0 || N <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
     if (ldw < (w_is_KxN ? N : K)) return BATQ_ERR_SHAPE;
     if (t->K != K) return BATQ_ERR_MISMATCH;
     const int nb = K / 32;
-    if (clip_w && !clip_ok(clip_w, nb)) return BATQ_ERR_CLIP_RANGE;
+    if (clip_a && !clip_ok(clip_a, nb)) return BATQ_ERR_CLIP_RANGE;
+    if (clip_b && !clip_ok(clip_b, nb)) return BATQ_ERR_CLIP_RANGE;
     batq_status st = check_device();
     if (st != BATQ_OK) return st;
 
@@ -258,21 +321,24 @@ batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, cons
     batq_weight* w = nullptr;
     st = alloc_weight(&w, K, N);
     if (st != BATQ_OK) return st;
-    float* d_clip_w = nullptr;
-    if (clip_w) {
-        st = upload(&d_clip_w, clip_w, (size_t)nb);
-        if (st != BATQ_OK) {
-            free_weight(w);
-            return st;
-        }
+    float* d_clip_a = nullptr;
+    float* d_clip_b = nullptr;
+    if (clip_a) st = upload(&d_clip_a, clip_a, (size_t)nb);
+    if (st == BATQ_OK && clip_b) st = upload(&d_clip_b, clip_b, (size_t)nb);
+    if (st != BATQ_OK) {
+        if (d_clip_a) (void)hipFree(d_clip_a);
+        free_weight(w);
+        return st;
     }
     // padding: zero codes (rows up to a multiple of 16, K up to a multiple of 256), neutral scales
     hipError_t e = hipMemsetAsync(w->d_scales, 127, batq::scale_bytes_internal(N, nb), s);
     if (e == hipSuccess) e = hipMemsetAsync(w->d_codes, 0, batq::code_bytes_blocked(N, nb), s);
     if (e == hipSuccess)
-        e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_w, w->d_codes, w->d_scales, s);
+        e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_a, d_clip_b, w->d_codes,
+                                        w->d_scales, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (d_clip_w) (void)hipFree(d_clip_w);
+    if (d_clip_a) (void)hipFree(d_clip_a);
+    if (d_clip_b) (void)hipFree(d_clip_b);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         free_weight(w);
@@ -280,6 +346,21 @@ batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, cons
     }
     *out = w;
     return BATQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
+                                int K, int N, int64_t ldw, int w_is_KxN, const float* clip_w, void* stream) {
+    return prepare_weight_impl(out, t, W, wdtype, K, N, ldw, w_is_KxN, clip_w, nullptr, false, stream);
+}
+
+batq_status batq_prepare_weight_minmax(batq_weight** out, const batq_transform* t, const void* W,
+                                       batq_dtype wdtype, int K, int N, int64_t ldw, int w_is_KxN,
+                                       const float* clip_w_min, const float* clip_w_max, void* stream) {
+    return prepare_weight_impl(out, t, W, wdtype, K, N, ldw, w_is_KxN, clip_w_min, clip_w_max, true, stream);
 }
 
 batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream) {

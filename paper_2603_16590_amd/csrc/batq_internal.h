@@ -13,12 +13,17 @@ constexpr int kBlock = 32;   // MXFP block size (Sec. 2, MXFP definition)
 // Learned parameters of one transform set, host-validated and resident on the device.
 struct batq_transform {
     int K = 0, nb = 0;
+    int form = BATQ_FORM_IDENTITY;
     int g_outer = 4, g_inner = 8;
-    bool has_transform = false;   // false: T_k = I
-    bool has_clip = false;
-    float* d_G = nullptr;         // [g_outer*g_outer]            (null when !has_transform)
-    float* d_P = nullptr;         // [nb][g_inner*g_inner]        (null when !has_transform)
+    bool has_transform = false;   // form != identity
+    bool minmax = false;          // two-ratio clipping (d_clip = ratios on the block minimum, d_clip_max on the maximum)
+    // Kronecker forms: factors as given; stride = elements between consecutive blocks (0: shared)
+    float* d_outer = nullptr;
+    float* d_inner = nullptr;
+    int outer_stride = 0, inner_stride = 0;
+    float* d_T = nullptr;         // dense form: [nb][32][32] fp32 forward blocks
     float* d_clip = nullptr;      // [nb], 1.0 when no clipping
+    float* d_clip_max = nullptr;  // [nb], only when minmax
     double* d_Tinv = nullptr;     // [nb][32][32] fp64 T_k^-1     (null when !has_transform)
     uint16_t* d_Tsplit = nullptr; // [nb][3][2][64][8] bf16 three-term split of T_k in MFMA operand order
 };
@@ -38,8 +43,9 @@ namespace batq {
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
-                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
-                                 uint8_t* scales, hipStream_t stream);
+                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
+                                 uint8_t* codes, uint8_t* scales, hipStream_t stream);
+// d_clip_w_max != null selects the two-ratio clipping (d_clip_w then holds the ratios on the minimum).
 // Weight scales are written in the internal layout (pad bytes must have been set to 127).
 // xscales_internal: activation scales in the grouped layout.
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,

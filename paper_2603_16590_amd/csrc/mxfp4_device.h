@@ -27,6 +27,10 @@ __device__ __forceinline__ float clamp_limit(float bound) {
 }
 __device__ __forceinline__ float clamp_keep_sign(float y, float b) { return __builtin_amdgcn_fmed3f(y, -b, b); }
 
+// Two-sided clamp of Eq. 3-4 as printed: below lo -> lo, else above hi -> hi, else unchanged (in this
+// order also when lo > hi, which ratios on an all-positive or all-negative block can produce).
+__device__ __forceinline__ float clamp_lo_hi(float y, float lo, float hi) { return y < lo ? lo : (y > hi ? hi : y); }
+
 // Eight fp32 values -> eight E2M1 codes in one dword, element 0 in bits 3:0.
 // The hardware convert rounds to nearest even on the E2M1 grid, saturates at 6 and
 // keeps the sign bit of results that round to zero.

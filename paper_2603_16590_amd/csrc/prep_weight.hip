@@ -1,5 +1,6 @@
 // Offline weight preparation (Alg. 2, "Offline Fusion for Deployment"):
-// W~ = P^-1 W per 32-row K-slab, optional block clip (Eq. 3-4), MXFP4 along K (Sec. 2).
+// W~ = P^-1 W per 32-row K-slab, optional block clip (Eq. 3-4, one ratio on the amax or two on min and
+// max), MXFP4 along K (Sec. 2).
 // Not on the timed path: written for accuracy (fp64 products with the host-inverted
 // fp64 blocks, one rounding to fp32) rather than speed.  gfx950 only.
 #include "batq_internal.h"
@@ -24,7 +25,7 @@ template <typename WT, bool TRANSFORM>
 __global__ void __launch_bounds__(256)
 prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, int nb,
                    const double* __restrict__ Tinv, const float* __restrict__ clip_w,
-                   uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+                   const float* __restrict__ clip_w_max, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     __shared__ double sT[TRANSFORM ? 32 * 32 : 1];
     const int k = blockIdx.y;
     if constexpr (TRANSFORM) {
@@ -53,10 +54,28 @@ prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, i
 #pragma unroll
         for (int j = 0; j < 32; ++j) y[j] = (float)w[j];
     }
-    float m = 0.f;
+    float bound;
+    if (clip_w_max) {
+        // Eq. 3-4 as printed: clamp to [r_min * min, r_max * max]; the scale comes from what is left
+        float mn = y[0], mx = y[0];
 #pragma unroll
-    for (int j = 0; j < 32; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[j]));
-    const float bound = clip_w ? clip_w[k] * m : m;
+        for (int j = 1; j < 32; ++j) {
+            mn = __builtin_fminf(mn, y[j]);
+            mx = __builtin_fmaxf(mx, y[j]);
+        }
+        const float lo = clip_w[k] * mn, hi = clip_w_max[k] * mx;
+        bound = 0.f;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            y[j] = clamp_lo_hi(y[j], lo, hi);
+            bound = __builtin_fmaxf(bound, __builtin_fabsf(y[j]));
+        }
+    } else {
+        float m = 0.f;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[j]));
+        bound = clip_w ? clip_w[k] * m : m;
+    }
     const uint32_t s = e8m0_of_bound(bound);
     const float sc = scale_operand(s);
     uint4 out;
@@ -71,26 +90,26 @@ prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, i
 }  // namespace
 
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
-                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, uint8_t* codes,
-                                 uint8_t* scales, hipStream_t stream) {
+                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
+                                 uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const int nb = K / 32;
     const dim3 grid((N + 255) / 256, nb), block(256);
     if (wdtype == BATQ_BF16) {
         auto Wp = static_cast<const uint16_t*>(W);
         if (t->has_transform)
             prep_weight_kernel<uint16_t, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
-                                                                           d_clip_w, codes, scales);
+                                                                           d_clip_w, d_clip_w_max, codes, scales);
         else
             prep_weight_kernel<uint16_t, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
-                                                                            d_clip_w, codes, scales);
+                                                                            d_clip_w, d_clip_w_max, codes, scales);
     } else {
         auto Wp = static_cast<const float*>(W);
         if (t->has_transform)
             prep_weight_kernel<float, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
-                                                                        d_clip_w, codes, scales);
+                                                                        d_clip_w, d_clip_w_max, codes, scales);
         else
             prep_weight_kernel<float, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
-                                                                         d_clip_w, codes, scales);
+                                                                         d_clip_w, d_clip_w_max, codes, scales);
     }
     return hipGetLastError();
 }

@@ -70,12 +70,16 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
         out = __builtin_fmaf((c3), dpp_quad<0xFF>(v), out); \
     } while (0)
 
-// GO = size of the shared factor G (4 or 8); the private factor is (32/GO) x (32/GO).
-// MODE 0: no transform; 1: transform.
+// GO = size of the outer factor (4 or 8); the inner factor is (32/GO) x (32/GO).  Block k uses
+// G + k * g_stride and P + k * p_stride (a stride of 0 = one factor shared by all blocks), which covers
+// the Global-and-Private form, the order Eq. 2 prints (private outer, shared inner) and the naive
+// Kronecker product (both private).  clip_max != null selects the two-ratio clipping of Eq. 3-4
+// (clip then holds the ratios on the block minimum).
 template <typename XT, int GO, bool TRANSFORM>
 __global__ void __launch_bounds__(256)
 quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
-               const float* __restrict__ G, const float* __restrict__ P, const float* __restrict__ clip,
+               const float* __restrict__ G, int g_stride, const float* __restrict__ P, int p_stride,
+               const float* __restrict__ clip, const float* __restrict__ clip_max,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     constexpr int GI = 32 / GO;
     const int q = threadIdx.x & 3;
@@ -91,7 +95,8 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
     float Gc[GO == 4 ? 4 : 16];
     if constexpr (TRANSFORM) {
 #pragma unroll
-        for (int i = 0; i < GI * GI; ++i) Pr[i] = P[(size_t)k * GI * GI + i];
+        for (int i = 0; i < GI * GI; ++i) Pr[i] = P[(size_t)k * p_stride + i];
+        G += (size_t)k * g_stride;
         if constexpr (GO == 4) {
             // lane q produces row a' = q of the mixed result: needs G[a][q], a = 0..3
 #pragma unroll
@@ -107,6 +112,7 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
         }
     }
     const float ck = clip[k];
+    const float ck_max = clip_max ? clip_max[k] : 0.f;
 
     const int row0 = blockIdx.y * rows_per_wg;
     const int row1 = min(M, row0 + rows_per_wg);
@@ -154,14 +160,33 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
             for (int i = 0; i < 8; ++i) y[i] = x[i];
         }
 
-        // block amax over the quad's 32 values
-        float m = __builtin_fabsf(y[0]);
+        float bound;
+        if (clip_max) {
+            // Eq. 3-4 as printed: block minimum and maximum over the quad, clamp to [r_min min, r_max max];
+            // the largest magnitude left is that of the clamped minimum or of the clamped maximum
+            float mn = y[0], mx = y[0];
 #pragma unroll
-        for (int i = 1; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(y[i]));
-        m = __builtin_fmaxf(m, dpp_quad<0xB1>(m));
-        m = __builtin_fmaxf(m, dpp_quad<0x4E>(m));
-
-        const float bound = ck * m;                     // one fp32 multiply
+            for (int i = 1; i < 8; ++i) {
+                mn = __builtin_fminf(mn, y[i]);
+                mx = __builtin_fmaxf(mx, y[i]);
+            }
+            mn = __builtin_fminf(mn, dpp_quad<0xB1>(mn));
+            mn = __builtin_fminf(mn, dpp_quad<0x4E>(mn));
+            mx = __builtin_fmaxf(mx, dpp_quad<0xB1>(mx));
+            mx = __builtin_fmaxf(mx, dpp_quad<0x4E>(mx));
+            const float lo = ck * mn, hi = ck_max * mx;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) y[i] = clamp_lo_hi(y[i], lo, hi);
+            bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)), __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
+        } else {
+            // block amax over the quad's 32 values
+            float m = __builtin_fabsf(y[0]);
+#pragma unroll
+            for (int i = 1; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(y[i]));
+            m = __builtin_fmaxf(m, dpp_quad<0xB1>(m));
+            m = __builtin_fmaxf(m, dpp_quad<0x4E>(m));
+            bound = ck * m;                             // one fp32 multiply
+        }
         const uint32_t s = e8m0_of_bound(bound);
         const uint32_t packed = encode8(y, bound, scale_operand(s));
         if (live) {
@@ -202,9 +227,12 @@ constexpr int kQuantLds = kQuantLdsCounter + 16;            // 148 KiB
 // next one is requested into the same slot; the code pieces and scale bytes of a unit are written
 // out one unit late, so that nothing waits on a store that was just issued (loads and stores share
 // one completion counter).
+// MINMAX selects the two-ratio clipping of Eq. 3-4 (clip = ratios on the block minimum, clip_max on the
+// maximum) instead of one ratio on the block amax.
+template <bool MINMAX>
 __global__ void __launch_bounds__(kQuantWaves * 64)
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int wpg,
-               const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
+               const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     extern __shared__ __align__(16) uint8_t qlds[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
@@ -348,14 +376,35 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
                     float y[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) y[r] = acc[r];
-                    float m = __builtin_fabsf(y[0]);
+                    float bound;
+                    if constexpr (MINMAX) {
+                        float mn = y[0], mx = y[0];
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
-                    // the other half of the block lives in lane ^ 32
-                    const float mo = __builtin_bit_cast(
-                        float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
-                    m = __builtin_fmaxf(m, mo);
-                    const float bound = clip[k0 + b] * m;   // one fp32 multiply
+                        for (int r = 1; r < 16; ++r) {
+                            mn = __builtin_fminf(mn, y[r]);
+                            mx = __builtin_fmaxf(mx, y[r]);
+                        }
+                        // the other half of the block lives in lane ^ 32
+                        mn = __builtin_fminf(mn, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
+                                                     (lane ^ 32) << 2, __builtin_bit_cast(int, mn))));
+                        mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
+                                                     (lane ^ 32) << 2, __builtin_bit_cast(int, mx))));
+                        const float lo = clip[k0 + b] * mn, hi = clip_max[k0 + b] * mx;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) y[r] = clamp_lo_hi(y[r], lo, hi);
+                        // the largest magnitude left is that of the clamped minimum or of the clamped maximum
+                        bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)),
+                                                __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
+                    } else {
+                        float m = __builtin_fabsf(y[0]);
+#pragma unroll
+                        for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
+                        // the other half of the block lives in lane ^ 32
+                        const float mo = __builtin_bit_cast(
+                            float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
+                        m = __builtin_fmaxf(m, mo);
+                        bound = clip[k0 + b] * m;           // one fp32 multiply
+                    }
                     const uint32_t s = e8m0_of_bound(bound);
                     const float sc = scale_operand(s);
                     out.x = encode8(y, bound, sc);
@@ -381,7 +430,10 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kQuantLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kQuantLds);
         if (e != hipSuccess) {
             cus = 0;
@@ -392,8 +444,13 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
     const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
     const int wpg = std::max(1, std::min(cus / groups, row_tiles));
     const int wgs = wpg * std::min(groups, cus);
-    quant_act_mfma<<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
-        X, ldx, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip, codes, scales);
+    const uint4* Ts = reinterpret_cast<const uint4*>(t->d_Tsplit);
+    if (t->minmax)
+        quant_act_mfma<true><<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
+            X, ldx, M, nb, wpg, Ts, t->d_clip, t->d_clip_max, codes, scales);
+    else
+        quant_act_mfma<false><<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
+            X, ldx, M, nb, wpg, Ts, t->d_clip, nullptr, codes, scales);
     return hipGetLastError();
 }
 
@@ -407,15 +464,88 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     while (rows_per_wg > 1 && (long)gx * ((M + rows_per_wg - 1) / rows_per_wg) < 2048) rows_per_wg >>= 1;
     while ((M + rows_per_wg - 1) / rows_per_wg > 65535) rows_per_wg <<= 1;      // grid.y limit
     const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
+    const float* cmax = t->minmax ? t->d_clip_max : nullptr;
     if (!t->has_transform)
-        quant_act_quad<XT, 4, false><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, nullptr,
-                                                                  t->d_clip, codes, scales);
+        quant_act_quad<XT, 4, false><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, 0, nullptr, 0,
+                                                                  t->d_clip, cmax, codes, scales);
     else if (t->g_outer == 4)
-        quant_act_quad<XT, 4, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
-                                                                 t->d_clip, codes, scales);
+        quant_act_quad<XT, 4, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+                                                                 t->outer_stride, t->d_inner, t->inner_stride,
+                                                                 t->d_clip, cmax, codes, scales);
     else
-        quant_act_quad<XT, 8, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_G, t->d_P,
-                                                                 t->d_clip, codes, scales);
+        quant_act_quad<XT, 8, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+                                                                 t->outer_stride, t->d_inner, t->inner_stride,
+                                                                 t->d_clip, cmax, codes, scales);
+    return hipGetLastError();
+}
+
+// Dense 32x32 block per MX block with fp32 input (the form Sec. 3.1.1 calls the dense P_i): one thread
+// per (row, block); T_k (fp32, 4 KiB) sits in LDS, the 32 products of an output element are
+// accumulated with fp32 fused multiply-adds in input order.  Not a tuned path: bf16 inputs of every
+// form take the matrix-core kernel.
+template <typename XT>
+__global__ void __launch_bounds__(256)
+quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const float* __restrict__ T,
+                const float* __restrict__ clip, const float* __restrict__ clip_max,
+                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    __shared__ float sT[32 * 32];
+    const int k = blockIdx.x;                               // includes the padding blocks of the last K group
+    const bool live = k < nb;
+    if (live)
+        for (int i = threadIdx.x; i < 1024; i += 256) sT[i] = T[(size_t)k * 1024 + i];
+    __syncthreads();
+    const int row = blockIdx.y * 256 + threadIdx.x;
+    if (row >= M) return;
+    if (!live) {
+        *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = uint4{0u, 0u, 0u, 0u};
+        scales[scale_index_internal(row, k, M)] = (uint8_t)127;
+        return;
+    }
+    float x[32], y[32];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, *reinterpret_cast<float(*)[8]>(x + 8 * q));
+#pragma unroll 4
+    for (int j2 = 0; j2 < 32; ++j2) {
+        float acc = x[0] * sT[j2];
+#pragma unroll
+        for (int j = 1; j < 32; ++j) acc = __builtin_fmaf(x[j], sT[j * 32 + j2], acc);
+        y[j2] = acc;
+    }
+    float bound;
+    if (clip_max) {
+        float mn = y[0], mx = y[0];
+#pragma unroll
+        for (int j = 1; j < 32; ++j) {
+            mn = __builtin_fminf(mn, y[j]);
+            mx = __builtin_fmaxf(mx, y[j]);
+        }
+        const float lo = clip[k] * mn, hi = clip_max[k] * mx;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) y[j] = clamp_lo_hi(y[j], lo, hi);
+        bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)), __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
+    } else {
+        float m = __builtin_fabsf(y[0]);
+#pragma unroll
+        for (int j = 1; j < 32; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[j]));
+        bound = clip[k] * m;
+    }
+    const uint32_t s = e8m0_of_bound(bound);
+    const float sc = scale_operand(s);
+    uint4 out;
+    out.x = encode8(y, bound, sc);
+    out.y = encode8(y + 8, bound, sc);
+    out.z = encode8(y + 16, bound, sc);
+    out.w = encode8(y + 24, bound, sc);
+    *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = out;
+    scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+}
+
+template <typename XT>
+hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes, uint8_t* scales,
+                        hipStream_t stream) {
+    const dim3 grid(scale_groups(t->nb) * 8, (M + 255) / 256), block(256);
+    quant_act_dense<XT><<<grid, block, 0, stream>>>(X, ldx, M, t->nb, t->d_T, t->d_clip,
+                                                     t->minmax ? t->d_clip_max : nullptr, codes, scales);
     return hipGetLastError();
 }
 
@@ -426,11 +556,13 @@ hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtyp
     (void)K;
     if (M == 0) return hipSuccess;
     if (xdtype == BATQ_BF16) {
-        // the matrix-core kernel addresses a 32-row tile with 32-bit byte offsets
+        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets
         if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
             return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+        if (t->form == BATQ_FORM_DENSE) return launch_dense(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
         return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
     }
+    if (t->form == BATQ_FORM_DENSE) return launch_dense(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
     return launch_quad(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
 }
 
