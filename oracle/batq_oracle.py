@@ -25,6 +25,11 @@ out x in, Sec. 3.1):
                          E2M1 elements, 32 per block, one UE8M0 scale; shared
                          exponent floor(log2 amax) - 2, round-to-nearest-even,
                          saturation at +-6.
+* ``mxfp8_quantize``   - the same definition for MXFP8 with E4M3 elements, the
+                         variant Sec. 2 adopts for 8-bit activations (W4A8):
+                         shared exponent floor(log2 amax) - 8, saturation at
+                         +-448; ``gemm_a8w4`` multiplies such activations with
+                         MXFP4 weights.
 * ``prepare_weight``   - Alg. 2 "Offline Fusion" (inverse transform of W,
                          clip, quantise).
 * ``gemm`` / ``linear``- the objective of Sec. 3.1, Q(XP) Q(P^-1 W^T).
@@ -216,6 +221,73 @@ def quantize_clipped(Xc: np.ndarray, bound: np.ndarray) -> tuple[np.ndarray, np.
     v = np.asarray(Xc, dtype=np.float64) * np.exp2(-E.astype(np.float64))[:, :, None]   # exact
     codes = e2m1_encode(v, np.signbit(Xc))
     return codes, (E + E8M0_BIAS).astype(np.uint8)
+
+
+# --------------------------------------------------------------------------- MXFP8 (E4M3) activations
+E4M3_EMAX = 8          # largest E4M3 value 448 = 1.75 * 2**8
+E4M3_MAX = 448.0
+
+
+def e4m3_value(code: np.ndarray) -> np.ndarray:
+    """Value of an 8-bit S|EEEE|MMM code, exponent bias 7; S.1111.111 (NaN) is never produced and
+    decodes to NaN."""
+    c = np.asarray(code, dtype=np.int64)
+    e, m = (c >> 3) & 15, c & 7
+    mag = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2(e - 7.0))
+    mag = np.where((c & 0x7F) == 0x7F, np.nan, mag)
+    return np.where(c & 0x80, -mag, mag)
+
+
+_E4M3_GRID = e4m3_value(np.arange(127))     # the 127 finite non-negative values, ascending, index = code
+
+
+def e4m3_encode(v: np.ndarray, negative: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 magnitude code of |v| (ties to the even code, saturating at 448), sign in bit 7."""
+    mag = np.minimum(np.abs(np.asarray(v, dtype=np.float64)), E4M3_MAX)
+    hi = np.clip(np.searchsorted(_E4M3_GRID, mag, side="left"), 1, 126)      # first grid value >= mag
+    lo = hi - 1
+    dl, dh = mag - _E4M3_GRID[lo], _E4M3_GRID[hi] - mag
+    code = np.where(dl < dh, lo, np.where(dh < dl, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(mag == 0, 0, code)
+    return (code | (np.asarray(negative, dtype=np.int64) << 7)).astype(np.uint8)
+
+
+def mxfp8_quantize(Xt32: np.ndarray, clip=None) -> tuple[np.ndarray, np.ndarray]:
+    """fp32 [R, K] -> (E4M3 codes u8 [R, K], E8M0 scales u8 [R, K/32]): symmetric clip as for MXFP4,
+    shared exponent E = floor(log2 bound) - 8 clamped to [-127, 127], round to nearest even, saturate."""
+    Xc, bound = clip_blocks(Xt32, clip)
+    b = np.asarray(bound, dtype=np.float64)
+    _, e = np.frexp(b)
+    E = np.clip(np.where(b > 0, e - 1 - E4M3_EMAX, -E8M0_BIAS), -127, 127).astype(np.int64)
+    v = np.asarray(Xc, dtype=np.float64) * np.exp2(-E.astype(np.float64))[:, :, None]     # exact
+    codes = e4m3_encode(v, np.signbit(Xc))
+    return codes.reshape(Xc.shape[0], -1), (E + E8M0_BIAS).astype(np.uint8)
+
+
+def dequantize_fp8(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """(E4M3 codes [R, K], scales [R, K/32]) -> fp64 [R, K]."""
+    s = np.exp2(np.asarray(scales, dtype=np.float64) - E8M0_BIAS)
+    return e4m3_value(codes) * np.repeat(s, BLOCK, axis=1)
+
+
+def quantize_act_fp8(X: np.ndarray, T, clip=None, chunk: int = 512) -> tuple[np.ndarray, np.ndarray]:
+    """Online activation path with MXFP8 output for dense blocks T [nb, 32, 32] (None = identity)."""
+    X = np.asarray(X)
+    cs, ss = [], []
+    for r0 in range(0, X.shape[0], chunk):
+        Xr = X[r0:r0 + chunk]
+        Xt = np.asarray(Xr, np.float64).astype(np.float32) if T is None else apply_blocks(Xr, T).astype(np.float32)
+        c, s_ = mxfp8_quantize(Xt, clip)
+        cs.append(c)
+        ss.append(s_)
+    if not cs:
+        return (np.zeros((0, X.shape[1]), np.uint8), np.zeros((0, X.shape[1] // BLOCK), np.uint8))
+    return np.concatenate(cs), np.concatenate(ss)
+
+
+def gemm_a8w4(xcodes8, xscales, wcodes, wscales) -> np.ndarray:
+    """Y[m, n] = sum_k dq8(x)[m, k] * dq4(w)[n, k] in fp64 (MXFP8 activations, MXFP4 weights)."""
+    return dequantize_fp8(xcodes8, xscales) @ dequantize(wcodes, wscales).T
 
 
 def pack_codes(codes: np.ndarray) -> np.ndarray:
