@@ -219,6 +219,34 @@ batq_status batq_linear(const batq_transform* t, const batq_weight* w,
                         void* Y, batq_dtype ydtype, int64_t ldy,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------
+ * W4A8: MXFP8 activations (E4M3 elements, the 8-bit variant Sec. 2 adopts) against the same MXFP4
+ * weights.  Same transform, clipping and scale layout as above; the shared exponent is
+ * E = clamp(floor(log2 bound) - 8, -127, 127), elements round to nearest even on the E4M3 grid
+ * (1 sign, 4 exponent bits with bias 7, 3 mantissa bits) and saturate at 448; the code 0x7F / 0xFF
+ * (NaN) is never produced.  One byte per element.
+ * Device order of 8-bit codes: batq_code8_bytes(rows, K) bytes in the same 1 KiB pieces of 16 rows x
+ * 64 bytes as the 4-bit codes, a piece now covering 2 MX blocks; elements 16h .. 16h+15 (h = 0, 1) of
+ * block k of `row` are the 16 bytes at batq_code8_slot_offset(row, k, h, K)
+ *   = ((row/16) * S8 + k/2) * 1024 + (row%16) * 64 + (((2*(k%2) + h) ^ ((row%16)/4)) * 16),
+ * S8 = 4 * ceil(K/256); rows padded to 32, K zero-padded to 256.  Row-major order: [rows][K].
+ * Alignment and error rules as for the 4-bit calls. */
+batq_status batq_quantize_act_mxfp8(const batq_transform* t, const void* X, batq_dtype xdtype,
+                                    int M, int K, int64_t ldx,
+                                    uint8_t* codes8, uint8_t* scales, void* stream);
+size_t batq_code8_bytes(int rows, int K);
+size_t batq_code8_slot_offset(int row, int k, int half, int K);
+batq_status batq_codes8_to_rowmajor(const uint8_t* device_order, uint8_t* rowmajor, int rows, int K, void* stream);
+batq_status batq_codes8_from_rowmajor(const uint8_t* rowmajor, uint8_t* device_order, int rows, int K, void* stream);
+/* Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} e4m3(xq8[m][32k+j]) val(wq[n][32k+j]) */
+batq_status batq_gemm_a8w4(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w,
+                           int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+size_t batq_linear_a8w4_workspace(int M, int K);
+batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w,
+                             const void* X, batq_dtype xdtype, int M, int64_t ldx,
+                             void* Y, batq_dtype ydtype, int64_t ldy,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

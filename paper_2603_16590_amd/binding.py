@@ -51,6 +51,14 @@ SYMBOLS = {
     "batq_gemm_mxfp4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
     "batq_linear_workspace": (_sz, [_i, _i]),
     "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_quantize_act_mxfp8": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp]),
+    "batq_code8_bytes": (_sz, [_i, _i]),
+    "batq_code8_slot_offset": (_sz, [_i, _i, _i, _i]),
+    "batq_codes8_to_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
+    "batq_codes8_from_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
+    "batq_gemm_a8w4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
+    "batq_linear_a8w4_workspace": (_sz, [_i, _i]),
+    "batq_linear_a8w4": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
 }
 
 
@@ -334,4 +342,73 @@ def batq_linear(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspace=No
                            X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
                            Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
                            workspace.numel(), _stream()), "batq_linear")
+    return Y
+
+
+# ---- W4A8: MXFP8 (E4M3) activations against the same MXFP4 weights
+def batq_code8_bytes(rows: int, K: int) -> int:
+    return int(lib.batq_code8_bytes(rows, K))
+
+
+def batq_quantize_act_mxfp8(t: Transform, X, codes8=None, scales=None):
+    """X: M x K device tensor. Returns (codes8, scales): flat uint8 tensors in device order."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if codes8 is None:
+        codes8 = torch.empty((batq_code8_bytes(M, K),), dtype=torch.uint8, device=X.device)
+    if scales is None:
+        scales = torch.empty((batq_scale_bytes(M, K),), dtype=torch.uint8, device=X.device)
+    ldx = X.stride(0) if M > 1 else max(K, X.stride(0))
+    _check(lib.batq_quantize_act_mxfp8(t.handle, X.data_ptr(), _dtype_code(X), M, K, ldx, codes8.data_ptr(),
+                                       scales.data_ptr(), _stream()), "batq_quantize_act_mxfp8")
+    return codes8, scales
+
+
+def batq_codes8_to_rowmajor(codes8, rows: int, K: int):
+    """Device-order 8-bit codes -> [rows, K] uint8 tensor."""
+    import torch
+    out = torch.empty((rows, K), dtype=torch.uint8, device=codes8.device)
+    _check(lib.batq_codes8_to_rowmajor(codes8.data_ptr(), out.data_ptr(), rows, K, _stream()), "batq_codes8_to_rowmajor")
+    return out
+
+
+def batq_codes8_from_rowmajor(rowmajor):
+    """[rows, K] uint8 tensor -> flat device-order 8-bit codes (K padding zeroed)."""
+    import torch
+    assert rowmajor.is_contiguous()
+    rows, K = rowmajor.shape
+    out = torch.empty((batq_code8_bytes(rows, K),), dtype=torch.uint8, device=rowmajor.device)
+    _check(lib.batq_codes8_from_rowmajor(rowmajor.data_ptr(), out.data_ptr(), rows, K, _stream()),
+           "batq_codes8_from_rowmajor")
+    return out
+
+
+def batq_gemm_a8w4(xcodes8, xscales, w: Weight, M: int, out_dtype=None, Y=None):
+    import torch
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes8.device)
+    _check(lib.batq_gemm_a8w4(xcodes8.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                              Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_a8w4")
+    return Y
+
+
+def batq_linear_a8w4_workspace(M: int, K: int) -> int:
+    return int(lib.batq_linear_a8w4_workspace(M, K))
+
+
+def batq_linear_a8w4(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspace=None):
+    """Y = Q8(X P) Q4(P^-1 W): MXFP8 activations, MXFP4 weights."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
+    need = batq_linear_a8w4_workspace(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+    _check(lib.batq_linear_a8w4(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
+                                X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
+                                Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
+                                workspace.numel(), _stream()), "batq_linear_a8w4")
     return Y

@@ -407,8 +407,12 @@ batq_status batq_weight_destroy(batq_weight* w) {
     return BATQ_OK;
 }
 
-batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                              int64_t ldx, uint8_t* codes, uint8_t* scales, void* stream) {
+}  // extern "C"
+
+namespace {
+
+batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K, int64_t ldx,
+                          uint8_t* codes, uint8_t* scales, bool fp8, void* stream) {
     if (!t) return BATQ_ERR_NULL;
     if (!dtype_ok(xdtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || K <= 0 || K % 32 != 0 || ldx < K) return BATQ_ERR_SHAPE;
@@ -419,11 +423,96 @@ batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype
     if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes) ||
         (reinterpret_cast<uintptr_t>(scales) & 7u) != 0)
         return BATQ_ERR_SHAPE;
-    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, static_cast<hipStream_t>(stream)) !=
+    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, codes, scales, fp8, static_cast<hipStream_t>(stream)) !=
         hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
+    return BATQ_OK;
+}
+
+batq_status gemm_impl(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
+                      batq_dtype ydtype, int64_t ldy, bool a8, void* stream) {
+    if (!w) return BATQ_ERR_NULL;
+    if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
+    if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M == 0) return BATQ_OK;
+    if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
+    if (!aligned16(xcodes) || (reinterpret_cast<uintptr_t>(xscales) & 7u) != 0) return BATQ_ERR_SHAPE;
+    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, a8, static_cast<hipStream_t>(stream)) !=
+        hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return BATQ_OK;
+}
+
+size_t workspace_impl(int M, int K, bool a8) {
+    if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
+    // activation codes (blocked layout, a multiple of 1 KiB) followed by their grouped scales
+    return (a8 ? batq::code8_bytes_blocked(M, K / 32) : batq::code_bytes_blocked(M, K / 32)) +
+           batq::scale_bytes_internal(M, K / 32);
+}
+
+batq_status linear_impl(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
+                        int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
+                        size_t workspace_bytes, bool a8, void* stream) {
+    if (!t || !w) return BATQ_ERR_NULL;
+    if (!dtype_ok(xdtype) || !dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
+    if (t->K != w->K) return BATQ_ERR_MISMATCH;
+    if (M < 0 || ldx < t->K || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M == 0) return BATQ_OK;
+    if (!X || !Y || !workspace) return BATQ_ERR_NULL;
+    if (workspace_bytes < workspace_impl(M, t->K, a8)) return BATQ_ERR_WORKSPACE;
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace)) return BATQ_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* codes = static_cast<uint8_t*>(workspace);
+    uint8_t* scales = codes + (a8 ? batq::code8_bytes_blocked(M, t->nb) : batq::code_bytes_blocked(M, t->nb));
+    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, a8, s);
+    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, s);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return BATQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                              int64_t ldx, uint8_t* codes, uint8_t* scales, void* stream) {
+    return quantize_impl(t, X, xdtype, M, K, ldx, codes, scales, false, stream);
+}
+
+batq_status batq_quantize_act_mxfp8(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                                    int64_t ldx, uint8_t* codes8, uint8_t* scales, void* stream) {
+    return quantize_impl(t, X, xdtype, M, K, ldx, codes8, scales, true, stream);
+}
+
+size_t batq_code8_bytes(int rows, int K) {
+    if (rows <= 0 || K <= 0 || K % 32 != 0) return 0;
+    return batq::code8_bytes_blocked(rows, K / 32);
+}
+
+size_t batq_code8_slot_offset(int row, int k, int half, int K) { return batq::code8_slot_offset(row, k, half, K / 32); }
+
+batq_status batq_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!blocked || !rowmajor) return BATQ_ERR_NULL;
+    if (!aligned16(blocked) || !aligned16(rowmajor)) return BATQ_ERR_SHAPE;
+    BATQ_HIP(batq::launch_codes8_to_rowmajor(blocked, rowmajor, rows, K / 32, static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
+}
+
+batq_status batq_codes8_from_rowmajor(const uint8_t* rowmajor, uint8_t* blocked, int rows, int K, void* stream) {
+    if (rows < 0 || K <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
+    if (rows == 0) return BATQ_OK;
+    if (!blocked || !rowmajor) return BATQ_ERR_NULL;
+    if (!aligned16(blocked) || !aligned16(rowmajor)) return BATQ_ERR_SHAPE;
+    BATQ_HIP(batq::launch_codes8_to_blocked(rowmajor, blocked, rows, K / 32, static_cast<hipStream_t>(stream)));
     return BATQ_OK;
 }
 
@@ -477,47 +566,27 @@ batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped,
 
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                             batq_dtype ydtype, int64_t ldy, void* stream) {
-    if (!w) return BATQ_ERR_NULL;
-    if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
-    if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
-    if (M == 0) return BATQ_OK;
-    if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
-    if (!aligned16(xcodes) || (reinterpret_cast<uintptr_t>(xscales) & 7u) != 0) return BATQ_ERR_SHAPE;
-    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, static_cast<hipStream_t>(stream)) !=
-        hipSuccess) {
-        (void)hipGetLastError();
-        return BATQ_ERR_DEVICE;
-    }
-    return BATQ_OK;
+    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, stream);
 }
 
-size_t batq_linear_workspace(int M, int K) {
-    if (M <= 0 || K <= 0 || K % 32 != 0) return 0;
-    // activation codes (blocked layout, a multiple of 1 KiB) followed by their grouped scales
-    return batq::code_bytes_blocked(M, K / 32) + batq::scale_bytes_internal(M, K / 32);
+batq_status batq_gemm_a8w4(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
+                           batq_dtype ydtype, int64_t ldy, void* stream) {
+    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, stream);
 }
+
+size_t batq_linear_workspace(int M, int K) { return workspace_impl(M, K, false); }
+size_t batq_linear_a8w4_workspace(int M, int K) { return workspace_impl(M, K, true); }
 
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                         int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                         size_t workspace_bytes, void* stream) {
-    if (!t || !w) return BATQ_ERR_NULL;
-    if (!dtype_ok(xdtype) || !dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
-    if (t->K != w->K) return BATQ_ERR_MISMATCH;
-    if (M < 0 || ldx < t->K || ldy < w->N) return BATQ_ERR_SHAPE;
-    if (M == 0) return BATQ_OK;
-    if (!X || !Y || !workspace) return BATQ_ERR_NULL;
-    if (workspace_bytes < batq_linear_workspace(M, t->K)) return BATQ_ERR_WORKSPACE;
-    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace)) return BATQ_ERR_SHAPE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    uint8_t* codes = static_cast<uint8_t*>(workspace);
-    uint8_t* scales = codes + batq::code_bytes_blocked(M, t->nb);
-    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, codes, scales, s);
-    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, s);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return BATQ_ERR_DEVICE;
-    }
-    return BATQ_OK;
+    return linear_impl(t, w, X, xdtype, M, ldx, Y, ydtype, ldy, workspace, workspace_bytes, false, stream);
+}
+
+batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
+                             int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    return linear_impl(t, w, X, xdtype, M, ldx, Y, ydtype, ldy, workspace, workspace_bytes, true, stream);
 }
 
 }  // extern "C"

@@ -38,10 +38,10 @@ struct batq_weight {
 namespace batq {
 
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
-// Codes are written in the blocked layout of code_layout.h, scales in the grouped layout of
-// scale_layout.h (padding blocks of the last K group included).
+// Codes are written in the blocked layout of code_layout.h (fp8: MXFP8 codes in its 8-bit variant),
+// scales in the grouped layout of scale_layout.h (padding blocks of the last K group included).
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
                                  int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
                                  uint8_t* codes, uint8_t* scales, hipStream_t stream);
@@ -49,7 +49,9 @@ hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dt
 // Weight scales are written in the internal layout (pad bytes must have been set to 127).
 // xscales_internal: activation scales in the grouped layout.
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream);
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream);
+hipError_t launch_codes8_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);
+hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream);
 hipError_t launch_scales_to_internal(const uint8_t* canon, uint8_t* internal, int rows, int nb, hipStream_t stream);

@@ -32,4 +32,19 @@ __host__ __device__ inline size_t code_chunk_offset(int row, int k, int nb) {
            (size_t)(((k & 3) ^ ((r >> 2) & 3)) << 4);
 }
 
+// ---- MXFP8 activation codes (1 byte per element): the same 1 KiB pieces of 16 rows x 64 bytes, a piece
+// now covering 64 K elements = 2 MX blocks; the 32 bytes of a block are two 16-byte slots
+// (elements 0-15 and 16-31), slot q = 2 (k % 2) + h of row r stored at q ^ ((r / 4) % 4).
+__host__ __device__ inline int code8_stages(int nb) { return ((nb + 7) >> 3) << 2; }     // Kp / 64
+
+__host__ __device__ inline size_t code8_bytes_blocked(int rows, int nb) {
+    return (size_t)(((rows + 31) >> 5) << 1) * (size_t)code8_stages(nb) * 1024;
+}
+
+__host__ __device__ inline size_t code8_slot_offset(int row, int k, int h, int nb) {
+    const int r = row & 15;
+    return ((size_t)(row >> 4) * (size_t)code8_stages(nb) + (size_t)(k >> 1)) * 1024 + (size_t)r * 64 +
+           (size_t)((((k & 1) << 1 | h) ^ ((r >> 2) & 3)) << 4);
+}
+
 }  // namespace batq

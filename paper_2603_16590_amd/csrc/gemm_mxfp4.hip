@@ -42,6 +42,21 @@ __device__ __forceinline__ v8i frag(const uint4 v) {
     return v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
 }
 
+// FP8 (E4M3) operand of one lane (verified on the device with one-hot operands): registers 0-3 hold
+// elements 16 kg .. 16 kg + 15 of the instruction's first MX block, registers 4-7 the same elements of
+// its second block (kg = lane / 32); the lane's scale byte is still that of block kg.
+__device__ __forceinline__ v8i frag8(const uint4 lo, const uint4 hi) {
+    return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+}
+
+// One block-scaled matrix instruction; A8 = the A operand is MXFP8 (cbsz 0) instead of MXFP4 (cbsz 4);
+// the B operand (weights) is always MXFP4.
+template <bool A8, int OPSEL>
+__device__ __forceinline__ v16f mx_mfma(const v8i a, const v8i b, const v16f c, int sa, int sb) {
+    if constexpr (A8) return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 4, OPSEL, sa, OPSEL, sb);
+    else return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 4, 4, OPSEL, sa, OPSEL, sb);
+}
+
 // ------------------------------------------------------------------------------------------
 // canonical [rows][nb]  <->  internal group-major scale layout
 __global__ void __launch_bounds__(256)
@@ -86,8 +101,31 @@ codes_to_rowmajor(const uint8_t* __restrict__ blocked, uint8_t* __restrict__ row
     }
 }
 
+// 8-bit codes: row-major [rows][nb*32]  <->  blocked 8-bit layout (one thread per 16-byte slot)
+__global__ void __launch_bounds__(256)
+codes8_to_blocked(const uint8_t* __restrict__ rowmajor, uint8_t* __restrict__ blocked, int rows, int nb) {
+    const int nbp = scale_groups(nb) * 8;
+    const size_t total = (size_t)rows * nbp * 2;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int row = (int)(i / (2 * nbp)), kh = (int)(i % (2 * nbp)), k = kh >> 1, h = kh & 1;
+        uint4 v = {0, 0, 0, 0};
+        if (k < nb) v = *reinterpret_cast<const uint4*>(rowmajor + ((size_t)row * nb + k) * 32 + h * 16);
+        *reinterpret_cast<uint4*>(blocked + code8_slot_offset(row, k, h, nb)) = v;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+codes8_to_rowmajor(const uint8_t* __restrict__ blocked, uint8_t* __restrict__ rowmajor, int rows, int nb) {
+    const size_t total = (size_t)rows * nb * 2;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int row = (int)(i / (2 * nb)), kh = (int)(i % (2 * nb));
+        *reinterpret_cast<uint4*>(rowmajor + i * 16) =
+            *reinterpret_cast<const uint4*>(blocked + code8_slot_offset(row, kh >> 1, kh & 1, nb));
+    }
+}
+
 // ------------------------------------------------------------------------------------------
-template <typename YT>
+template <typename YT, bool A8>
 __global__ void __launch_bounds__(256)
 gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
             const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy) {
@@ -99,25 +137,33 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
     const int am = min(m0 + i, M - 1), bn = min(n0 + i, N - 1);   // rows past the edge are computed, not stored
     v16f acc = {};
     const int steps = nb >> 1;
+    auto load_a = [&](int k) -> v8i {
+        if constexpr (A8)   // half kg of both blocks of the step (K is zero-padded to whole groups)
+            return frag8(*reinterpret_cast<const uint4*>(xc + code8_slot_offset(am, k & ~1, kg, nb)),
+                         *reinterpret_cast<const uint4*>(xc + code8_slot_offset(am, k | 1, kg, nb)));
+        else
+            return frag(*reinterpret_cast<const uint4*>(xc + code_chunk_offset(am, k, nb)));
+    };
     for (int s = 0; s < steps; ++s) {
-        const uint4 a = *reinterpret_cast<const uint4*>(xc + code_chunk_offset(am, 2 * s + kg, nb));
+        const v8i a = load_a(2 * s + kg);
         const uint4 b = *reinterpret_cast<const uint4*>(wc + code_chunk_offset(bn, 2 * s + kg, nb));
         const int sa = xs[scale_index_internal(am, 2 * s + kg, M)];
         const int sb = ws[scale_index_internal(bn, 2 * s + kg, N)];
-        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, 0, sa, 0, sb);
+        acc = mx_mfma<A8, 0>(a, frag(b), acc, sa, sb);
     }
     if (nb & 1) {
         // odd block count: the upper half-wave contributes an all-zero operand
         const int s = steps;
-        uint4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+        v8i a = {0, 0, 0, 0, 0, 0, 0, 0};
+        uint4 b = {0, 0, 0, 0};
         int sa = 127, sb = 127;
+        if (A8 || kg == 0) a = load_a(2 * s);              // 8-bit: every lane holds half of the last block
         if (kg == 0) {
-            a = *reinterpret_cast<const uint4*>(xc + code_chunk_offset(am, 2 * s, nb));
             b = *reinterpret_cast<const uint4*>(wc + code_chunk_offset(bn, 2 * s, nb));
             sa = xs[scale_index_internal(am, 2 * s, M)];
             sb = ws[scale_index_internal(bn, 2 * s, N)];
         }
-        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, 0, sa, 0, sb);
+        acc = mx_mfma<A8, 0>(a, frag(b), acc, sa, sb);
     }
     const int col = n0 + i;
     if (col < N) {
@@ -138,7 +184,8 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 // operands, so there is no K tail.
 constexpr int kSkinnyWaves = 8;
 
-template <typename YT, int RT>      // RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads
+// RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads; A8 = MXFP8 activations
+template <typename YT, int RT, bool A8>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
             const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy) {
@@ -159,23 +206,34 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
     for (int t = 0; t < RT; ++t) {
         am[t] = min(32 * t + i, M - 1);
         const int ra = am[t] & 15;
-        pa[t] = xc + (size_t)(am[t] >> 4) * code_stages(nb) * 1024 + ra * 64;
+        pa[t] = xc + (size_t)(am[t] >> 4) * (A8 ? code8_stages(nb) : code_stages(nb)) * 1024 + ra * 64;
         swa[t] = (ra >> 2) & 3;
     }
+    constexpr int AR = A8 ? 2 : 1;                          // 16-byte slots of A per lane and matrix instruction
     v16f acc[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) acc[t] = v16f{};
     // operands of group g are fetched while group g-1 is multiplied
-    uint4 a[RT][4], b[4], an[RT][4], bn4[4];
+    uint4 a[RT][4][AR], b[4], an[RT][4][AR], bn4[4];
     int sa[RT], sb = 0, san[RT], sbn = 0;
-    auto load_group = [&](int g, uint4 (&ga)[RT][4], uint4 (&gb)[4], int (&gsa)[RT], int& gsb) {
+    auto load_group = [&](int g, uint4 (&ga)[RT][4][AR], uint4 (&gb)[4], int (&gsa)[RT], int& gsb) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int piece = 2 * g + (j >> 1), slot = 2 * (j & 1) + kg;
             gb[j] = *reinterpret_cast<const uint4*>(pb + (size_t)piece * 1024 + ((slot ^ swb) << 4));
 #pragma unroll
-            for (int t = 0; t < RT; ++t)
-                ga[t][j] = *reinterpret_cast<const uint4*>(pa[t] + (size_t)piece * 1024 + ((slot ^ swa[t]) << 4));
+            for (int t = 0; t < RT; ++t) {
+                if constexpr (A8) {
+                    // 8-bit pieces hold the 2 blocks of one matrix instruction: piece 4 g + j, and the lane takes
+                    // elements 16 kg .. 16 kg + 15 of both (slots kg and 2 + kg)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        ga[t][j][h] = *reinterpret_cast<const uint4*>(pa[t] + (size_t)(4 * g + j) * 1024 +
+                                                                     (((2 * h + kg) ^ swa[t]) << 4));
+                } else {
+                    ga[t][j][0] = *reinterpret_cast<const uint4*>(pa[t] + (size_t)piece * 1024 + ((slot ^ swa[t]) << 4));
+                }
+            }
         }
         // byte j of the dword at 4 kg of the row's scale word is the scale of block 8 g + 2 j + kg
         gsb = *reinterpret_cast<const int*>(ws + ((size_t)g * N + bn) * 8 + 4 * kg);
@@ -185,18 +243,24 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
     if (g_begin < g_end) load_group(g_begin, a, b, sa, sb);
     for (int g = g_begin; g < g_end; ++g) {
         if (g + 1 < g_end) load_group(g + 1, an, bn4, san, sbn);
+        auto afrag = [&](int t, int j) -> v8i {
+            if constexpr (A8) return frag8(a[t][j][0], a[t][j][1]);
+            else return frag(a[t][j][0]);
+        };
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][0]), frag(b[0]), acc[t], 4, 4, 0, sa[t], 0, sb);
-            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][1]), frag(b[1]), acc[t], 4, 4, 1, sa[t], 1, sb);
-            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][2]), frag(b[2]), acc[t], 4, 4, 2, sa[t], 2, sb);
-            acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a[t][3]), frag(b[3]), acc[t], 4, 4, 3, sa[t], 3, sb);
+            acc[t] = mx_mfma<A8, 0>(afrag(t, 0), frag(b[0]), acc[t], sa[t], sb);
+            acc[t] = mx_mfma<A8, 1>(afrag(t, 1), frag(b[1]), acc[t], sa[t], sb);
+            acc[t] = mx_mfma<A8, 2>(afrag(t, 2), frag(b[2]), acc[t], sa[t], sb);
+            acc[t] = mx_mfma<A8, 3>(afrag(t, 3), frag(b[3]), acc[t], sa[t], sb);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             b[j] = bn4[j];
 #pragma unroll
-            for (int t = 0; t < RT; ++t) a[t][j] = an[t][j];
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int h = 0; h < AR; ++h) a[t][j][h] = an[t][j][h];
         }
         sb = sbn;
 #pragma unroll
@@ -697,12 +761,14 @@ int choose_bands(int M, int N, int strips_n) {
     return best;
 }
 
-template <typename YT>
+// A8: the activation codes are MXFP8 in the blocked 8-bit layout.
+template <typename YT, bool A8>
 hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight* w, int M, YT* Y, int64_t ldy,
                         hipStream_t stream) {
     const int N = w->N, nb = w->nb;
-    const bool fits32 = code_bytes_blocked(M, nb) < (1ull << 31) && code_bytes_blocked(N, nb) < (1ull << 31);
-    if (M > 64 && fits32) {
+    const size_t xbytes = A8 ? code8_bytes_blocked(M, nb) : code_bytes_blocked(M, nb);
+    const bool fits32 = xbytes < (1ull << 31) && code_bytes_blocked(N, nb) < (1ull << 31);
+    if (M > 64 && fits32 && !A8) {
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
@@ -723,11 +789,13 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
                                                                             pl, Y, ldy);
     } else if (M <= 64) {
         const dim3 grid((N + 31) / 32), block(kSkinnyWaves * 64);
-        if (M <= 32) gemm_skinny<YT, 1><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
-        else gemm_skinny<YT, 2><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+        if (M <= 32)
+            gemm_skinny<YT, 1, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+        else
+            gemm_skinny<YT, 2, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
     } else {
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
-        gemm_direct<YT><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+        gemm_direct<YT, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
     }
     return hipGetLastError();
 }
@@ -762,12 +830,31 @@ hipError_t launch_codes_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, i
     return hipGetLastError();
 }
 
+hipError_t launch_codes8_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream) {
+    const size_t total = (size_t)rows * scale_groups(nb) * 16;
+    const int grid = (int)std::min<size_t>((total + 255) / 256, 8192);
+    codes8_to_blocked<<<grid, 256, 0, stream>>>(rowmajor, blocked, rows, nb);
+    return hipGetLastError();
+}
+
+hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream) {
+    const size_t total = (size_t)rows * nb * 2;
+    const int grid = (int)std::min<size_t>((total + 255) / 256, 8192);
+    codes8_to_rowmajor<<<grid, 256, 0, stream>>>(blocked, rowmajor, rows, nb);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, hipStream_t stream) {
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream) {
     if (M == 0) return hipSuccess;
-    if (ydtype == BATQ_BF16)
-        return launch_typed<uint16_t>(xcodes, xscales_internal, w, M, static_cast<uint16_t*>(Y), ldy, stream);
-    return launch_typed<float>(xcodes, xscales_internal, w, M, static_cast<float*>(Y), ldy, stream);
+    if (ydtype == BATQ_BF16) {
+        uint16_t* Yp = static_cast<uint16_t*>(Y);
+        return a8 ? launch_typed<uint16_t, true>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
+                  : launch_typed<uint16_t, false>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+    }
+    float* Yp = static_cast<float*>(Y);
+    return a8 ? launch_typed<float, true>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
+              : launch_typed<float, false>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
 }
 
 }  // namespace batq

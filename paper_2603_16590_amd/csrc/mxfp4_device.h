@@ -1,5 +1,6 @@
-// Device-side MXFP4 encoding helpers (Sec. 2 of the paper: E2M1 elements, one UE8M0
-// scale per 32 elements), written for gfx950's scaled fp32->fp4 convert instruction.
+// Device-side MX encoding helpers (Sec. 2 of the paper: E2M1 elements for MXFP4, E4M3 for MXFP8,
+// one UE8M0 scale per 32 elements), written for gfx950's scaled fp32->fp4 / fp32->fp8 convert
+// instructions.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -42,6 +43,29 @@ __device__ __forceinline__ uint32_t encode8(const float* y, float bound, float s
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[4], b), clamp_keep_sign(y[5], b), sc, 2);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, clamp_keep_sign(y[6], b), clamp_keep_sign(y[7], b), sc, 3);
     return r;
+}
+
+// ---- MXFP8 (E4M3 elements, the 8-bit activation format of Sec. 2): E = floor(log2 bound) - 8.
+__device__ __forceinline__ uint32_t e8m0_of_bound_fp8(float bound) {
+    uint32_t field = __float_as_uint(bound) >> 23;
+    return field > 8u ? field - 8u : 0u;
+}
+
+typedef short batq_v2s __attribute__((ext_vector_type(2)));
+
+// Eight fp32 values -> eight E4M3 codes in two dwords, element 0 in the lowest byte.  The hardware
+// convert rounds to nearest even and keeps the sign of zero, but turns magnitudes from 480 * 2^E up
+// into the NaN code, so the clamp limit is the smaller of the block's bound and 448 * 2^E
+// (= 1.75 * 2^(byte - 119)).
+__device__ __forceinline__ uint2 encode8_fp8(const float* y, float bound, uint32_t e8m0, float sc) {
+    const float top = 1.75f * __uint_as_float((e8m0 + 8u) << 23);
+    const float b = clamp_limit(__builtin_fminf(bound, top));
+    batq_v2s lo = {0, 0}, hi = {0, 0};
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(lo, clamp_keep_sign(y[0], b), clamp_keep_sign(y[1], b), sc, false);
+    lo = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(lo, clamp_keep_sign(y[2], b), clamp_keep_sign(y[3], b), sc, true);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(hi, clamp_keep_sign(y[4], b), clamp_keep_sign(y[5], b), sc, false);
+    hi = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(hi, clamp_keep_sign(y[6], b), clamp_keep_sign(y[7], b), sc, true);
+    return uint2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }

@@ -75,7 +75,8 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
 // the Global-and-Private form, the order Eq. 2 prints (private outer, shared inner) and the naive
 // Kronecker product (both private).  clip_max != null selects the two-ratio clipping of Eq. 3-4
 // (clip then holds the ratios on the block minimum).
-template <typename XT, int GO, bool TRANSFORM>
+// FP8 selects MXFP8 (E4M3) output, one byte per element in the blocked 8-bit code layout.
+template <typename XT, int GO, bool TRANSFORM, bool FP8>
 __global__ void __launch_bounds__(256)
 quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
                const float* __restrict__ G, int g_stride, const float* __restrict__ P, int p_stride,
@@ -187,15 +188,28 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
             m = __builtin_fmaxf(m, dpp_quad<0x4E>(m));
             bound = ck * m;                             // one fp32 multiply
         }
-        const uint32_t s = e8m0_of_bound(bound);
-        const uint32_t packed = encode8(y, bound, scale_operand(s));
-        if (live) {
-            *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, k, nb) + q * 4) = packed;
-            if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
-        } else if (pad) {
-            // padding blocks up to the next multiple of 8: zero codes, neutral scale
-            *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, kpad, nb) + q * 4) = 0u;
-            if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+        if constexpr (FP8) {
+            // the lane's 8 codes are bytes 8 (q % 2) .. + 7 of 16-byte slot q / 2 of the block
+            const uint32_t s = e8m0_of_bound_fp8(bound);
+            const uint2 packed = encode8_fp8(y, bound, s, scale_operand(s));
+            if (live) {
+                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row, k, q >> 1, nb) + (q & 1) * 8) = packed;
+                if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+            } else if (pad) {
+                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row, kpad, q >> 1, nb) + (q & 1) * 8) = uint2{0u, 0u};
+                if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+            }
+        } else {
+            const uint32_t s = e8m0_of_bound(bound);
+            const uint32_t packed = encode8(y, bound, scale_operand(s));
+            if (live) {
+                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, k, nb) + q * 4) = packed;
+                if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+            } else if (pad) {
+                // padding blocks up to the next multiple of 8: zero codes, neutral scale
+                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, kpad, nb) + q * 4) = 0u;
+                if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+            }
         }
     }
 }
@@ -207,15 +221,22 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // Lane layout of the pre-split transform operand (built by the host, see batq_api.hip):
 //   Tsplit[k][term][half][lane] = 8 bf16: T_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)], e = 0..7,
 //   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3); terms 0, 1, 2 = hi, mid, lo.
-constexpr int kQuantWaves = 10;         // waves of the persistent workgroup (one workgroup per compute unit)
 constexpr int kTsplitBlock = 3 * 2 * 64 * 16;               // bytes of pre-split transform operand per MX block
 constexpr int kXSlot = 32 * 256;        // one unit of X: 32 rows x 128 bf16
-constexpr int kCodeStage = 2048;        // the two 1 KiB code pieces a unit produces
 constexpr int kQuantLdsT = 8 * kTsplitBlock;
-constexpr int kQuantLdsX = kQuantLdsT;
-constexpr int kQuantLdsStage = kQuantLdsX + kQuantWaves * kXSlot;
-constexpr int kQuantLdsCounter = kQuantLdsStage + kQuantWaves * kCodeStage;
-constexpr int kQuantLds = kQuantLdsCounter + 16;            // 148 KiB
+
+// LDS plan of the persistent workgroup (one per compute unit): transform operands of one K group, then per
+// wave one X slot and the staging area for the code pieces of a unit (two 1 KiB pieces for 4-bit codes,
+// four for 8-bit codes, which leaves room for 9 waves instead of 10), then the unit counter.
+template <bool FP8>
+struct QuantPlan {
+    static constexpr int kWaves = FP8 ? 9 : 10;
+    static constexpr int kCodeStage = FP8 ? 4096 : 2048;
+    static constexpr int kLdsX = kQuantLdsT;
+    static constexpr int kLdsStage = kLdsX + kWaves * kXSlot;
+    static constexpr int kLdsCounter = kLdsStage + kWaves * kCodeStage;
+    static constexpr int kLds = kLdsCounter + 16;           // 148 KiB / 156 KiB
+};
 
 // Persistent kernel.  Work comes in units of (32-row tile, half K group = 4 MX blocks = 256 bytes per
 // row), numbered K group by K group; a workgroup takes an equal contiguous range of them and its
@@ -229,8 +250,10 @@ constexpr int kQuantLds = kQuantLdsCounter + 16;            // 148 KiB
 // one completion counter).
 // MINMAX selects the two-ratio clipping of Eq. 3-4 (clip = ratios on the block minimum, clip_max on the
 // maximum) instead of one ratio on the block amax.
-template <bool MINMAX>
-__global__ void __launch_bounds__(kQuantWaves * 64)
+// FP8 selects MXFP8 (E4M3) output in the blocked 8-bit code layout (a unit then fills four pieces:
+// two piece columns of 2 blocks each, times two 16-row groups).
+template <bool MINMAX, bool FP8>
+__global__ void __launch_bounds__(QuantPlan<FP8>::kWaves * 64)
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int wpg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
@@ -241,14 +264,16 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     const int l32 = lane & 31, kg = lane >> 5;
     const int row_tiles = (M + 31) >> 5;
     const int groups = scale_groups(nb);
-    const size_t piece_stride = (size_t)code_stages(nb) * 1024;
+    using Plan = QuantPlan<FP8>;
+    constexpr int kQuantWaves = Plan::kWaves;
+    const size_t piece_stride = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb)) * 1024;
 
     uint8_t* const tlds = qlds;
-    uint8_t* const xslot = qlds + kQuantLdsX + wave * kXSlot;
-    uint8_t* const my = qlds + kQuantLdsStage + wave * kCodeStage;
-    uint32_t* const counter = reinterpret_cast<uint32_t*>(qlds + kQuantLdsCounter);
+    uint8_t* const xslot = qlds + Plan::kLdsX + wave * kXSlot;
+    uint8_t* const my = qlds + Plan::kLdsStage + wave * Plan::kCodeStage;
+    uint32_t* const counter = reinterpret_cast<uint32_t*>(qlds + Plan::kLdsCounter);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte*)qlds;
-    const uint32_t xslot_lds = lds_base + kQuantLdsX + wave * kXSlot;
+    const uint32_t xslot_lds = lds_base + Plan::kLdsX + wave * kXSlot;
 
     // `wpg` workgroups share a K group, each taking an equal range of its row tiles; with more groups
     // than workgroups (wpg = 1) a workgroup takes every (gridDim.x)-th group
@@ -281,8 +306,8 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     };
 
     const int r16 = l32 & 15;
-    // this lane's 8 code bytes of a block inside the staging area [row group][1 KiB]
-    const int st_base = (l32 >> 4) * 1024 + r16 * 64 + 8 * kg;
+    // this lane's row inside the staging area [piece column][row group][1 KiB]
+    const int st_row = (l32 >> 4) * 1024 + r16 * 64;
     const int st_swz = (r16 >> 2) & 3;
 
     // stores of the unit finished last
@@ -291,15 +316,19 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     auto flush = [&]() {
         if (pend_u < 0) return;
         const int tile = pend_u >> 1, half = pend_u & 1;
+        // pieces (piece column pc of the unit, rows 0-15) and (pc, rows 16-31); the code array is padded to
+        // whole 32-row tiles, so all of them exist.  Streamed out past the caches' keep-lists: nothing in
+        // this kernel reads them again.
+        constexpr int kCols = FP8 ? 2 : 1;                  // piece columns per unit
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            // (column `half` of the group, rows 0-15) and (rows 16-31); the code array is padded to whole
-            // 32-row tiles, so both pieces always exist
-            // streamed out past the caches' keep-lists: nothing in this kernel reads them again
-            const u32x4 v = *reinterpret_cast<const u32x4*>(my + p * 1024 + lane * 16);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(codes + (size_t)(2 * tile + p) * piece_stride +
-                                                                    (size_t)(2 * pend_g + half) * 1024 + lane * 16));
-        }
+        for (int pc = 0; pc < kCols; ++pc)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(my + (pc * 2 + p) * 1024 + lane * 16);
+                __builtin_nontemporal_store(
+                    v, reinterpret_cast<u32x4*>(codes + (size_t)(2 * tile + p) * piece_stride +
+                                                (size_t)(kCols * (2 * pend_g + half) + pc) * 1024 + lane * 16));
+            }
         // the unit's four scale bytes of the row's 8-byte word: even blocks at 2 half, 2 half + 1,
         // odd blocks at 4 + 2 half, 4 + 2 half + 1; lane kg writes pair kg
         const int row = tile * 32 + l32;
@@ -356,7 +385,7 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
 #pragma unroll
             for (int bb = 0; bb < 4; ++bb) {
                 const int b = 4 * half + bb;                // block inside the K group
-                uint2 out = {0u, 0u};                       // padding blocks: zero codes
+                uint2 out = {0u, 0u}, out2 = {0u, 0u};      // padding blocks: zero codes
                 if (bb < nreal) {
                     const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
                     uint4 tfr[6];
@@ -405,13 +434,27 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
                         m = __builtin_fmaxf(m, mo);
                         bound = clip[k0 + b] * m;           // one fp32 multiply
                     }
-                    const uint32_t s = e8m0_of_bound(bound);
-                    const float sc = scale_operand(s);
-                    out.x = encode8(y, bound, sc);
-                    out.y = encode8(y + 8, bound, sc);
-                    sc4[bb] = s;
+                    if constexpr (FP8) {
+                        const uint32_t s = e8m0_of_bound_fp8(bound);
+                        const float sc = scale_operand(s);
+                        out = encode8_fp8(y, bound, s, sc);
+                        out2 = encode8_fp8(y + 8, bound, s, sc);
+                        sc4[bb] = s;
+                    } else {
+                        const uint32_t s = e8m0_of_bound(bound);
+                        const float sc = scale_operand(s);
+                        out.x = encode8(y, bound, sc);
+                        out.y = encode8(y + 8, bound, sc);
+                        sc4[bb] = s;
+                    }
                 }
-                *reinterpret_cast<uint2*>(my + st_base + ((bb ^ st_swz) << 4)) = out;
+                if constexpr (FP8) {
+                    // the lane's 16 codes are 16-byte slot 2 (bb % 2) + kg of its row in piece column bb / 2
+                    *reinterpret_cast<uint4*>(my + (bb >> 1) * 2048 + st_row + (((2 * (bb & 1) + kg) ^ st_swz) << 4)) =
+                        uint4{out.x, out.y, out2.x, out2.y};
+                } else {
+                    *reinterpret_cast<uint2*>(my + st_row + 8 * kg + ((bb ^ st_swz) << 4)) = out;
+                }
             }
             pend_u = u;
             pend_g = g;
@@ -421,40 +464,48 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     flush();
 }
 
-hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
-                       uint8_t* scales, hipStream_t stream) {
+template <bool MINMAX, bool FP8>
+hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
+                          uint8_t* scales, int cus, hipStream_t stream) {
+    using Plan = QuantPlan<FP8>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<MINMAX, FP8>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Plan::kLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // whole K groups per workgroup set: floor(compute units / groups) workgroups share a group
     const int nb = t->nb;
+    const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
+    const int wpg = std::max(1, std::min(cus / groups, row_tiles));
+    const int wgs = wpg * std::min(groups, cus);
+    quant_act_mfma<MINMAX, FP8><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
+        X, ldx, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
+        MINMAX ? t->d_clip_max : nullptr, codes, scales);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
+                       uint8_t* scales, bool fp8, hipStream_t stream) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kQuantLds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kQuantLds);
         if (e != hipSuccess) {
             cus = 0;
             return e;
         }
     }
-    // whole K groups per workgroup set: floor(compute units / groups) workgroups share a group
-    const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
-    const int wpg = std::max(1, std::min(cus / groups, row_tiles));
-    const int wgs = wpg * std::min(groups, cus);
-    const uint4* Ts = reinterpret_cast<const uint4*>(t->d_Tsplit);
-    if (t->minmax)
-        quant_act_mfma<true><<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
-            X, ldx, M, nb, wpg, Ts, t->d_clip, t->d_clip_max, codes, scales);
-    else
-        quant_act_mfma<false><<<dim3(wgs), dim3(kQuantWaves * 64), kQuantLds, stream>>>(
-            X, ldx, M, nb, wpg, Ts, t->d_clip, nullptr, codes, scales);
-    return hipGetLastError();
+    if (fp8)
+        return t->minmax ? launch_mfma_as<true, true>(t, X, M, ldx, codes, scales, cus, stream)
+                         : launch_mfma_as<false, true>(t, X, M, ldx, codes, scales, cus, stream);
+    return t->minmax ? launch_mfma_as<true, false>(t, X, M, ldx, codes, scales, cus, stream)
+                     : launch_mfma_as<false, false>(t, X, M, ldx, codes, scales, cus, stream);
 }
 
-template <typename XT>
+template <typename XT, bool FP8>
 hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes,
                        uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
@@ -466,16 +517,16 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
     const float* cmax = t->minmax ? t->d_clip_max : nullptr;
     if (!t->has_transform)
-        quant_act_quad<XT, 4, false><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, 0, nullptr, 0,
-                                                                  t->d_clip, cmax, codes, scales);
+        quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, 0, nullptr,
+                                                                       0, t->d_clip, cmax, codes, scales);
     else if (t->g_outer == 4)
-        quant_act_quad<XT, 4, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
-                                                                 t->outer_stride, t->d_inner, t->inner_stride,
-                                                                 t->d_clip, cmax, codes, scales);
+        quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+                                                                      t->outer_stride, t->d_inner, t->inner_stride,
+                                                                      t->d_clip, cmax, codes, scales);
     else
-        quant_act_quad<XT, 8, true><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
-                                                                 t->outer_stride, t->d_inner, t->inner_stride,
-                                                                 t->d_clip, cmax, codes, scales);
+        quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+                                                                      t->outer_stride, t->d_inner, t->inner_stride,
+                                                                      t->d_clip, cmax, codes, scales);
     return hipGetLastError();
 }
 
@@ -483,7 +534,7 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
 // per (row, block); T_k (fp32, 4 KiB) sits in LDS, the 32 products of an output element are
 // accumulated with fp32 fused multiply-adds in input order.  Not a tuned path: bf16 inputs of every
 // form take the matrix-core kernel.
-template <typename XT>
+template <typename XT, bool FP8>
 __global__ void __launch_bounds__(256)
 quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const float* __restrict__ T,
                 const float* __restrict__ clip, const float* __restrict__ clip_max,
@@ -497,7 +548,12 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
     const int row = blockIdx.y * 256 + threadIdx.x;
     if (row >= M) return;
     if (!live) {
-        *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = uint4{0u, 0u, 0u, 0u};
+        if constexpr (FP8) {
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, 0, nb)) = uint4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, 1, nb)) = uint4{0u, 0u, 0u, 0u};
+        } else {
+            *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = uint4{0u, 0u, 0u, 0u};
+        }
         scales[scale_index_internal(row, k, M)] = (uint8_t)127;
         return;
     }
@@ -529,41 +585,61 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
         for (int j = 1; j < 32; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[j]));
         bound = clip[k] * m;
     }
-    const uint32_t s = e8m0_of_bound(bound);
-    const float sc = scale_operand(s);
-    uint4 out;
-    out.x = encode8(y, bound, sc);
-    out.y = encode8(y + 8, bound, sc);
-    out.z = encode8(y + 16, bound, sc);
-    out.w = encode8(y + 24, bound, sc);
-    *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = out;
-    scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+    if constexpr (FP8) {
+        const uint32_t s = e8m0_of_bound_fp8(bound);
+        const float sc = scale_operand(s);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint2 a = encode8_fp8(y + 16 * h, bound, s, sc), b = encode8_fp8(y + 16 * h + 8, bound, s, sc);
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, h, nb)) = uint4{a.x, a.y, b.x, b.y};
+        }
+        scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+    } else {
+        const uint32_t s = e8m0_of_bound(bound);
+        const float sc = scale_operand(s);
+        uint4 out;
+        out.x = encode8(y, bound, sc);
+        out.y = encode8(y + 8, bound, sc);
+        out.z = encode8(y + 16, bound, sc);
+        out.w = encode8(y + 24, bound, sc);
+        *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = out;
+        scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+    }
 }
 
-template <typename XT>
+template <typename XT, bool FP8>
 hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes, uint8_t* scales,
                         hipStream_t stream) {
     const dim3 grid(scale_groups(t->nb) * 8, (M + 255) / 256), block(256);
-    quant_act_dense<XT><<<grid, block, 0, stream>>>(X, ldx, M, t->nb, t->d_T, t->d_clip,
-                                                     t->minmax ? t->d_clip_max : nullptr, codes, scales);
+    quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, M, t->nb, t->d_T, t->d_clip,
+                                                          t->minmax ? t->d_clip_max : nullptr, codes, scales);
     return hipGetLastError();
+}
+
+template <bool FP8>
+hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
+                              uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+    if (xdtype == BATQ_BF16) {
+        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets
+        if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
+            return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, FP8, stream);
+        if (t->form == BATQ_FORM_DENSE)
+            return launch_dense<uint16_t, FP8>(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+        return launch_quad<uint16_t, FP8>(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+    }
+    if (t->form == BATQ_FORM_DENSE)
+        return launch_dense<float, FP8>(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
+    return launch_quad<float, FP8>(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
 }
 
 }  // namespace
 
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    if (xdtype == BATQ_BF16) {
-        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets
-        if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
-            return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
-        if (t->form == BATQ_FORM_DENSE) return launch_dense(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
-        return launch_quad(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
-    }
-    if (t->form == BATQ_FORM_DENSE) return launch_dense(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
-    return launch_quad(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
+    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, codes, scales, stream)
+               : launch_quantize_as<false>(t, X, xdtype, M, ldx, codes, scales, stream);
 }
 
 }  // namespace batq

@@ -113,3 +113,38 @@ def rowmajor_to_blocked(rm: np.ndarray) -> np.ndarray:
     idx = off[:, :, None] + np.arange(16)[None, None, :]
     out[idx.reshape(-1)] = rm.reshape(-1)
     return out
+
+
+# ---- 8-bit (MXFP8) activation codes: the documented device order, written out in NumPy
+def _slot8_offsets(rows, k0, k1, nb_total):
+    """byte offset of 16-byte slot h of block k of each row: [rows, k1-k0, 2]"""
+    S8 = 4 * ((nb_total + 7) // 8)
+    row = np.arange(rows)[:, None, None]
+    k = np.arange(k0, k1)[None, :, None]
+    h = np.arange(2)[None, None, :]
+    r = row % 16
+    return ((row // 16) * S8 + k // 2) * 1024 + r * 64 + ((((2 * (k % 2) + h)) ^ ((r // 4) % 4)) * 16)
+
+
+def blocked8_to_rowmajor(blocked: np.ndarray, rows: int, nb: int) -> np.ndarray:
+    S8 = 4 * ((nb + 7) // 8)
+    assert blocked.size == ((rows + 31) // 32) * 2 * S8 * 1024
+    off = _slot8_offsets(rows, 0, nb, nb)
+    idx = off[..., None] + np.arange(16)
+    out = blocked.reshape(-1)[idx].reshape(rows, nb * 32)
+    nbp = ((nb + 7) // 8) * 8
+    if nbp > nb:                                     # K padding must hold zero codes
+        offp = _slot8_offsets(rows, nb, nbp, nb)
+        assert np.all(blocked.reshape(-1)[offp[..., None] + np.arange(16)] == 0)
+    return np.ascontiguousarray(out)
+
+
+def rowmajor_to_blocked8(rm: np.ndarray) -> np.ndarray:
+    rows, K = rm.shape
+    nb = K // 32
+    S8 = 4 * ((nb + 7) // 8)
+    out = np.zeros(((rows + 31) // 32) * 2 * S8 * 1024, dtype=np.uint8)
+    off = _slot8_offsets(rows, 0, nb, nb)
+    idx = off[..., None] + np.arange(16)
+    out[idx.reshape(-1)] = rm.reshape(-1)
+    return out
