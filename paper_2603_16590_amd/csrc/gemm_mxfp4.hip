@@ -564,6 +564,96 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
     }
 }
 
+// Epilogue of a tile: accumulators (4 x NJ matrix tiles of this wave, rows wm*128.., columns wn*32*NJ..) -> Y.
+// `ep_lds` is the wave's private 4 KiB LDS staging area.
+template <int NJ, typename YT>
+__device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, int lane, int wm, int wn, const Tile& t,
+                                           int M, int N, YT* __restrict__ Y, int64_t ldy) {
+    // ---- epilogue: accumulators -> Y
+    // (lane-derived addresses are recomputed per tile rather than kept in registers across the main loop)
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int m0 = t.m0, n0 = t.n0;
+    if constexpr (sizeof(YT) == 2) {
+        // bf16: transpose through a wave-private LDS buffer so that every lane stores 16 contiguous
+        // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
+        const bool fast = n0 + kStrip * NJ <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+        if (fast) {
+            uint8_t* ep = ep_lds;   // [16 rows][256 bytes]
+            const int odd = lane_e & 1, l32 = lane_e & 31, kg = lane_e >> 5;
+            // Lanes pair up: from its two packed values (rows r, r+1 of its column) and the neighbour's,
+            // the even lane assembles row r and the odd lane row r+1 of the column pair.
+            const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+            // Value pair (j, u) of a 16-row block goes to block row 8 (u / 2) + 2 (u % 2) + (4 kg + odd) and
+            // 16-byte chunk (4 j + l32 / 8) ^ swizzle(row); the swizzle only depends on the lane
+            // (row & 1 = odd, (row >> 2) & 1 = kg), so it folds into per-lane base pointers, one per j.
+            uint8_t* pj[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                pj[j] = ep + (4 * kg + odd) * 256 + ((4 * (j ^ (odd | (kg << 1))) + (l32 >> 3)) << 4) + ((l32 >> 1) & 3) * 4;
+            // read-back: one instruction covers kRows rows of 4 NJ 16-byte units (NJ = 3 leaves lanes
+            // 48..63 idle); row pointers advance by additions only
+            constexpr int kUnits = 4 * NJ, kRows = NJ == 3 ? 4 : 64 / kUnits;
+            const int rl = lane_e / kUnits, unit = lane_e % kUnits;
+            const bool lane_on = NJ != 3 || lane_e < 48;
+            int row = m0 + wm * 128 + rl;
+            YT* yrow = Y + (size_t)row * ldy + n0 + wn * 32 * NJ + unit * 8;
+            const int64_t ystep = (int64_t)kRows * ldy;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    __builtin_amdgcn_sched_barrier(0);      // one 16-row block at a time: keeps register use flat
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            f32x2 pr;
+                            pr.x = acc[i][j][8 * h + 2 * u];
+                            pr.y = acc[i][j][8 * h + 2 * u + 1];
+                            const int mine = __builtin_bit_cast(int, __builtin_convertvector(pr, bf16x2));
+                            const int theirs = __builtin_amdgcn_mov_dpp(mine, 0xB1, 0xF, 0xF, true);
+                            *reinterpret_cast<uint32_t*>(pj[j] + (8 * (u >> 1) + 2 * (u & 1)) * 256) =
+                                __builtin_amdgcn_perm((uint32_t)theirs, (uint32_t)mine, sel);
+                        }
+                    // wave-private buffer: the wave's own LDS operations complete in order
+#pragma unroll
+                    for (int it = 0; it < 16 / kRows; ++it) {
+                        const int R = it * kRows + rl;
+                        const int chunk = unit ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
+                        const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
+                        if (lane_on && row < M) *reinterpret_cast<uint4*>(yrow) = v;
+                        row += kRows;
+                        yrow += ystep;
+                    }
+                }
+            return;
+        }
+    }
+    // general path: element-wise stores with edge checks; rows visited in increasing order per lane
+    const int col0 = n0 + wn * 32 * NJ + (lane_e & 31);
+    int row = m0 + wm * 128 + 4 * (lane_e >> 5);
+    YT* yp = Y + (size_t)row * ldy + col0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (row < M) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        if (col0 + 32 * j < N) store_y<YT>(yp + 32 * j, acc[i][j][4 * q + r]);
+                }
+                ++row;
+                yp += ldy;
+            }
+            row += 4;
+            yp += 4 * ldy;
+        }
+}
+
 // One output tile: on entry the loads of its first stages are in flight (issue_prologue); before
 // the epilogue the loads of the next tile's first stages are started, so they run underneath it.
 template <int NJ, typename YT>
@@ -616,88 +706,8 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     }
 
     // ---- epilogue: accumulators -> Y
-    // (lane-derived addresses are recomputed per tile rather than kept in registers across the main loop)
-    int lane_e = lane;
-    asm volatile("" : "+v"(lane_e));
-    const int m0 = t.m0, n0 = t.n0;
-    if constexpr (sizeof(YT) == 2) {
-        // bf16: transpose through a wave-private LDS buffer so that every lane stores 16 contiguous
-        // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
-        const bool fast = n0 + kStrip * NJ <= c.N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
-        if (fast) {
-            uint8_t* ep = const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds;   // [16 rows][256 bytes]
-            const int odd = lane_e & 1, l32 = lane_e & 31, kg = lane_e >> 5;
-            // Lanes pair up: from its two packed values (rows r, r+1 of its column) and the neighbour's,
-            // the even lane assembles row r and the odd lane row r+1 of the column pair.
-            const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
-            // Value pair (j, u) of a 16-row block goes to block row 8 (u / 2) + 2 (u % 2) + (4 kg + odd) and
-            // 16-byte chunk (4 j + l32 / 8) ^ swizzle(row); the swizzle only depends on the lane
-            // (row & 1 = odd, (row >> 2) & 1 = kg), so it folds into per-lane base pointers, one per j.
-            uint8_t* pj[NJ];
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                pj[j] = ep + (4 * kg + odd) * 256 + ((4 * (j ^ (odd | (kg << 1))) + (l32 >> 3)) << 4) + ((l32 >> 1) & 3) * 4;
-            // read-back: one instruction covers kRows rows of 4 NJ 16-byte units (NJ = 3 leaves lanes
-            // 48..63 idle); row pointers advance by additions only
-            constexpr int kUnits = 4 * NJ, kRows = NJ == 3 ? 4 : 64 / kUnits;
-            const int rl = lane_e / kUnits, unit = lane_e % kUnits;
-            const bool lane_on = NJ != 3 || lane_e < 48;
-            int row = m0 + wm * 128 + rl;
-            YT* yrow = Y + (size_t)row * ldy + n0 + wn * 32 * NJ + unit * 8;
-            const int64_t ystep = (int64_t)kRows * ldy;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    __builtin_amdgcn_sched_barrier(0);      // one 16-row block at a time: keeps register use flat
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            f32x2 pr;
-                            pr.x = acc[i][j][8 * h + 2 * u];
-                            pr.y = acc[i][j][8 * h + 2 * u + 1];
-                            const int mine = __builtin_bit_cast(int, __builtin_convertvector(pr, bf16x2));
-                            const int theirs = __builtin_amdgcn_mov_dpp(mine, 0xB1, 0xF, 0xF, true);
-                            *reinterpret_cast<uint32_t*>(pj[j] + (8 * (u >> 1) + 2 * (u & 1)) * 256) =
-                                __builtin_amdgcn_perm((uint32_t)theirs, (uint32_t)mine, sel);
-                        }
-                    // wave-private buffer: the wave's own LDS operations complete in order
-#pragma unroll
-                    for (int it = 0; it < 16 / kRows; ++it) {
-                        const int R = it * kRows + rl;
-                        const int chunk = unit ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
-                        const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
-                        if (lane_on && row < c.M) *reinterpret_cast<uint4*>(yrow) = v;
-                        row += kRows;
-                        yrow += ystep;
-                    }
-                }
-            return;
-        }
-    }
-    // general path: element-wise stores with edge checks; rows visited in increasing order per lane
-    const int col0 = n0 + wn * 32 * NJ + (lane_e & 31);
-    int row = m0 + wm * 128 + 4 * (lane_e >> 5);
-    YT* yp = Y + (size_t)row * ldy + col0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (row < c.M) {
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j)
-                        if (col0 + 32 * j < c.N) store_y<YT>(yp + 32 * j, acc[i][j][4 * q + r]);
-                }
-                ++row;
-                yp += ldy;
-            }
-            row += 4;
-            yp += 4 * ldy;
-        }
+    store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
+                       c.M, c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
@@ -745,6 +755,286 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Tiled kernel for MXFP8 activations (W4A8).  Same persistent work split, tile shapes, LDS-direct
+// loads and epilogue as gemm_tiled; what differs follows from the 8-bit A operand: a matrix
+// instruction takes twice as long (the pipe runs at the FP8 rate), so a stage is one K step of 64
+// elements: 256 rows x 64 bytes of A (whole 1 KiB pieces of the 8-bit code layout) and 256 rows x 32
+// bytes of B (half of each row of a 4-bit piece, gathered by the load's per-lane addresses).  Ring
+// of 4 stages x 24 KiB.  Always 256 rows of B are loaded, whatever the tile width, so that every
+// wave issues the same number of loads per stage (6, plus 4 for the scales of a K group with its
+// first stage).
+constexpr int kA8StageA = kTile * 64;                       // 16 KiB
+constexpr int kA8StageB = kTile * 32;                       // 8 KiB
+constexpr int kA8Stage = kA8StageA + kA8StageB;
+constexpr int kA8ScaleLds0 = kRing * kA8Stage;              // 96 KiB
+constexpr int kA8EpilogueLds0 = kA8ScaleLds0 + 2 * kScaleGroupLds;
+constexpr int kA8Lds = kA8EpilogueLds0 + 4 * kEpilogueWaveLds;      // 120 KiB
+
+struct A8Ctx {
+    const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
+    uint32_t aoff[4], boff[2], sao[2], sbo[2];
+    uint32_t lds0, lds_sc;
+    int M, N, T, wave, lane;          // T = stages = K / 64 (K padded to 256)
+    const uint8_t* smem;
+    int a_rd, b_rd, sc_a_rd, sc_b_rd, kg;
+
+    __device__ __forceinline__ void aim(const Tile& t) {
+        const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
+        int lane = this->lane;
+        asm volatile("" : "+v"(lane));      // recompute the lane terms per tile instead of keeping them in registers
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
+        // B: load q of wave w fills LDS rows 32 (2 w + q) .. + 31 (32 bytes each); lane i -> row i / 2, 16-byte
+        // position i % 2, which holds block (i % 2) ^ ((row / 4) % 2) of the K step; in the 4-bit piece
+        // (16 rows x 64 bytes, 2 K steps) that block sits in slot (2 (s % 2) + block) ^ ((row % 16) / 4);
+        // the offset below is for an even stage, an odd stage flips bit 5.
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int rho = lane >> 1, p = lane & 1;
+            const int r16 = rho & 15;
+            const int blk = p ^ ((rho >> 2) & 1);
+            const int rg = min((t.n0 >> 4) + 2 * (2 * wave + q) + (rho >> 4), rgB - 1);
+            boff[q] = (uint32_t)rg * (uint32_t)((T >> 1) * 1024) + r16 * 64 + ((blk ^ ((r16 >> 2) & 3)) << 4);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int d = 128 * wave + 64 * j + lane;
+            sao[j] = ((uint32_t)min(t.m0 + (d >> 1), M - 1) * 2 + (d & 1)) * 4;
+            sbo[j] = ((uint32_t)min(t.n0 + (d >> 1), N - 1) * 2 + (d & 1)) * 4;
+        }
+    }
+    // loads of stage s in their fixed order: parts 0..3 A pieces, 4..5 B, 6 = scales (first stage of a K group)
+    template <int PART, int PAR>
+    __device__ __forceinline__ void issue_part(int s) const {
+        const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kA8Stage;
+        if constexpr (PART < 4) {
+            dma16(xc + (size_t)s * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
+        } else if constexpr (PART < 6) {
+            dma16(wc + (size_t)(s >> 1) * 1024, boff[PART - 4] ^ ((PAR & 1) << 5),
+                  buf + kA8StageA + (uint32_t)(2 * wave + PART - 4) * 1024);
+        } else if constexpr (PAR == 0) {
+            const int g = s >> 2;
+            const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
+            const uint8_t* sag = xs + (size_t)g * M * 8;
+            const uint8_t* sbg = ws + (size_t)g * N * 8;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
+        }
+    }
+    template <int PAR>
+    __device__ __forceinline__ void issue_stage(int s) const {
+        issue_part<0, PAR>(s); issue_part<1, PAR>(s); issue_part<2, PAR>(s); issue_part<3, PAR>(s);
+        issue_part<4, PAR>(s); issue_part<5, PAR>(s); issue_part<6, PAR>(s);
+    }
+    __device__ __forceinline__ void aim_reads(int nj, int wm, int wn, int l32) {
+        const int sw = (l32 >> 2) & 3;
+        // A: this lane's halves (kg) of the two blocks of the step: slots kg and 2 + kg of its 64-byte row
+        a_rd = (wm * 128 + l32) * 64 + ((kg ^ sw) << 4);
+        // B: block kg of the step, 32-byte rows
+        b_rd = kA8StageA + (wn * 32 * nj + l32) * 32 + ((kg ^ (sw & 1)) << 4);
+        sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
+        sc_b_rd = kTile * 8 + ((wn * 32 * nj + l32) * 2 + kg) * 4;
+    }
+    // fragment `idx` of stage s in consumption order: 0 = a0, 1..NJ = b0.., NJ+1.. = a1..a3 (an A fragment is
+    // two 16-byte reads: slot ^ 2 is the second block's half)
+    template <int NJ>
+    __device__ __forceinline__ void read_frag(int s, int idx, uint4 (&fa)[4][2], uint4 (&fb)[NJ]) const {
+        const uint8_t* base = smem + (s & (kRing - 1)) * kA8Stage;
+        if (idx == 0 || idx > NJ) {
+            const int i = idx == 0 ? 0 : idx - NJ;
+            fa[i][0] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * 64);
+            fa[i][1] = *reinterpret_cast<const uint4*>(base + (a_rd ^ 32) + i * 32 * 64);
+        } else {
+            fb[idx - 1] = *reinterpret_cast<const uint4*>(base + b_rd + (idx - 1) * 32 * 32);
+        }
+    }
+    template <int NJ>
+    __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[NJ]) const {
+        const uint8_t* sp = smem + kA8ScaleLds0 + (g & 1) * kScaleGroupLds;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sb[j] = *reinterpret_cast<const int*>(sp + sc_b_rd + j * 256);
+    }
+};
+
+template <int PAR, bool ZERO>
+__device__ __forceinline__ void a8_mfma(v16f& acc, const uint4 (&a)[2], const uint4& b, int sa, int sb) {
+    if constexpr (ZERO)
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag8(a[0], a[1]), frag(b), v16f{}, 0, 4, PAR, sa, PAR, sb);
+    else
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag8(a[0], a[1]), frag(b), acc, 0, 4, PAR, sa, PAR, sb);
+}
+
+// Matrix instructions Q .. 2 NJ - 1 of the second half of a stage (tile rows 2 and 3), each followed by its
+// share of the reads of stage s+1's fragments (4 + NJ), of the next group's scales (PAR 3) and of the 7 load
+// parts of stage s+4.
+template <int NJ, int PAR, bool NEXT, bool ISSUE, int Q>
+__device__ __forceinline__ void a8_second_half(const A8Ctx& c, int s, v16f (&acc)[4][NJ], const uint4 (&a)[4][2],
+                                               const uint4 (&b)[NJ], const int (&sa)[4], const int (&sb)[NJ],
+                                               uint4 (&an)[4][2], uint4 (&bn)[NJ]) {
+    if constexpr (Q < 2 * NJ) {
+        constexpr int i = 2 + Q / NJ, j = Q % NJ;
+        constexpr int kSlots = 2 * NJ, kFrags = 4 + NJ, kParts = 7;
+        a8_mfma<PAR, false>(acc[i][j], a[i], b[j], sa[i], sb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NEXT) {
+#pragma unroll
+            for (int f = Q * kFrags / kSlots; f < (Q + 1) * kFrags / kSlots; ++f) c.read_frag<NJ>(s + 1, f, an, bn);
+        }
+        if constexpr (ISSUE) {
+            constexpr int p0 = Q * kParts / kSlots, p1 = (Q + 1) * kParts / kSlots;
+            if constexpr (p0 <= 0 && 0 < p1) c.issue_part<0, PAR>(s + 4);
+            if constexpr (p0 <= 1 && 1 < p1) c.issue_part<1, PAR>(s + 4);
+            if constexpr (p0 <= 2 && 2 < p1) c.issue_part<2, PAR>(s + 4);
+            if constexpr (p0 <= 3 && 3 < p1) c.issue_part<3, PAR>(s + 4);
+            if constexpr (p0 <= 4 && 4 < p1) c.issue_part<4, PAR>(s + 4);
+            if constexpr (p0 <= 5 && 5 < p1) c.issue_part<5, PAR>(s + 4);
+            if constexpr (p0 <= 6 && 6 < p1) c.issue_part<6, PAR>(s + 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        a8_second_half<NJ, PAR, NEXT, ISSUE, Q + 1>(c, s, acc, a, b, sa, sb, an, bn);
+    }
+}
+
+// One stage = one K step.  PAR = s % 4 (scale byte); WAIT = loads that may stay in flight once stage s+1 has
+// landed (-1: last stage); ISSUE: start stage s+4; FIRST: start the accumulators from zero.
+// (a, b) hold stage s on entry; (an, bn) receive stage s+1.
+template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+__device__ __forceinline__ void a8_stage(const A8Ctx& c, int s, v16f (&acc)[4][NJ], const uint4 (&a)[4][2],
+                                         const uint4 (&b)[NJ], uint4 (&an)[4][2], uint4 (&bn)[NJ], int (&sa)[4],
+                                         int (&sb)[NJ]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) a8_mfma<PAR, FIRST>(acc[i][j], a[i], b[j], sa[i], sb[j]);
+    __builtin_amdgcn_sched_barrier(0);
+    int sna[4], snb[NJ];
+    if constexpr (WAIT >= 0) {
+        // every wave holds stage s in registers; once all have also seen stage s+1 land, slot s can be refilled
+        wait_vmcnt<WAIT>();
+        __syncthreads();
+        if constexpr (PAR == 3) c.read_scales<NJ>((s + 1) >> 2, sna, snb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (FIRST) {
+        // rows 2 and 3 also start from zero
+#pragma unroll
+        for (int i = 2; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = v16f{};
+    }
+    a8_second_half<NJ, PAR, (WAIT >= 0), ISSUE, 0>(c, s, acc, a, b, sa, sb, an, bn);
+    if constexpr (WAIT >= 0 && PAR == 3) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sa[i] = sna[i];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) sb[j] = snb[j];
+    }
+}
+
+template <int NJ, typename YT>
+__device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_next, const Tile& next,
+                                            YT* __restrict__ Y, int64_t ldy) {
+    const int lane = c.lane, wave = c.wave;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int T = c.T, G = T >> 2;
+    c.aim_reads(NJ, wm, wn, lane & 31);
+
+    v16f acc[4][NJ];
+    uint4 a0[4][2], a1[4][2], b0[NJ], b1[NJ];
+    int sa[4], sb[NJ];
+
+    // per thread and stage: 6 loads, 4 more with the first stage of a K group, completing in issue order
+    wait_vmcnt<18>();                                       // stages 1..3 may still be in flight
+    __syncthreads();
+    c.read_scales<NJ>(0, sa, sb);
+#pragma unroll
+    for (int f = 0; f < 4 + NJ; ++f) c.read_frag<NJ>(0, f, a0, b0);
+
+    // stage s waits for stage s+1 and leaves stages s+2, s+3 in flight: 12 loads, 16 if one of them opens a group
+    if (G >= 2) {
+        a8_stage<NJ, 0, 12, true, true>(c, 0, acc, a0, b0, a1, b1, sa, sb);
+        a8_stage<NJ, 1, 16, true, false>(c, 1, acc, a1, b1, a0, b0, sa, sb);
+        a8_stage<NJ, 2, 16, true, false>(c, 2, acc, a0, b0, a1, b1, sa, sb);
+        a8_stage<NJ, 3, 12, true, false>(c, 3, acc, a1, b1, a0, b0, sa, sb);
+        for (int g = 1; g + 1 < G; ++g) {
+            a8_stage<NJ, 0, 12, true, false>(c, 4 * g, acc, a0, b0, a1, b1, sa, sb);
+            a8_stage<NJ, 1, 16, true, false>(c, 4 * g + 1, acc, a1, b1, a0, b0, sa, sb);
+            a8_stage<NJ, 2, 16, true, false>(c, 4 * g + 2, acc, a0, b0, a1, b1, sa, sb);
+            a8_stage<NJ, 3, 12, true, false>(c, 4 * g + 3, acc, a1, b1, a0, b0, sa, sb);
+        }
+        a8_stage<NJ, 0, 12, false, false>(c, T - 4, acc, a0, b0, a1, b1, sa, sb);
+    } else {
+        a8_stage<NJ, 0, 12, false, true>(c, 0, acc, a0, b0, a1, b1, sa, sb);
+    }
+    a8_stage<NJ, 1, 6, false, false>(c, T - 3, acc, a1, b1, a0, b0, sa, sb);
+    a8_stage<NJ, 2, 0, false, false>(c, T - 2, acc, a0, b0, a1, b1, sa, sb);
+    a8_stage<NJ, 3, -1, false, false>(c, T - 1, acc, a1, b1, a0, b0, sa, sb);
+
+    __syncthreads();                                      // every wave is done with the stage ring
+    if (has_next) {
+        c.aim(next);
+        c.issue_stage<0>(0);
+        c.issue_stage<1>(1);
+        c.issue_stage<2>(2);
+        c.issue_stage<3>(3);
+    }
+    store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
+                       c.M, c.N, Y, ldy);
+}
+
+// Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
+template <typename YT>
+__global__ void __launch_bounds__(256, 1)
+gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
+              const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+
+    const int per_xcd = pl.workers >> 3;
+    const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n;
+    int cur = (int)(total * share / pl.workers);
+    const int end = (int)(total * (share + 1) / pl.workers);
+
+    Tile t, next;
+    if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
+
+    const int lane = threadIdx.x & 63;
+    A8Ctx c;
+    c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
+    c.M = M; c.N = N; c.smem = smem;
+    c.T = 4 * ((nb + 7) >> 3);                                // stages of 64 K elements (K zero-padded to 256)
+    c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    c.lane = lane;
+    c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;
+    c.lds_sc = c.lds0 + kA8ScaleLds0;
+    c.kg = lane >> 5;
+
+    c.aim(t);
+    c.issue_stage<0>(0);
+    c.issue_stage<1>(1);
+    c.issue_stage<2>(2);
+    c.issue_stage<3>(3);
+    for (;;) {
+        const bool has_next = next_tile(pl, cur, end, next);
+        switch (t.nj) {
+            case 4: a8_run_tile<4, YT>(c, t, has_next, next, Y, ldy); break;
+            case 3: a8_run_tile<3, YT>(c, t, has_next, next, Y, ldy); break;
+            case 2: a8_run_tile<2, YT>(c, t, has_next, next, Y, ldy); break;
+            default: a8_run_tile<1, YT>(c, t, has_next, next, Y, ldy); break;
+        }
+        if (!has_next) break;
+        t = next;
+    }
+}
+
 // Column bands: with b bands an XCD's block spans 1/b of N and b/8 of M, so the bytes all XCDs
 // pull through their L2s are proportional to b M + (8 / b) N; take the b that minimises it.
 int choose_bands(int M, int N, int strips_n) {
@@ -768,11 +1058,13 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
     const int N = w->N, nb = w->nb;
     const size_t xbytes = A8 ? code8_bytes_blocked(M, nb) : code_bytes_blocked(M, nb);
     const bool fits32 = xbytes < (1ull << 31) && code_bytes_blocked(N, nb) < (1ull << 31);
-    if (M > 64 && fits32 && !A8) {
+    if (M > 64 && fits32) {
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
+            hipError_t e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<YT>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
+                              : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
@@ -785,8 +1077,12 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         pl.strips_n = (N + kStrip - 1) / kStrip;
         pl.bands = choose_bands(M, N, pl.strips_n);
         pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
-        gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb,
-                                                                            pl, Y, ldy);
+        if constexpr (A8)
+            gemm_tiled_a8<YT><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
+                                                                                nb, pl, Y, ldy);
+        else
+            gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
+                                                                                nb, pl, Y, ldy);
     } else if (M <= 64) {
         const dim3 grid((N + 31) / 32), block(kSkinnyWaves * 64);
         if (M <= 32)

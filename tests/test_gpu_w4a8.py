@@ -189,7 +189,37 @@ def test_a8w4_gemm_random_codes(B, M, K, N):
     assert np.all(np.abs(gotb - refb) <= ulp * 1.0001 + tol)
 
 
-@pytest.mark.parametrize("cfg", [0, 1, 2])
+@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
+def test_a8w4_tile_schedule_shapes(B, M, K, N):
+    """Several tiles per persistent workgroup, every tile width, ragged edges, 4 to 20 K stages; every
+    output element is checked (exponents kept within 4 binades so that the products sum exactly)."""
+    import torch
+    rng = np.random.default_rng(M + K + N)
+    e = rng.integers(5, 9, size=(M, K)); m = rng.integers(0, 8, size=(M, K)); sg = rng.integers(0, 2, size=(M, K))
+    xc = ((sg << 7) | (e << 3) | m).astype(np.uint8)
+    xs = rng.integers(124, 130, size=(M, K // 32), dtype=np.uint8)
+    wc = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    ws = rng.integers(124, 130, size=(N, K // 32), dtype=np.uint8)
+    wh = B.batq_weight_import(torch.from_numpy(wc).cuda(), torch.from_numpy(ws).cuda(), K, N)
+    ref = o.gemm_a8w4(xc, xs, wc, ws)
+    dxc = torch.from_numpy(rowmajor_to_blocked8(xc)).cuda()
+    dxs = torch.from_numpy(rowmajor_to_grouped(xs)).cuda()
+    Y = B.batq_gemm_a8w4(dxc, dxs, wh, M, torch.float32)
+    torch.cuda.synchronize()
+    got = y_to_f32(Y)
+    tol = 2e-6 * (np.abs(o.dequantize_fp8(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
+    bad = np.argwhere(np.abs(got - ref) > tol + 1e-30)
+    assert bad.size == 0, f"{len(bad)} wrong elements, first at {bad[0]}"
+    Yb = B.batq_gemm_a8w4(dxc, dxs, wh, M, torch.bfloat16)
+    torch.cuda.synchronize()
+    refb = o.bf16_round(ref).astype(np.float64)
+    gotb = y_to_f32(Yb).astype(np.float64)
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+    bad = np.argwhere(np.abs(gotb - refb) > ulp * 1.0001 + tol)
+    assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
 def test_a8w4_linear_configs(B, cfg):
     import torch
     w = bi.make_workload(cfg)
