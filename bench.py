@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP4_TFLOPS = 10100.0    # MI355X dense MXFP4 MFMA
+PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA: the rate of a block-scaled instruction with an 8-bit operand
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 
 
@@ -39,6 +40,7 @@ def main():
                     help="which synthetic configuration is the timed workload (default: 8B-class prefill up/gate)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
+    ap.add_argument("--no-w4a8", action="store_true", help="skip the W4A8 side measurement")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
                     "loop, streaming HBM kernels)")
     args = ap.parse_args()
@@ -60,27 +62,31 @@ def main():
             return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
-    def run_config(cfg: int, steps: int, warmup: int):
+    def run_config(cfg: int, steps: int, warmup: int, a8: bool = False):
+        # a8: the W4A8 variant of the same layer (MXFP8 activations, same MXFP4 weights)
+        linear = B.batq_linear_a8w4 if a8 else B.batq_linear
+        quantize = B.batq_quantize_act_mxfp8 if a8 else B.batq_quantize_act
+        gemm = B.batq_gemm_a8w4 if a8 else B.batq_gemm_mxfp4
         w = bi.make_workload(cfg)
         t = B.Transform(w.K, w.G, w.P, w.clip)
         wh = B.batq_prepare_weight(t, to_dev(w.W, w.dtype))
         ydt = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
         xbytes = 2 if w.dtype == "bf16" else 4
         ybytes = 2 if w.out_dtype == "bf16" else 4
-        wsz = B.batq_linear_workspace(w.M, w.K)
+        wsz = B.batq_linear_a8w4_workspace(w.M, w.K) if a8 else B.batq_linear_workspace(w.M, w.K)
         per_set = w.M * w.K * xbytes + wsz + w.M * w.N * ybytes
         nsets = max(2, min(64, -(-(600 << 20) // per_set)))
         X0 = to_dev(w.X, w.dtype)
         Xs = [X0] + [X0.clone() for _ in range(nsets - 1)]
         Ws = [torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
         Ys = [torch.empty((w.M, w.N), dtype=ydt, device="cuda") for _ in range(nsets)]
-        cb = B.batq_code_bytes(w.M, w.K)
+        cb = B.batq_code8_bytes(w.M, w.K) if a8 else B.batq_code_bytes(w.M, w.K)
         codes = [wk[:cb] for wk in Ws]
         scales = [wk[cb: wsz] for wk in Ws]
 
         def step(i):
             j = i % nsets
-            B.batq_linear(t, wh, Xs[j], Y=Ys[j], workspace=Ws[j])
+            linear(t, wh, Xs[j], Y=Ys[j], workspace=Ws[j])
 
         for i in range(warmup):
             step(i)
@@ -105,12 +111,12 @@ def main():
             e1.synchronize()
             return e0.elapsed_time(e1) / n
 
-        ms_quant = timed(lambda i: B.batq_quantize_act(t, Xs[i % nsets], codes[i % nsets], scales[i % nsets]), steps)
-        ms_gemm = timed(lambda i: B.batq_gemm_mxfp4(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets]), steps)
-        ms_quant_warm = timed(lambda i: B.batq_quantize_act(t, Xs[0], codes[0], scales[0]), steps)
+        ms_quant = timed(lambda i: quantize(t, Xs[i % nsets], codes[i % nsets], scales[i % nsets]), steps)
+        ms_gemm = timed(lambda i: gemm(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets]), steps)
+        ms_quant_warm = timed(lambda i: quantize(t, Xs[0], codes[0], scales[0]), steps)
 
         flops = 2.0 * w.M * w.K * w.N
-        qbytes = w.M * w.K * (xbytes + 0.5 + 1.0 / 32)
+        qbytes = w.M * w.K * (xbytes + (1.0 if a8 else 0.5) + 1.0 / 32)
         res = {
             "workload": f"cfg{cfg}:{w.name} M={w.M} K={w.K} N={w.N} x={w.dtype} y={w.out_dtype}",
             "ms_per_step": ms_step,
@@ -145,6 +151,15 @@ def main():
             continue
         _, _, _, r, _, _ = run_config(c, max(10, args.steps // 4), max(3, args.warmup // 4))
         also[f"cfg{c}"] = r
+        torch.cuda.empty_cache()
+
+    # the W4A8 variant of the same workload (MXFP8 activations): its matrix instructions run at the FP8 rate
+    w4a8 = None
+    if not args.no_w4a8:
+        _, _, _, r8, _, _ = run_config(args.workload, max(10, args.steps // 4), max(3, args.warmup // 4), a8=True)
+        r8["gemm_frac_of_fp8_rate_peak"] = r8["gemm_tflops"] / PEAK_FP8_TFLOPS
+        r8["quant_frac_of_hbm_peak"] = r8["quant_gbs"] / PEAK_HBM_GBS
+        w4a8 = r8
         torch.cuda.empty_cache()
 
     ceilings = None
@@ -208,6 +223,7 @@ def main():
         "measured_ceilings": ceilings,
         "cpu_baseline": cpu,
         "also": also,
+        "w4a8": w4a8,
     }
     print(json.dumps(line))
 

@@ -239,15 +239,14 @@ struct QuantPlan {
 };
 
 // Persistent kernel.  Work comes in units of (32-row tile, half K group = 4 MX blocks = 256 bytes per
-// row), numbered K group by K group; a workgroup takes an equal contiguous range of them and its
-// waves draw units from an LDS counter.  The transform operands of the current K group (48 KiB) sit
-// in LDS and are replaced when the range enters the next group.  A wave's unit of X is fetched
-// global -> LDS with LDS-direct loads (no registers are tied up while it is in flight), as rows of 16
-// chunks of 16 bytes, chunk c of row r at position c ^ (r & 7) so that the operand reads (all lanes
-// the same chunk, 32 different rows) spread over the banks.  As soon as the unit is in registers the
-// next one is requested into the same slot; the code pieces and scale bytes of a unit are written
-// out one unit late, so that nothing waits on a store that was just issued (loads and stores share
-// one completion counter).
+// row).  `wpg` workgroups share a K group and split its row tiles evenly, so a workgroup fetches the
+// group's transform operands (48 KiB, kept in LDS) exactly once; its waves draw units from an LDS
+// counter.  A wave's unit of X is fetched global -> LDS with LDS-direct loads (no registers are tied up
+// while it is in flight), as rows of 16 chunks of 16 bytes, chunk c of row r at position c ^ (r & 7) so
+// that the operand reads (all lanes the same chunk, 32 different rows) spread over the banks.  As soon
+// as the unit is in registers the next one is requested into the same slot; the code pieces and scale
+// bytes of a unit are written out one unit late, so that nothing waits on a store that was just issued
+// (loads and stores share one completion counter).
 // MINMAX selects the two-ratio clipping of Eq. 3-4 (clip = ratios on the block minimum, clip_max on the
 // maximum) instead of one ratio on the block amax.
 // FP8 selects MXFP8 (E4M3) output in the blocked 8-bit code layout (a unit then fills four pieces:
