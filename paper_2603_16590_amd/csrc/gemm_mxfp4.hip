@@ -787,14 +787,15 @@ struct A8Ctx {
         for (int j = 0; j < 4; ++j)
             aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
         // B: load q of wave w fills LDS rows 32 (2 w + q) .. + 31 (32 bytes each); lane i -> row i / 2, 16-byte
-        // position i % 2, which holds block (i % 2) ^ ((row / 4) % 2) of the K step; in the 4-bit piece
+        // position i % 2, which holds block (i % 2) ^ ((row / 8) % 2) of the K step (8 rows of 32 bytes span
+        // all LDS banks once); in the 4-bit piece
         // (16 rows x 64 bytes, 2 K steps) that block sits in slot (2 (s % 2) + block) ^ ((row % 16) / 4);
         // the offset below is for an even stage, an odd stage flips bit 5.
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int rho = lane >> 1, p = lane & 1;
             const int r16 = rho & 15;
-            const int blk = p ^ ((rho >> 2) & 1);
+            const int blk = p ^ ((rho >> 3) & 1);
             const int rg = min((t.n0 >> 4) + 2 * (2 * wave + q) + (rho >> 4), rgB - 1);
             boff[q] = (uint32_t)rg * (uint32_t)((T >> 1) * 1024) + r16 * 64 + ((blk ^ ((r16 >> 2) & 3)) << 4);
         }
@@ -835,7 +836,7 @@ struct A8Ctx {
         // A: this lane's halves (kg) of the two blocks of the step: slots kg and 2 + kg of its 64-byte row
         a_rd = (wm * 128 + l32) * 64 + ((kg ^ sw) << 4);
         // B: block kg of the step, 32-byte rows
-        b_rd = kA8StageA + (wn * 32 * nj + l32) * 32 + ((kg ^ (sw & 1)) << 4);
+        b_rd = kA8StageA + (wn * 32 * nj + l32) * 32 + ((kg ^ ((l32 >> 3) & 1)) << 4);
         sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
         sc_b_rd = kTile * 8 + ((wn * 32 * nj + l32) * 2 + kg) * 4;
     }
