@@ -247,6 +247,33 @@ batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w,
                              void* Y, batq_dtype ydtype, int64_t ldy,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------
+ * Options form of the online calls, for fusing the step before the quantiser (Sec. 3.2 places the
+ * transforms behind the normalisation layers):
+ *   act_bits   4 (or 0): MXFP4 activations; 8: MXFP8 (the *_mxfp8 / *_a8w4 calls above)
+ *   row_scale  DEVICE fp32 [M] (4-byte aligned) or NULL: every transformed row is multiplied by
+ *              row_scale[m] (one fp32 multiply per element) before clipping and quantisation.  With
+ *              row_scale = 1/rms(x_m) (batq_row_rms_scale) and the norm weight folded into the
+ *              transform blocks, T'_k = diag(gamma_k) T_k (dense form), this is RMSNorm -> transform
+ *              -> quantise in one pass over X:  RMSNorm(x) T = r (x diag(gamma)) T.
+ * A NULL `opt` is the plain call.  The workspace of batq_linear_ex is batq_linear_workspace or
+ * batq_linear_a8w4_workspace according to act_bits. */
+typedef struct {
+    int act_bits;
+    const float* row_scale;
+} batq_act_options;
+batq_status batq_quantize_act_ex(const batq_transform* t, const void* X, batq_dtype xdtype,
+                                 int M, int K, int64_t ldx, const batq_act_options* opt,
+                                 uint8_t* codes, uint8_t* scales, void* stream);
+batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w,
+                           const void* X, batq_dtype xdtype, int M, int64_t ldx,
+                           const batq_act_options* opt,
+                           void* Y, batq_dtype ydtype, int64_t ldy,
+                           void* workspace, size_t workspace_bytes, void* stream);
+/* row_scale[m] = 1 / sqrt(mean_j X[m][j]^2 + eps), fp32 accumulation; X as for batq_quantize_act. */
+batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps,
+                               float* row_scale, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

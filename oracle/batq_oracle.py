@@ -30,6 +30,10 @@ out x in, Sec. 3.1):
                          shared exponent floor(log2 amax) - 8, saturation at
                          +-448; ``gemm_a8w4`` multiplies such activations with
                          MXFP4 weights.
+* ``rmsnorm`` / ``fold_norm_weight`` / ``row_rms_scale`` - the normalisation layer
+                         the transforms sit behind (Sec. 3.2, placement of P_qkv and
+                         P_up) and the identity that lets it be fused:
+                         RMSNorm(x) T = r (x diag(gamma)) T.
 * ``prepare_weight``   - Alg. 2 "Offline Fusion" (inverse transform of W,
                          clip, quantise).
 * ``gemm`` / ``linear``- the objective of Sec. 3.1, Q(XP) Q(P^-1 W^T).
@@ -323,21 +327,46 @@ def mxfp4_quantize_minmax(Xt32: np.ndarray, r_min, r_max) -> tuple[np.ndarray, n
     return pack_codes(codes), scales
 
 
+def rmsnorm(X: np.ndarray, gamma: np.ndarray, eps: float) -> np.ndarray:
+    """RMSNorm as a plain definition, fp64: x_j * gamma_j / sqrt(mean_j x_j^2 + eps)."""
+    X = np.asarray(X, dtype=np.float64)
+    return X / np.sqrt(np.mean(X * X, axis=1, keepdims=True) + eps) * np.asarray(gamma, dtype=np.float64)[None, :]
+
+
+def row_rms_scale(X: np.ndarray, eps: float) -> np.ndarray:
+    """r_m = 1 / sqrt(mean_j x_mj^2 + eps), fp64."""
+    X = np.asarray(X, dtype=np.float64)
+    return 1.0 / np.sqrt(np.mean(X * X, axis=1) + eps)
+
+
+def fold_norm_weight(T: np.ndarray, gamma: np.ndarray) -> np.ndarray:
+    """T'_k = diag(gamma_k) T_k: the norm weight moved into the transform blocks."""
+    T = np.asarray(T, dtype=np.float64)
+    return T * np.asarray(gamma, dtype=np.float64).reshape(T.shape[0], BLOCK, 1)
+
+
 def quantize_act_blocks(X: np.ndarray, T, clip=None, clip_min=None, clip_max=None,
-                        chunk: int = 512) -> tuple[np.ndarray, np.ndarray]:
-    """Online activation path for dense blocks T [nb, 32, 32] (None = identity): Eq. 1, then either the
-    symmetric clip (``clip``) or the two-ratio clip of Eq. 3-4 (``clip_min``, ``clip_max``), then MXFP4."""
+                        chunk: int = 512, row_scale=None, fp8: bool = False) -> tuple[np.ndarray, np.ndarray]:
+    """Online activation path for dense blocks T [nb, 32, 32] (None = identity): optional row factors,
+    Eq. 1, then either the symmetric clip (``clip``) or the two-ratio clip of Eq. 3-4 (``clip_min``,
+    ``clip_max``), then MXFP4 (MXFP8 with ``fp8``)."""
     X = np.asarray(X)
     assert (clip_min is None) == (clip_max is None) and (clip is None or clip_min is None)
+    assert not (fp8 and clip_min is not None)
     cs, ss = [], []
     for r0 in range(0, X.shape[0], chunk):
-        Xr = X[r0:r0 + chunk]
-        Xt = np.asarray(Xr, np.float64).astype(np.float32) if T is None else apply_blocks(Xr, T).astype(np.float32)
-        c, s = mxfp4_quantize(Xt, clip) if clip_min is None else mxfp4_quantize_minmax(Xt, clip_min, clip_max)
+        Xr = np.asarray(X[r0:r0 + chunk], dtype=np.float64)
+        if row_scale is not None:                       # each row times its factor (e.g. RMSNorm's 1/rms)
+            Xr = Xr * np.asarray(row_scale, dtype=np.float64)[r0:r0 + chunk, None]
+        Xt = Xr.astype(np.float32) if T is None else apply_blocks(Xr, T).astype(np.float32)
+        if fp8:
+            c, s = mxfp8_quantize(Xt, clip)
+        else:
+            c, s = mxfp4_quantize(Xt, clip) if clip_min is None else mxfp4_quantize_minmax(Xt, clip_min, clip_max)
         cs.append(c)
         ss.append(s)
     if not cs:
-        return (np.zeros((0, X.shape[1] // 2), np.uint8), np.zeros((0, X.shape[1] // BLOCK), np.uint8))
+        return (np.zeros((0, X.shape[1] // (1 if fp8 else 2)), np.uint8), np.zeros((0, X.shape[1] // BLOCK), np.uint8))
     return np.concatenate(cs), np.concatenate(ss)
 
 

@@ -59,6 +59,9 @@ SYMBOLS = {
     "batq_gemm_a8w4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
     "batq_linear_a8w4_workspace": (_sz, [_i, _i]),
     "batq_linear_a8w4": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_quantize_act_ex": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp, _vp]),
+    "batq_linear_ex": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_row_rms_scale": (_i, [_vp, _i, _i, _i, _i64, C.c_float, _vp, _vp]),
 }
 
 
@@ -411,4 +414,63 @@ def batq_linear_a8w4(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspa
                                 X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
                                 Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
                                 workspace.numel(), _stream()), "batq_linear_a8w4")
+    return Y
+
+
+# ---- options form: fused row scaling (RMSNorm) and activation width
+class ActOptions(C.Structure):
+    """batq_act_options of include/batq.h."""
+    _fields_ = [("act_bits", _i), ("row_scale", _vp)]
+
+
+def _opts(act_bits: int, row_scale):
+    o = ActOptions()
+    o.act_bits = act_bits
+    if row_scale is not None:
+        import torch
+        assert row_scale.is_cuda and row_scale.dtype == torch.float32 and row_scale.is_contiguous()
+        o.row_scale = row_scale.data_ptr()
+    return o
+
+
+def batq_row_rms_scale(X, eps: float = 1e-6):
+    """1 / sqrt(mean(x^2) + eps) per row, fp32 device tensor [M]."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    out = torch.empty((M,), dtype=torch.float32, device=X.device)
+    _check(lib.batq_row_rms_scale(X.data_ptr(), _dtype_code(X), M, K, X.stride(0) if M > 1 else max(K, X.stride(0)),
+                                  eps, out.data_ptr(), _stream()), "batq_row_rms_scale")
+    return out
+
+
+def batq_quantize_act_ex(t: Transform, X, act_bits: int = 4, row_scale=None):
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    nbytes = batq_code8_bytes(M, K) if act_bits == 8 else batq_code_bytes(M, K)
+    codes = torch.empty((nbytes,), dtype=torch.uint8, device=X.device)
+    scales = torch.empty((batq_scale_bytes(M, K),), dtype=torch.uint8, device=X.device)
+    o = _opts(act_bits, row_scale)
+    _check(lib.batq_quantize_act_ex(t.handle, X.data_ptr(), _dtype_code(X), M, K,
+                                    X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), codes.data_ptr(),
+                                    scales.data_ptr(), _stream()), "batq_quantize_act_ex")
+    return codes, scales
+
+
+def batq_linear_ex(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=None, out_dtype=None, Y=None,
+                   workspace=None):
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if Y is None:
+        Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
+    need = batq_linear_a8w4_workspace(M, K) if act_bits == 8 else batq_linear_workspace(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+    o = _opts(act_bits, row_scale)
+    _check(lib.batq_linear_ex(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
+                              X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), Y.data_ptr(),
+                              _dtype_code(Y), Y.stride(0) if M > 1 else max(w.N, Y.stride(0)),
+                              workspace.data_ptr(), workspace.numel(), _stream()), "batq_linear_ex")
     return Y

@@ -40,8 +40,12 @@ namespace batq {
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
 // Codes are written in the blocked layout of code_layout.h (fp8: MXFP8 codes in its 8-bit variant),
 // scales in the grouped layout of scale_layout.h (padding blocks of the last K group included).
+// row_scale: DEVICE fp32 [M] or null; each transformed row is multiplied by its factor before clipping.
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream);
+                               int64_t ldx, const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8,
+                               hipStream_t stream);
+hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
+                                hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
                                  int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
                                  uint8_t* codes, uint8_t* scales, hipStream_t stream);

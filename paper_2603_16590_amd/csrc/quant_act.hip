@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(256)
 quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
                const float* __restrict__ G, int g_stride, const float* __restrict__ P, int p_stride,
                const float* __restrict__ clip, const float* __restrict__ clip_max,
-               uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+               const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     constexpr int GI = 32 / GO;
     const int q = threadIdx.x & 3;
     int k = blockIdx.x * 64 + (threadIdx.x >> 2);
@@ -161,6 +161,12 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
             for (int i = 0; i < 8; ++i) y[i] = x[i];
         }
 
+        if (row_scale) {
+            // fused row scaling (e.g. RMSNorm's 1/rms): the transformed row times row_scale[row]
+            const float rs = row_scale[row];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) y[i] *= rs;
+        }
         float bound;
         if (clip_max) {
             // Eq. 3-4 as printed: block minimum and maximum over the quad, clamp to [r_min min, r_max max];
@@ -255,7 +261,7 @@ template <bool MINMAX, bool FP8>
 __global__ void __launch_bounds__(QuantPlan<FP8>::kWaves * 64)
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int wpg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
-               uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+               const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     extern __shared__ __align__(16) uint8_t qlds[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -380,6 +386,8 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
             if (my_u < u_end) request(g, my_u);
             flush();
 
+            // fused row scaling (e.g. RMSNorm's 1/rms): this lane's row of the tile
+            const float rs = row_scale ? row_scale[min((u >> 1) * 32 + l32, M - 1)] : 1.0f;
             uint32_t sc4[4] = {127u, 127u, 127u, 127u};    // padding blocks keep the neutral scale
 #pragma unroll
             for (int bb = 0; bb < 4; ++bb) {
@@ -404,6 +412,10 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
                     float y[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) y[r] = acc[r];
+                    if (row_scale) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) y[r] *= rs;
+                    }
                     float bound;
                     if constexpr (MINMAX) {
                         float mn = y[0], mx = y[0];
@@ -464,8 +476,8 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
 }
 
 template <bool MINMAX, bool FP8>
-hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
-                          uint8_t* scales, int cus, hipStream_t stream) {
+hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const float* row_scale,
+                          uint8_t* codes, uint8_t* scales, int cus, hipStream_t stream) {
     using Plan = QuantPlan<FP8>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -481,12 +493,12 @@ hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int
     const int wgs = wpg * std::min(groups, cus);
     quant_act_mfma<MINMAX, FP8><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
         X, ldx, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
-        MINMAX ? t->d_clip_max : nullptr, codes, scales);
+        MINMAX ? t->d_clip_max : nullptr, row_scale, codes, scales);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, uint8_t* codes,
-                       uint8_t* scales, bool fp8, hipStream_t stream) {
+hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const float* row_scale,
+                       uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0;
@@ -498,15 +510,15 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
         }
     }
     if (fp8)
-        return t->minmax ? launch_mfma_as<true, true>(t, X, M, ldx, codes, scales, cus, stream)
-                         : launch_mfma_as<false, true>(t, X, M, ldx, codes, scales, cus, stream);
-    return t->minmax ? launch_mfma_as<true, false>(t, X, M, ldx, codes, scales, cus, stream)
-                     : launch_mfma_as<false, false>(t, X, M, ldx, codes, scales, cus, stream);
+        return t->minmax ? launch_mfma_as<true, true>(t, X, M, ldx, row_scale, codes, scales, cus, stream)
+                         : launch_mfma_as<false, true>(t, X, M, ldx, row_scale, codes, scales, cus, stream);
+    return t->minmax ? launch_mfma_as<true, false>(t, X, M, ldx, row_scale, codes, scales, cus, stream)
+                     : launch_mfma_as<false, false>(t, X, M, ldx, row_scale, codes, scales, cus, stream);
 }
 
 template <typename XT, bool FP8>
-hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes,
-                       uint8_t* scales, hipStream_t stream) {
+hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, const float* row_scale,
+                       uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
     const int gx = (scale_groups(nb) * 8 + 63) / 64;
     // aim at >= 4 workgroups per CU while keeping the per-lane factor loads amortised
@@ -517,15 +529,15 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     const float* cmax = t->minmax ? t->d_clip_max : nullptr;
     if (!t->has_transform)
         quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, 0, nullptr,
-                                                                       0, t->d_clip, cmax, codes, scales);
+                                                                       0, t->d_clip, cmax, row_scale, codes, scales);
     else if (t->g_outer == 4)
         quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
-                                                                      t->d_clip, cmax, codes, scales);
+                                                                      t->d_clip, cmax, row_scale, codes, scales);
     else
         quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
-                                                                      t->d_clip, cmax, codes, scales);
+                                                                      t->d_clip, cmax, row_scale, codes, scales);
     return hipGetLastError();
 }
 
@@ -537,7 +549,7 @@ template <typename XT, bool FP8>
 __global__ void __launch_bounds__(256)
 quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const float* __restrict__ T,
                 const float* __restrict__ clip, const float* __restrict__ clip_max,
-                uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     __shared__ float sT[32 * 32];
     const int k = blockIdx.x;                               // includes the padding blocks of the last K group
     const bool live = k < nb;
@@ -565,6 +577,11 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
 #pragma unroll
         for (int j = 1; j < 32; ++j) acc = __builtin_fmaf(x[j], sT[j * 32 + j2], acc);
         y[j2] = acc;
+    }
+    if (row_scale) {
+        const float rs = row_scale[row];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) y[j] *= rs;
     }
     float bound;
     if (clip_max) {
@@ -607,38 +624,69 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
 }
 
 template <typename XT, bool FP8>
-hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, uint8_t* codes, uint8_t* scales,
-                        hipStream_t stream) {
+hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, const float* row_scale,
+                        uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const dim3 grid(scale_groups(t->nb) * 8, (M + 255) / 256), block(256);
     quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, M, t->nb, t->d_T, t->d_clip,
-                                                          t->minmax ? t->d_clip_max : nullptr, codes, scales);
+                                                          t->minmax ? t->d_clip_max : nullptr, row_scale, codes, scales);
     return hipGetLastError();
 }
 
 template <bool FP8>
 hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
-                              uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                              const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     if (xdtype == BATQ_BF16) {
+        auto Xp = static_cast<const uint16_t*>(X);
         // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets
         if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
-            return launch_mfma(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, FP8, stream);
-        if (t->form == BATQ_FORM_DENSE)
-            return launch_dense<uint16_t, FP8>(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
-        return launch_quad<uint16_t, FP8>(t, static_cast<const uint16_t*>(X), M, ldx, codes, scales, stream);
+            return launch_mfma(t, Xp, M, ldx, row_scale, codes, scales, FP8, stream);
+        if (t->form == BATQ_FORM_DENSE) return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
+        return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
     }
-    if (t->form == BATQ_FORM_DENSE)
-        return launch_dense<float, FP8>(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
-    return launch_quad<float, FP8>(t, static_cast<const float*>(X), M, ldx, codes, scales, stream);
+    auto Xp = static_cast<const float*>(X);
+    if (t->form == BATQ_FORM_DENSE) return launch_dense<float, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
+    return launch_quad<float, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
+}
+
+// 1 / sqrt(mean_j x_j^2 + eps) per row (RMSNorm's row factor), one wave per row, fp32 accumulation.
+template <typename XT>
+__global__ void __launch_bounds__(256)
+row_rms_scale(const XT* __restrict__ X, int64_t ldx, int M, int K, float eps, float* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;                                   // wave-uniform
+    float acc = 0.f;
+    for (int c = lane * 8; c < K; c += 64 * 8) {            // K is a multiple of 32, so whole groups of 8
+        float x[8];
+        load8(X + (size_t)row * ldx + c, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = __builtin_fmaf(x[i], x[i], acc);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) out[row] = 1.0f / __builtin_sqrtf(acc / (float)K + eps);
 }
 
 }  // namespace
 
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
+                               int64_t ldx, const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8,
+                               hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, codes, scales, stream)
-               : launch_quantize_as<false>(t, X, xdtype, M, ldx, codes, scales, stream);
+    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, row_scale, codes, scales, stream)
+               : launch_quantize_as<false>(t, X, xdtype, M, ldx, row_scale, codes, scales, stream);
+}
+
+hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
+                                hipStream_t stream) {
+    if (M == 0) return hipSuccess;
+    const dim3 grid((M + 3) / 4), block(256);
+    if (xdtype == BATQ_BF16)
+        row_rms_scale<uint16_t><<<grid, block, 0, stream>>>(static_cast<const uint16_t*>(X), ldx, M, K, eps, out);
+    else
+        row_rms_scale<float><<<grid, block, 0, stream>>>(static_cast<const float*>(X), ldx, M, K, eps, out);
+    return hipGetLastError();
 }
 
 }  // namespace batq
