@@ -1,0 +1,69 @@
+"""The online calls only enqueue kernels (no allocation, no host synchronisation): they must work on a
+non-default stream and inside a captured HIP graph, replayed several times with eager work in between."""
+import numpy as np
+import pytest
+
+import batq_inputs as bi
+from gpu_util import require_gpu, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    require_gpu()
+    import paper_2603_16590_amd as b
+    return b
+
+
+def _setup(B, M, K, N, seed):
+    w = bi.make_small(M, K, N, seed=seed, dtype="bf16")
+    t = B.Transform(w.K, w.G, w.P, w.clip)
+    wh = B.batq_prepare_weight(t, to_dev(w.W, "bf16"))
+    return w, t, wh
+
+
+@pytest.mark.parametrize("M", [16, 384])
+def test_linear_on_a_side_stream(B, M):
+    import torch
+    w, t, wh = _setup(B, M, 32 * 20, 320, seed=M)
+    X = to_dev(w.X, "bf16")
+    ref = B.batq_linear(t, wh, X, torch.bfloat16)
+    ref8 = B.batq_linear_a8w4(t, wh, X, torch.bfloat16)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    work = torch.empty(B.batq_linear_a8w4_workspace(M, w.K), dtype=torch.uint8, device="cuda")
+    Y = torch.empty_like(ref)
+    Y8 = torch.empty_like(ref)
+    with torch.cuda.stream(side):
+        B.batq_linear(t, wh, X, Y=Y, workspace=work)
+        B.batq_linear_a8w4(t, wh, X, Y=Y8, workspace=work)
+    side.synchronize()
+    assert torch.equal(Y, ref) and torch.equal(Y8, ref8)
+
+
+@pytest.mark.parametrize("M", [16, 384])
+def test_linear_inside_a_captured_graph(B, M):
+    import torch
+    w, t, wh = _setup(B, M, 32 * 20, 320, seed=100 + M)
+    rng = np.random.default_rng(M)
+    X = to_dev(w.X, "bf16")
+    work = torch.empty(B.batq_linear_workspace(M, w.K), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((M, w.N), dtype=torch.bfloat16, device="cuda")
+    B.batq_linear(t, wh, X, Y=Y, workspace=work)              # first call outside the capture (one-time set-up)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.batq_linear(t, wh, X, Y=Y, workspace=work)
+    for rep in range(4):
+        # new input in place, eager reference, some unrelated eager work, then the replay
+        Xn = bi.f32_to_bf16_bits((rng.standard_normal((M, w.K)) * (rep + 1)).astype(np.float32))
+        X.copy_(to_dev(Xn, "bf16"))
+        ref = B.batq_linear(t, wh, X, torch.bfloat16)
+        junk = (torch.randn(257, 129, device="cuda") @ torch.randn(129, 65, device="cuda")).sum()
+        torch.cuda.synchronize()
+        Y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, ref), rep
+        assert bool(torch.isfinite(junk))
