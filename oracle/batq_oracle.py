@@ -34,6 +34,10 @@ out x in, Sec. 3.1):
                          the transforms sit behind (Sec. 3.2, placement of P_qkv and
                          P_up) and the identity that lets it be fused:
                          RMSNorm(x) T = r (x diag(gamma)) T.
+* ``silu`` / ``swiglu`` / ``swiglu_bf16`` - the gated activation whose output is the input of the
+                         down projection (Sec. 3.2, placement of P_down): silu(gate) * up
+                         as a plain definition, and its rounding to the bf16 tensor a model
+                         hands to the layer.
 * ``prepare_weight``   - Alg. 2 "Offline Fusion" (inverse transform of W,
                          clip, quantise).
 * ``gemm`` / ``linear``- the objective of Sec. 3.1, Q(XP) Q(P^-1 W^T).
@@ -343,6 +347,24 @@ def fold_norm_weight(T: np.ndarray, gamma: np.ndarray) -> np.ndarray:
     """T'_k = diag(gamma_k) T_k: the norm weight moved into the transform blocks."""
     T = np.asarray(T, dtype=np.float64)
     return T * np.asarray(gamma, dtype=np.float64).reshape(T.shape[0], BLOCK, 1)
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    """x * sigmoid(x) = x / (1 + exp(-x)), fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    with np.errstate(over="ignore"):
+        return x / (1.0 + np.exp(-x))
+
+
+def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """silu(gate) * up element by element, fp64."""
+    return silu(gate) * np.asarray(up, dtype=np.float64)
+
+
+def swiglu_bf16(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """The gated activation as the bf16 tensor the down projection receives: one rounding of the
+    fp64 product to bf16 (returned as fp32)."""
+    return bf16_round(swiglu(gate, up))
 
 
 def quantize_act_blocks(X: np.ndarray, T, clip=None, clip_min=None, clip_max=None,
