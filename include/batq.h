@@ -256,11 +256,20 @@ batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w,
  *              row_scale = 1/rms(x_m) (batq_row_rms_scale) and the norm weight folded into the
  *              transform blocks, T'_k = diag(gamma_k) T_k (dense form), this is RMSNorm -> transform
  *              -> quantise in one pass over X:  RMSNorm(x) T = r (x diag(gamma)) T.
- * A NULL `opt` is the plain call.  The workspace of batq_linear_ex is batq_linear_workspace or
+ *   up, ld_up  DEVICE bf16 [M][K] with row stride ld_up elements (16-byte aligned rows), or NULL.  With
+ *              `up`, X is the gate of a gated activation (the producer of the down projection's
+ *              input, which Sec. 3.2 puts P_down in front of) and the quantiser's input is
+ *              h = bf16(silu(X) * up): the product in fp32 (about 2^-21 relative; magnitudes below
+ *              2^-100 may come out as zero), rounded once to bf16 as an unfused model would store
+ *              it.  X must then be BATQ_BF16 (else BATQ_ERR_DTYPE); gate and up may be the two
+ *              halves of one [M][2K] tensor (ldx = ld_up = 2K).
+ * A NULL `opt` is the plain call; zero-initialise the struct and set what is needed.  The workspace of batq_linear_ex is batq_linear_workspace or
  * batq_linear_a8w4_workspace according to act_bits. */
 typedef struct {
     int act_bits;
     const float* row_scale;
+    const void* up;
+    int64_t ld_up;
 } batq_act_options;
 batq_status batq_quantize_act_ex(const batq_transform* t, const void* X, batq_dtype xdtype,
                                  int M, int K, int64_t ldx, const batq_act_options* opt,

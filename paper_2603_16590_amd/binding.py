@@ -420,16 +420,20 @@ def batq_linear_a8w4(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspa
 # ---- options form: fused row scaling (RMSNorm) and activation width
 class ActOptions(C.Structure):
     """batq_act_options of include/batq.h."""
-    _fields_ = [("act_bits", _i), ("row_scale", _vp)]
+    _fields_ = [("act_bits", _i), ("row_scale", _vp), ("up", _vp), ("ld_up", C.c_int64)]
 
 
-def _opts(act_bits: int, row_scale):
+def _opts(act_bits: int, row_scale, up=None, X=None):
     o = ActOptions()
     o.act_bits = act_bits
     if row_scale is not None:
         import torch
         assert row_scale.is_cuda and row_scale.dtype == torch.float32 and row_scale.is_contiguous()
         o.row_scale = row_scale.data_ptr()
+    if up is not None:
+        assert up.is_cuda and up.shape == X.shape and up.dtype == X.dtype and up.stride(1) == 1
+        o.up = up.data_ptr()
+        o.ld_up = up.stride(0) if up.shape[0] > 1 else max(up.shape[1], up.stride(0))
     return o
 
 
@@ -444,14 +448,14 @@ def batq_row_rms_scale(X, eps: float = 1e-6):
     return out
 
 
-def batq_quantize_act_ex(t: Transform, X, act_bits: int = 4, row_scale=None):
+def batq_quantize_act_ex(t: Transform, X, act_bits: int = 4, row_scale=None, up=None):
     import torch
     assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
     M, K = X.shape
     nbytes = batq_code8_bytes(M, K) if act_bits == 8 else batq_code_bytes(M, K)
     codes = torch.empty((nbytes,), dtype=torch.uint8, device=X.device)
     scales = torch.empty((batq_scale_bytes(M, K),), dtype=torch.uint8, device=X.device)
-    o = _opts(act_bits, row_scale)
+    o = _opts(act_bits, row_scale, up, X)
     _check(lib.batq_quantize_act_ex(t.handle, X.data_ptr(), _dtype_code(X), M, K,
                                     X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), codes.data_ptr(),
                                     scales.data_ptr(), _stream()), "batq_quantize_act_ex")
@@ -459,7 +463,7 @@ def batq_quantize_act_ex(t: Transform, X, act_bits: int = 4, row_scale=None):
 
 
 def batq_linear_ex(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=None, out_dtype=None, Y=None,
-                   workspace=None):
+                   workspace=None, up=None):
     import torch
     assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
     M, K = X.shape
@@ -468,7 +472,7 @@ def batq_linear_ex(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=None
     need = batq_linear_a8w4_workspace(M, K) if act_bits == 8 else batq_linear_workspace(M, K)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
-    o = _opts(act_bits, row_scale)
+    o = _opts(act_bits, row_scale, up, X)
     _check(lib.batq_linear_ex(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
                               X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), Y.data_ptr(),
                               _dtype_code(Y), Y.stride(0) if M > 1 else max(w.N, Y.stride(0)),

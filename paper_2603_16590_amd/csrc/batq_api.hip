@@ -411,8 +411,25 @@ batq_status batq_weight_destroy(batq_weight* w) {
 
 namespace {
 
+// The optional inputs of the online path: per-row factors and the up tensor of a gated activation.
+struct ActExtras {
+    const float* row_scale = nullptr;
+    const void* up = nullptr;
+    int64_t ld_up = 0;
+};
+
+// Gated input: bf16 only (the rounding of silu(gate) * up is to bf16), up laid out like X.
+batq_status check_extras(const ActExtras& ex, batq_dtype xdtype, int K) {
+    if ((reinterpret_cast<uintptr_t>(ex.row_scale) & 3u) != 0) return BATQ_ERR_SHAPE;
+    if (ex.up) {
+        if (xdtype != BATQ_BF16) return BATQ_ERR_DTYPE;
+        if (ex.ld_up < K || !aligned16(ex.up) || (ex.ld_up * 2) % 16 != 0) return BATQ_ERR_SHAPE;
+    }
+    return BATQ_OK;
+}
+
 batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K, int64_t ldx,
-                          const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8, void* stream) {
+                          const ActExtras& ex, uint8_t* codes, uint8_t* scales, bool fp8, void* stream) {
     if (!t) return BATQ_ERR_NULL;
     if (!dtype_ok(xdtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || K <= 0 || K % 32 != 0 || ldx < K) return BATQ_ERR_SHAPE;
@@ -423,8 +440,8 @@ batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdt
     if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(codes) ||
         (reinterpret_cast<uintptr_t>(scales) & 7u) != 0)
         return BATQ_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(row_scale) & 3u) != 0) return BATQ_ERR_SHAPE;
-    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, row_scale, codes, scales, fp8,
+    if (batq_status st = check_extras(ex, xdtype, K); st != BATQ_OK) return st;
+    if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales, fp8,
                                   static_cast<hipStream_t>(stream)) != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
@@ -456,7 +473,7 @@ size_t workspace_impl(int M, int K, bool a8) {
 }
 
 batq_status linear_impl(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
-                        int64_t ldx, const float* row_scale, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
+                        int64_t ldx, const ActExtras& ex, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                         size_t workspace_bytes, bool a8, void* stream) {
     if (!t || !w) return BATQ_ERR_NULL;
     if (!dtype_ok(xdtype) || !dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
@@ -465,13 +482,14 @@ batq_status linear_impl(const batq_transform* t, const batq_weight* w, const voi
     if (M == 0) return BATQ_OK;
     if (!X || !Y || !workspace) return BATQ_ERR_NULL;
     if (workspace_bytes < workspace_impl(M, t->K, a8)) return BATQ_ERR_WORKSPACE;
-    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace) ||
-        (reinterpret_cast<uintptr_t>(row_scale) & 3u) != 0)
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace))
         return BATQ_ERR_SHAPE;
+    if (batq_status st = check_extras(ex, xdtype, t->K); st != BATQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* codes = static_cast<uint8_t*>(workspace);
     uint8_t* scales = codes + (a8 ? batq::code8_bytes_blocked(M, t->nb) : batq::code_bytes_blocked(M, t->nb));
-    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, row_scale, codes, scales, a8, s);
+    hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales,
+                                             a8, s);
     if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, s);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -486,12 +504,12 @@ extern "C" {
 
 batq_status batq_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                               int64_t ldx, uint8_t* codes, uint8_t* scales, void* stream) {
-    return quantize_impl(t, X, xdtype, M, K, ldx, nullptr, codes, scales, false, stream);
+    return quantize_impl(t, X, xdtype, M, K, ldx, ActExtras{}, codes, scales, false, stream);
 }
 
 batq_status batq_quantize_act_mxfp8(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                     int64_t ldx, uint8_t* codes8, uint8_t* scales, void* stream) {
-    return quantize_impl(t, X, xdtype, M, K, ldx, nullptr, codes8, scales, true, stream);
+    return quantize_impl(t, X, xdtype, M, K, ldx, ActExtras{}, codes8, scales, true, stream);
 }
 
 size_t batq_code8_bytes(int rows, int K) {
@@ -583,21 +601,25 @@ size_t batq_linear_a8w4_workspace(int M, int K) { return workspace_impl(M, K, tr
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                         int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                         size_t workspace_bytes, void* stream) {
-    return linear_impl(t, w, X, xdtype, M, ldx, nullptr, Y, ydtype, ldy, workspace, workspace_bytes, false, stream);
+    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, false, stream);
 }
 
 batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                              int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                              size_t workspace_bytes, void* stream) {
-    return linear_impl(t, w, X, xdtype, M, ldx, nullptr, Y, ydtype, ldy, workspace, workspace_bytes, true, stream);
+    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, true, stream);
 }
 
 // ---- options form of the online calls
-static bool act_options_ok(const batq_act_options* opt, bool* a8) {
+static bool act_options_ok(const batq_act_options* opt, bool* a8, ActExtras* ex) {
     *a8 = false;
+    *ex = ActExtras{};
     if (!opt) return true;
     if (opt->act_bits != 0 && opt->act_bits != 4 && opt->act_bits != 8) return false;
     *a8 = opt->act_bits == 8;
+    ex->row_scale = opt->row_scale;
+    ex->up = opt->up;
+    ex->ld_up = opt->ld_up;
     return true;
 }
 
@@ -605,17 +627,18 @@ batq_status batq_quantize_act_ex(const batq_transform* t, const void* X, batq_dt
                                  int64_t ldx, const batq_act_options* opt, uint8_t* codes, uint8_t* scales,
                                  void* stream) {
     bool a8;
-    if (!act_options_ok(opt, &a8)) return BATQ_ERR_UNSUPPORTED;
-    return quantize_impl(t, X, xdtype, M, K, ldx, opt ? opt->row_scale : nullptr, codes, scales, a8, stream);
+    ActExtras ex;
+    if (!act_options_ok(opt, &a8, &ex)) return BATQ_ERR_UNSUPPORTED;
+    return quantize_impl(t, X, xdtype, M, K, ldx, ex, codes, scales, a8, stream);
 }
 
 batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                            int64_t ldx, const batq_act_options* opt, void* Y, batq_dtype ydtype, int64_t ldy,
                            void* workspace, size_t workspace_bytes, void* stream) {
     bool a8;
-    if (!act_options_ok(opt, &a8)) return BATQ_ERR_UNSUPPORTED;
-    return linear_impl(t, w, X, xdtype, M, ldx, opt ? opt->row_scale : nullptr, Y, ydtype, ldy, workspace,
-                       workspace_bytes, a8, stream);
+    ActExtras ex;
+    if (!act_options_ok(opt, &a8, &ex)) return BATQ_ERR_UNSUPPORTED;
+    return linear_impl(t, w, X, xdtype, M, ldx, ex, Y, ydtype, ldy, workspace, workspace_bytes, a8, stream);
 }
 
 batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps,

@@ -41,9 +41,10 @@ namespace batq {
 // Codes are written in the blocked layout of code_layout.h (fp8: MXFP8 codes in its 8-bit variant),
 // scales in the grouped layout of scale_layout.h (padding blocks of the last K group included).
 // row_scale: DEVICE fp32 [M] or null; each transformed row is multiplied by its factor before clipping.
+// U: DEVICE tensor like X (same dtype, row stride ldu) or null; with U the input is bf16(silu(X) * U).
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8,
-                               hipStream_t stream);
+                               int64_t ldx, const void* U, int64_t ldu, const float* row_scale, uint8_t* codes,
+                               uint8_t* scales, bool fp8, hipStream_t stream);
 hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
                                 hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,

@@ -61,6 +61,32 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
     x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xFFFF0000u);
 }
 
+// Gated activation feeding the down projection (Sec. 3.2, P_down): silu(g) * u = g u / (1 + 2^(-g log2 e)) in
+// fp32 (hardware exp2 and reciprocal, about 2^-21 relative), rounded once to bf16: the tensor an unfused
+// model would have written.  Magnitudes below 2^-100 may come out as zero.
+__device__ __forceinline__ float swiglu_f32(float g, float u) {
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * g);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+// two bf16 pairs (gate, up) -> the bf16 pair of their gated products
+__device__ __forceinline__ uint32_t swiglu_pair(uint32_t g2, uint32_t u2) {
+    const f32x2 h = {swiglu_f32(__uint_as_float(g2 << 16), __uint_as_float(u2 << 16)),
+                     swiglu_f32(__uint_as_float(g2 & 0xFFFF0000u), __uint_as_float(u2 & 0xFFFF0000u))};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(h, bf16x2v));
+}
+// register form for the kernels that hold fp32 copies: x <- bf16(silu(x) * u)
+__device__ __forceinline__ void swiglu8(float (&x)[8], const float (&u)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        const f32x2 h = {swiglu_f32(x[i], u[i]), swiglu_f32(x[i + 1], u[i + 1])};
+        const uint32_t b = __builtin_bit_cast(uint32_t, __builtin_convertvector(h, bf16x2v));
+        x[i] = __uint_as_float(b << 16);
+        x[i + 1] = __uint_as_float(b & 0xFFFF0000u);
+    }
+}
+
 // Mix across the quad: out = sum over source lanes s of coef[s] * (value held by lane s).
 #define BATQ_QUAD_MIX(out, v, c0, c1, c2, c3)            \
     do {                                                  \
@@ -76,9 +102,11 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
 // Kronecker product (both private).  clip_max != null selects the two-ratio clipping of Eq. 3-4
 // (clip then holds the ratios on the block minimum).
 // FP8 selects MXFP8 (E4M3) output, one byte per element in the blocked 8-bit code layout.
+// U != null: X is the gate and U the up tensor of a gated activation; the input is bf16(silu(X) * U).
 template <typename XT, int GO, bool TRANSFORM, bool FP8>
 __global__ void __launch_bounds__(256)
-quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_per_wg,
+quant_act_quad(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, int64_t ldu, int M, int nb,
+               int rows_per_wg,
                const float* __restrict__ G, int g_stride, const float* __restrict__ P, int p_stride,
                const float* __restrict__ clip, const float* __restrict__ clip_max,
                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
@@ -120,6 +148,11 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, int M, int nb, int rows_pe
     for (int row = row0; row < row1; ++row) {
         float x[8], y[8];
         load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, x);
+        if (U) {
+            float u[8];
+            load8(U + (size_t)row * ldu + (size_t)k * 32 + q * 8, u);
+            swiglu8(x, u);
+        }
         if constexpr (TRANSFORM) {
             float v[8];
             if constexpr (GO == 4) {
@@ -233,15 +266,18 @@ constexpr int kQuantLdsT = 8 * kTsplitBlock;
 
 // LDS plan of the persistent workgroup (one per compute unit): transform operands of one K group, then per
 // wave one X slot and the staging area for the code pieces of a unit (two 1 KiB pieces for 4-bit codes,
-// four for 8-bit codes, which leaves room for 9 waves instead of 10), then the unit counter.
-template <bool FP8>
+// four for 8-bit codes, which leaves room for 9 waves instead of 10), then the unit counter.  With a gated
+// input a wave's slot holds the unit of the gate and the unit of the up tensor (6 and 5 waves; the bytes
+// in flight per compute unit stay about the same).
+template <bool FP8, bool SWIGLU>
 struct QuantPlan {
-    static constexpr int kWaves = FP8 ? 9 : 10;
+    static constexpr int kWaves = SWIGLU ? (FP8 ? 5 : 6) : (FP8 ? 9 : 10);
+    static constexpr int kSlot = SWIGLU ? 2 * kXSlot : kXSlot;
     static constexpr int kCodeStage = FP8 ? 4096 : 2048;
     static constexpr int kLdsX = kQuantLdsT;
-    static constexpr int kLdsStage = kLdsX + kWaves * kXSlot;
+    static constexpr int kLdsStage = kLdsX + kWaves * kSlot;
     static constexpr int kLdsCounter = kLdsStage + kWaves * kCodeStage;
-    static constexpr int kLds = kLdsCounter + 16;           // 148 KiB / 156 KiB
+    static constexpr int kLds = kLdsCounter + 16;           // 148 KiB / 156 KiB (gated: 156 KiB / 148 KiB)
 };
 
 // Persistent kernel.  Work comes in units of (32-row tile, half K group = 4 MX blocks = 256 bytes per
@@ -257,9 +293,12 @@ struct QuantPlan {
 // maximum) instead of one ratio on the block amax.
 // FP8 selects MXFP8 (E4M3) output in the blocked 8-bit code layout (a unit then fills four pieces:
 // two piece columns of 2 blocks each, times two 16-row groups).
-template <bool MINMAX, bool FP8>
-__global__ void __launch_bounds__(QuantPlan<FP8>::kWaves * 64)
-quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int wpg,
+// SWIGLU: X is the gate and U the up tensor of a gated activation; both units are fetched, and the operand
+// the matrix pipe sees is bf16(silu(X) * U), formed in registers.
+template <bool MINMAX, bool FP8, bool SWIGLU>
+__global__ void __launch_bounds__((QuantPlan<FP8, SWIGLU>::kWaves * 64))
+quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ U, int64_t ldu, int M,
+               int nb, int wpg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     extern __shared__ __align__(16) uint8_t qlds[];
@@ -269,16 +308,16 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     const int l32 = lane & 31, kg = lane >> 5;
     const int row_tiles = (M + 31) >> 5;
     const int groups = scale_groups(nb);
-    using Plan = QuantPlan<FP8>;
+    using Plan = QuantPlan<FP8, SWIGLU>;
     constexpr int kQuantWaves = Plan::kWaves;
     const size_t piece_stride = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb)) * 1024;
 
     uint8_t* const tlds = qlds;
-    uint8_t* const xslot = qlds + Plan::kLdsX + wave * kXSlot;
+    uint8_t* const xslot = qlds + Plan::kLdsX + wave * Plan::kSlot;
     uint8_t* const my = qlds + Plan::kLdsStage + wave * Plan::kCodeStage;
     uint32_t* const counter = reinterpret_cast<uint32_t*>(qlds + Plan::kLdsCounter);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte*)qlds;
-    const uint32_t xslot_lds = lds_base + Plan::kLdsX + wave * kXSlot;
+    const uint32_t xslot_lds = lds_base + Plan::kLdsX + wave * Plan::kSlot;
 
     // `wpg` workgroups share a K group, each taking an equal range of its row tiles; with more groups
     // than workgroups (wpg = 1) a workgroup takes every (gridDim.x)-th group
@@ -296,6 +335,8 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
         const int nreal = min(4, nb - kb);                  // blocks that exist (the rest of the group is padding)
         if (nreal <= 0) return;
         const uint8_t* base = reinterpret_cast<const uint8_t*>(X) + ((size_t)tile * 32 * ldx + (size_t)kb * 32) * 2;
+        const uint8_t* ubase =
+            SWIGLU ? reinterpret_cast<const uint8_t*>(U) + ((size_t)tile * 32 * ldu + (size_t)kb * 32) * 2 : nullptr;
         const int rows_left = M - 1 - tile * 32;            // rows past the end repeat the last one: computed, not stored
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -307,6 +348,11 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
             // the pending output lines out of the L2
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
                          :: "v"(voff), "s"(base), "s"(xslot_lds + (uint32_t)j * 1024) : "memory");
+            if constexpr (SWIGLU) {
+                const uint32_t uoff = (uint32_t)min(r, rows_left) * (uint32_t)(ldu * 2) + (uint32_t)c * 16;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                             :: "v"(uoff), "s"(ubase), "s"(xslot_lds + (uint32_t)(kXSlot + j * 1024)) : "memory");
+            }
         }
     };
 
@@ -368,23 +414,39 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
             const int nreal = min(4, nb - (k0 + 4 * half));
             __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): the unit has landed (older stores are long done)
             u32x4 x[4][2] = {};
+            u32x4 up[SWIGLU ? 4 : 1][2] = {};
             if (nreal > 0) {
 #pragma unroll
                 for (int bb = 0; bb < 4; ++bb)
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         const int c = 4 * bb + 2 * kg + h;
-                        x[bb][h] = *reinterpret_cast<const u32x4*>(xslot + l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4));
+                        const int at = l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4);
+                        x[bb][h] = *reinterpret_cast<const u32x4*>(xslot + at);
+                        if constexpr (SWIGLU) up[bb][h] = *reinterpret_cast<const u32x4*>(xslot + kXSlot + at);
                     }
                 // the slot is refilled next: its contents must be in registers first
 #pragma unroll
                 for (int bb = 0; bb < 4; ++bb)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) asm volatile("" : "+v"(x[bb][h]));
+                    for (int h = 0; h < 2; ++h) {
+                        asm volatile("" : "+v"(x[bb][h]));
+                        if constexpr (SWIGLU) asm volatile("" : "+v"(up[bb][h]));
+                    }
             }
             my_u = grab();
             if (my_u < u_end) request(g, my_u);
             flush();
+            if constexpr (SWIGLU) {
+                if (nreal > 0) {
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) x[bb][h][i] = swiglu_pair(x[bb][h][i], up[bb][h][i]);
+                }
+            }
 
             // fused row scaling (e.g. RMSNorm's 1/rms): this lane's row of the tile
             const float rs = row_scale ? row_scale[min((u >> 1) * 32 + l32, M - 1)] : 1.0f;
@@ -475,13 +537,14 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int w
     flush();
 }
 
-template <bool MINMAX, bool FP8>
-hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const float* row_scale,
-                          uint8_t* codes, uint8_t* scales, int cus, hipStream_t stream) {
-    using Plan = QuantPlan<FP8>;
+template <bool MINMAX, bool FP8, bool SWIGLU>
+hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U,
+                          int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales, int cus,
+                          hipStream_t stream) {
+    using Plan = QuantPlan<FP8, SWIGLU>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<MINMAX, FP8>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<MINMAX, FP8, SWIGLU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Plan::kLds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -491,14 +554,15 @@ hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int
     const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
     const int wpg = std::max(1, std::min(cus / groups, row_tiles));
     const int wgs = wpg * std::min(groups, cus);
-    quant_act_mfma<MINMAX, FP8><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
-        X, ldx, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
+    quant_act_mfma<MINMAX, FP8, SWIGLU><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
+        X, ldx, U, ldu, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
         MINMAX ? t->d_clip_max : nullptr, row_scale, codes, scales);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const float* row_scale,
-                       uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
+template <bool SWIGLU>
+hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U, int64_t ldu,
+                       const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0;
@@ -510,15 +574,17 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
         }
     }
     if (fp8)
-        return t->minmax ? launch_mfma_as<true, true>(t, X, M, ldx, row_scale, codes, scales, cus, stream)
-                         : launch_mfma_as<false, true>(t, X, M, ldx, row_scale, codes, scales, cus, stream);
-    return t->minmax ? launch_mfma_as<true, false>(t, X, M, ldx, row_scale, codes, scales, cus, stream)
-                     : launch_mfma_as<false, false>(t, X, M, ldx, row_scale, codes, scales, cus, stream);
+        return t->minmax
+                   ? launch_mfma_as<true, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream)
+                   : launch_mfma_as<false, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream);
+    return t->minmax
+               ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream)
+               : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream);
 }
 
 template <typename XT, bool FP8>
-hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, const float* row_scale,
-                       uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, const XT* U, int64_t ldu,
+                       const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const int nb = t->nb;
     const int gx = (scale_groups(nb) * 8 + 63) / 64;
     // aim at >= 4 workgroups per CU while keeping the per-lane factor loads amortised
@@ -528,14 +594,14 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
     const float* cmax = t->minmax ? t->d_clip_max : nullptr;
     if (!t->has_transform)
-        quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, nullptr, 0, nullptr,
+        quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, nullptr, 0, nullptr,
                                                                        0, t->d_clip, cmax, row_scale, codes, scales);
     else if (t->g_outer == 4)
-        quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+        quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
                                                                       t->d_clip, cmax, row_scale, codes, scales);
     else
-        quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, M, nb, rows_per_wg, t->d_outer,
+        quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
                                                                       t->d_clip, cmax, row_scale, codes, scales);
     return hipGetLastError();
@@ -547,7 +613,8 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
 // form take the matrix-core kernel.
 template <typename XT, bool FP8>
 __global__ void __launch_bounds__(256)
-quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const float* __restrict__ T,
+quant_act_dense(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, int64_t ldu, int M, int nb,
+                const float* __restrict__ T,
                 const float* __restrict__ clip, const float* __restrict__ clip_max,
                 const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     __shared__ float sT[32 * 32];
@@ -570,7 +637,15 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
     }
     float x[32], y[32];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, *reinterpret_cast<float(*)[8]>(x + 8 * q));
+    for (int q = 0; q < 4; ++q) {
+        float(&xq)[8] = *reinterpret_cast<float(*)[8]>(x + 8 * q);
+        load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, xq);
+        if (U) {                                            // gated input: bf16(silu(X) * U)
+            float u[8];
+            load8(U + (size_t)row * ldu + (size_t)k * 32 + q * 8, u);
+            swiglu8(xq, u);
+        }
+    }
 #pragma unroll 4
     for (int j2 = 0; j2 < 32; ++j2) {
         float acc = x[0] * sT[j2];
@@ -624,28 +699,40 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, int M, int nb, const floa
 }
 
 template <typename XT, bool FP8>
-hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, const float* row_scale,
-                        uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, const XT* U, int64_t ldu,
+                        const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const dim3 grid(scale_groups(t->nb) * 8, (M + 255) / 256), block(256);
-    quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, M, t->nb, t->d_T, t->d_clip,
+    quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, t->nb, t->d_T, t->d_clip,
                                                           t->minmax ? t->d_clip_max : nullptr, row_scale, codes, scales);
     return hipGetLastError();
 }
 
+constexpr int kQuadMaxRows = 128;
+
 template <bool FP8>
 hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
-                              const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                              const void* U, int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales,
+                              hipStream_t stream) {
     if (xdtype == BATQ_BF16) {
         auto Xp = static_cast<const uint16_t*>(X);
-        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets
-        if (t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25))
-            return launch_mfma(t, Xp, M, ldx, row_scale, codes, scales, FP8, stream);
-        if (t->form == BATQ_FORM_DENSE) return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
-        return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
+        auto Up = static_cast<const uint16_t*>(U);
+        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets.  With few
+        // rows (decode steps) the register-level kernel is the faster one for the Kronecker forms: it has no
+        // 48 KiB of transform operands per K group to stage before the first row (2.4 us against 4.6 us at
+        // 16 rows; the two meet at about 256 rows).
+        const bool few_rows = M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE;
+        if (!few_rows && t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25))
+            return Up ? launch_mfma<true>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, FP8, stream)
+                      : launch_mfma<false>(t, Xp, M, ldx, nullptr, 0, row_scale, codes, scales, FP8, stream);
+        if (t->form == BATQ_FORM_DENSE)
+            return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
+        return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
     }
     auto Xp = static_cast<const float*>(X);
-    if (t->form == BATQ_FORM_DENSE) return launch_dense<float, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
-    return launch_quad<float, FP8>(t, Xp, M, ldx, row_scale, codes, scales, stream);
+    auto Up = static_cast<const float*>(U);
+    if (t->form == BATQ_FORM_DENSE)
+        return launch_dense<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
+    return launch_quad<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
 }
 
 // 1 / sqrt(mean_j x_j^2 + eps) per row (RMSNorm's row factor), one wave per row, fp32 accumulation.
@@ -670,12 +757,12 @@ row_rms_scale(const XT* __restrict__ X, int64_t ldx, int M, int K, float eps, fl
 }  // namespace
 
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
-                               int64_t ldx, const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8,
-                               hipStream_t stream) {
+                               int64_t ldx, const void* U, int64_t ldu, const float* row_scale, uint8_t* codes,
+                               uint8_t* scales, bool fp8, hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, row_scale, codes, scales, stream)
-               : launch_quantize_as<false>(t, X, xdtype, M, ldx, row_scale, codes, scales, stream);
+    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, stream)
+               : launch_quantize_as<false>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, stream);
 }
 
 hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
