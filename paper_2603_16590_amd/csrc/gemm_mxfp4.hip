@@ -17,6 +17,9 @@
 //   gemm_direct - one wave per 32x32 tile with operands straight from global memory; only for
 //                 operand arrays of 2 GiB or more (the tiled kernel uses 32-bit load offsets).
 #include <algorithm>
+#include <map>
+#include <mutex>
+#include <utility>
 
 #include "batq_internal.h"
 #include "code_layout.h"
@@ -29,6 +32,7 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <typename YT>
@@ -188,14 +192,18 @@ constexpr int kSkinnyWaves = 8;
 template <typename YT, int RT, bool A8>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
-            const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy) {
+            const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy,
+            float* __restrict__ partial) {
     __shared__ float part[kSkinnyWaves][16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n0 = blockIdx.x * 32;
     const int i = lane & 31, kg = lane >> 5;
     const int bn = min(n0 + i, N - 1);                      // rows and columns past the edge are computed, not stored
     const int groups = scale_groups(nb);
-    const int g_begin = groups * wave / kSkinnyWaves, g_end = groups * (wave + 1) / kSkinnyWaves;
+    // gridDim.y > 1: the K groups are first cut into gridDim.y parts, one per workgroup row, whose sums go
+    // to partial[part][M][N] (fp32) for splitk_reduce_rows
+    const int p_begin = groups * blockIdx.y / gridDim.y, p_groups = groups * (blockIdx.y + 1) / gridDim.y - p_begin;
+    const int g_begin = p_begin + p_groups * wave / kSkinnyWaves, g_end = p_begin + p_groups * (wave + 1) / kSkinnyWaves;
     // block k = 8 g + 2 j + kg (j = 0..3): chunk (k / 4, k % 4) = (2 g + j / 2, 2 (j % 2) + kg)
     const int rb = bn & 15;
     const uint8_t* pb = wc + (size_t)(bn >> 4) * code_stages(nb) * 1024 + rb * 64;
@@ -281,7 +289,10 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 #pragma unroll
             for (int w = 1; w < kSkinnyWaves; ++w) v += part[w][r][l];
             const int row = 32 * t + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), col = n0 + (l & 31);
-            if (row < M && col < N) store_y<YT>(Y + (size_t)row * ldy + col, v);
+            if (row < M && col < N) {
+                if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v;
+                else store_y<YT>(Y + (size_t)row * ldy + col, v);
+            }
         }
     }
 }
@@ -320,26 +331,40 @@ struct TilePlan {
     int strips_n;     // column strips of 64
     int bands;        // column bands (1, 2, 4 or 8)
     int workers;      // workgroups launched, a multiple of 8
+    int ksplit;       // parts the K groups are cut into (1: every tile runs over all of K)
+    int groups;       // K groups of 256 elements
 };
 
 struct Tile {
     int m0, n0, nj;
+    int part, g0, ng;   // K part, its first K group and its number of K groups
 };
 
-// Takes the next tile off the share [cur, end) of the linear strip order.
+// Takes the next tile off the share [cur, end) of the linear order: K part by K part, inside a part the
+// strip order (column bands -> row panels -> strips).
 __device__ __forceinline__ bool next_tile(const TilePlan& pl, int& cur, int end, Tile& t) {
     if (cur >= end) return false;
+    int part = 0, at = cur, stop = end;
+    if (pl.ksplit > 1) {
+        const int per_part = pl.tiles_m * pl.strips_n;
+        part = cur / per_part;
+        at = cur - part * per_part;
+        stop = min(end - part * per_part, per_part);      // a tile does not reach into the next K part
+    }
     int b = 0;
-    while (b + 1 < pl.bands && cur >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
+    while (b + 1 < pl.bands && at >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
     const int bs = b * pl.strips_n / pl.bands, be = (b + 1) * pl.strips_n / pl.bands;
     const int width = be - bs;
-    const int local = cur - pl.tiles_m * bs;
+    const int local = at - pl.tiles_m * bs;
     const int p = local / width, sl = local - p * width;
-    const int run = min(end - cur, width - sl);          // strips left in this row panel of the band
+    const int run = min(stop - at, width - sl);           // strips left in this row panel of the band
     const int nt = (run + 3) >> 2;                        // tiles the run is cut into, near-equal widths
     t.nj = (run + nt - 1) / nt;
     t.m0 = p * kTile;
     t.n0 = (bs + sl) * kStrip;
+    t.part = part;
+    t.g0 = pl.groups * part / pl.ksplit;
+    t.ng = pl.groups * (part + 1) / pl.ksplit - t.g0;
     cur += t.nj;
     return true;
 }
@@ -379,8 +404,9 @@ struct TiledCtx {
     // global -> LDS
     const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
     uint32_t aoff[4], boff[4], sao[2], sbo[2];
-    uint32_t lds0, lds_sc;
-    int M, N, T, wave, lane;
+    uint32_t lds0, lds_sc, row_group_bytes;   // bytes of one 16-row group of a code array (all of K)
+    int M, N, wave, lane;
+    int T, s0;        // stages of the aimed tile and the first of them (stage = 128 K elements; K parts start on K groups)
     // LDS -> registers
     const uint8_t* smem;
     int a_rd, b_rd, sc_a_rd, sc_b_rd, kg, fsw;
@@ -394,10 +420,12 @@ struct TiledCtx {
         const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
         int lane = this->lane;
         asm volatile("" : "+v"(lane));      // recompute the lane terms per tile instead of keeping them in registers
+        T = 2 * t.ng;
+        s0 = 2 * t.g0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
-            boff[j] = (uint32_t)min((t.n0 >> 4) + t.nj * wave + j, rgB - 1) * (uint32_t)(T * 1024) + lane * 16;
+            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * row_group_bytes + lane * 16;
+            boff[j] = (uint32_t)min((t.n0 >> 4) + t.nj * wave + j, rgB - 1) * row_group_bytes + lane * 16;
         }
         // scales: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords 128 w .. 128 w + 127
         // of each (two pieces of 64).  B rows beyond the tile's 64 nj are fetched and not used.
@@ -414,8 +442,8 @@ struct TiledCtx {
     __device__ __forceinline__ void issue_scales(int s) const {
         const int g = s >> 1;
         const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
-        const uint8_t* sag = xs + (size_t)g * M * 8;
-        const uint8_t* sbg = ws + (size_t)g * N * 8;
+        const uint8_t* sag = xs + (size_t)(g + (s0 >> 1)) * M * 8;
+        const uint8_t* sbg = ws + (size_t)(g + (s0 >> 1)) * N * 8;
 #pragma unroll
         for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
 #pragma unroll
@@ -425,10 +453,10 @@ struct TiledCtx {
     __device__ __forceinline__ void issue_part(int s, int nj, bool even) const {
         const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds;
         if constexpr (PART < 4) {
-            dma16(xc + (size_t)s * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
+            dma16(xc + (size_t)(s + s0) * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
         } else {
             if (PART < 4 + nj)
-                dma16(wc + (size_t)s * 1024, boff[(PART - 4) & 3], buf + kOperandStage + (uint32_t)(nj * wave + PART - 4) * 1024);
+                dma16(wc + (size_t)(s + s0) * 1024, boff[(PART - 4) & 3], buf + kOperandStage + (uint32_t)(nj * wave + PART - 4) * 1024);
             else if (PART == 4 + nj && even)
                 issue_scales(s);
         }
@@ -654,11 +682,36 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, 
         }
 }
 
+// Partial sums of a K part, in the order the accumulators hold them: 32x32 blocks, block (rb, cb) of the
+// padded output as 4 pieces of 64 lanes x 4 floats; piece q of lane (l32, kg) = rows 32 rb + 8 q + 4 kg .. + 3
+// of column 32 cb + l32.  Every store instruction writes 1 KiB of consecutive memory.
+constexpr int kPartialBlockFloats = 32 * 32;
+template <int NJ>
+__device__ __forceinline__ void store_partial(v16f (&acc)[4][NJ], float* __restrict__ P, int lane, int wm, int wn,
+                                              const Tile& t, int col_blocks) {
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int rb0 = (t.m0 >> 5) + 4 * wm, cb0 = (t.n0 >> 5) + NJ * wn;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            float* blk = P + ((size_t)(rb0 + i) * col_blocks + cb0 + j) * kPartialBlockFloats + lane_e * 4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *reinterpret_cast<f32x4*>(blk + q * 256) = v;
+            }
+        }
+}
+
 // One output tile: on entry the loads of its first stages are in flight (issue_prologue); before
 // the epilogue the loads of the next tile's first stages are started, so they run underneath it.
+// With K parts (YT = float), Y is the partial-sum array in accumulator order (store_partial), `ldy` its number
+// of 32-column blocks and `part_stride` the floats of one part; else part_stride = 0.
 template <int NJ, typename YT>
 __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_next, const Tile& next,
-                                         YT* __restrict__ Y, int64_t ldy) {
+                                         YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
     const int lane = c.lane, wave = c.wave;
     const int wm = wave >> 1, wn = wave & 1;
     const int T = c.T, G = T >> 1;
@@ -706,22 +759,31 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     }
 
     // ---- epilogue: accumulators -> Y
+    if constexpr (sizeof(YT) == 4) {
+        if (part_stride != 0) {
+            store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
+            return;
+        }
+    }
     store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
                        c.M, c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
+// pl.ksplit > 1: tiles cover one K part each and store their partial sums to Y + part * part_stride
+// (fp32, summed by splitk_reduce); used when there are fewer strips than workgroups.
 template <typename YT>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
-           const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy) {
+           const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy,
+           int64_t part_stride) {
     extern __shared__ __align__(16) uint8_t smem[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
     // this workgroup's share of the linear strip order
     const int per_xcd = pl.workers >> 3;
     const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n;
+    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
     int cur = (int)(total * share / pl.workers);
     const int end = (int)(total * (share + 1) / pl.workers);
 
@@ -732,7 +794,7 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     TiledCtx c;
     c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
     c.M = M; c.N = N; c.smem = smem;
-    c.T = 2 * ((nb + 7) >> 3);                                // stages of 128 K elements (K zero-padded to 256)
+    c.row_group_bytes = (uint32_t)(2 * ((nb + 7) >> 3)) * 1024u;   // stages of 128 K elements (K zero-padded to 256)
     c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     c.lane = lane;
     c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;            // LDS byte address of the stage ring
@@ -745,10 +807,10 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     for (;;) {
         const bool has_next = next_tile(pl, cur, end, next);
         switch (t.nj) {
-            case 4: run_tile<4, YT>(c, t, has_next, next, Y, ldy); break;
-            case 3: run_tile<3, YT>(c, t, has_next, next, Y, ldy); break;
-            case 2: run_tile<2, YT>(c, t, has_next, next, Y, ldy); break;
-            default: run_tile<1, YT>(c, t, has_next, next, Y, ldy); break;
+            case 4: run_tile<4, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            case 3: run_tile<3, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            case 2: run_tile<2, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            default: run_tile<1, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
         }
         if (!has_next) break;
         t = next;
@@ -1036,6 +1098,82 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     }
 }
 
+// Sum of the K parts' partial blocks (store_partial order), in part order (fixed, so the result does not depend
+// on timing), to Y.  One workgroup per 32x32 block: wave q sums piece q into an LDS tile, then the tile leaves
+// row by row, four columns per lane.
+template <typename YT>
+__global__ void __launch_bounds__(256)
+splitk_reduce(const float* __restrict__ P, int parts, int64_t part_stride, int col_blocks, int M, int N,
+              YT* __restrict__ Y, int64_t ldy) {
+    constexpr int kPitch = 32 + 4;
+    __shared__ float tile[32 * kPitch];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int rb = blockIdx.y, cb = blockIdx.x;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const float* src = P + ((size_t)rb * col_blocks + cb) * kPartialBlockFloats + q * 256 + lane * 4;
+    f32x4 a = *reinterpret_cast<const f32x4*>(src);
+    for (int p = 1; p < parts; ++p) a += *reinterpret_cast<const f32x4*>(src + (size_t)p * part_stride);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[(8 * q + 4 * kg + r) * kPitch + l32] = a[r];
+    __syncthreads();
+    // 32 rows x 32 columns: thread -> (row, 4 columns)
+    const int row = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+    const int m = 32 * rb + row, n = 32 * cb + c0;
+    if (m >= M || n >= N) return;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(tile + row * kPitch + c0);
+    YT* dst = Y + (size_t)m * ldy + n;
+    const bool whole = n + 4 <= N && (reinterpret_cast<uintptr_t>(dst) & (4 * sizeof(YT) - 1)) == 0;
+    if (whole) {
+        if constexpr (sizeof(YT) == 2) {
+            const f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+            *reinterpret_cast<uint2*>(dst) = uint2{__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2)),
+                                                   __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2))};
+        } else {
+            *reinterpret_cast<f32x4*>(dst) = v;
+        }
+        return;
+    }
+    for (int i = 0; i < 4 && n + i < N; ++i) store_y<YT>(dst + i, v[i]);
+}
+
+// The same for row-major partial sums partial[part][M][N] (the small-M kernel): one thread per output element.
+template <typename YT>
+__global__ void __launch_bounds__(256)
+splitk_reduce_rows(const float* __restrict__ P, int parts, int M, int N, YT* __restrict__ Y, int64_t ldy) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)M * N) return;
+    const int m = (int)(e / N), n = (int)(e - (int64_t)m * N);
+    float acc = P[e];
+    for (int p = 1; p < parts; ++p) acc += P[(int64_t)p * M * N + e];
+    store_y<YT>(Y + (int64_t)m * ldy + n, acc);
+}
+
+// Partial-sum memory of the K-split launches: one buffer per (device, stream), created at the first launch
+// that needs it and kept until the process ends.  Kernels of one stream run in order, so the launches of a
+// stream can share it; launches on different streams never do.  While a stream is being captured into a graph
+// no memory is allocated: a stream without a buffer then gets none (the caller falls back to the unsplit kernel).
+constexpr size_t kSplitScratchBytes = size_t(32) << 20;
+float* splitk_scratch(int dev, hipStream_t stream) {
+    static std::mutex mu;
+    static std::map<std::pair<int, hipStream_t>, float*> buffers;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = buffers.find({dev, stream});
+    if (it != buffers.end()) return it->second;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (cap != hipStreamCaptureStatusNone) return nullptr;
+    void* p = nullptr;
+    if (hipMalloc(&p, kSplitScratchBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    buffers[{dev, stream}] = static_cast<float*>(p);
+    return static_cast<float*>(p);
+}
+
 // Column bands: with b bands an XCD's block spans 1/b of N and b/8 of M, so the bytes all XCDs
 // pull through their L2s are proportional to b M + (8 / b) N; take the b that minimises it.
 int choose_bands(int M, int N, int strips_n) {
@@ -1078,18 +1216,60 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         pl.strips_n = (N + kStrip - 1) / kStrip;
         pl.bands = choose_bands(M, N, pl.strips_n);
         pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
-        if constexpr (A8)
+        pl.ksplit = 1;
+        pl.groups = scale_groups(nb);
+        if constexpr (A8) {
             gemm_tiled_a8<YT><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
                                                                                 nb, pl, Y, ldy);
-        else
-            gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
-                                                                                nb, pl, Y, ldy);
+        } else {
+            // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
+            // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
+            // sums' round trip costs more than the idle compute units.
+            const int strips = pl.tiles_m * pl.strips_n;
+            const int col_blocks = 2 * pl.strips_n;
+            const size_t part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
+            int ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
+            while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
+            float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
+            if (parts) {
+                static bool attr_f32_set = false;
+                if (!attr_f32_set) {
+                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
+                    if (e != hipSuccess) return e;
+                    attr_f32_set = true;
+                }
+                pl.ksplit = ksplit;
+                gemm_tiled<float><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
+                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
+                splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
+                    parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
+            } else {
+                gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
+                                                                                    N, nb, pl, Y, ldy, 0);
+            }
+        }
     } else if (M <= 64) {
-        const dim3 grid((N + 31) / 32), block(kSkinnyWaves * 64);
+        // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two
+        // workgroup rows then take half of K each (64 x 14336 x 4096: 15.8 -> 12.0 us).  More parts, or shorter
+        // K, lose more to the second kernel than they gain.
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        const int cols = (N + 31) / 32;
+        int ksplit = (2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
+        float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
+        if (!parts || (size_t)ksplit * M * N * sizeof(float) > kSplitScratchBytes) ksplit = 1;
+        const dim3 grid(cols, ksplit), block(kSkinnyWaves * 64);
         if (M <= 32)
-            gemm_skinny<YT, 1, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+            gemm_skinny<YT, 1, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
         else
-            gemm_skinny<YT, 2, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+            gemm_skinny<YT, 2, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+        if (ksplit > 1) {
+            const int64_t total = (int64_t)M * N;
+            splitk_reduce_rows<YT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(parts, ksplit, M, N, Y, ldy);
+        }
     } else {
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
         gemm_direct<YT, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);

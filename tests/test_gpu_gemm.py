@@ -110,6 +110,30 @@ def test_tile_schedule_shapes(B, M, K, N):
     assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
 
 
+@pytest.mark.parametrize("M,K,N", [(130, 8192, 320), (300, 8192 + 32, 200), (256, 8192 + 256, 1000), (97, 6144, 64),
+                                   (65, 12288 + 64, 2100), (520, 16384, 136), (64, 12288 + 32, 2070), (7, 16384, 96)])
+def test_split_k_shapes(B, M, K, N):
+    """Few strips and a long K: the tiled kernel cuts K into 2 to 8 parts (partial tiles summed in a second
+    kernel), with ragged panels, strips and part lengths; every output element is checked, on the current
+    stream and on a side stream (each stream has its own partial-sum memory)."""
+    import torch
+    test_tile_schedule_shapes(B, M, K, N)
+    rng = np.random.default_rng(M + K + N)
+    xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
+    wc, ws, dwc, dws = _rand_q(rng, N, K, lo=122, hi=132)
+    wh = B.batq_weight_import(dwc, dws, K, N)
+    dxc_b, dxs_g = _xc(xc), _xs(xs)
+    Y0 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        Y1 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
+        Y2 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
+    Y3 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)      # overlaps with the side stream's launches
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y1) and torch.equal(Y0, Y2) and torch.equal(Y0, Y3)
+
+
 def test_extreme_scales(B):
     import torch
     rng = np.random.default_rng(5)

@@ -67,3 +67,46 @@ def test_linear_inside_a_captured_graph(B, M):
         torch.cuda.synchronize()
         assert torch.equal(Y, ref), rep
         assert bool(torch.isfinite(junk))
+
+
+def test_split_k_gemm_in_graphs(B):
+    """A long-K, few-strip GEMM cuts K into parts and keeps partial sums in memory owned by the stream.  A
+    capture on a stream that has none yet must not allocate (the unsplit kernel is recorded instead); a
+    capture on a stream that has run the shape before records the split kernels.  Both replay correctly."""
+    import torch
+    M, K, N = 130, 8192, 320
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    wc = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=g)
+    ws = torch.randint(122, 132, (N, K // 32), dtype=torch.uint8, device="cuda", generator=g)
+    wh = B.batq_weight_import(wc, ws, K, N)
+    xs = B.batq_scales_from_rowmajor(torch.randint(122, 132, (M, K // 32), dtype=torch.uint8, device="cuda", generator=g))
+    xr = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda", generator=g)
+    xc = B.batq_codes_from_rowmajor(xr)
+    ref = B.batq_gemm_mxfp4(xc, xs, wh, M, torch.float32)            # eager, current stream: split
+    torch.cuda.synchronize()
+    scale = float(ref.abs().max())
+    for warm in (False, True):
+        st = torch.cuda.Stream()
+        Y = torch.zeros_like(ref)
+        if warm:
+            with torch.cuda.stream(st):
+                B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y)
+            st.synchronize()
+            assert torch.equal(Y, ref)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=st):
+            B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y)
+        outs = []
+        for rep in range(3):
+            Y.zero_()
+            junk = torch.randn(300, 300, device="cuda") @ torch.randn(300, 300, device="cuda")
+            torch.cuda.synchronize()
+            gr.replay()
+            torch.cuda.synchronize()
+            outs.append(Y.clone())
+            assert bool(torch.isfinite(junk).all())
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+        # split and unsplit kernels differ only in the order of fp32 additions
+        assert float((outs[0] - ref).abs().max()) <= 1e-5 * scale
+        if warm:
+            assert torch.equal(outs[0], ref)
