@@ -836,8 +836,9 @@ constexpr int kA8Lds = kA8EpilogueLds0 + 4 * kEpilogueWaveLds;      // 120 KiB
 struct A8Ctx {
     const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
     uint32_t aoff[4], boff[2], sao[2], sbo[2];
-    uint32_t lds0, lds_sc;
-    int M, N, T, wave, lane;          // T = stages = K / 64 (K padded to 256)
+    uint32_t lds0, lds_sc, row_group_bytes;   // bytes of one 16-row group of the 8-bit code array (all of K)
+    int M, N, wave, lane;
+    int T, s0;        // stages of the aimed tile and the first of them (stage = 64 K elements; K parts start on K groups)
     const uint8_t* smem;
     int a_rd, b_rd, sc_a_rd, sc_b_rd, kg;
 
@@ -845,9 +846,11 @@ struct A8Ctx {
         const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
         int lane = this->lane;
         asm volatile("" : "+v"(lane));      // recompute the lane terms per tile instead of keeping them in registers
+        T = 4 * t.ng;
+        s0 = 4 * t.g0;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * (uint32_t)(T * 1024) + lane * 16;
+            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * row_group_bytes + lane * 16;
         // B: load q of wave w fills LDS rows 32 (2 w + q) .. + 31 (32 bytes each); lane i -> row i / 2, 16-byte
         // position i % 2, which holds block (i % 2) ^ ((row / 8) % 2) of the K step (8 rows of 32 bytes span
         // all LDS banks once); in the 4-bit piece
@@ -859,7 +862,7 @@ struct A8Ctx {
             const int r16 = rho & 15;
             const int blk = p ^ ((rho >> 3) & 1);
             const int rg = min((t.n0 >> 4) + 2 * (2 * wave + q) + (rho >> 4), rgB - 1);
-            boff[q] = (uint32_t)rg * (uint32_t)((T >> 1) * 1024) + r16 * 64 + ((blk ^ ((r16 >> 2) & 3)) << 4);
+            boff[q] = (uint32_t)rg * (row_group_bytes >> 1) + r16 * 64 + ((blk ^ ((r16 >> 2) & 3)) << 4);
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -873,15 +876,15 @@ struct A8Ctx {
     __device__ __forceinline__ void issue_part(int s) const {
         const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kA8Stage;
         if constexpr (PART < 4) {
-            dma16(xc + (size_t)s * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
+            dma16(xc + (size_t)(s + s0) * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
         } else if constexpr (PART < 6) {
-            dma16(wc + (size_t)(s >> 1) * 1024, boff[PART - 4] ^ ((PAR & 1) << 5),
+            dma16(wc + (size_t)((s + s0) >> 1) * 1024, boff[PART - 4] ^ ((PAR & 1) << 5),
                   buf + kA8StageA + (uint32_t)(2 * wave + PART - 4) * 1024);
         } else if constexpr (PAR == 0) {
             const int g = s >> 2;
             const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
-            const uint8_t* sag = xs + (size_t)g * M * 8;
-            const uint8_t* sbg = ws + (size_t)g * N * 8;
+            const uint8_t* sag = xs + (size_t)(g + (s0 >> 2)) * M * 8;
+            const uint8_t* sbg = ws + (size_t)(g + (s0 >> 2)) * N * 8;
 #pragma unroll
             for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
 #pragma unroll
@@ -1003,7 +1006,7 @@ __device__ __forceinline__ void a8_stage(const A8Ctx& c, int s, v16f (&acc)[4][N
 
 template <int NJ, typename YT>
 __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_next, const Tile& next,
-                                            YT* __restrict__ Y, int64_t ldy) {
+                                            YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
     const int lane = c.lane, wave = c.wave;
     const int wm = wave >> 1, wn = wave & 1;
     const int T = c.T, G = T >> 2;
@@ -1048,6 +1051,12 @@ __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_ne
         c.issue_stage<2>(2);
         c.issue_stage<3>(3);
     }
+    if constexpr (sizeof(YT) == 4) {
+        if (part_stride != 0) {
+            store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
+            return;
+        }
+    }
     store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
                        c.M, c.N, Y, ldy);
 }
@@ -1056,13 +1065,14 @@ __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_ne
 template <typename YT>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
-              const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy) {
+              const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy,
+              int64_t part_stride) {
     extern __shared__ __align__(16) uint8_t smem[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
     const int per_xcd = pl.workers >> 3;
     const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n;
+    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
     int cur = (int)(total * share / pl.workers);
     const int end = (int)(total * (share + 1) / pl.workers);
 
@@ -1073,7 +1083,7 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     A8Ctx c;
     c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
     c.M = M; c.N = N; c.smem = smem;
-    c.T = 4 * ((nb + 7) >> 3);                                // stages of 64 K elements (K zero-padded to 256)
+    c.row_group_bytes = (uint32_t)(4 * ((nb + 7) >> 3)) * 1024u;   // stages of 64 K elements (K zero-padded to 256)
     c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     c.lane = lane;
     c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;
@@ -1088,10 +1098,10 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     for (;;) {
         const bool has_next = next_tile(pl, cur, end, next);
         switch (t.nj) {
-            case 4: a8_run_tile<4, YT>(c, t, has_next, next, Y, ldy); break;
-            case 3: a8_run_tile<3, YT>(c, t, has_next, next, Y, ldy); break;
-            case 2: a8_run_tile<2, YT>(c, t, has_next, next, Y, ldy); break;
-            default: a8_run_tile<1, YT>(c, t, has_next, next, Y, ldy); break;
+            case 4: a8_run_tile<4, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            case 3: a8_run_tile<3, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            case 2: a8_run_tile<2, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+            default: a8_run_tile<1, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
         }
         if (!has_next) break;
         t = next;
@@ -1218,36 +1228,40 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
         pl.ksplit = 1;
         pl.groups = scale_groups(nb);
-        if constexpr (A8) {
-            gemm_tiled_a8<YT><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
-                                                                                nb, pl, Y, ldy);
-        } else {
-            // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
-            // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
-            // sums' round trip costs more than the idle compute units.
-            const int strips = pl.tiles_m * pl.strips_n;
-            const int col_blocks = 2 * pl.strips_n;
-            const size_t part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
-            int ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
-            while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
-            float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
-            if (parts) {
-                static bool attr_f32_set = false;
-                if (!attr_f32_set) {
-                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
-                    if (e != hipSuccess) return e;
-                    attr_f32_set = true;
-                }
-                pl.ksplit = ksplit;
+        // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
+        // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
+        // sums' round trip costs more than the idle compute units.
+        const int strips = pl.tiles_m * pl.strips_n;
+        const int col_blocks = 2 * pl.strips_n;
+        const size_t part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
+        int ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
+        while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
+        float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
+        if (parts) {
+            static bool attr_f32_set = false;
+            if (!attr_f32_set) {
+                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<float>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
+                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
+                if (e != hipSuccess) return e;
+                attr_f32_set = true;
+            }
+            pl.ksplit = ksplit;
+            if constexpr (A8)
+                gemm_tiled_a8<float><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
+                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
+            else
                 gemm_tiled<float><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
                     xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
-                splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
-                    parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
-            } else {
-                gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
-                                                                                    N, nb, pl, Y, ldy, 0);
-            }
+            splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
+                parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
+        } else if constexpr (A8) {
+            gemm_tiled_a8<YT><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
+                                                                                nb, pl, Y, ldy, 0);
+        } else {
+            gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
+                                                                                nb, pl, Y, ldy, 0);
         }
     } else if (M <= 64) {
         // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two

@@ -189,7 +189,8 @@ def test_a8w4_gemm_random_codes(B, M, K, N):
     assert np.all(np.abs(gotb - refb) <= ulp * 1.0001 + tol)
 
 
-@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
+@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000),
+                                   (300, 8192 + 32, 200), (130, 12288, 320), (520, 16384, 136)])
 def test_a8w4_tile_schedule_shapes(B, M, K, N):
     """Several tiles per persistent workgroup, every tile width, ragged edges, 4 to 20 K stages; every
     output element is checked (exponents kept within 4 binades so that the products sum exactly)."""
