@@ -38,6 +38,10 @@ out x in, Sec. 3.1):
                          down projection (Sec. 3.2, placement of P_down): silu(gate) * up
                          as a plain definition, and its rounding to the bf16 tensor a model
                          hands to the layer.
+* ``inverse_transpose_blocks`` / ``apply_blocks`` - the key/value-cache placement of Sec. 3.2
+                         (P_k, P_v head by head): keys are stored as Q(k T), the query side
+                         takes q T^-T so that (q T^-T)(k T)^T = q k^T; values are stored as
+                         Q(v T) and the attention output takes T^-1.
 * ``prepare_weight``   - Alg. 2 "Offline Fusion" (inverse transform of W,
                          clip, quantise).
 * ``gemm`` / ``linear``- the objective of Sec. 3.1, Q(XP) Q(P^-1 W^T).
@@ -432,6 +436,18 @@ def invert(Tk: np.ndarray) -> np.ndarray:
             if r != col:
                 A[r] -= A[r, col] * A[col]
     return A[:, n:]
+
+
+def inverse_transpose_blocks(T: np.ndarray) -> np.ndarray:
+    """T_k^-T for every block: the query-side companion of a key transform, (q T^-T)(k T)^T = q k^T."""
+    T = np.asarray(T, dtype=np.float64)
+    return np.stack([invert(T[k]).T for k in range(T.shape[0])])
+
+
+def inverse_blocks(T: np.ndarray) -> np.ndarray:
+    """T_k^-1 for every block (undoes a value transform on the attention output)."""
+    T = np.asarray(T, dtype=np.float64)
+    return np.stack([invert(T[k]) for k in range(T.shape[0])])
 
 
 def inverse_transform_weight(W: np.ndarray, G, P) -> np.ndarray:
