@@ -283,6 +283,29 @@ batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w,
 batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps,
                                float* row_scale, void* stream);
 
+/* ------------------------------------------------------------------------------------
+ * Key/value cache (Sec. 3.2, "Self-Attention Module": P_k and P_v transform the key and value cache head by
+ * head).  A cache row is written with batq_quantize_act[_ex] on the [tokens][kv_heads * head_dim] key or value
+ * tensor: the blocks of a head (head_dim / 32 of them) each carry their own T_k, act_bits 4 or 8 gives KV4 or
+ * KV8.  The two calls below are the pieces around it for an attention kernel that works on 16-bit tensors.
+ *
+ * batq_dequantize: codes (DEVICE, device order of the given width) and scales (DEVICE, grouped order) of `M`
+ *   rows -> out[m][j] = value(code) * 2^(scale - 127), row-major with row stride ldo elements (16-byte aligned
+ *   rows), bf16 or fp32.  Exact in fp32 (subnormal results included; scale byte 255 and the E4M3 NaN codes
+ *   give NaN); bf16 rounds only results below 2^-126.  bits = 4 or 8, else BATQ_ERR_UNSUPPORTED.
+ *
+ * batq_transform_apply: out = X T_k (FORWARD), X T_k^-1 (INVERSE) or X T_k^-T (INVERSE_T) block by block, no
+ *   clipping or quantisation: products and sums in fp64 with the handle's fp64 blocks, one rounding to fp32
+ *   (and one to bf16 for bf16 output).  The query side of a transformed key cache takes INVERSE_T
+ *   ((q T^-T)(k T)^T = q k^T), the attention output over a transformed value cache takes INVERSE.  X and out
+ *   as for batq_quantize_act (DEVICE, row strides in elements); not in place (BATQ_ERR_SHAPE). */
+typedef enum { BATQ_APPLY_FORWARD = 0, BATQ_APPLY_INVERSE = 1, BATQ_APPLY_INVERSE_T = 2 } batq_apply_mode;
+batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits,
+                            void* out, batq_dtype odtype, int64_t ldo, void* stream);
+batq_status batq_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                                 int64_t ldx, batq_apply_mode mode, void* out, batq_dtype odtype, int64_t ldo,
+                                 void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -62,6 +62,8 @@ SYMBOLS = {
     "batq_quantize_act_ex": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp, _vp]),
     "batq_linear_ex": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_row_rms_scale": (_i, [_vp, _i, _i, _i, _i64, C.c_float, _vp, _vp]),
+    "batq_dequantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _i, _i64, _vp]),
+    "batq_transform_apply": (_i, [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _i, _i64, _vp]),
 }
 
 
@@ -445,6 +447,33 @@ def batq_row_rms_scale(X, eps: float = 1e-6):
     out = torch.empty((M,), dtype=torch.float32, device=X.device)
     _check(lib.batq_row_rms_scale(X.data_ptr(), _dtype_code(X), M, K, X.stride(0) if M > 1 else max(K, X.stride(0)),
                                   eps, out.data_ptr(), _stream()), "batq_row_rms_scale")
+    return out
+
+
+APPLY_FORWARD, APPLY_INVERSE, APPLY_INVERSE_T = 0, 1, 2
+
+
+def batq_dequantize(codes, scales, M: int, K: int, bits: int = 4, out_dtype=None, out=None):
+    """Device-order codes + grouped scales -> row-major [M, K] tensor (bf16 by default)."""
+    import torch
+    if out is None:
+        out = torch.empty((M, K), dtype=out_dtype or torch.bfloat16, device=codes.device)
+    _check(lib.batq_dequantize(codes.data_ptr(), scales.data_ptr(), M, K, bits, out.data_ptr(), _dtype_code(out),
+                               out.stride(0) if M > 1 else max(K, out.stride(0)), _stream()), "batq_dequantize")
+    return out
+
+
+def batq_transform_apply(t: Transform, X, mode: int = APPLY_FORWARD, out_dtype=None, out=None):
+    """X T_k, X T_k^-1 or X T_k^-T block by block, without quantisation."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, K), dtype=out_dtype or X.dtype, device=X.device)
+    _check(lib.batq_transform_apply(t.handle, X.data_ptr(), _dtype_code(X), M, K,
+                                    X.stride(0) if M > 1 else max(K, X.stride(0)), mode, out.data_ptr(),
+                                    _dtype_code(out), out.stride(0) if M > 1 else max(K, out.stride(0)), _stream()),
+           "batq_transform_apply")
     return out
 
 

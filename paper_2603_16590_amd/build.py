@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbatq.so")
 CEILINGS = os.path.join(HERE, "batq_ceilings")     # standalone tool: measured chip ceilings
-SOURCES = ["batq_api.hip", "quant_act.hip", "prep_weight.hip", "gemm_mxfp4.hip"]
+SOURCES = ["batq_api.hip", "quant_act.hip", "prep_weight.hip", "gemm_mxfp4.hip", "kv_cache.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

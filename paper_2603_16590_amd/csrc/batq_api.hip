@@ -112,6 +112,7 @@ void free_transform(batq_transform* t) {
     if (t->d_clip) (void)hipFree(t->d_clip);
     if (t->d_clip_max) (void)hipFree(t->d_clip_max);
     if (t->d_Tinv) (void)hipFree(t->d_Tinv);
+    if (t->d_Tf64) (void)hipFree(t->d_Tf64);
     if (t->d_Tsplit) (void)hipFree(t->d_Tsplit);
     delete t;
 }
@@ -261,6 +262,7 @@ batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_
     if (st == BATQ_OK && form == BATQ_FORM_DENSE) st = upload(&t->d_T, Tf.data(), Tf.size());
     if (st == BATQ_OK && t->has_transform) {
         st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
+        if (st == BATQ_OK) st = upload(&t->d_Tf64, T.data(), T.size());
         if (st == BATQ_OK) st = upload(&t->d_Tsplit, Tsplit.data(), Tsplit.size());
     }
     if (st != BATQ_OK) {
@@ -639,6 +641,38 @@ batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w, const 
     ActExtras ex;
     if (!act_options_ok(opt, &a8, &ex)) return BATQ_ERR_UNSUPPORTED;
     return linear_impl(t, w, X, xdtype, M, ldx, ex, Y, ydtype, ldy, workspace, workspace_bytes, a8, stream);
+}
+
+batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits, void* out,
+                            batq_dtype odtype, int64_t ldo, void* stream) {
+    if (bits != 4 && bits != 8) return BATQ_ERR_UNSUPPORTED;
+    if (!dtype_ok(odtype)) return BATQ_ERR_DTYPE;
+    if (M < 0 || K <= 0 || K % 32 != 0 || ldo < K) return BATQ_ERR_SHAPE;
+    if (M == 0) return BATQ_OK;
+    if (!codes || !scales || !out) return BATQ_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(out) || (ldo * (int64_t)dtype_size(odtype)) % 16 != 0) return BATQ_ERR_SHAPE;
+    batq_status st = check_device();
+    if (st != BATQ_OK) return st;
+    BATQ_HIP(batq::launch_dequantize(codes, scales, M, K / 32, bits == 8, out, odtype, ldo,
+                                     static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
+}
+
+batq_status batq_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
+                                 int64_t ldx, batq_apply_mode mode, void* out, batq_dtype odtype, int64_t ldo,
+                                 void* stream) {
+    if (!t) return BATQ_ERR_NULL;
+    if (!dtype_ok(xdtype) || !dtype_ok(odtype)) return BATQ_ERR_DTYPE;
+    if (mode != BATQ_APPLY_FORWARD && mode != BATQ_APPLY_INVERSE && mode != BATQ_APPLY_INVERSE_T)
+        return BATQ_ERR_UNSUPPORTED;
+    if (M < 0 || K <= 0 || K % 32 != 0 || ldx < K || ldo < K) return BATQ_ERR_SHAPE;
+    if (t->K != K) return BATQ_ERR_MISMATCH;
+    if (M == 0) return BATQ_OK;
+    if (!X || !out) return BATQ_ERR_NULL;
+    if (X == out) return BATQ_ERR_SHAPE;                  // not in place: a block's outputs need all its inputs
+    BATQ_HIP(batq::launch_transform_apply(t, X, xdtype, M, ldx, (int)mode, out, odtype, ldo,
+                                          static_cast<hipStream_t>(stream)));
+    return BATQ_OK;
 }
 
 batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps,

@@ -25,6 +25,7 @@ struct batq_transform {
     float* d_clip = nullptr;      // [nb], 1.0 when no clipping
     float* d_clip_max = nullptr;  // [nb], only when minmax
     double* d_Tinv = nullptr;     // [nb][32][32] fp64 T_k^-1     (null when !has_transform)
+    double* d_Tf64 = nullptr;     // [nb][32][32] fp64 T_k        (null when !has_transform)
     uint16_t* d_Tsplit = nullptr; // [nb][3][2][64][8] bf16 three-term split of T_k in MFMA operand order
 };
 
@@ -45,6 +46,12 @@ namespace batq {
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                int64_t ldx, const void* U, int64_t ldu, const float* row_scale, uint8_t* codes,
                                uint8_t* scales, bool fp8, hipStream_t stream);
+// Blocked codes (fp8: the 8-bit variant) + grouped scales -> row-major out (bf16 or fp32, row stride ldo).
+hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int nb, bool fp8, void* out,
+                             batq_dtype odtype, int64_t ldo, hipStream_t stream);
+// out = X T_k, X T_k^-1 or X T_k^-T block by block (mode = batq_apply_mode), no quantisation.
+hipError_t launch_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
+                                  int mode, void* out, batq_dtype odtype, int64_t ldo, hipStream_t stream);
 hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
                                 hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
