@@ -236,3 +236,29 @@ def test_linear_argument_errors(B):
     assert lib.batq_gemm_mxfp4(xc.data_ptr(), xs.data_ptr(), wh.handle, 8, Y.data_ptr(), 5, 16, None) == 3
     torch.cuda.synchronize()
     assert bool((Y == 0).all())
+
+
+def test_weight_codes_of_two_gib(B):
+    """Maximum sizes: a weight whose code array reaches 2 GiB cannot be addressed with the tiled kernel's 32-bit
+    offsets; rows > 64 then take the direct kernel, rows <= 64 the small-M kernel with 64-bit addressing.
+    Sampled output columns against the oracle."""
+    import torch
+    K, N = 65536, 65536
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    dwc = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=g)
+    dws = torch.randint(122, 132, (N, K // 32), dtype=torch.uint8, device="cuda", generator=g)
+    wh = B.batq_weight_import(dwc, dws, K, N)
+    cols = np.concatenate([[0, 1, 31, 32, N - 1, N - 33], sample_rows(N, 42, seed=3)])
+    wc = dwc[torch.from_numpy(cols).cuda()].cpu().numpy()
+    ws = dws[torch.from_numpy(cols).cuda()].cpu().numpy()
+    del dwc, dws
+    rng = np.random.default_rng(12)
+    for M in (65, 40):
+        xc, xs, _, _ = _rand_q(rng, M, K, lo=122, hi=132)
+        Y = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, M, torch.float32)
+        torch.cuda.synchronize()
+        got = Y[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+        ref = o.gemm(xc, xs, wc, ws)
+        tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
+        assert np.all(np.abs(got - ref) <= tol + 1e-30), M
+        assert bool(torch.isfinite(Y).all())

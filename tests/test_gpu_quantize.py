@@ -250,3 +250,25 @@ def test_argument_errors_leave_outputs_untouched(B):
     assert lib.batq_quantize_act(t.handle, None, 1, 4, 64, 64, codes.data_ptr(), scales.data_ptr(), None) == 1
     torch.cuda.synchronize()
     assert bool((codes == 0xAB).all()) and bool((scales == 0xCD).all())
+
+
+def test_row_stride_beyond_the_matrix_core_kernels_offsets(B):
+    """A bf16 input whose row stride is 2^25 elements or more cannot be addressed with the matrix-core kernel's
+    32-bit tile offsets: such calls take the register-level or the dense kernel.  Same bar as elsewhere."""
+    import torch
+    M, K, ld = 5, 32 * 9, 1 << 25
+    w = bi.make_small(M, K, 8, seed=77, dtype="bf16")
+    big = torch.zeros((M, ld), dtype=torch.bfloat16, device="cuda")
+    big[:, :K] = to_dev(w.X, "bf16")
+    T = o.kron_blocks(w.G, w.P)
+    for t in (B.Transform(K, w.G, w.P, w.clip), B.Transform.general(K, dense=T.astype(np.float32), clip=w.clip)):
+        c, s = B.batq_quantize_act(t, big[:, :K])
+        c0, s0 = B.batq_quantize_act(t, to_dev(w.X, "bf16"))
+        torch.cuda.synchronize()
+        gc = blocked_to_rowmajor(c.cpu().numpy(), M, K // 32)
+        gs = grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
+        oc, os_ = o.quantize_act_blocks(w.X_f32(), T, w.clip)
+        assert np.mean(gs != os_) <= 0.01 and np.mean(code_value_mismatch(gc, oc)) <= 1e-3
+        # and the same codes as the contiguous call wherever the two kernels agree on ties
+        g0 = blocked_to_rowmajor(c0.cpu().numpy(), M, K // 32)
+        assert np.mean(code_value_mismatch(gc, g0)) <= 1e-3
