@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
     ap.add_argument("--no-w4a8", action="store_true", help="skip the W4A8 side measurement")
+    ap.add_argument("--no-mlp", action="store_true", help="skip the MLP-block side measurement (gate/up, SwiGLU, down)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
                     "loop, streaming HBM kernels)")
     args = ap.parse_args()
@@ -162,6 +163,67 @@ def main():
         w4a8 = r8
         torch.cuda.empty_cache()
 
+    # The MLP block the two headline shapes come from (hidden 4096, intermediate 14336; cfg2 = gate/up, cfg3 =
+    # down): P_up quantise -> gate/up GEMM -> silu(gate) * up -> P_down quantise -> down GEMM, with the gated
+    # activation (a) left to a separate elementwise pass, (b) fused into the down projection's quantiser,
+    # (c) fused into the gate/up GEMM's epilogue.  Side measurement; the headline value is the single layer.
+    mlp = None
+    if not args.no_mlp and args.workload in (2, 3):
+        Mm, D, Fh = 2048, 4096, 14336
+        rng = np.random.default_rng(7)
+
+        def mk(K):
+            nbk = K // 32
+            G = (np.eye(4) + 0.05 * rng.standard_normal((4, 4))).astype(np.float32)
+            P = (np.eye(8)[None] + 0.05 * rng.standard_normal((nbk, 8, 8))).astype(np.float32)
+            return B.Transform(K, G, P, rng.uniform(0.85, 1.0, nbk).astype(np.float32))
+
+        t_up, t_down = mk(D), mk(Fh)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(7)
+        Wg = (torch.randn((D, Fh), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        Wu = (torch.randn((D, Fh), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        Wd = (torch.randn((Fh, D), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        w_gu = B.batq_prepare_weight_gate_up(t_up, Wg, Wu)
+        w_d = B.batq_prepare_weight(t_down, Wd)
+        del Wg, Wu, Wd
+        Xm = torch.randn((Mm, D), device="cuda", generator=gen).to(torch.bfloat16)
+        ws1 = torch.empty(B.batq_linear_workspace(Mm, D), dtype=torch.uint8, device="cuda")
+        ws2 = torch.empty(B.batq_linear_workspace(Mm, Fh), dtype=torch.uint8, device="cuda")
+        GU = torch.empty((Mm, 2 * Fh), dtype=torch.bfloat16, device="cuda")
+        Hh = torch.empty((Mm, Fh), dtype=torch.bfloat16, device="cuda")
+        Ym = torch.empty((Mm, D), dtype=torch.bfloat16, device="cuda")
+        # in the interleaved weight gate and up alternate in groups of 32 columns: views for the unfused chains
+        GU3 = GU.view(Mm, Fh // 32, 2, 32)
+
+        def chain_separate():
+            B.batq_linear(t_up, w_gu, Xm, Y=GU, workspace=ws1)
+            torch.mul(torch.nn.functional.silu(GU3[:, :, 0, :]), GU3[:, :, 1, :], out=Hh.view(Mm, Fh // 32, 32))
+            B.batq_linear(t_down, w_d, Hh, Y=Ym, workspace=ws2)
+
+        def chain_epilogue():
+            B.batq_linear_glu(t_up, w_gu, Xm, H=Hh, workspace=ws1)
+            B.batq_linear(t_down, w_d, Hh, Y=Ym, workspace=ws2)
+
+        def time_chain(fn, n=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        ms_sep, ms_epi = time_chain(chain_separate), time_chain(chain_epilogue)
+        mlp = {"shape": f"{Mm} tokens, hidden {D}, intermediate {Fh}", "flops": 6.0 * Mm * D * Fh,
+               "ms_separate_activation_pass": ms_sep, "ms_gated_epilogue": ms_epi,
+               "tflops_gated_epilogue": 6.0 * Mm * D * Fh / ms_epi / 1e9}
+        del w_gu, w_d, GU, Hh, Ym, ws1, ws2, Xm
+        torch.cuda.empty_cache()
+
     ceilings = None
     tool = os.path.join(ROOT, "paper_2603_16590_amd", "batq_ceilings")
     if not args.no_ceilings and os.path.exists(tool):
@@ -224,6 +286,7 @@ def main():
         "cpu_baseline": cpu,
         "also": also,
         "w4a8": w4a8,
+        "mlp_block": mlp,
     }
     print(json.dumps(line))
 

@@ -284,6 +284,30 @@ batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, i
                                float* row_scale, void* stream);
 
 /* ------------------------------------------------------------------------------------
+ * Gate and up projection as one GEMM with the gated activation in its epilogue (Sec. 3.2, "MLP Module": P_up
+ * sits in front of up_proj and gate_proj, which therefore share their quantised input).
+ *
+ * batq_prepare_weight_gate_up: like batq_prepare_weight for two matrices of the same shape (K x F or F x K,
+ *   same dtype, leading dimension and clip ratios): the prepared weight has N = 2 F columns, gate and up
+ *   interleaved in groups of 32 (column 64 p + j = gate column 32 p + j, column 64 p + 32 + j = up column
+ *   32 p + j, j < 32).  F must be a multiple of 32.  batq_weight_export / batq_gemm_mxfp4 see the 2 F columns in
+ *   this order.
+ * batq_gemm_glu: H[m][f] = silu(g) * u with g, u the fp32 sums of batq_gemm_mxfp4 (act_bits 4 or 0) or
+ *   batq_gemm_a8w4 (act_bits 8) for the gate and up column of f; the product is formed in fp32 (about 2^-21
+ *   relative) and rounded once to the output type.  H is M x N/2 (DEVICE, row stride ldh >= N/2 elements).  The
+ *   weight's N must be a multiple of 64 (BATQ_ERR_SHAPE); with M > 64, operand code arrays of 2 GiB or more
+ *   are not supported (BATQ_ERR_UNSUPPORTED).  K parts are not used, so nothing is allocated.
+ * batq_linear_glu: batq_linear_ex (same options and workspace) followed by the gated epilogue. */
+batq_status batq_prepare_weight_gate_up(batq_weight** out, const batq_transform* t, const void* W_gate,
+                                        const void* W_up, batq_dtype wdtype, int K, int F, int64_t ldw,
+                                        int w_is_KxN, const float* clip_w, void* stream);
+batq_status batq_gemm_glu(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M,
+                          int act_bits, void* H, batq_dtype hdtype, int64_t ldh, void* stream);
+batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype,
+                            int M, int64_t ldx, const batq_act_options* opt, void* H, batq_dtype hdtype,
+                            int64_t ldh, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------
  * Key/value cache (Sec. 3.2, "Self-Attention Module": P_k and P_v transform the key and value cache head by
  * head).  A cache row is written with batq_quantize_act[_ex] on the [tokens][kv_heads * head_dim] key or value
  * tensor: the blocks of a head (head_dim / 32 of them) each carry their own T_k, act_bits 4 or 8 gives KV4 or

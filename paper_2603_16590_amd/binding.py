@@ -62,6 +62,9 @@ SYMBOLS = {
     "batq_quantize_act_ex": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp, _vp]),
     "batq_linear_ex": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_row_rms_scale": (_i, [_vp, _i, _i, _i, _i64, C.c_float, _vp, _vp]),
+    "batq_prepare_weight_gate_up": (_i, [C.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i64, _i, _fp, _vp]),
+    "batq_gemm_glu": (_i, [_vp, _vp, _vp, _i, _i, _vp, _i, _i64, _vp]),
+    "batq_linear_glu": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_dequantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _i, _i64, _vp]),
     "batq_transform_apply": (_i, [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _i, _i64, _vp]),
 }
@@ -233,6 +236,20 @@ def batq_prepare_weight(t: Transform, W, w_is_KxN: bool = True, clip_w: Optional
     return Weight(h)
 
 
+def batq_prepare_weight_gate_up(t: Transform, W_gate, W_up, w_is_KxN: bool = True,
+                                clip_w: Optional[np.ndarray] = None) -> Weight:
+    """Gate and up projection (same shape, dtype and row stride) as one weight of 2 F interleaved columns."""
+    assert W_gate.is_cuda and W_gate.dim() == 2 and W_gate.stride(1) == 1
+    assert W_up.is_cuda and W_up.shape == W_gate.shape and W_up.dtype == W_gate.dtype and W_up.stride() == W_gate.stride()
+    K, F = (W_gate.shape[0], W_gate.shape[1]) if w_is_KxN else (W_gate.shape[1], W_gate.shape[0])
+    clip_w = None if clip_w is None else np.ascontiguousarray(clip_w, dtype=np.float32)
+    h = _vp()
+    _check(lib.batq_prepare_weight_gate_up(C.byref(h), t.handle, W_gate.data_ptr(), W_up.data_ptr(), _dtype_code(W_gate),
+                                           K, F, W_gate.stride(0), 1 if w_is_KxN else 0, _fptr(clip_w), _stream()),
+           "batq_prepare_weight_gate_up")
+    return Weight(h)
+
+
 def batq_prepare_weight_minmax(t: Transform, W, clip_w_min: np.ndarray, clip_w_max: np.ndarray,
                                w_is_KxN: bool = True) -> Weight:
     """As batq_prepare_weight with the two-ratio clipping (ratios on the block minimum and maximum)."""
@@ -327,6 +344,17 @@ def batq_gemm_mxfp4(xcodes, xscales, w: Weight, M: int, out_dtype=None, Y=None):
     _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
                                Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_mxfp4")
     return Y
+
+
+def batq_gemm_glu(xcodes, xscales, w: Weight, M: int, act_bits: int = 4, out_dtype=None, H=None):
+    """silu(gate) * up of the gate/up GEMM on device-order activation codes. Returns H (M x N/2)."""
+    import torch
+    F = w.N // 2
+    if H is None:
+        H = torch.empty((M, F), dtype=out_dtype or torch.bfloat16, device=xcodes.device)
+    _check(lib.batq_gemm_glu(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, act_bits, H.data_ptr(), _dtype_code(H),
+                             H.stride(0) if M > 1 else max(F, H.stride(0)), _stream()), "batq_gemm_glu")
+    return H
 
 
 def batq_linear_workspace(M: int, K: int) -> int:
@@ -448,6 +476,26 @@ def batq_row_rms_scale(X, eps: float = 1e-6):
     _check(lib.batq_row_rms_scale(X.data_ptr(), _dtype_code(X), M, K, X.stride(0) if M > 1 else max(K, X.stride(0)),
                                   eps, out.data_ptr(), _stream()), "batq_row_rms_scale")
     return out
+
+
+def batq_linear_glu(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=None, out_dtype=None, H=None,
+                    workspace=None, up=None):
+    """Quantise X (options as batq_linear_ex), multiply with a gate/up weight, return silu(gate) * up."""
+    import torch
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    F = w.N // 2
+    if H is None:
+        H = torch.empty((M, F), dtype=out_dtype or torch.bfloat16, device=X.device)
+    need = batq_linear_a8w4_workspace(M, K) if act_bits == 8 else batq_linear_workspace(M, K)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+    o = _opts(act_bits, row_scale, up, X)
+    _check(lib.batq_linear_glu(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
+                               X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), H.data_ptr(),
+                               _dtype_code(H), H.stride(0) if M > 1 else max(F, H.stride(0)),
+                               workspace.data_ptr(), workspace.numel(), _stream()), "batq_linear_glu")
+    return H
 
 
 APPLY_FORWARD, APPLY_INVERSE, APPLY_INVERSE_T = 0, 1, 2

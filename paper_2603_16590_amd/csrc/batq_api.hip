@@ -304,10 +304,14 @@ namespace {
 
 // clip_a / clip_b: symmetric ratios in clip_a (clip_b null), or the ratios on the block minimum and
 // maximum (two_ratio).
-batq_status prepare_weight_impl(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
-                                int K, int N, int64_t ldw, int w_is_KxN, const float* clip_a, const float* clip_b,
-                                bool two_ratio, void* stream) {
+// W_up != null: W is the gate projection and W_up the up projection (same shape and layout); the prepared
+// weight has 2 N rows, gate and up interleaved in groups of 32.
+batq_status prepare_weight_impl(batq_weight** out, const batq_transform* t, const void* W, const void* W_up,
+                                batq_dtype wdtype, int K, int N, int64_t ldw, int w_is_KxN, const float* clip_a,
+                                const float* clip_b, bool two_ratio, void* stream) {
     if (!out || !t || !W) return BATQ_ERR_NULL;
+    if (W_up && N % 32 != 0) return BATQ_ERR_SHAPE;
+    const int N_out = W_up ? 2 * N : N;
     if (two_ratio && (!clip_a || !clip_b)) return BATQ_ERR_NULL;
     if (!dtype_ok(wdtype)) return BATQ_ERR_DTYPE;
     if (K <= 0 || N <= 0 || K % 32 != 0) return BATQ_ERR_SHAPE;
@@ -321,7 +325,7 @@ batq_status prepare_weight_impl(batq_weight** out, const batq_transform* t, cons
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     batq_weight* w = nullptr;
-    st = alloc_weight(&w, K, N);
+    st = alloc_weight(&w, K, N_out);
     if (st != BATQ_OK) return st;
     float* d_clip_a = nullptr;
     float* d_clip_b = nullptr;
@@ -333,11 +337,14 @@ batq_status prepare_weight_impl(batq_weight** out, const batq_transform* t, cons
         return st;
     }
     // padding: zero codes (rows up to a multiple of 16, K up to a multiple of 256), neutral scales
-    hipError_t e = hipMemsetAsync(w->d_scales, 127, batq::scale_bytes_internal(N, nb), s);
-    if (e == hipSuccess) e = hipMemsetAsync(w->d_codes, 0, batq::code_bytes_blocked(N, nb), s);
+    hipError_t e = hipMemsetAsync(w->d_scales, 127, batq::scale_bytes_internal(N_out, nb), s);
+    if (e == hipSuccess) e = hipMemsetAsync(w->d_codes, 0, batq::code_bytes_blocked(N_out, nb), s);
     if (e == hipSuccess)
-        e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, d_clip_a, d_clip_b, w->d_codes,
-                                        w->d_scales, s);
+        e = batq::launch_prepare_weight(t, W, wdtype, K, N, ldw, w_is_KxN, N_out, W_up ? 0 : -1, d_clip_a, d_clip_b,
+                                        w->d_codes, w->d_scales, s);
+    if (e == hipSuccess && W_up)
+        e = batq::launch_prepare_weight(t, W_up, wdtype, K, N, ldw, w_is_KxN, N_out, 32, d_clip_a, d_clip_b,
+                                        w->d_codes, w->d_scales, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (d_clip_a) (void)hipFree(d_clip_a);
     if (d_clip_b) (void)hipFree(d_clip_b);
@@ -356,13 +363,20 @@ extern "C" {
 
 batq_status batq_prepare_weight(batq_weight** out, const batq_transform* t, const void* W, batq_dtype wdtype,
                                 int K, int N, int64_t ldw, int w_is_KxN, const float* clip_w, void* stream) {
-    return prepare_weight_impl(out, t, W, wdtype, K, N, ldw, w_is_KxN, clip_w, nullptr, false, stream);
+    return prepare_weight_impl(out, t, W, nullptr, wdtype, K, N, ldw, w_is_KxN, clip_w, nullptr, false, stream);
+}
+
+batq_status batq_prepare_weight_gate_up(batq_weight** out, const batq_transform* t, const void* W_gate,
+                                        const void* W_up, batq_dtype wdtype, int K, int F, int64_t ldw,
+                                        int w_is_KxN, const float* clip_w, void* stream) {
+    if (!W_up) return BATQ_ERR_NULL;
+    return prepare_weight_impl(out, t, W_gate, W_up, wdtype, K, F, ldw, w_is_KxN, clip_w, nullptr, false, stream);
 }
 
 batq_status batq_prepare_weight_minmax(batq_weight** out, const batq_transform* t, const void* W,
                                        batq_dtype wdtype, int K, int N, int64_t ldw, int w_is_KxN,
                                        const float* clip_w_min, const float* clip_w_max, void* stream) {
-    return prepare_weight_impl(out, t, W, wdtype, K, N, ldw, w_is_KxN, clip_w_min, clip_w_max, true, stream);
+    return prepare_weight_impl(out, t, W, nullptr, wdtype, K, N, ldw, w_is_KxN, clip_w_min, clip_w_max, true, stream);
 }
 
 batq_status batq_weight_export(const batq_weight* w, uint8_t* codes, uint8_t* scales, void* stream) {
@@ -451,15 +465,17 @@ batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdt
     return BATQ_OK;
 }
 
+// glu: Y = silu(gate) * up, M x N/2, for a weight prepared by batq_prepare_weight_gate_up
 batq_status gemm_impl(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
-                      batq_dtype ydtype, int64_t ldy, bool a8, void* stream) {
+                      batq_dtype ydtype, int64_t ldy, bool a8, bool glu, void* stream) {
     if (!w) return BATQ_ERR_NULL;
     if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
-    if (M < 0 || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M < 0 || ldy < (glu ? w->N / 2 : w->N)) return BATQ_ERR_SHAPE;
+    if (glu && !batq::gemm_glu_supported(w, M, a8)) return w->N % 64 != 0 ? BATQ_ERR_SHAPE : BATQ_ERR_UNSUPPORTED;
     if (M == 0) return BATQ_OK;
     if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
     if (!aligned16(xcodes) || (reinterpret_cast<uintptr_t>(xscales) & 7u) != 0) return BATQ_ERR_SHAPE;
-    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, a8, static_cast<hipStream_t>(stream)) !=
+    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, a8, glu, static_cast<hipStream_t>(stream)) !=
         hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
@@ -476,11 +492,12 @@ size_t workspace_impl(int M, int K, bool a8) {
 
 batq_status linear_impl(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                         int64_t ldx, const ActExtras& ex, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
-                        size_t workspace_bytes, bool a8, void* stream) {
+                        size_t workspace_bytes, bool a8, bool glu, void* stream) {
     if (!t || !w) return BATQ_ERR_NULL;
     if (!dtype_ok(xdtype) || !dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
     if (t->K != w->K) return BATQ_ERR_MISMATCH;
-    if (M < 0 || ldx < t->K || ldy < w->N) return BATQ_ERR_SHAPE;
+    if (M < 0 || ldx < t->K || ldy < (glu ? w->N / 2 : w->N)) return BATQ_ERR_SHAPE;
+    if (glu && !batq::gemm_glu_supported(w, M, a8)) return w->N % 64 != 0 ? BATQ_ERR_SHAPE : BATQ_ERR_UNSUPPORTED;
     if (M == 0) return BATQ_OK;
     if (!X || !Y || !workspace) return BATQ_ERR_NULL;
     if (workspace_bytes < workspace_impl(M, t->K, a8)) return BATQ_ERR_WORKSPACE;
@@ -492,7 +509,7 @@ batq_status linear_impl(const batq_transform* t, const batq_weight* w, const voi
     uint8_t* scales = codes + (a8 ? batq::code8_bytes_blocked(M, t->nb) : batq::code_bytes_blocked(M, t->nb));
     hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales,
                                              a8, s);
-    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, s);
+    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, glu, s);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
@@ -589,12 +606,12 @@ batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped,
 
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                             batq_dtype ydtype, int64_t ldy, void* stream) {
-    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, stream);
+    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, false, stream);
 }
 
 batq_status batq_gemm_a8w4(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                            batq_dtype ydtype, int64_t ldy, void* stream) {
-    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, stream);
+    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, false, stream);
 }
 
 size_t batq_linear_workspace(int M, int K) { return workspace_impl(M, K, false); }
@@ -603,13 +620,13 @@ size_t batq_linear_a8w4_workspace(int M, int K) { return workspace_impl(M, K, tr
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                         int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                         size_t workspace_bytes, void* stream) {
-    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, false, stream);
+    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, false, false, stream);
 }
 
 batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                              int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
                              size_t workspace_bytes, void* stream) {
-    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, true, stream);
+    return linear_impl(t, w, X, xdtype, M, ldx, ActExtras{}, Y, ydtype, ldy, workspace, workspace_bytes, true, false, stream);
 }
 
 // ---- options form of the online calls
@@ -640,7 +657,22 @@ batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w, const 
     bool a8;
     ActExtras ex;
     if (!act_options_ok(opt, &a8, &ex)) return BATQ_ERR_UNSUPPORTED;
-    return linear_impl(t, w, X, xdtype, M, ldx, ex, Y, ydtype, ldy, workspace, workspace_bytes, a8, stream);
+    return linear_impl(t, w, X, xdtype, M, ldx, ex, Y, ydtype, ldy, workspace, workspace_bytes, a8, false, stream);
+}
+
+batq_status batq_gemm_glu(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, int act_bits,
+                          void* H, batq_dtype hdtype, int64_t ldh, void* stream) {
+    if (act_bits != 0 && act_bits != 4 && act_bits != 8) return BATQ_ERR_UNSUPPORTED;
+    return gemm_impl(xcodes, xscales, w, M, H, hdtype, ldh, act_bits == 8, true, stream);
+}
+
+batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
+                            int64_t ldx, const batq_act_options* opt, void* H, batq_dtype hdtype, int64_t ldh,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    bool a8;
+    ActExtras ex;
+    if (!act_options_ok(opt, &a8, &ex)) return BATQ_ERR_UNSUPPORTED;
+    return linear_impl(t, w, X, xdtype, M, ldx, ex, H, hdtype, ldh, workspace, workspace_bytes, a8, true, stream);
 }
 
 batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits, void* out,

@@ -55,13 +55,18 @@ hipError_t launch_transform_apply(const batq_transform* t, const void* X, batq_d
 hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,
                                 hipStream_t stream);
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
-                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
-                                 uint8_t* codes, uint8_t* scales, hipStream_t stream);
+                                 int64_t ldw, int w_is_KxN, int N_out, int il_off, const float* d_clip_w,
+                                 const float* d_clip_w_max, uint8_t* codes, uint8_t* scales, hipStream_t stream);
+// N_out / il_off: rows of the prepared weight and the interleave offset (-1: column n -> row n; 0 / 32: gate /
+// up columns of an MLP interleaved in groups of 32, N_out = 2 N).
 // d_clip_w_max != null selects the two-ratio clipping (d_clip_w then holds the ratios on the minimum).
 // Weight scales are written in the internal layout (pad bytes must have been set to 127).
 // xscales_internal: activation scales in the grouped layout.
+// glu: gated output, Y = silu(gate) * up is M x N/2 for a weight with interleaved gate / up columns
+// (gemm_glu_supported says whether the shapes allow it).
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream);
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, hipStream_t stream);
+bool gemm_glu_supported(const batq_weight* w, int M, bool a8);
 hipError_t launch_codes8_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);

@@ -188,26 +188,34 @@ gemm_direct(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 // operands, so there is no K tail.
 constexpr int kSkinnyWaves = 8;
 
-// RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads; A8 = MXFP8 activations
-template <typename YT, int RT, bool A8>
+// RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads; A8 = MXFP8 activations;
+// GLU = gated output: a workgroup owns 32 output columns = the 32 gate and the 32 up columns of one
+// 64-column group of the interleaved weight (sharing the loads of X), and stores silu(gate) * up to M x N/2.
+template <typename YT, int RT, bool A8, bool GLU>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
             const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy,
             float* __restrict__ partial) {
+    constexpr int NG = GLU ? 2 : 1;                         // 32-column groups of the weight per workgroup
     __shared__ float part[kSkinnyWaves][16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n0 = blockIdx.x * 32;
+    const int n0 = blockIdx.x * 32 * NG;                    // first weight column
     const int i = lane & 31, kg = lane >> 5;
-    const int bn = min(n0 + i, N - 1);                      // rows and columns past the edge are computed, not stored
     const int groups = scale_groups(nb);
     // gridDim.y > 1: the K groups are first cut into gridDim.y parts, one per workgroup row, whose sums go
     // to partial[part][M][N] (fp32) for splitk_reduce_rows
     const int p_begin = groups * blockIdx.y / gridDim.y, p_groups = groups * (blockIdx.y + 1) / gridDim.y - p_begin;
     const int g_begin = p_begin + p_groups * wave / kSkinnyWaves, g_end = p_begin + p_groups * (wave + 1) / kSkinnyWaves;
     // block k = 8 g + 2 j + kg (j = 0..3): chunk (k / 4, k % 4) = (2 g + j / 2, 2 (j % 2) + kg)
-    const int rb = bn & 15;
-    const uint8_t* pb = wc + (size_t)(bn >> 4) * code_stages(nb) * 1024 + rb * 64;
-    const int swb = (rb >> 2) & 3;
+    int bn[NG], swb[NG];
+    const uint8_t* pb[NG];
+#pragma unroll
+    for (int c = 0; c < NG; ++c) {
+        bn[c] = min(n0 + 32 * c + i, N - 1);                // rows and columns past the edge are computed, not stored
+        const int rb = bn[c] & 15;
+        pb[c] = wc + (size_t)(bn[c] >> 4) * code_stages(nb) * 1024 + rb * 64;
+        swb[c] = (rb >> 2) & 3;
+    }
     int am[RT], swa[RT];
     const uint8_t* pa[RT];
 #pragma unroll
@@ -218,17 +226,21 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
         swa[t] = (ra >> 2) & 3;
     }
     constexpr int AR = A8 ? 2 : 1;                          // 16-byte slots of A per lane and matrix instruction
-    v16f acc[RT];
+    v16f acc[RT][NG];
 #pragma unroll
-    for (int t = 0; t < RT; ++t) acc[t] = v16f{};
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int c = 0; c < NG; ++c) acc[t][c] = v16f{};
     // operands of group g are fetched while group g-1 is multiplied
-    uint4 a[RT][4][AR], b[4], an[RT][4][AR], bn4[4];
-    int sa[RT], sb = 0, san[RT], sbn = 0;
-    auto load_group = [&](int g, uint4 (&ga)[RT][4][AR], uint4 (&gb)[4], int (&gsa)[RT], int& gsb) {
+    uint4 a[RT][4][AR], b[NG][4], an[RT][4][AR], bn4[NG][4];
+    int sa[RT], sb[NG], san[RT], sbn[NG];
+    auto load_group = [&](int g, uint4 (&ga)[RT][4][AR], uint4 (&gb)[NG][4], int (&gsa)[RT], int (&gsb)[NG]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int piece = 2 * g + (j >> 1), slot = 2 * (j & 1) + kg;
-            gb[j] = *reinterpret_cast<const uint4*>(pb + (size_t)piece * 1024 + ((slot ^ swb) << 4));
+#pragma unroll
+            for (int c = 0; c < NG; ++c)
+                gb[c][j] = *reinterpret_cast<const uint4*>(pb[c] + (size_t)piece * 1024 + ((slot ^ swb[c]) << 4));
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
                 if constexpr (A8) {
@@ -244,7 +256,8 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
             }
         }
         // byte j of the dword at 4 kg of the row's scale word is the scale of block 8 g + 2 j + kg
-        gsb = *reinterpret_cast<const int*>(ws + ((size_t)g * N + bn) * 8 + 4 * kg);
+#pragma unroll
+        for (int c = 0; c < NG; ++c) gsb[c] = *reinterpret_cast<const int*>(ws + ((size_t)g * N + bn[c]) * 8 + 4 * kg);
 #pragma unroll
         for (int t = 0; t < RT; ++t) gsa[t] = *reinterpret_cast<const int*>(xs + ((size_t)g * M + am[t]) * 8 + 4 * kg);
     };
@@ -256,42 +269,63 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
             else return frag(a[t][j][0]);
         };
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            acc[t] = mx_mfma<A8, 0>(afrag(t, 0), frag(b[0]), acc[t], sa[t], sb);
-            acc[t] = mx_mfma<A8, 1>(afrag(t, 1), frag(b[1]), acc[t], sa[t], sb);
-            acc[t] = mx_mfma<A8, 2>(afrag(t, 2), frag(b[2]), acc[t], sa[t], sb);
-            acc[t] = mx_mfma<A8, 3>(afrag(t, 3), frag(b[3]), acc[t], sa[t], sb);
-        }
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int c = 0; c < NG; ++c) {
+                acc[t][c] = mx_mfma<A8, 0>(afrag(t, 0), frag(b[c][0]), acc[t][c], sa[t], sb[c]);
+                acc[t][c] = mx_mfma<A8, 1>(afrag(t, 1), frag(b[c][1]), acc[t][c], sa[t], sb[c]);
+                acc[t][c] = mx_mfma<A8, 2>(afrag(t, 2), frag(b[c][2]), acc[t][c], sa[t], sb[c]);
+                acc[t][c] = mx_mfma<A8, 3>(afrag(t, 3), frag(b[c][3]), acc[t][c], sa[t], sb[c]);
+            }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            b[j] = bn4[j];
+#pragma unroll
+            for (int c = 0; c < NG; ++c) b[c][j] = bn4[c][j];
 #pragma unroll
             for (int t = 0; t < RT; ++t)
 #pragma unroll
                 for (int h = 0; h < AR; ++h) a[t][j][h] = an[t][j][h];
         }
-        sb = sbn;
+#pragma unroll
+        for (int c = 0; c < NG; ++c) sb[c] = sbn[c];
 #pragma unroll
         for (int t = 0; t < RT; ++t) sa[t] = san[t];
     }
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        if (t > 0) __syncthreads();                         // the previous tile's partial sums have been read
+        // 1024 outputs per 32 x 32 tile, two per thread; element (r, l) of the tile is
+        // (8 (r / 4) + 4 (l / 32) + r % 4, l % 32)
+        float v[NG][2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[t][r];
-        __syncthreads();
-        // 1024 outputs, two per thread; element (r, l) of the tile is (8 (r / 4) + 4 (l / 32) + r % 4, l % 32)
+        for (int c = 0; c < NG; ++c) {
+            if (t > 0 || c > 0) __syncthreads();            // the previous tile's partial sums have been read
+#pragma unroll
+            for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[t][c][r];
+            __syncthreads();
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e = threadIdx.x + h * kSkinnyWaves * 64;
+                const int r = e >> 6, l = e & 63;
+                float sum = part[0][r][l];
+#pragma unroll
+                for (int w = 1; w < kSkinnyWaves; ++w) sum += part[w][r][l];
+                v[c][h] = sum;
+            }
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int e = threadIdx.x + h * kSkinnyWaves * 64;
             const int r = e >> 6, l = e & 63;
-            float v = part[0][r][l];
-#pragma unroll
-            for (int w = 1; w < kSkinnyWaves; ++w) v += part[w][r][l];
-            const int row = 32 * t + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), col = n0 + (l & 31);
-            if (row < M && col < N) {
-                if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v;
-                else store_y<YT>(Y + (size_t)row * ldy + col, v);
+            const int row = 32 * t + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+            if constexpr (GLU) {
+                const int col = blockIdx.x * 32 + (l & 31);
+                if (row < M && col < N / 2) store_y<YT>(Y + (size_t)row * ldy + col, swiglu_f32(v[0][h], v[1][h]));
+            } else {
+                const int col = n0 + (l & 31);
+                if (row < M && col < N) {
+                    if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v[0][h];
+                    else store_y<YT>(Y + (size_t)row * ldy + col, v[0][h]);
+                }
             }
         }
     }
@@ -333,6 +367,8 @@ struct TilePlan {
     int workers;      // workgroups launched, a multiple of 8
     int ksplit;       // parts the K groups are cut into (1: every tile runs over all of K)
     int groups;       // K groups of 256 elements
+    int pair;         // 64-column strips per scheduling unit: 1, or 2 when tiles must be an even number of strips
+                      // wide (gated output; strips_n then counts units of 128 columns)
 };
 
 struct Tile {
@@ -357,15 +393,17 @@ __device__ __forceinline__ bool next_tile(const TilePlan& pl, int& cur, int end,
     const int width = be - bs;
     const int local = at - pl.tiles_m * bs;
     const int p = local / width, sl = local - p * width;
-    const int run = min(stop - at, width - sl);           // strips left in this row panel of the band
-    const int nt = (run + 3) >> 2;                        // tiles the run is cut into, near-equal widths
-    t.nj = (run + nt - 1) / nt;
+    const int run = min(stop - at, width - sl);           // units left in this row panel of the band
+    const int most = 4 / pl.pair;                         // units per tile at most (a tile is at most 4 strips wide)
+    const int nt = (run + most - 1) / most;               // tiles the run is cut into, near-equal widths
+    const int units = (run + nt - 1) / nt;
+    t.nj = units * pl.pair;
     t.m0 = p * kTile;
-    t.n0 = (bs + sl) * kStrip;
+    t.n0 = (bs + sl) * kStrip * pl.pair;
     t.part = part;
     t.g0 = pl.groups * part / pl.ksplit;
     t.ng = pl.groups * (part + 1) / pl.ksplit - t.g0;
-    cur += t.nj;
+    cur += units;
     return true;
 }
 
@@ -592,16 +630,16 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
     }
 }
 
-// Epilogue of a tile: accumulators (4 x NJ matrix tiles of this wave, rows wm*128.., columns wn*32*NJ..) -> Y.
+// Epilogue of a tile: 4 x NJ output tiles of 32 x 32 of this wave (rows m0 + wm*128.., columns n0 + wn*32*NJ..)
+// -> Y; value(i, j, e) = element e (accumulator register order) of output tile (i, j).
 // `ep_lds` is the wave's private 4 KiB LDS staging area.
-template <int NJ, typename YT>
-__device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, int lane, int wm, int wn, const Tile& t,
-                                           int M, int N, YT* __restrict__ Y, int64_t ldy) {
+template <int NJ, typename YT, typename F>
+__device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int lane, int wm, int wn, int m0, int n0,
+                                                int M, int N, YT* __restrict__ Y, int64_t ldy) {
     // ---- epilogue: accumulators -> Y
     // (lane-derived addresses are recomputed per tile rather than kept in registers across the main loop)
     int lane_e = lane;
     asm volatile("" : "+v"(lane_e));
-    const int m0 = t.m0, n0 = t.n0;
     if constexpr (sizeof(YT) == 2) {
         // bf16: transpose through a wave-private LDS buffer so that every lane stores 16 contiguous
         // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
@@ -637,8 +675,8 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, 
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
                             f32x2 pr;
-                            pr.x = acc[i][j][8 * h + 2 * u];
-                            pr.y = acc[i][j][8 * h + 2 * u + 1];
+                            pr.x = value(i, j, 8 * h + 2 * u);
+                            pr.y = value(i, j, 8 * h + 2 * u + 1);
                             const int mine = __builtin_bit_cast(int, __builtin_convertvector(pr, bf16x2));
                             const int theirs = __builtin_amdgcn_mov_dpp(mine, 0xB1, 0xF, 0xF, true);
                             *reinterpret_cast<uint32_t*>(pj[j] + (8 * (u >> 1) + 2 * (u & 1)) * 256) =
@@ -672,7 +710,7 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, 
                 if (row < M) {
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        if (col0 + 32 * j < N) store_y<YT>(yp + 32 * j, acc[i][j][4 * q + r]);
+                        if (col0 + 32 * j < N) store_y<YT>(yp + 32 * j, value(i, j, 4 * q + r));
                 }
                 ++row;
                 yp += ldy;
@@ -680,6 +718,21 @@ __device__ __forceinline__ void store_tile(v16f (&acc)[4][NJ], uint8_t* ep_lds, 
             row += 4;
             yp += 4 * ldy;
         }
+}
+
+// GLU: the weight columns interleave gate and up in groups of 32 (columns 64 p .. 64 p + 31 = gate columns
+// 32 p .., 64 p + 32 .. 64 p + 63 = the matching up columns), so matrix tiles 2 j and 2 j + 1 of a wave hold
+// gate and up of the same outputs in the same lanes and registers; what is stored is silu(gate) * up, to the
+// M x N/2 array Y (N here = its column count).  NJ must be even.
+template <int NJ, typename YT, bool GLU>
+__device__ __forceinline__ void store_tile(v16f (&acc_in)[4][NJ], uint8_t* ep_lds, int lane, int wm, int wn,
+                                           const Tile& t, int M, int N, YT* __restrict__ Y, int64_t ldy) {
+    static_assert(!GLU || NJ % 2 == 0, "gated output needs gate/up tile pairs");
+    auto value = [&](int i, int j, int e) -> float {
+        if constexpr (GLU) return swiglu_f32(acc_in[i][2 * j][e], acc_in[i][2 * j + 1][e]);
+        else return acc_in[i][j][e];
+    };
+    store_tile_impl<(GLU ? NJ / 2 : NJ), YT>(value, ep_lds, lane, wm, wn, t.m0, GLU ? t.n0 / 2 : t.n0, M, N, Y, ldy);
 }
 
 // Partial sums of a K part, in the order the accumulators hold them: 32x32 blocks, block (rb, cb) of the
@@ -709,7 +762,7 @@ __device__ __forceinline__ void store_partial(v16f (&acc)[4][NJ], float* __restr
 // the epilogue the loads of the next tile's first stages are started, so they run underneath it.
 // With K parts (YT = float), Y is the partial-sum array in accumulator order (store_partial), `ldy` its number
 // of 32-column blocks and `part_stride` the floats of one part; else part_stride = 0.
-template <int NJ, typename YT>
+template <int NJ, typename YT, bool GLU>
 __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_next, const Tile& next,
                                          YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
     const int lane = c.lane, wave = c.wave;
@@ -759,20 +812,21 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     }
 
     // ---- epilogue: accumulators -> Y
-    if constexpr (sizeof(YT) == 4) {
+    if constexpr (sizeof(YT) == 4 && !GLU) {
         if (part_stride != 0) {
             store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
             return;
         }
     }
-    store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
-                       c.M, c.N, Y, ldy);
+    store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn,
+                            t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
 // pl.ksplit > 1: tiles cover one K part each and store their partial sums to Y + part * part_stride
 // (fp32, summed by splitk_reduce); used when there are fewer strips than workgroups.
-template <typename YT>
+// GLU: gated output (see store_tile); the plan then hands out tiles 2 or 4 strips wide, and Y is M x N/2.
+template <typename YT, bool GLU>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
            const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy,
@@ -806,11 +860,16 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     c.issue_prologue(t.nj);
     for (;;) {
         const bool has_next = next_tile(pl, cur, end, next);
-        switch (t.nj) {
-            case 4: run_tile<4, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            case 3: run_tile<3, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            case 2: run_tile<2, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            default: run_tile<1, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+        if constexpr (GLU) {
+            if (t.nj == 4) run_tile<4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+            else run_tile<2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+        } else {
+            switch (t.nj) {
+                case 4: run_tile<4, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 3: run_tile<3, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 2: run_tile<2, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                default: run_tile<1, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+            }
         }
         if (!has_next) break;
         t = next;
@@ -1004,7 +1063,7 @@ __device__ __forceinline__ void a8_stage(const A8Ctx& c, int s, v16f (&acc)[4][N
     }
 }
 
-template <int NJ, typename YT>
+template <int NJ, typename YT, bool GLU>
 __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_next, const Tile& next,
                                             YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
     const int lane = c.lane, wave = c.wave;
@@ -1051,18 +1110,18 @@ __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_ne
         c.issue_stage<2>(2);
         c.issue_stage<3>(3);
     }
-    if constexpr (sizeof(YT) == 4) {
+    if constexpr (sizeof(YT) == 4 && !GLU) {
         if (part_stride != 0) {
             store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
             return;
         }
     }
-    store_tile<NJ, YT>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn, t,
-                       c.M, c.N, Y, ldy);
+    store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm,
+                            wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
-template <typename YT>
+template <typename YT, bool GLU>
 __global__ void __launch_bounds__(256, 1)
 gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
               const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy,
@@ -1097,11 +1156,16 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     c.issue_stage<3>(3);
     for (;;) {
         const bool has_next = next_tile(pl, cur, end, next);
-        switch (t.nj) {
-            case 4: a8_run_tile<4, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            case 3: a8_run_tile<3, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            case 2: a8_run_tile<2, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
-            default: a8_run_tile<1, YT>(c, t, has_next, next, Y, ldy, part_stride); break;
+        if constexpr (GLU) {
+            if (t.nj == 4) a8_run_tile<4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+            else a8_run_tile<2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+        } else {
+            switch (t.nj) {
+                case 4: a8_run_tile<4, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 3: a8_run_tile<3, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 2: a8_run_tile<2, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                default: a8_run_tile<1, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+            }
         }
         if (!has_next) break;
         t = next;
@@ -1200,8 +1264,8 @@ int choose_bands(int M, int N, int strips_n) {
     return best;
 }
 
-// A8: the activation codes are MXFP8 in the blocked 8-bit layout.
-template <typename YT, bool A8>
+// A8: the activation codes are MXFP8 in the blocked 8-bit layout.  GLU: gated output (Y is M x N/2, N % 64 == 0).
+template <typename YT, bool A8, bool GLU>
 hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight* w, int M, YT* Y, int64_t ldy,
                         hipStream_t stream) {
     const int N = w->N, nb = w->nb;
@@ -1210,9 +1274,9 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
     if (M > 64 && fits32) {
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<YT>),
+            hipError_t e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<YT, GLU>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
-                              : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT>),
+                              : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT, GLU>),
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
             if (e != hipSuccess) return e;
             attr_set = true;
@@ -1222,46 +1286,52 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
         TilePlan pl;
+        pl.pair = GLU ? 2 : 1;
         pl.tiles_m = (M + kTile - 1) / kTile;
-        pl.strips_n = (N + kStrip - 1) / kStrip;
+        pl.strips_n = (N + kStrip * pl.pair - 1) / (kStrip * pl.pair);
         pl.bands = choose_bands(M, N, pl.strips_n);
         pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
         pl.ksplit = 1;
         pl.groups = scale_groups(nb);
-        // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
-        // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
-        // sums' round trip costs more than the idle compute units.
-        const int strips = pl.tiles_m * pl.strips_n;
-        const int col_blocks = 2 * pl.strips_n;
-        const size_t part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
-        int ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
-        while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
-        float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
+        float* parts = nullptr;
+        int ksplit = 1, col_blocks = 0;
+        size_t part_floats = 0;
+        if constexpr (!GLU) {
+            // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
+            // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
+            // sums' round trip costs more than the idle compute units.
+            const int strips = pl.tiles_m * pl.strips_n;
+            col_blocks = 2 * pl.strips_n;
+            part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
+            ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
+            while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
+            parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
+        }
         if (parts) {
             static bool attr_f32_set = false;
             if (!attr_f32_set) {
-                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<float>),
+                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<float, false>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
-                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float>),
+                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float, false>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
                 if (e != hipSuccess) return e;
                 attr_f32_set = true;
             }
             pl.ksplit = ksplit;
             if constexpr (A8)
-                gemm_tiled_a8<float><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
+                gemm_tiled_a8<float, false><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
                     xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
             else
-                gemm_tiled<float><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
+                gemm_tiled<float, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
                     xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
             splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
                 parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
         } else if constexpr (A8) {
-            gemm_tiled_a8<YT><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
-                                                                                nb, pl, Y, ldy, 0);
+            gemm_tiled_a8<YT, GLU><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales,
+                                                                                     M, N, nb, pl, Y, ldy, 0);
         } else {
-            gemm_tiled<YT><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N,
-                                                                                nb, pl, Y, ldy, 0);
+            gemm_tiled<YT, GLU><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
+                                                                                     N, nb, pl, Y, ldy, 0);
         }
     } else if (M <= 64) {
         // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two
@@ -1271,20 +1341,21 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        const int cols = (N + 31) / 32;
-        int ksplit = (2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
+        const int cols = (N + (GLU ? 63 : 31)) / (GLU ? 64 : 32);
+        int ksplit = (!GLU && 2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
         float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
         if (!parts || (size_t)ksplit * M * N * sizeof(float) > kSplitScratchBytes) ksplit = 1;
         const dim3 grid(cols, ksplit), block(kSkinnyWaves * 64);
         if (M <= 32)
-            gemm_skinny<YT, 1, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+            gemm_skinny<YT, 1, A8, GLU><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
         else
-            gemm_skinny<YT, 2, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+            gemm_skinny<YT, 2, A8, GLU><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
         if (ksplit > 1) {
             const int64_t total = (int64_t)M * N;
             splitk_reduce_rows<YT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(parts, ksplit, M, N, Y, ldy);
         }
     } else {
+        if constexpr (GLU) return hipErrorNotSupported;       // callers check gemm_glu_supported first
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
         gemm_direct<YT, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
     }
@@ -1335,17 +1406,31 @@ hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, 
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream) {
-    if (M == 0) return hipSuccess;
+bool gemm_glu_supported(const batq_weight* w, int M, bool a8) {
+    if (w->N % 64 != 0) return false;
+    if (M <= 64) return true;
+    const size_t xbytes = a8 ? code8_bytes_blocked(M, w->nb) : code_bytes_blocked(M, w->nb);
+    return xbytes < (1ull << 31) && code_bytes_blocked(w->N, w->nb) < (1ull << 31);
+}
+
+template <bool GLU>
+static hipError_t launch_gemm_as(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
+                                 void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream) {
     if (ydtype == BATQ_BF16) {
         uint16_t* Yp = static_cast<uint16_t*>(Y);
-        return a8 ? launch_typed<uint16_t, true>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
-                  : launch_typed<uint16_t, false>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+        return a8 ? launch_typed<uint16_t, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
+                  : launch_typed<uint16_t, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
     }
     float* Yp = static_cast<float*>(Y);
-    return a8 ? launch_typed<float, true>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
-              : launch_typed<float, false>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+    return a8 ? launch_typed<float, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
+              : launch_typed<float, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+}
+
+hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, hipStream_t stream) {
+    if (M == 0) return hipSuccess;
+    return glu ? launch_gemm_as<true>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, stream)
+               : launch_gemm_as<false>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, stream);
 }
 
 }  // namespace batq

@@ -68,6 +68,14 @@ __device__ __forceinline__ uint2 encode8_fp8(const float* y, float bound, uint32
     return uint2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
 }
 
+// Gated activation of the MLP (Sec. 3.2: its output is what P_down transforms): silu(g) * u =
+// g u / (1 + 2^(-g log2 e)) in fp32 (hardware exp2 and reciprocal, about 2^-21 relative).  Magnitudes below
+// 2^-100 may come out as zero.
+__device__ __forceinline__ float swiglu_f32(float g, float u) {
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * g);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs).

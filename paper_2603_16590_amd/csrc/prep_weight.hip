@@ -20,10 +20,12 @@ __device__ __forceinline__ double load_w<uint16_t>(const uint16_t* p) { return (
 
 // One thread per (K-block k, output column n).  blockIdx.y = k, blockIdx.x tiles N by 256.
 // Codes go to the blocked code layout, scales to the grouped layout (padding of both is
-// initialised by the caller).
+// initialised by the caller).  Column n of W becomes row n of the prepared weight (N_out = N rows), or, with
+// il_off >= 0, row 64 (n / 32) + il_off + n % 32 of a weight of N_out = 2 N rows: the gate (il_off 0) and up
+// (il_off 32) projections of an MLP interleaved in groups of 32 columns for the GEMM's gated output.
 template <typename WT, bool TRANSFORM>
 __global__ void __launch_bounds__(256)
-prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, int nb,
+prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, int N_out, int il_off, int nb,
                    const double* __restrict__ Tinv, const float* __restrict__ clip_w,
                    const float* __restrict__ clip_w_max, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     __shared__ double sT[TRANSFORM ? 32 * 32 : 1];
@@ -83,32 +85,33 @@ prep_weight_kernel(const WT* __restrict__ W, int64_t ldw, int w_is_KxN, int N, i
     out.y = encode8(y + 8, bound, sc);
     out.z = encode8(y + 16, bound, sc);
     out.w = encode8(y + 24, bound, sc);
-    *reinterpret_cast<uint4*>(codes + code_chunk_offset(n, k, nb)) = out;
-    scales[scale_index_internal(n, k, N)] = (uint8_t)s;
+    const int n_out = il_off >= 0 ? 64 * (n >> 5) + il_off + (n & 31) : n;
+    *reinterpret_cast<uint4*>(codes + code_chunk_offset(n_out, k, nb)) = out;
+    scales[scale_index_internal(n_out, k, N_out)] = (uint8_t)s;
 }
 
 }  // namespace
 
 hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dtype wdtype, int K, int N,
-                                 int64_t ldw, int w_is_KxN, const float* d_clip_w, const float* d_clip_w_max,
-                                 uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                                 int64_t ldw, int w_is_KxN, int N_out, int il_off, const float* d_clip_w,
+                                 const float* d_clip_w_max, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
     const int nb = K / 32;
     const dim3 grid((N + 255) / 256, nb), block(256);
     if (wdtype == BATQ_BF16) {
         auto Wp = static_cast<const uint16_t*>(W);
         if (t->has_transform)
-            prep_weight_kernel<uint16_t, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
+            prep_weight_kernel<uint16_t, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, N_out, il_off, nb, t->d_Tinv,
                                                                            d_clip_w, d_clip_w_max, codes, scales);
         else
-            prep_weight_kernel<uint16_t, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
+            prep_weight_kernel<uint16_t, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, N_out, il_off, nb, nullptr,
                                                                             d_clip_w, d_clip_w_max, codes, scales);
     } else {
         auto Wp = static_cast<const float*>(W);
         if (t->has_transform)
-            prep_weight_kernel<float, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, t->d_Tinv,
+            prep_weight_kernel<float, true><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, N_out, il_off, nb, t->d_Tinv,
                                                                         d_clip_w, d_clip_w_max, codes, scales);
         else
-            prep_weight_kernel<float, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, nb, nullptr,
+            prep_weight_kernel<float, false><<<grid, block, 0, stream>>>(Wp, ldw, w_is_KxN, N, N_out, il_off, nb, nullptr,
                                                                          d_clip_w, d_clip_w_max, codes, scales);
     }
     return hipGetLastError();

@@ -61,13 +61,6 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&x)[8]) {
     x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xFFFF0000u);
 }
 
-// Gated activation feeding the down projection (Sec. 3.2, P_down): silu(g) * u = g u / (1 + 2^(-g log2 e)) in
-// fp32 (hardware exp2 and reciprocal, about 2^-21 relative), rounded once to bf16: the tensor an unfused
-// model would have written.  Magnitudes below 2^-100 may come out as zero.
-__device__ __forceinline__ float swiglu_f32(float g, float u) {
-    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * g);
-    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
-}
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 // two bf16 pairs (gate, up) -> the bf16 pair of their gated products
