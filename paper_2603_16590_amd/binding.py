@@ -65,6 +65,7 @@ SYMBOLS = {
     "batq_prepare_weight_gate_up": (_i, [C.POINTER(_vp), _vp, _vp, _vp, _i, _i, _i, _i64, _i, _fp, _vp]),
     "batq_gemm_glu": (_i, [_vp, _vp, _vp, _i, _i, _vp, _i, _i64, _vp]),
     "batq_linear_glu": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_debug_tile_schedule": (_i, [_i, _i, _i, _i, _i, _i, _vp, _i]),
     "batq_dequantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _i, _i64, _vp]),
     "batq_transform_apply": (_i, [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _i, _i64, _vp]),
 }

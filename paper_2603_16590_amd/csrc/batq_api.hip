@@ -675,6 +675,14 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
     return linear_impl(t, w, X, xdtype, M, ldx, ex, H, hdtype, ldh, workspace, workspace_bytes, a8, true, stream);
 }
 
+int batq_debug_tile_schedule(int M, int N, int K, int compute_units, int glu, int allow_ksplit, int* tiles,
+                             int capacity) {
+    if (M <= 64 || N <= 0 || K <= 0 || K % 32 != 0 || compute_units < 8 || capacity < 0 || (capacity > 0 && !tiles))
+        return -1;
+    if (glu && N % 64 != 0) return -1;
+    return batq::tile_schedule(M, N, K, compute_units, glu != 0, allow_ksplit != 0, tiles, capacity);
+}
+
 batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits, void* out,
                             batq_dtype odtype, int64_t ldo, void* stream) {
     if (bits != 4 && bits != 8) return BATQ_ERR_UNSUPPORTED;

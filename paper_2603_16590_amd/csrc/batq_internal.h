@@ -67,6 +67,9 @@ hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dt
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
                              void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, hipStream_t stream);
 bool gemm_glu_supported(const batq_weight* w, int M, bool a8);
+// Host replay of the tiled kernels' work split: 7 ints per tile (workgroup, first row, first column, strips, K part,
+// first K group, K groups) into out[capacity * 7]; returns the number of tiles.
+int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_ksplit, int* out, int capacity);
 hipError_t launch_codes8_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, int rows, int nb, hipStream_t stream);
 hipError_t launch_codes_to_blocked(const uint8_t* rowmajor, uint8_t* blocked, int rows, int nb, hipStream_t stream);

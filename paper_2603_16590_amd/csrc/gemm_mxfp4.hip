@@ -25,6 +25,7 @@
 #include "code_layout.h"
 #include "mxfp4_device.h"
 #include "scale_layout.h"
+#include "tile_plan.h"
 
 namespace batq {
 namespace {
@@ -345,8 +346,6 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 // which it cuts into tiles of at most 4 strips.  Workgroups go to the 8 XCDs round-robin, so
 // workgroup b works on share (b % 8) * (workgroups / 8) + b / 8: the shares of one XCD are
 // contiguous and its L2 sees a compact block of the output.
-constexpr int kTile = 256;                 // tile rows
-constexpr int kStrip = 64;                 // tile columns come in strips of 64
 constexpr int kStageBytes = 64;            // code bytes per row per stage (128 elements, 4 MX blocks)
 constexpr int kOperandStage = kTile * kStageBytes;        // 16 KiB per operand per stage
 constexpr int kStageLds = 2 * kOperandStage;               // A then B
@@ -359,53 +358,6 @@ constexpr int kTiledLds = kEpilogueLds0 + 4 * kEpilogueWaveLds;     // 152 KiB
 // 16-byte slot swizzle inside a 64-byte LDS row: the 32 rows a fragment read touches, and the
 // 16 rows x 4 slots an LDS-direct load writes, both spread over all banks.
 __device__ __forceinline__ int slot_swizzle(int row) { return (row >> 2) & 3; }
-
-struct TilePlan {
-    int tiles_m;      // row panels of 256
-    int strips_n;     // column strips of 64
-    int bands;        // column bands (1, 2, 4 or 8)
-    int workers;      // workgroups launched, a multiple of 8
-    int ksplit;       // parts the K groups are cut into (1: every tile runs over all of K)
-    int groups;       // K groups of 256 elements
-    int pair;         // 64-column strips per scheduling unit: 1, or 2 when tiles must be an even number of strips
-                      // wide (gated output; strips_n then counts units of 128 columns)
-};
-
-struct Tile {
-    int m0, n0, nj;
-    int part, g0, ng;   // K part, its first K group and its number of K groups
-};
-
-// Takes the next tile off the share [cur, end) of the linear order: K part by K part, inside a part the
-// strip order (column bands -> row panels -> strips).
-__device__ __forceinline__ bool next_tile(const TilePlan& pl, int& cur, int end, Tile& t) {
-    if (cur >= end) return false;
-    int part = 0, at = cur, stop = end;
-    if (pl.ksplit > 1) {
-        const int per_part = pl.tiles_m * pl.strips_n;
-        part = cur / per_part;
-        at = cur - part * per_part;
-        stop = min(end - part * per_part, per_part);      // a tile does not reach into the next K part
-    }
-    int b = 0;
-    while (b + 1 < pl.bands && at >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
-    const int bs = b * pl.strips_n / pl.bands, be = (b + 1) * pl.strips_n / pl.bands;
-    const int width = be - bs;
-    const int local = at - pl.tiles_m * bs;
-    const int p = local / width, sl = local - p * width;
-    const int run = min(stop - at, width - sl);           // units left in this row panel of the band
-    const int most = 4 / pl.pair;                         // units per tile at most (a tile is at most 4 strips wide)
-    const int nt = (run + most - 1) / most;               // tiles the run is cut into, near-equal widths
-    const int units = (run + nt - 1) / nt;
-    t.nj = units * pl.pair;
-    t.m0 = p * kTile;
-    t.n0 = (bs + sl) * kStrip * pl.pair;
-    t.part = part;
-    t.g0 = pl.groups * part / pl.ksplit;
-    t.ng = pl.groups * (part + 1) / pl.ksplit - t.g0;
-    cur += units;
-    return true;
-}
 
 // LDS-direct loads: lane i of the wave writes its 16 (4) bytes at LDS address m0 + 16 i (4 i).
 // `gbase` and `lds_addr` are wave-uniform.  Completion is tracked by vmcnt, in issue order.
@@ -835,11 +787,8 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
     // this workgroup's share of the linear strip order
-    const int per_xcd = pl.workers >> 3;
-    const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
-    int cur = (int)(total * share / pl.workers);
-    const int end = (int)(total * (share + 1) / pl.workers);
+    int cur, end;
+    worker_share(pl, blockIdx.x, cur, end);
 
     Tile t, next;
     if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
@@ -1129,11 +1078,8 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     extern __shared__ __align__(16) uint8_t smem[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
 
-    const int per_xcd = pl.workers >> 3;
-    const int share = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
-    int cur = (int)(total * share / pl.workers);
-    const int end = (int)(total * (share + 1) / pl.workers);
+    int cur, end;
+    worker_share(pl, blockIdx.x, cur, end);
 
     Tile t, next;
     if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
@@ -1248,22 +1194,6 @@ float* splitk_scratch(int dev, hipStream_t stream) {
     return static_cast<float*>(p);
 }
 
-// Column bands: with b bands an XCD's block spans 1/b of N and b/8 of M, so the bytes all XCDs
-// pull through their L2s are proportional to b M + (8 / b) N; take the b that minimises it.
-int choose_bands(int M, int N, int strips_n) {
-    int best = 1;
-    double best_cost = 1e300;
-    for (int b = 1; b <= 8; b *= 2) {
-        if (b > strips_n) break;
-        const double cost = (double)b * M + (8.0 / b) * N;
-        if (cost < best_cost) {
-            best_cost = cost;
-            best = b;
-        }
-    }
-    return best;
-}
-
 // A8: the activation codes are MXFP8 in the blocked 8-bit layout.  GLU: gated output (Y is M x N/2, N % 64 == 0).
 template <typename YT, bool A8, bool GLU>
 hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight* w, int M, YT* Y, int64_t ldy,
@@ -1285,26 +1215,15 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        TilePlan pl;
-        pl.pair = GLU ? 2 : 1;
-        pl.tiles_m = (M + kTile - 1) / kTile;
-        pl.strips_n = (N + kStrip * pl.pair - 1) / (kStrip * pl.pair);
-        pl.bands = choose_bands(M, N, pl.strips_n);
-        pl.workers = 8 * std::max(1, cus / 8);                // one persistent workgroup per compute unit
-        pl.ksplit = 1;
-        pl.groups = scale_groups(nb);
+        TilePlan pl = make_plan(M, N, nb, cus, GLU);
         float* parts = nullptr;
         int ksplit = 1, col_blocks = 0;
         size_t part_floats = 0;
         if constexpr (!GLU) {
-            // Fewer strips than half the workgroups (few rows, narrow N) and a long K: cut K into parts so
-            // that every compute unit has a tile.  A part keeps at least 12 K groups: below that the partial
-            // sums' round trip costs more than the idle compute units.
-            const int strips = pl.tiles_m * pl.strips_n;
+            // K parts for few-strip, long-K shapes (choose_ksplit), if the stream has partial-sum memory
             col_blocks = 2 * pl.strips_n;
             part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
-            ksplit = std::min({pl.workers / strips, pl.groups / 12, 8});
-            while (ksplit > 1 && ksplit * part_floats * sizeof(float) > kSplitScratchBytes) --ksplit;
+            ksplit = choose_ksplit(pl, part_floats * sizeof(float), kSplitScratchBytes);
             parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
         }
         if (parts) {
@@ -1404,6 +1323,29 @@ hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, 
     const int grid = (int)std::min<size_t>((total + 255) / 256, 8192);
     codes8_to_rowmajor<<<grid, 256, 0, stream>>>(blocked, rowmajor, rows, nb);
     return hipGetLastError();
+}
+
+int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_ksplit, int* out, int capacity) {
+    const int nb = K / 32;
+    TilePlan pl = make_plan(M, N, nb, compute_units, glu);
+    if (allow_ksplit && !glu) {
+        const size_t part_bytes = (size_t)pl.tiles_m * 8 * 2 * pl.strips_n * kPartialBlockFloats * sizeof(float);
+        pl.ksplit = choose_ksplit(pl, part_bytes, kSplitScratchBytes);
+    }
+    int n = 0;
+    for (int b = 0; b < pl.workers; ++b) {
+        int cur, end;
+        worker_share(pl, b, cur, end);
+        Tile t;
+        while (next_tile(pl, cur, end, t)) {
+            if (n < capacity) {
+                int* o = out + (size_t)n * 7;
+                o[0] = b; o[1] = t.m0; o[2] = t.n0; o[3] = t.nj; o[4] = t.part; o[5] = t.g0; o[6] = t.ng;
+            }
+            ++n;
+        }
+    }
+    return n;
 }
 
 bool gemm_glu_supported(const batq_weight* w, int M, bool a8) {

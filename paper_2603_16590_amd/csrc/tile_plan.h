@@ -1,0 +1,113 @@
+// Work split of the tiled GEMM kernels: which output tiles a persistent workgroup computes, in which order.
+// Shared by the kernels (device) and the launch code (host); the host can replay the whole schedule
+// (batq_debug_tile_schedule) so that it can be checked without a GPU.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace batq {
+
+constexpr int kTile = 256;                 // tile rows
+constexpr int kStrip = 64;                 // tile columns come in strips of 64
+
+struct TilePlan {
+    int tiles_m;      // row panels of 256
+    int strips_n;     // column strips of 64
+    int bands;        // column bands (1, 2, 4 or 8)
+    int workers;      // workgroups launched, a multiple of 8
+    int ksplit;       // parts the K groups are cut into (1: every tile runs over all of K)
+    int groups;       // K groups of 256 elements
+    int pair;         // 64-column strips per scheduling unit: 1, or 2 when tiles must be an even number of strips
+                      // wide (gated output; strips_n then counts units of 128 columns)
+};
+
+struct Tile {
+    int m0, n0, nj;
+    int part, g0, ng;   // K part, its first K group and its number of K groups
+};
+
+// Takes the next tile off the share [cur, end) of the linear order: K part by K part, inside a part the
+// strip order (column bands -> row panels -> strips).
+__host__ __device__ inline bool next_tile(const TilePlan& pl, int& cur, int end, Tile& t) {
+    if (cur >= end) return false;
+    int part = 0, at = cur, stop = end;
+    if (pl.ksplit > 1) {
+        const int per_part = pl.tiles_m * pl.strips_n;
+        part = cur / per_part;
+        at = cur - part * per_part;
+        stop = (end - part * per_part) < per_part ? (end - part * per_part) : per_part;      // a tile does not reach into the next K part
+    }
+    int b = 0;
+    while (b + 1 < pl.bands && at >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
+    const int bs = b * pl.strips_n / pl.bands, be = (b + 1) * pl.strips_n / pl.bands;
+    const int width = be - bs;
+    const int local = at - pl.tiles_m * bs;
+    const int p = local / width, sl = local - p * width;
+    const int run = (stop - at) < (width - sl) ? (stop - at) : (width - sl);           // units left in this row panel of the band
+    const int most = 4 / pl.pair;                         // units per tile at most (a tile is at most 4 strips wide)
+    const int nt = (run + most - 1) / most;               // tiles the run is cut into, near-equal widths
+    const int units = (run + nt - 1) / nt;
+    t.nj = units * pl.pair;
+    t.m0 = p * kTile;
+    t.n0 = (bs + sl) * kStrip * pl.pair;
+    t.part = part;
+    t.g0 = pl.groups * part / pl.ksplit;
+    t.ng = pl.groups * (part + 1) / pl.ksplit - t.g0;
+    cur += units;
+    return true;
+}
+
+// Column bands: with b bands an XCD's block spans 1/b of N and b/8 of M, so the bytes all XCDs
+// pull through their L2s are proportional to b M + (8 / b) N; take the b that minimises it.
+inline int choose_bands(int M, int N, int strips_n) {
+    int best = 1;
+    double best_cost = 1e300;
+    for (int b = 1; b <= 8; b *= 2) {
+        if (b > strips_n) break;
+        const double cost = (double)b * M + (8.0 / b) * N;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = b;
+        }
+    }
+    return best;
+}
+
+
+// The share of the linear order that workgroup `block` of `pl.workers` works on: workgroups go to the 8 XCDs
+// round-robin, so workgroup b takes share (b % 8) * (workers / 8) + b / 8 and the shares of one XCD are
+// contiguous.
+__host__ __device__ inline void worker_share(const TilePlan& pl, int block, int& cur, int& end) {
+    const int per_xcd = pl.workers >> 3;
+    const int share = (block & 7) * per_xcd + (block >> 3);
+    const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
+    cur = (int)(total * share / pl.workers);
+    end = (int)(total * (share + 1) / pl.workers);
+}
+
+// K parts wanted for a plan without them: fewer strips than half the workgroups (few rows, narrow N) and a
+// long K.  A part keeps at least 12 K groups: below that the partial sums' round trip costs more than the
+// idle compute units.  `part_bytes` = partial-sum bytes of one part, `scratch_bytes` = what is available.
+inline int choose_ksplit(const TilePlan& pl, size_t part_bytes, size_t scratch_bytes) {
+    const int strips = pl.tiles_m * pl.strips_n;
+    int ksplit = pl.workers / strips;
+    if (pl.groups / 12 < ksplit) ksplit = pl.groups / 12;
+    if (ksplit > 8) ksplit = 8;
+    while (ksplit > 1 && (size_t)ksplit * part_bytes > scratch_bytes) --ksplit;
+    return ksplit < 1 ? 1 : ksplit;
+}
+
+// Plan of a launch without K parts (ksplit = 1); `glu`: gated output, tiles an even number of strips wide.
+inline TilePlan make_plan(int M, int N, int nb, int cus, bool glu) {
+    TilePlan pl;
+    pl.pair = glu ? 2 : 1;
+    pl.tiles_m = (M + kTile - 1) / kTile;
+    pl.strips_n = (N + kStrip * pl.pair - 1) / (kStrip * pl.pair);
+    pl.bands = choose_bands(M, N, pl.strips_n);
+    pl.workers = 8 * (cus / 8 > 1 ? cus / 8 : 1);       // one persistent workgroup per compute unit
+    pl.ksplit = 1;
+    pl.groups = (nb + 7) / 8;
+    return pl;
+}
+
+}  // namespace batq

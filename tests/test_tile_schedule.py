@@ -1,0 +1,96 @@
+"""Host-side check of the tiled GEMM kernels' work split (no GPU): the library replays the schedule its
+persistent workgroups walk, and every (row panel, 64-column strip, K group) must be covered exactly once."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2603_16590_amd import binding
+    return binding.lib
+
+
+def _schedule(lib, M, N, K, cus, glu, ksplit):
+    n = lib.batq_debug_tile_schedule(M, N, K, cus, int(glu), int(ksplit), None, 0)
+    assert n > 0
+    buf = (C.c_int * (7 * n))()
+    assert lib.batq_debug_tile_schedule(M, N, K, cus, int(glu), int(ksplit), buf, n) == n
+    return np.frombuffer(buf, dtype=np.int32).reshape(n, 7).copy()
+
+
+def _check(lib, M, N, K, cus, glu, ksplit):
+    t = _schedule(lib, M, N, K, cus, glu, ksplit)
+    wg, m0, n0, nj, part, g0, ng = t.T
+    panels, groups = -(-M // 256), -(-K // 256)
+    unit = 128 if glu else 64
+    strips = -(-N // unit) * (unit // 64)
+    workers = 8 * max(1, cus // 8)
+    assert wg.min() >= 0 and wg.max() < workers
+    assert np.all(m0 % 256 == 0) and np.all(m0 < panels * 256)
+    assert np.all(n0 % unit == 0) and np.all((nj >= 1) & (nj <= 4)) and np.all(n0 // 64 + nj <= strips)
+    if glu:
+        assert np.all(nj % 2 == 0)
+    assert np.all(ng >= 1) and np.all(g0 >= 0) and np.all(g0 + ng <= groups)
+    cover = np.zeros((panels, strips, groups), dtype=np.int32)
+    for i in range(len(t)):
+        cover[m0[i] // 256, n0[i] // 64:n0[i] // 64 + nj[i], g0[i]:g0[i] + ng[i]] += 1
+    assert np.all(cover == 1), (M, N, K, cus, glu, ksplit, int(cover.min()), int(cover.max()))
+    nparts = part.max() + 1
+    if nparts > 1:
+        assert ksplit and not glu and nparts <= 8
+        assert np.all(ng >= 12)                                   # a part keeps at least 12 K groups
+        assert panels * (strips // (unit // 64)) * 2 <= workers   # only when at most half the workgroups had a strip
+        for p in range(nparts):                                   # same K range for every tile of a part
+            assert len(set(zip(g0[part == p], ng[part == p]))) == 1
+    # equal shares: strips x K groups per workgroup differ by at most one unit's worth
+    load = np.zeros(workers, dtype=np.int64)
+    np.add.at(load, wg, (nj // (unit // 64)).astype(np.int64))
+    assert load.max() - load.min() <= 1
+    return t
+
+
+def test_headline_shapes(lib):
+    # cfg2: 1792 strips over 256 workgroups = 7 each, as a 4-strip and a 3-strip tile
+    t = _check(lib, 2048, 14336, 4096, 256, False, True)
+    assert len(t) == 512 and sorted(set(t[:, 3])) == [3, 4] and t[:, 4].max() == 0
+    # cfg3: one 256 x 256 tile per workgroup
+    t = _check(lib, 4096, 4096, 14336, 256, False, True)
+    assert len(t) == 256 and np.all(t[:, 3] == 4) and np.all(t[:, 6] == 56)
+    # down projection at 256 rows: 64 strips, K cut into 4 parts of 14 groups
+    t = _check(lib, 256, 4096, 14336, 256, False, True)
+    assert t[:, 4].max() == 3 and np.all(t[:, 6] == 14) and len(t) == 256
+    t = _check(lib, 256, 4096, 14336, 256, False, False)
+    assert t[:, 4].max() == 0 and len(t) == 64
+    # gated gate/up GEMM of cfg2's block: tiles 2 or 4 strips wide
+    t = _check(lib, 2048, 28672, 4096, 256, True, True)
+    assert sorted(set(t[:, 3])) == [2, 4]
+
+
+def test_random_shapes(lib):
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        M = int(rng.integers(65, 5000))
+        N = int(rng.integers(1, 20000))
+        K = 32 * int(rng.integers(1, 700))
+        cus = int(rng.choice([8, 40, 64, 256, 304]))
+        glu = bool(rng.integers(0, 2))
+        if glu:
+            N = 64 * max(1, N // 64)
+        _check(lib, M, N, K, cus, glu, bool(rng.integers(0, 2)))
+    # few-strip, long-K corner: every split factor from 2 to 8
+    seen = set()
+    for N in (64, 128, 192, 640, 1024, 2048, 4096):
+        for K in (6144, 8192, 14336, 32768):
+            for M in (65, 256, 257, 700):
+                t = _check(lib, M, N, K, 256, False, True)
+                seen.add(int(t[:, 4].max()) + 1)
+    assert seen >= {1, 2, 4, 8}, seen
+
+
+def test_invalid_arguments(lib):
+    assert lib.batq_debug_tile_schedule(64, 128, 256, 256, 0, 0, None, 0) == -1     # M <= 64 takes the small-M kernel
+    assert lib.batq_debug_tile_schedule(100, 128, 100, 256, 0, 0, None, 0) == -1
+    assert lib.batq_debug_tile_schedule(100, 96, 256, 256, 1, 0, None, 0) == -1     # gated output needs N % 64 == 0
+    assert lib.batq_debug_tile_schedule(100, 128, 256, 256, 0, 0, None, 5) == -1
