@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
     ap.add_argument("--no-w4a8", action="store_true", help="skip the W4A8 side measurement")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape side measurement (cfg1)")
     ap.add_argument("--no-mlp", action="store_true", help="skip the MLP-block side measurement (gate/up, SwiGLU, down)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
                     "loop, streaming HBM kernels)")
@@ -112,7 +113,15 @@ def main():
             e1.synchronize()
             return e0.elapsed_time(e1) / n
 
-        ms_quant = timed(lambda i: quantize(t, Xs[i % nsets], codes[i % nsets], scales[i % nsets]), steps)
+        # the quantiser alone touches only X and the codes: rotate over enough sets of those that their footprint
+        # exceeds twice the 256 MB memory-side cache
+        nq = max(nsets, min(64, -(-(600 << 20) // (w.M * w.K * xbytes + wsz))))
+        for _ in range(nq - nsets):
+            Xs.append(X0.clone())
+            Ws.append(torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda"))
+        qcodes = [wk[:cb] for wk in Ws]
+        qscales = [wk[cb: wsz] for wk in Ws]
+        ms_quant = timed(lambda i: quantize(t, Xs[i % nq], qcodes[i % nq], qscales[i % nq]), steps)
         ms_gemm = timed(lambda i: gemm(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets]), steps)
         ms_quant_warm = timed(lambda i: quantize(t, Xs[0], codes[0], scales[0]), steps)
 
@@ -125,7 +134,7 @@ def main():
             "quant_ms": ms_quant, "quant_gbs": qbytes / ms_quant / 1e6,
             "quant_gbs_cache_warm": qbytes / ms_quant_warm / 1e6,
             "gemm_ms": ms_gemm, "gemm_tflops": flops / ms_gemm / 1e9,
-            "buffer_sets": nsets,
+            "buffer_sets": nsets, "quant_buffer_sets": nq,
         }
         return w, t, wh, res, flops, qbytes
 
@@ -224,6 +233,51 @@ def main():
         del w_gu, w_d, GU, Hh, Ym, ws1, ws2, Xm
         torch.cuda.empty_cache()
 
+    # Decode shape (cfg1: 16 tokens): the GEMM is one pass over the weight codes, so it is reported as a
+    # streaming rate over the weight's codes and scales, with 32 copies of the weight taking turns (285 MB, more
+    # than the memory-side cache).  The kernels take a few microseconds, less than a launch from Python, so
+    # they are timed as replays of a captured graph of 32 calls.
+    decode = None
+    if not args.no_decode:
+        w1 = bi.make_workload(1)
+        t1_ = B.Transform(w1.K, w1.G, w1.P, w1.clip)
+        Wd1 = to_dev(w1.W, w1.dtype)
+        whs = [B.batq_prepare_weight(t1_, Wd1) for _ in range(32)]
+        X1 = to_dev(w1.X, w1.dtype)
+        ws1_ = torch.empty(B.batq_linear_workspace(w1.M, w1.K), dtype=torch.uint8, device="cuda")
+        cb1 = B.batq_code_bytes(w1.M, w1.K)
+        Y1 = torch.empty((w1.M, w1.N), dtype=torch.bfloat16, device="cuda")
+        side = torch.cuda.Stream()
+
+        def graph_us(fn):
+            with torch.cuda.stream(side):
+                for i in range(32):
+                    fn(i)
+            side.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                for i in range(32):
+                    fn(i)
+            gr.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                gr.replay()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / (20 * 32) * 1e3
+
+        us_lin = graph_us(lambda i: B.batq_linear(t1_, whs[i], X1, Y=Y1, workspace=ws1_))
+        us_q = graph_us(lambda i: B.batq_quantize_act(t1_, X1, ws1_[:cb1], ws1_[cb1:]))
+        us_g = graph_us(lambda i: B.batq_gemm_mxfp4(ws1_[:cb1], ws1_[cb1:], whs[i], w1.M, Y=Y1))
+        wbytes = w1.K * w1.N * (0.5 + 1.0 / 32)
+        decode = {"workload": f"cfg1:{w1.name} M={w1.M} K={w1.K} N={w1.N}", "linear_us": us_lin, "quant_us": us_q,
+                  "gemm_us": us_g, "gemm_weight_stream_gbs": wbytes / us_g / 1e3,
+                  "note": "graph replays of 32 calls (launch gaps between dependent kernels included), 32 weight copies"}
+        del whs, Wd1
+        torch.cuda.empty_cache()
+
     ceilings = None
     tool = os.path.join(ROOT, "paper_2603_16590_amd", "batq_ceilings")
     if not args.no_ceilings and os.path.exists(tool):
@@ -287,6 +341,7 @@ def main():
         "also": also,
         "w4a8": w4a8,
         "mlp_block": mlp,
+        "decode": decode,
     }
     print(json.dumps(line))
 
