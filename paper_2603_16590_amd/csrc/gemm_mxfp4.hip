@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <map>
 #include <mutex>
+#include <type_traits>
 #include <utility>
 
 #include "batq_internal.h"
@@ -34,6 +35,8 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// element type of the K-split kernels' partial-sum array (selects the partial-sum epilogue)
+struct partial_f32 { float v; };
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <typename YT>
@@ -712,8 +715,8 @@ __device__ __forceinline__ void store_partial(v16f (&acc)[4][NJ], float* __restr
 
 // One output tile: on entry the loads of its first stages are in flight (issue_prologue); before
 // the epilogue the loads of the next tile's first stages are started, so they run underneath it.
-// With K parts (YT = float), Y is the partial-sum array in accumulator order (store_partial), `ldy` its number
-// of 32-column blocks and `part_stride` the floats of one part; else part_stride = 0.
+// YT = partial_f32 (K parts): Y is the partial-sum array in accumulator order (store_partial), `ldy` its number
+// of 32-column blocks and `part_stride` the floats of one part; for every other YT part_stride is unused.
 template <int NJ, typename YT, bool GLU>
 __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_next, const Tile& next,
                                          YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
@@ -764,14 +767,12 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     }
 
     // ---- epilogue: accumulators -> Y
-    if constexpr (sizeof(YT) == 4 && !GLU) {
-        if (part_stride != 0) {
-            store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
-            return;
-        }
+    if constexpr (std::is_same_v<YT, partial_f32>) {
+        store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
+    } else {
+        store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm,
+                                wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
     }
-    store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm, wn,
-                            t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
@@ -1059,14 +1060,12 @@ __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_ne
         c.issue_stage<2>(2);
         c.issue_stage<3>(3);
     }
-    if constexpr (sizeof(YT) == 4 && !GLU) {
-        if (part_stride != 0) {
-            store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
-            return;
-        }
+    if constexpr (std::is_same_v<YT, partial_f32>) {
+        store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
+    } else {
+        store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm,
+                                wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
     }
-    store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kA8EpilogueLds0 + wave * kEpilogueWaveLds, lane, wm,
-                            wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
 }
 
 // Requires operand code arrays below 2 GiB (32-bit load offsets) and gridDim.x == pl.workers.
@@ -1229,20 +1228,22 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         if (parts) {
             static bool attr_f32_set = false;
             if (!attr_f32_set) {
-                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<float, false>),
+                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<partial_f32, false>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
-                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<float, false>),
+                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<partial_f32, false>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
                 if (e != hipSuccess) return e;
                 attr_f32_set = true;
             }
             pl.ksplit = ksplit;
             if constexpr (A8)
-                gemm_tiled_a8<float, false><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
-                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
+                gemm_tiled_a8<partial_f32, false><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
+                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
+                    (int64_t)col_blocks, (int64_t)part_floats);
             else
-                gemm_tiled<float, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
-                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, parts, (int64_t)col_blocks, (int64_t)part_floats);
+                gemm_tiled<partial_f32, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
+                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
+                    (int64_t)col_blocks, (int64_t)part_floats);
             splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
                 parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
         } else if constexpr (A8) {
