@@ -259,18 +259,19 @@ constexpr int kQuantLdsT = 8 * kTsplitBlock;
 
 // LDS plan of the persistent workgroup (one per compute unit): transform operands of one K group, then per
 // wave one X slot and the staging area for the code pieces of a unit (two 1 KiB pieces for 4-bit codes,
-// four for 8-bit codes, which leaves room for 9 waves instead of 10), then the unit counter.  With a gated
-// input a wave's slot holds the unit of the gate and the unit of the up tensor (6 and 5 waves; the bytes
-// in flight per compute unit stay about the same).
+// four for 8-bit codes), then the unit counter.  8 waves: 64 KiB of X in flight per compute unit saturate the
+// stream, and more waves only lengthen the last round of units (10 waves measured 5 % slower on cfg2, 1 % on
+// cfg3 and cfg4).  With a gated input a wave's slot holds the unit of the gate and the unit of the up tensor
+// (6 and 5 waves, about the same bytes in flight).
 template <bool FP8, bool SWIGLU>
 struct QuantPlan {
-    static constexpr int kWaves = SWIGLU ? (FP8 ? 5 : 6) : (FP8 ? 9 : 10);
+    static constexpr int kWaves = SWIGLU ? (FP8 ? 5 : 6) : 8;
     static constexpr int kSlot = SWIGLU ? 2 * kXSlot : kXSlot;
     static constexpr int kCodeStage = FP8 ? 4096 : 2048;
     static constexpr int kLdsX = kQuantLdsT;
     static constexpr int kLdsStage = kLdsX + kWaves * kSlot;
     static constexpr int kLdsCounter = kLdsStage + kWaves * kCodeStage;
-    static constexpr int kLds = kLdsCounter + 16;           // 148 KiB / 156 KiB (gated: 156 KiB / 148 KiB)
+    static constexpr int kLds = kLdsCounter + 16;           // 128 KiB / 144 KiB (gated: 156 KiB / 148 KiB)
 };
 
 // Persistent kernel.  Work comes in units of (32-row tile, half K group = 4 MX blocks = 256 bytes per
