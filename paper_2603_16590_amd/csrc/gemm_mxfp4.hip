@@ -195,12 +195,15 @@ constexpr int kSkinnyWaves = 8;
 // RT = 32-row tiles of X handled together (1 or 2), sharing the weight loads; A8 = MXFP8 activations;
 // GLU = gated output: a workgroup owns 32 output columns = the 32 gate and the 32 up columns of one
 // 64-column group of the interleaved weight (sharing the loads of X), and stores silu(gate) * up to M x N/2.
-template <typename YT, int RT, bool A8, bool GLU>
+// WIDE (not with GLU): a workgroup owns 64 output columns instead of 32, which halves how often the X codes
+// are read; used when N is large enough that 64-column workgroups still fill the chip.
+template <typename YT, int RT, bool A8, bool GLU, bool WIDE>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
             const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy,
             float* __restrict__ partial) {
-    constexpr int NG = GLU ? 2 : 1;                         // 32-column groups of the weight per workgroup
+    static_assert(!(GLU && WIDE), "the gated kernel already takes two column groups");
+    constexpr int NG = (GLU || WIDE) ? 2 : 1;               // 32-column groups of the weight per workgroup
     __shared__ float part[kSkinnyWaves][16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n0 = blockIdx.x * 32 * NG;                    // first weight column
@@ -325,10 +328,13 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
                 const int col = blockIdx.x * 32 + (l & 31);
                 if (row < M && col < N / 2) store_y<YT>(Y + (size_t)row * ldy + col, swiglu_f32(v[0][h], v[1][h]));
             } else {
-                const int col = n0 + (l & 31);
-                if (row < M && col < N) {
-                    if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v[0][h];
-                    else store_y<YT>(Y + (size_t)row * ldy + col, v[0][h]);
+#pragma unroll
+                for (int c = 0; c < NG; ++c) {
+                    const int col = n0 + 32 * c + (l & 31);
+                    if (row < M && col < N) {
+                        if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v[c][h];
+                        else store_y<YT>(Y + (size_t)row * ldy + col, v[c][h]);
+                    }
                 }
             }
         }
@@ -1261,15 +1267,31 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        const int cols = (N + (GLU ? 63 : 31)) / (GLU ? 64 : 32);
-        int ksplit = (!GLU && 2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
+        // 64 columns per workgroup pay with two row tiles (the X codes are the larger share of a workgroup's
+        // loads then) when they make one full round of workgroups: between three quarters of and all the compute
+        // units (64 x 4096 x 14336: 15.4 -> 12.9 us; with one row tile, or a second partial round, it loses).  Not
+        // for the 8-bit kernel, which would not fit its registers.
+        const int cols64 = (N + 63) / 64;
+        const bool wide = !GLU && !A8 && M > 32 && cols64 <= cus && 4 * cols64 >= 3 * cus;
+        const int cols = (GLU || wide) ? (N + 63) / 64 : (N + 31) / 32;
+        int ksplit = (!GLU && !wide && 2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
         float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
         if (!parts || (size_t)ksplit * M * N * sizeof(float) > kSplitScratchBytes) ksplit = 1;
         const dim3 grid(cols, ksplit), block(kSkinnyWaves * 64);
-        if (M <= 32)
-            gemm_skinny<YT, 1, A8, GLU><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-        else
-            gemm_skinny<YT, 2, A8, GLU><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+        if constexpr (GLU) {
+            if (M <= 32)
+                gemm_skinny<YT, 1, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+            else
+                gemm_skinny<YT, 2, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+        } else if (wide) {
+            if constexpr (!A8)
+                gemm_skinny<YT, 2, false, false, true><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+        } else {
+            if (M <= 32)
+                gemm_skinny<YT, 1, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+            else
+                gemm_skinny<YT, 2, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
+        }
         if (ksplit > 1) {
             const int64_t total = (int64_t)M * N;
             splitk_reduce_rows<YT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(parts, ksplit, M, N, Y, ldy);

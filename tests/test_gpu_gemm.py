@@ -238,6 +238,13 @@ def test_linear_argument_errors(B):
     assert bool((Y == 0).all())
 
 
+@pytest.mark.parametrize("M,K,N", [(16, 256, 14336 + 40), (33, 512, 13000), (64, 96, 12288 + 17), (50, 2048, 16384)])
+def test_small_m_wide_n(B, M, K, N):
+    """33 to 64 rows and an N for which the small-M kernel gives a workgroup 64 columns (12288 <= N <= 16384 on
+    256 compute units): every element, ragged last column groups included; and its neighbours."""
+    test_tile_schedule_shapes(B, M, K, N)
+
+
 def test_weight_codes_of_two_gib(B):
     """Maximum sizes: a weight whose code array reaches 2 GiB cannot be addressed with the tiled kernel's 32-bit
     offsets; rows > 64 then take the direct kernel, rows <= 64 the small-M kernel with 64-bit addressing.

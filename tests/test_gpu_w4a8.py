@@ -190,7 +190,8 @@ def test_a8w4_gemm_random_codes(B, M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000),
-                                   (300, 8192 + 32, 200), (130, 12288, 320), (520, 16384, 136)])
+                                   (300, 8192 + 32, 200), (130, 12288, 320), (520, 16384, 136),
+                                   (20, 128, 12288 + 40), (50, 96, 12300)])
 def test_a8w4_tile_schedule_shapes(B, M, K, N):
     """Several tiles per persistent workgroup, every tile width, ragged edges, 4 to 20 K stages; every
     output element is checked (exponents kept within 4 binades so that the products sum exactly)."""
