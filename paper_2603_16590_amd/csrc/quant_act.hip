@@ -445,82 +445,133 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
             // fused row scaling (e.g. RMSNorm's 1/rms): this lane's row of the tile
             const float rs = row_scale ? row_scale[min((u >> 1) * 32 + l32, M - 1)] : 1.0f;
             uint32_t sc4[4] = {127u, 127u, 127u, 127u};    // padding blocks keep the neutral scale
+            // Quantisation of block bb of the unit in two steps, so that the four blocks of a unit can go through
+            // each step together (the cross-lane exchange in between has a long latency).
+            // Step 1: y = the transformed values (acc: element 16 kg + r of this lane's row, times the row
+            // factor); returns this lane's partial extrema (amax in `a`, or minimum and maximum in `a`, `b2`).
+            auto block_extrema = [&](const v16f& acc, float (&y)[16], float& a, float& b2) {
 #pragma unroll
-            for (int bb = 0; bb < 4; ++bb) {
+                for (int r = 0; r < 16; ++r) y[r] = acc[r];
+                if (row_scale) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) y[r] *= rs;
+                }
+                if constexpr (MINMAX) {
+                    a = y[0];
+                    b2 = y[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) {
+                        a = __builtin_fminf(a, y[r]);
+                        b2 = __builtin_fmaxf(b2, y[r]);
+                    }
+                } else {
+                    a = __builtin_fabsf(y[0]);
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) a = __builtin_fmaxf(a, __builtin_fabsf(y[r]));
+                    b2 = 0.f;
+                }
+            };
+            // the other half of the block lives in lane ^ 32
+            auto other_half = [&](float v) -> float {
+                return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, v)));
+            };
+            // Step 2: block extrema (own and the other half's) -> clip, scale, codes into the staging area;
+            // sc4[bb] = the block's scale byte.
+            auto block_finish = [&](int bb, float (&y)[16], float a, float b2, float oa, float ob) {
                 const int b = 4 * half + bb;                // block inside the K group
-                uint2 out = {0u, 0u}, out2 = {0u, 0u};      // padding blocks: zero codes
-                if (bb < nreal) {
-                    const uint4* tf = reinterpret_cast<const uint4*>(tlds + b * kTsplitBlock) + lane;
-                    uint4 tfr[6];
+                float bound;
+                if constexpr (MINMAX) {
+                    const float mn = __builtin_fminf(a, oa), mx = __builtin_fmaxf(b2, ob);
+                    const float lo = clip[k0 + b] * mn, hi = clip_max[k0 + b] * mx;
 #pragma unroll
-                    for (int i = 0; i < 6; ++i) tfr[i] = tf[i * 64];
-                    // one accumulation chain over 3 terms x 2 K halves, smallest terms first; other waves of the
-                    // SIMD fill the matrix pipe while this chain waits on itself
-                    v16f acc = {};
-#pragma unroll
-                    for (int t = 2; t >= 0; --t) {
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 0]),
-                                                                      __builtin_bit_cast(bf16x8, x[bb][0]), acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + 1]),
-                                                                      __builtin_bit_cast(bf16x8, x[bb][1]), acc, 0, 0, 0);
-                    }
-                    // y[r] = transformed element 16 kg + r of this lane's row
-                    float y[16];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) y[r] = acc[r];
-                    if (row_scale) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) y[r] *= rs;
-                    }
-                    float bound;
-                    if constexpr (MINMAX) {
-                        float mn = y[0], mx = y[0];
-#pragma unroll
-                        for (int r = 1; r < 16; ++r) {
-                            mn = __builtin_fminf(mn, y[r]);
-                            mx = __builtin_fmaxf(mx, y[r]);
-                        }
-                        // the other half of the block lives in lane ^ 32
-                        mn = __builtin_fminf(mn, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                                     (lane ^ 32) << 2, __builtin_bit_cast(int, mn))));
-                        mx = __builtin_fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                                     (lane ^ 32) << 2, __builtin_bit_cast(int, mx))));
-                        const float lo = clip[k0 + b] * mn, hi = clip_max[k0 + b] * mx;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) y[r] = clamp_lo_hi(y[r], lo, hi);
-                        // the largest magnitude left is that of the clamped minimum or of the clamped maximum
-                        bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)),
-                                                __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
-                    } else {
-                        float m = __builtin_fabsf(y[0]);
-#pragma unroll
-                        for (int r = 1; r < 16; ++r) m = __builtin_fmaxf(m, __builtin_fabsf(y[r]));
-                        // the other half of the block lives in lane ^ 32
-                        const float mo = __builtin_bit_cast(
-                            float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, m)));
-                        m = __builtin_fmaxf(m, mo);
-                        bound = clip[k0 + b] * m;           // one fp32 multiply
-                    }
-                    if constexpr (FP8) {
-                        const uint32_t s = e8m0_of_bound_fp8(bound);
-                        const float sc = scale_operand(s);
-                        out = encode8_fp8(y, bound, s, sc);
-                        out2 = encode8_fp8(y + 8, bound, s, sc);
-                        sc4[bb] = s;
-                    } else {
-                        const uint32_t s = e8m0_of_bound(bound);
-                        const float sc = scale_operand(s);
-                        out.x = encode8(y, bound, sc);
-                        out.y = encode8(y + 8, bound, sc);
-                        sc4[bb] = s;
-                    }
+                    for (int r = 0; r < 16; ++r) y[r] = clamp_lo_hi(y[r], lo, hi);
+                    // the largest magnitude left is that of the clamped minimum or of the clamped maximum
+                    bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)),
+                                            __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
+                } else {
+                    bound = clip[k0 + b] * __builtin_fmaxf(a, oa);      // one fp32 multiply
                 }
                 if constexpr (FP8) {
+                    const uint32_t sb = e8m0_of_bound_fp8(bound);
+                    const float sc = scale_operand(sb);
+                    const uint2 out = encode8_fp8(y, bound, sb, sc), out2 = encode8_fp8(y + 8, bound, sb, sc);
+                    sc4[bb] = sb;
                     // the lane's 16 codes are 16-byte slot 2 (bb % 2) + kg of its row in piece column bb / 2
                     *reinterpret_cast<uint4*>(my + (bb >> 1) * 2048 + st_row + (((2 * (bb & 1) + kg) ^ st_swz) << 4)) =
                         uint4{out.x, out.y, out2.x, out2.y};
                 } else {
+                    const uint32_t sb = e8m0_of_bound(bound);
+                    const float sc = scale_operand(sb);
+                    uint2 out;
+                    out.x = encode8(y, bound, sc);
+                    out.y = encode8(y + 8, bound, sc);
+                    sc4[bb] = sb;
                     *reinterpret_cast<uint2*>(my + st_row + 8 * kg + ((bb ^ st_swz) << 4)) = out;
+                }
+            };
+            auto quantise_block = [&](int bb, const v16f& acc) {
+                float y[16], a, b2;
+                block_extrema(acc, y, a, b2);
+                const float oa = other_half(a), ob = MINMAX ? other_half(b2) : 0.f;
+                block_finish(bb, y, a, b2, oa, ob);
+            };
+            auto zero_block = [&](int bb) {                 // padding block: zero codes
+                if constexpr (FP8)
+                    *reinterpret_cast<uint4*>(my + (bb >> 1) * 2048 + st_row + (((2 * (bb & 1) + kg) ^ st_swz) << 4)) =
+                        uint4{0u, 0u, 0u, 0u};
+                else
+                    *reinterpret_cast<uint2*>(my + st_row + 8 * kg + ((bb ^ st_swz) << 4)) = uint2{0u, 0u};
+            };
+            if (nreal == 4) {
+                // All four blocks at once: the 24 operand reads go out together, and the four accumulation
+                // chains (3 terms x 2 K halves each, smallest terms first) are interleaved, so that neither the
+                // LDS latency nor the latency of a matrix instruction's result is waited for block by block.
+                uint4 tfr[4][6];
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    const uint4* tf = reinterpret_cast<const uint4*>(tlds + (4 * half + bb) * kTsplitBlock) + lane;
+#pragma unroll
+                    for (int i = 0; i < 6; ++i) tfr[bb][i] = tf[i * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);          // all 24 reads are issued before the first product
+                v16f acc[4] = {};
+#pragma unroll
+                for (int t = 2; t >= 0; --t)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int bb = 0; bb < 4; ++bb)
+                            acc[bb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[bb][t * 2 + h]),
+                                                                          __builtin_bit_cast(bf16x8, x[bb][h]), acc[bb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                float y[4][16], a[4], b2[4], oa[4], ob[4];
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) block_extrema(acc[bb], y[bb], a[bb], b2[bb]);
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    oa[bb] = other_half(a[bb]);
+                    ob[bb] = MINMAX ? other_half(b2[bb]) : 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);          // the four exchanges are in flight together
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) block_finish(bb, y[bb], a[bb], b2[bb], oa[bb], ob[bb]);
+            } else {
+                // last, partly padded half group: block by block
+#pragma unroll
+                for (int bb = 0; bb < 4; ++bb) {
+                    if (bb < nreal) {
+                        const uint4* tf = reinterpret_cast<const uint4*>(tlds + (4 * half + bb) * kTsplitBlock) + lane;
+                        v16f acc = {};
+#pragma unroll
+                        for (int t = 2; t >= 0; --t)
+#pragma unroll
+                            for (int h = 0; h < 2; ++h)
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + h) * 64]),
+                                                                          __builtin_bit_cast(bf16x8, x[bb][h]), acc, 0, 0, 0);
+                        quantise_block(bb, acc);
+                    } else {
+                        zero_block(bb);
+                    }
                 }
             }
             pend_u = u;
