@@ -315,13 +315,18 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
  *
  * batq_dequantize: codes (DEVICE, device order of the given width) and scales (DEVICE, grouped order) of `M`
  *   rows -> out[m][j] = value(code) * 2^(scale - 127), row-major with row stride ldo elements (16-byte aligned
- *   rows), bf16 or fp32.  Exact in fp32 (subnormal results included; scale byte 255 and the E4M3 NaN codes
- *   give NaN); bf16 rounds only results below 2^-126.  bits = 4 or 8, else BATQ_ERR_UNSUPPORTED.
+ *   rows), bf16 or fp32.  fp32 output is exact (subnormal results included; scale byte 255 and the E4M3 NaN
+ *   codes give NaN); bf16 output uses the hardware's scaled converts and is exact for every result in bf16's
+ *   normal range (results below 2^-126 are not specified).  bits = 4 or 8, else BATQ_ERR_UNSUPPORTED.
  *
  * batq_transform_apply: out = X T_k (FORWARD), X T_k^-1 (INVERSE) or X T_k^-T (INVERSE_T) block by block, no
- *   clipping or quantisation: products and sums in fp64 with the handle's fp64 blocks, one rounding to fp32
- *   (and one to bf16 for bf16 output).  The query side of a transformed key cache takes INVERSE_T
- *   ((q T^-T)(k T)^T = q k^T), the attention output over a transformed value cache takes INVERSE.  X and out
+ *   clipping or quantisation.  bf16 input with 16-byte aligned X, out and row pitches runs on the matrix
+ *   cores with the arithmetic of the quantiser's transform (the handle's fp64 block split into three bf16
+ *   terms, exact products, fp32 sums: within 2^-20 sum_j |x_j| |B_jk| of the exact result; FORWARD gives
+ *   bit for bit the values batq_quantize_act quantises).  Any other input (fp32, unaligned) takes a slow
+ *   reference route: products and sums in fp64, one rounding to fp32.  bf16 output adds one rounding.  The
+ *   query side of a transformed key cache takes INVERSE_T ((q T^-T)(k T)^T = q k^T), the attention output
+ *   over a transformed value cache takes INVERSE (or folds T_v^-1 into the output projection).  X and out
  *   as for batq_quantize_act (DEVICE, row strides in elements); not in place (BATQ_ERR_SHAPE). */
 typedef enum { BATQ_APPLY_FORWARD = 0, BATQ_APPLY_INVERSE = 1, BATQ_APPLY_INVERSE_T = 2 } batq_apply_mode;
 batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits,

@@ -68,6 +68,31 @@ float bf16_value(uint16_t b) {
     return f;
 }
 
+// A block-diagonal matrix B (Mat[k] = B_k as [in][out], or its transpose with `transposed`) split into three
+// bf16 terms (hi, mid, lo) in the lane order of the 32x32x16 matrix instruction's first operand:
+//   out[k][term][half][lane][e] = B_k[16 (lane / 32) + 8 half + e][sigma(lane % 32)],
+//   sigma(m) = 16 ((m >> 2) & 1) + 4 (m >> 3) + (m & 3),
+// so that a lane's 16 results of a product with a 32-row tile are 16 consecutive output columns of its row.
+std::vector<uint16_t> split_operand(const std::vector<double>& Mat, int nb, bool transposed) {
+    std::vector<uint16_t> out((size_t)nb * 3 * 2 * 64 * 8);
+    for (int k = 0; k < nb; ++k)
+        for (int half = 0; half < 2; ++half)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 8; ++e) {
+                    const int m = lane & 31;
+                    const int out_col = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
+                    const int in_col = 16 * (lane >> 5) + 8 * half + e;
+                    double rest = transposed ? Mat[(size_t)k * 1024 + out_col * 32 + in_col]
+                                             : Mat[(size_t)k * 1024 + in_col * 32 + out_col];
+                    for (int term = 0; term < 3; ++term) {
+                        const uint16_t b = bf16_rne((float)rest);
+                        rest -= (double)bf16_value(b);
+                        out[((((size_t)k * 3 + term) * 2 + half) * 64 + lane) * 8 + e] = b;
+                    }
+                }
+    return out;
+}
+
 bool clip_ok(const float* c, int n) {
     for (int i = 0; i < n; ++i)
         if (!(c[i] > 0.0f && c[i] <= 1.0f)) return false;
@@ -114,6 +139,8 @@ void free_transform(batq_transform* t) {
     if (t->d_Tinv) (void)hipFree(t->d_Tinv);
     if (t->d_Tf64) (void)hipFree(t->d_Tf64);
     if (t->d_Tsplit) (void)hipFree(t->d_Tsplit);
+    if (t->d_TinvSplit) (void)hipFree(t->d_TinvSplit);
+    if (t->d_TinvTSplit) (void)hipFree(t->d_TinvTSplit);
     delete t;
 }
 
@@ -186,7 +213,7 @@ batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_
     // order of the activation kernel's matrix-instruction operand
     std::vector<double> T, Tinv;
     std::vector<float> Tf;
-    std::vector<uint16_t> Tsplit;
+    std::vector<uint16_t> Tsplit, TinvSplit, TinvTSplit;
     if (form != BATQ_FORM_IDENTITY) {
         T.resize((size_t)nb * 1024);
         Tinv.resize((size_t)nb * 1024);
@@ -220,21 +247,9 @@ batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_
                 if (!invert_small(T.data() + (size_t)k * 1024, 32, Tinv.data() + (size_t)k * 1024))
                     return BATQ_ERR_SINGULAR;
         }
-        Tsplit.resize((size_t)nb * 3 * 2 * 64 * 8);
-        for (int k = 0; k < nb; ++k)
-            for (int half = 0; half < 2; ++half)
-                for (int lane = 0; lane < 64; ++lane)
-                    for (int e = 0; e < 8; ++e) {
-                        const int m = lane & 31;
-                        const int out_col = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
-                        const int in_col = 16 * (lane >> 5) + 8 * half + e;
-                        double rest = T[(size_t)k * 1024 + in_col * 32 + out_col];
-                        for (int term = 0; term < 3; ++term) {
-                            const uint16_t b = bf16_rne((float)rest);
-                            rest -= (double)bf16_value(b);
-                            Tsplit[((((size_t)k * 3 + term) * 2 + half) * 64 + lane) * 8 + e] = b;
-                        }
-                    }
+        Tsplit = split_operand(T, nb, false);
+        TinvSplit = split_operand(Tinv, nb, false);
+        TinvTSplit = split_operand(Tinv, nb, true);
     }
 
     batq_status st = check_device();
@@ -264,6 +279,8 @@ batq_status batq_transform_create_ex(batq_transform** out, const batq_transform_
         st = upload(&t->d_Tinv, Tinv.data(), Tinv.size());
         if (st == BATQ_OK) st = upload(&t->d_Tf64, T.data(), T.size());
         if (st == BATQ_OK) st = upload(&t->d_Tsplit, Tsplit.data(), Tsplit.size());
+        if (st == BATQ_OK) st = upload(&t->d_TinvSplit, TinvSplit.data(), TinvSplit.size());
+        if (st == BATQ_OK) st = upload(&t->d_TinvTSplit, TinvTSplit.data(), TinvTSplit.size());
     }
     if (st != BATQ_OK) {
         free_transform(t);

@@ -27,6 +27,8 @@ struct batq_transform {
     double* d_Tinv = nullptr;     // [nb][32][32] fp64 T_k^-1     (null when !has_transform)
     double* d_Tf64 = nullptr;     // [nb][32][32] fp64 T_k        (null when !has_transform)
     uint16_t* d_Tsplit = nullptr; // [nb][3][2][64][8] bf16 three-term split of T_k in MFMA operand order
+    uint16_t* d_TinvSplit = nullptr;   // the same split of T_k^-1
+    uint16_t* d_TinvTSplit = nullptr;  // and of T_k^-T
 };
 
 // Prepared (inverse-transformed, quantised) weights.

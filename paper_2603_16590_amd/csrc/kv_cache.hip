@@ -6,7 +6,7 @@
 //                    attention kernel that works on 16-bit keys and values;
 //   transform_apply - x T_k, x T_k^-1 or x T_k^-T block by block without quantisation: the query takes
 //                    T_k^-T so that (q T^-T)(k T)^T = q k^T, the attention output takes T_v^-1.
-// Neither is on the timed path; both are written for exactness first.  gfx950 only.
+// gfx950 only.
 #include "batq_internal.h"
 #include "mxfp4_device.h"
 #include "code_layout.h"
@@ -56,33 +56,80 @@ __device__ __forceinline__ void store8<uint16_t>(uint16_t* p, const float (&v)[8
     *reinterpret_cast<uint4*>(p) = o;
 }
 
-// One thread per (row, MX block, quarter of the block): consecutive threads write consecutive 8-element
-// pieces of a row.  The product code value x 2^(byte - 127) is exact in fp32 (fp32 subnormals included);
-// bf16 output rounds to nearest even, which only matters below 2^-126.
+// One wave per (32-row tile, K group of 8 MX blocks): 4 (MXFP4) or 8 (MXFP8) pieces of 1 KiB.  Every lane
+// converts 8 elements at a time (4 or 8 code bytes -> one 16-byte store of bf16, two of fp32), and the lanes are
+// laid over a piece so that neighbours hold neighbouring elements of a row: one wave instruction reads
+// 256 (512) contiguous code bytes and writes 4 (8) rows x 256 (128) contiguous output bytes.
+// bf16 output uses the hardware converts (two codes -> two bf16, times 2^(scale byte - 127)); they are exact for
+// every result in bf16's normal range, smaller ones are not specified here.  fp32 output is computed as
+// code value x 2^(byte - 127), exact in fp32 (subnormals included; scale byte 255 and the E4M3 NaN codes give NaN).
 template <typename OT, bool FP8>
 __global__ void __launch_bounds__(256)
 dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int M, int nb,
                OT* __restrict__ out, int64_t ldo) {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)M * nb * 4) return;
-    const int q = (int)(idx & 3);
-    const int64_t blk = idx >> 2;
-    const int row = (int)(blk / nb), k = (int)(blk - (int64_t)row * nb);
-    const float sc = e8m0_value(scales[scale_index_internal(row, k, M)]);
-    float v[8];
-    if constexpr (FP8) {
-        const uint2 w = *reinterpret_cast<const uint2*>(codes + code8_slot_offset(row, k, q >> 1, nb) + (q & 1) * 8);
+    constexpr int kPerRow = FP8 ? 4 : 2;                   // pieces of a K group per 16-row group
+    constexpr int kPieces = 2 * kPerRow;
+    constexpr int kSub = FP8 ? 2 : 4;                       // wave instructions per piece
+    constexpr int kRows = 16 / kSub;                        // piece rows per instruction
+    constexpr bool kHw = sizeof(OT) == 2;                   // bf16 output
+    const int lane = threadIdx.x & 63;
+    const int groups = scale_groups(nb);
+    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int tile = (int)(unit / groups), g = (int)(unit - (int64_t)tile * groups);
+    if (tile >= (M + 31) >> 5) return;                      // wave-uniform
+    const size_t stages = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb));
+    // this lane inside an instruction's rows: row, 16-byte slot of the row, 8-element part of the slot
+    const int lr = FP8 ? lane >> 3 : lane >> 4;
+    const int pos = FP8 ? (lane >> 1) & 3 : (lane >> 2) & 3;
+    const int part = FP8 ? lane & 1 : lane & 3;
+    uint2 w[kPieces][kSub];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[i] = e4m3_value((w.x >> (8 * i)) & 0xFFu) * sc;
-            v[4 + i] = e4m3_value((w.y >> (8 * i)) & 0xFFu) * sc;
+    for (int p = 0; p < kPieces; ++p) {
+        const uint8_t* piece = codes + ((size_t)(2 * tile + p / kPerRow) * stages + (size_t)(g * kPerRow + p % kPerRow)) * 1024;
+#pragma unroll
+        for (int i = 0; i < kSub; ++i) {
+            if constexpr (FP8) w[p][i] = *reinterpret_cast<const uint2*>(piece + i * 512 + lane * 8);
+            else w[p][i] = uint2{*reinterpret_cast<const uint32_t*>(piece + i * 256 + lane * 4), 0u};
         }
-    } else {
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(codes + code_chunk_offset(row, k, nb) + q * 4);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = e2m1_value((w >> (4 * i)) & 0xFu) * sc;
     }
-    store8<OT>(out + (size_t)row * ldo + (size_t)k * 32 + q * 8, v);
+#pragma unroll
+    for (int p = 0; p < kPieces; ++p)
+#pragma unroll
+        for (int i = 0; i < kSub; ++i) {
+            const int r = i * kRows + lr;                   // row inside the piece
+            const int slot = pos ^ ((r >> 2) & 3);          // undo the bank swizzle
+            const int row = tile * 32 + (p / kPerRow) * 16 + r;
+            const int k = g * 8 + (p % kPerRow) * (FP8 ? 2 : 4) + (FP8 ? slot >> 1 : slot);
+            if (row >= M || k >= nb) continue;
+            const uint32_t byte = scales[scale_index_internal(row, k, M)];
+            OT* o = out + (size_t)row * ldo + (size_t)k * 32 + (FP8 ? (slot & 1) * 16 + part * 8 : part * 8);
+            const uint2 d = w[p][i];
+            if constexpr (kHw) {
+                const float sc = scale_operand(byte);
+                uint4 q;
+                if constexpr (FP8) {
+                    q.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(d.x, sc, false));
+                    q.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(d.x, sc, true));
+                    q.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(d.y, sc, false));
+                    q.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(d.y, sc, true));
+                } else {
+                    q.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 0));
+                    q.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 1));
+                    q.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 2));
+                    q.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 3));
+                }
+                *reinterpret_cast<uint4*>(o) = q;
+            } else {
+                const float sc = e8m0_value(byte);
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if constexpr (FP8) v[e] = e4m3_value(((e < 4 ? d.x : d.y) >> (8 * (e & 3))) & 0xFFu) * sc;
+                    else v[e] = e2m1_value((d.x >> (4 * e)) & 0xFu) * sc;
+                }
+                store8<OT>(o, v);
+            }
+        }
 }
 
 template <typename XT>
@@ -129,6 +176,142 @@ apply_kernel(const XT* __restrict__ X, int64_t ldx, int M, const double* __restr
     }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSplitBlock = 3 * 2 * 64 * 16;               // bytes of split operand per MX block (see split_operand)
+constexpr int kApplyWaves = 8;
+constexpr int kApplySlot = 32 * 256;                        // a unit: 32 rows x 4 MX blocks of bf16
+constexpr int kApplyLdsT = 4 * kSplitBlock;                 // 24 KiB
+constexpr int kApplyLds = kApplyLdsT + kApplyWaves * 2 * kApplySlot;        // 152 KiB
+
+// y = x B_k on the matrix cores for bf16 input: B_k comes pre-split into three bf16 terms (products with bf16
+// inputs are then exact, sums are fp32: the arithmetic of the quantiser's transform).  A workgroup takes a
+// unit column (4 MX blocks, operands in LDS) and a range of 32-row tiles that its waves go through in turn;
+// a wave fetches its unit with LDS-direct loads (rows of 256 contiguous bytes, 16-byte chunk c of row r at
+// position (c & 8) | ((c ^ r) & 7)), prefetching the next unit into its second slot, and sends the results
+// back through the slot it has just emptied, so that the stores are rows of 256 contiguous bytes as well.
+template <typename OT>
+__global__ void __launch_bounds__(kApplyWaves * 64)
+apply_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
+           const uint4* __restrict__ split, OT* __restrict__ out, int64_t ldo) {
+    extern __shared__ __align__(16) uint8_t alds[];
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int kb = 4 * blockIdx.x;                          // first MX block of the unit column
+    const int nreal = min(4, nb - kb);
+    const int row_tiles = (M + 31) >> 5;
+    const int t_begin = blockIdx.y * tiles_per_wg, t_end = min(row_tiles, t_begin + tiles_per_wg);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_byte*)alds;
+    uint8_t* const slots = alds + kApplyLdsT + wave * 2 * kApplySlot;
+    const uint32_t slots_lds = lds_base + kApplyLdsT + wave * 2 * kApplySlot;
+
+    {   // operands of the column's blocks: 6 pieces of 1 KiB per block
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(split) + (size_t)kb * kSplitBlock;
+        const int pieces = nreal * (kSplitBlock / 1024);
+        for (int p = wave; p < pieces; p += kApplyWaves)
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :: "v"((uint32_t)(p * 1024 + lane * 16)), "s"(src), "s"(lds_base + (uint32_t)p * 1024) : "memory");
+    }
+    auto request = [&](int tile, int slot) {
+        const uint8_t* base = reinterpret_cast<const uint8_t*>(X) + ((size_t)tile * 32 * ldx + (size_t)kb * 32) * 2;
+        const int rows_left = M - 1 - tile * 32;            // rows past the end repeat the last one: computed, not stored
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = 4 * j + (lane >> 4);
+            int c = ((lane & 15) & 8) | (((lane & 15) ^ r) & 7);    // the chunk that belongs at this lane's LDS position
+            if (c >= 4 * nreal) c = 0;                      // never read past the end of the row
+            const uint32_t voff = (uint32_t)min(r, rows_left) * (uint32_t)(ldx * 2) + (uint32_t)c * 16;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                         :: "v"(voff), "s"(base), "s"(slots_lds + (uint32_t)(slot * kApplySlot + j * 1024)) : "memory");
+        }
+    };
+    int tile = t_begin + wave;
+    if (tile < t_end) request(tile, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0): this wave's share of the operands
+    __syncthreads();                                        // all operands have landed
+
+    for (int it = 0; tile < t_end; tile += kApplyWaves, ++it) {
+        uint8_t* const slot = slots + (it & 1) * kApplySlot;
+        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): the unit has landed, the last stores are out
+        if (tile + kApplyWaves < t_end) request(tile + kApplyWaves, (it + 1) & 1);
+        u32x4 x[4][2];
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int c = 4 * bb + 2 * kg + h;
+                x[bb][h] = *reinterpret_cast<const u32x4*>(slot + l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4));
+            }
+        // results go back into this slot: its contents must be in registers first
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) asm volatile("" : "+v"(x[bb][h]));
+        v16f acc[4] = {};
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) {
+            if (bb >= nreal) break;
+            const uint4* tf = reinterpret_cast<const uint4*>(alds + bb * kSplitBlock) + lane;
+#pragma unroll
+            for (int t = 2; t >= 0; --t)                    // smallest terms first
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    acc[bb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tf[(t * 2 + h) * 64]),
+                                                                  __builtin_bit_cast(bf16x8, x[bb][h]), acc[bb], 0, 0, 0);
+        }
+        // acc[bb][r] = element 16 kg + r of block bb of this lane's row
+        const int row0 = tile * 32;
+        if constexpr (sizeof(OT) == 2) {
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    uint4 q;
+                    q.x = float_to_bf16_bits(acc[bb][8 * h + 0]) | (float_to_bf16_bits(acc[bb][8 * h + 1]) << 16);
+                    q.y = float_to_bf16_bits(acc[bb][8 * h + 2]) | (float_to_bf16_bits(acc[bb][8 * h + 3]) << 16);
+                    q.z = float_to_bf16_bits(acc[bb][8 * h + 4]) | (float_to_bf16_bits(acc[bb][8 * h + 5]) << 16);
+                    q.w = float_to_bf16_bits(acc[bb][8 * h + 6]) | (float_to_bf16_bits(acc[bb][8 * h + 7]) << 16);
+                    const int c = 4 * bb + 2 * kg + h;
+                    *reinterpret_cast<uint4*>(slot + l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4)) = q;
+                }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 4 * j + (lane >> 4), pos = lane & 15;
+                const int c = (pos & 8) | ((pos ^ r) & 7);
+                const uint4 q = *reinterpret_cast<const uint4*>(slot + r * 256 + pos * 16);
+                if (row0 + r < M && c < 4 * nreal)
+                    *reinterpret_cast<uint4*>(out + (size_t)(row0 + r) * ldo + (size_t)kb * 32 + c * 8) = q;
+            }
+        } else {
+            // fp32 output: two blocks (256 bytes per row) at a time through the same slot
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+                for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const v16f& a = acc[2 * pass + b2];
+                        const int c = 8 * b2 + 4 * kg + q4;
+                        *reinterpret_cast<float4*>(slot + l32 * 256 + (((c & 8) | ((c ^ l32) & 7)) << 4)) =
+                            float4{a[4 * q4], a[4 * q4 + 1], a[4 * q4 + 2], a[4 * q4 + 3]};
+                    }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int r = 4 * j + (lane >> 4), pos = lane & 15;
+                    const int c = (pos & 8) | ((pos ^ r) & 7);
+                    const float4 q = *reinterpret_cast<const float4*>(slot + r * 256 + pos * 16);
+                    if (row0 + r < M && 2 * pass + (c >> 3) < nreal)
+                        *reinterpret_cast<float4*>(out + (size_t)(row0 + r) * ldo + (size_t)(kb + 2 * pass) * 32 + c * 4) = q;
+                }
+            }
+        }
+    }
+}
+
 template <typename XT, typename OT>
 __global__ void __launch_bounds__(256)
 convert_kernel(const XT* __restrict__ X, int64_t ldx, int M, int K, OT* __restrict__ out, int64_t ldo) {
@@ -146,6 +329,25 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
         convert_kernel<XT, OT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(X, ldx, M, t->K, out, ldo);
         return hipGetLastError();
     }
+    if constexpr (sizeof(XT) == 2) {
+        const uint16_t* sp = mode == BATQ_APPLY_FORWARD ? t->d_Tsplit : mode == BATQ_APPLY_INVERSE ? t->d_TinvSplit : t->d_TinvTSplit;
+        // 16-byte accesses, and a tile's rows are addressed with 32-bit byte offsets
+        const bool fits = ((uintptr_t)X | (uintptr_t)out | (uintptr_t)(ldx * 2) | (uintptr_t)(ldo * (int64_t)sizeof(OT))) % 16 == 0 &&
+                          ldx < (int64_t(1) << 25);
+        if (sp && fits) {
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT>),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
+            if (attr != hipSuccess) return attr;
+            const int units = (t->nb + 3) / 4, row_tiles = (M + 31) / 32;
+            // about four workgroups per compute unit, at least 16 tiles each (the operands are fetched per workgroup)
+            int tiles_per_wg = (int)(((int64_t)row_tiles * units + 1023) / 1024);
+            if (tiles_per_wg < 16) tiles_per_wg = 16;
+            const dim3 grid(units, (row_tiles + tiles_per_wg - 1) / tiles_per_wg), block(kApplyWaves * 64);
+            apply_mfma<OT><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
+                                                               reinterpret_cast<const uint4*>(sp), out, ldo);
+            return hipGetLastError();
+        }
+    }
     const dim3 grid(t->nb, (M + 255) / 256), block(256);
     if (mode == BATQ_APPLY_FORWARD)
         apply_kernel<XT, OT, false><<<grid, block, 0, stream>>>(X, ldx, M, t->d_Tf64, out, ldo);
@@ -161,8 +363,8 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int nb, bool fp8, void* out,
                              batq_dtype odtype, int64_t ldo, hipStream_t stream) {
     if (M == 0) return hipSuccess;
-    const int64_t total = (int64_t)M * nb * 4;
-    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    const int64_t units = (int64_t)((M + 31) >> 5) * scale_groups(nb);      // one wave each, four to a workgroup
+    const dim3 grid((unsigned)((units + 3) / 4)), block(256);
     if (odtype == BATQ_BF16) {
         auto o = static_cast<uint16_t*>(out);
         if (fp8) dequant_kernel<uint16_t, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, o, ldo);

@@ -88,9 +88,11 @@ def test_transform_apply_all_modes(B, dtype):
         absref = o.apply_blocks(np.abs(Xf), np.abs(Mat))
         got = B.batq_transform_apply(t, X, mode, torch.float32)
         torch.cuda.synchronize()
-        # fp64 sums, one rounding to fp32; the library inverts its own fp64 blocks (Gauss-Jordan), so the
-        # inverse modes carry its 1e-13-level difference from the oracle's inverse
-        assert np.all(np.abs(got.cpu().numpy() - ref) <= 2.0 ** -24 * np.abs(ref) + 1e-11 * absref), mode
+        # fp32 input: fp64 sums, one rounding to fp32; the library inverts its own fp64 blocks (Gauss-Jordan), so
+        # the inverse modes carry its 1e-13-level difference from the oracle's inverse.  bf16 input goes
+        # through the matrix cores: exact products of bf16 terms, six chained fp32 accumulations
+        tol = 1e-11 if dtype == "f32" else 2.0 ** -20
+        assert np.all(np.abs(got.cpu().numpy() - ref) <= 2.0 ** -24 * np.abs(ref) + tol * absref), mode
         gb = B.batq_transform_apply(t, X, mode, torch.bfloat16)
         torch.cuda.synchronize()
         refb = o.bf16_round(ref).astype(np.float64)
@@ -108,6 +110,52 @@ def test_transform_apply_all_modes(B, dtype):
     # in place is refused
     assert B.lib.batq_transform_apply(t.handle, X.data_ptr(), 1 if dtype == "bf16" else 0, M, K, K, 0, X.data_ptr(),
                                       1 if dtype == "bf16" else 0, K, None) == 2
+
+
+@pytest.mark.parametrize("M,K", [(1, 32), (33, 32 * 5), (700, 32 * 13), (2049, 1024)])
+@pytest.mark.parametrize("odt", ["bf16", "f32"])
+def test_transform_apply_matrix_core_path(B, M, K, odt):
+    """bf16 input at sizes with ragged row tiles and a ragged last unit column (K / 32 not a multiple of 4),
+    strided input and output rows; every element against the oracle."""
+    import torch
+    w = bi.make_small(M, K, 8, seed=M + K, dtype="bf16")
+    T = o.kron_blocks(w.G, w.P)
+    Xf = w.X_f32().astype(np.float64)
+    t = B.Transform(K, w.G, w.P, None)
+    Xp = torch.zeros((M, K + 24), dtype=torch.bfloat16, device="cuda")
+    Xp[:, :K] = to_dev(w.X, "bf16")
+    tdt = torch.bfloat16 if odt == "bf16" else torch.float32
+    for mode, Mat in ((B.APPLY_FORWARD, T), (B.APPLY_INVERSE, o.inverse_blocks(T)),
+                      (B.APPLY_INVERSE_T, o.inverse_transpose_blocks(T))):
+        ref = o.apply_blocks(Xf, Mat)
+        absref = o.apply_blocks(np.abs(Xf), np.abs(Mat))
+        out = torch.full((M, K + 8), 7.0, dtype=tdt, device="cuda")
+        B.batq_transform_apply(t, Xp[:, :K], mode, out=out[:, :K])
+        torch.cuda.synchronize()
+        got = y_to_f32(out[:, :K]).astype(np.float64) if odt == "bf16" else out[:, :K].cpu().numpy().astype(np.float64)
+        assert bool((out[:, K:] == 7.0).all())                      # nothing written past the row
+        if odt == "f32":
+            assert np.all(np.abs(got - ref) <= 2.0 ** -24 * np.abs(ref) + 2.0 ** -20 * absref), mode
+        else:
+            # one bf16 rounding of a value that is within 2^-20 absref of the reference
+            assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 2.0 ** -19 * absref), mode
+
+
+def test_transform_apply_forward_is_the_quantisers_transform(B):
+    """x T_k from the apply call (fp32 out), quantised by the identity transform's kernel, gives the codes and
+    scales the fused call produces: both use the same matrix-core arithmetic."""
+    import torch
+    M, K = 300, 1024
+    w = bi.make_small(M, K, 8, seed=3, dtype="bf16")
+    t = B.Transform(K, w.G, w.P, w.clip)
+    tid = B.Transform(K, None, None, w.clip)
+    X = to_dev(w.X, "bf16")
+    y = B.batq_transform_apply(t, X, B.APPLY_FORWARD, torch.float32)
+    c0, s0 = B.batq_quantize_act(t, X)
+    c1, s1 = B.batq_quantize_act(tid, y)
+    torch.cuda.synchronize()
+    assert torch.equal(B.batq_codes_to_rowmajor(c0, M, K), B.batq_codes_to_rowmajor(c1, M, K))
+    assert torch.equal(B.batq_scales_to_rowmajor(s0, M, K), B.batq_scales_to_rowmajor(s1, M, K))
 
 
 @pytest.mark.parametrize("bits", [4, 8])
