@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
     ap.add_argument("--no-w4a8", action="store_true", help="skip the W4A8 side measurement")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape side measurement (cfg1)")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="skip the two-stream side measurement (its overlapping kernels distort a kernel trace)")
+    ap.add_argument("--no-kv", action="store_true", help="skip the key/value-cache side measurement")
     ap.add_argument("--no-mlp", action="store_true", help="skip the MLP-block side measurement (gate/up, SwiGLU, down)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
                     "loop, streaming HBM kernels)")
@@ -102,17 +105,19 @@ def main():
 
         # the same steps handed to two streams in turn (independent batches, as a server with more than one
         # request in flight would): the tail of one step's GEMM overlaps with the head of the next step
-        two = [torch.cuda.Stream(), torch.cuda.Stream()]
-        for i in range(warmup):
-            with torch.cuda.stream(two[i & 1]):
-                step(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            with torch.cuda.stream(two[i & 1]):
-                step(i)
-        torch.cuda.synchronize()
-        ms_step_two = (time.perf_counter() - t0) * 1e3 / steps
+        ms_step_two = None
+        if not args.no_two_streams:
+            two = [torch.cuda.Stream(), torch.cuda.Stream()]
+            for i in range(warmup):
+                with torch.cuda.stream(two[i & 1]):
+                    step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                with torch.cuda.stream(two[i & 1]):
+                    step(i)
+            torch.cuda.synchronize()
+            ms_step_two = (time.perf_counter() - t0) * 1e3 / steps
 
         # per-kernel durations: HIP events on the stream the kernels are launched on
         def timed(fn, n):
@@ -145,7 +150,8 @@ def main():
             "workload": f"cfg{cfg}:{w.name} M={w.M} K={w.K} N={w.N} x={w.dtype} y={w.out_dtype}",
             "ms_per_step": ms_step,
             "linear_tflops": flops / ms_step / 1e9,
-            "ms_per_step_two_streams": ms_step_two, "linear_tflops_two_streams": flops / ms_step_two / 1e9,
+            "ms_per_step_two_streams": ms_step_two,
+            "linear_tflops_two_streams": flops / ms_step_two / 1e9 if ms_step_two else None,
             "quant_ms": ms_quant, "quant_gbs": qbytes / ms_quant / 1e6,
             "quant_gbs_cache_warm": qbytes / ms_quant_warm / 1e6,
             "gemm_ms": ms_gemm, "gemm_tflops": flops / ms_gemm / 1e9,
@@ -293,6 +299,61 @@ def main():
         del whs, Wd1
         torch.cuda.empty_cache()
 
+    # Key/value-cache helpers (Sec. 3.2): a cache of 32768 tokens x 8 heads x 128 channels written by the
+    # quantiser (KV4 and KV8) and read back as bf16, and the query-side transform at the headline token count.
+    # Rates are algorithmic bytes (input + output of the call) over the time per call, 20 calls back to back
+    # (sizes at which a kernel outlasts the issue of the next call from Python).
+    kv = None
+    if not args.no_kv:
+        Mk, Kk, Mq, Kq = 32768, 1024, 8192, 4096
+        rk = np.random.default_rng(77)
+        Gk, Pk, ck = bi.make_factors(Kk // 32, rk, rk, rk, 0.7)
+        Gq, Pq, _ = bi.make_factors(Kq // 32, rk, rk, rk, 0.7)
+        tk, tq = B.Transform(Kk, Gk, Pk, ck), B.Transform(Kq, Gq, Pq, None)
+        Xk = torch.randn((Mk, Kk), device="cuda").to(torch.bfloat16)
+        Xq = torch.randn((Mq, Kq), device="cuda").to(torch.bfloat16)
+        Ok = torch.empty_like(Xk)
+        Oq = torch.empty_like(Xq)
+
+        def per_call_us(fn, n=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            best = None
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(n):
+                    fn()
+                e1.record()
+                e1.synchronize()
+                us = e0.elapsed_time(e1) / n * 1e3
+                best = us if best is None else min(best, us)
+            return best
+
+        kv = {"cache": f"{Mk} tokens x {Kk} channels (8 heads x 128), bf16 in / out", "query": f"{Mq} x {Kq} bf16"}
+        for bits in (4, 8):
+            cbytes = Mk * Kk * ((0.5 if bits == 4 else 1.0) + 1.0 / 32)
+            kc = torch.empty(B.batq_code8_bytes(Mk, Kk) if bits == 8 else B.batq_code_bytes(Mk, Kk), dtype=torch.uint8,
+                             device="cuda")
+            ksc = torch.empty(B.batq_scale_bytes(Mk, Kk), dtype=torch.uint8, device="cuda")
+            if bits == 4:
+                us_w = per_call_us(lambda: B.batq_quantize_act(tk, Xk, kc, ksc))
+            else:
+                kc, ksc = B.batq_quantize_act_ex(tk, Xk, act_bits=8)
+                us_w = per_call_us(lambda: B.batq_quantize_act_ex(tk, Xk, act_bits=8))
+            us_r = per_call_us(lambda: B.batq_dequantize(kc, ksc, Mk, Kk, bits, out=Ok))
+            kv[f"kv{bits}"] = {"quantize_us": us_w, "quantize_gbs": (Mk * Kk * 2 + cbytes) / us_w / 1e3,
+                               "dequantize_us": us_r, "dequantize_gbs": (Mk * Kk * 2 + cbytes) / us_r / 1e3}
+        us_a = per_call_us(lambda: B.batq_transform_apply(tq, Xq, B.APPLY_INVERSE_T, out=Oq))
+        us_ak = per_call_us(lambda: B.batq_transform_apply(tk, Xk, B.APPLY_INVERSE, out=Ok))
+        kv["apply_inverse_t_query_us"] = us_a
+        kv["apply_inverse_t_query_gbs"] = Mq * Kq * 4 / us_a / 1e3
+        kv["apply_inverse_cache_shape_us"] = us_ak
+        kv["apply_inverse_cache_shape_gbs"] = Mk * Kk * 4 / us_ak / 1e3
+        del Xk, Xq, Ok, Oq
+        torch.cuda.empty_cache()
+
     ceilings = None
     tool = os.path.join(ROOT, "paper_2603_16590_amd", "batq_ceilings")
     if not args.no_ceilings and os.path.exists(tool):
@@ -358,6 +419,7 @@ def main():
         "also": also,
         "w4a8": w4a8,
         "mlp_block": mlp,
+        "kv_cache": kv,
         "decode": decode,
     }
     print(json.dumps(line))

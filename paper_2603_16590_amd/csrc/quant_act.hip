@@ -323,11 +323,11 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         if (lane == 0) v = (int)__hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         return __builtin_amdgcn_readfirstlane(v);
     };
-    auto request = [&](int g, int u) {
+    auto request = [&](int g, int u) -> bool {              // false: nothing to fetch (a half group of padding)
         const int tile = u >> 1, half = u & 1;
         const int kb = 8 * g + 4 * half;                    // first MX block of the unit
         const int nreal = min(4, nb - kb);                  // blocks that exist (the rest of the group is padding)
-        if (nreal <= 0) return;
+        if (nreal <= 0) return false;
         const uint8_t* base = reinterpret_cast<const uint8_t*>(X) + ((size_t)tile * 32 * ldx + (size_t)kb * 32) * 2;
         const uint8_t* ubase =
             SWIGLU ? reinterpret_cast<const uint8_t*>(U) + ((size_t)tile * 32 * ldu + (size_t)kb * 32) * 2 : nullptr;
@@ -348,6 +348,7 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
                              :: "v"(uoff), "s"(ubase), "s"(xslot_lds + (uint32_t)(kXSlot + j * 1024)) : "memory");
             }
         }
+        return true;
     };
 
     const int r16 = l32 & 15;
@@ -398,8 +399,10 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         }
         __syncthreads();                                    // the counter is set
         int my_u = grab();
-        if (my_u < u_end) request(g, my_u);
-        __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's share of the operands (and its unit)
+        // this wave's share of the operands has landed once only the unit's loads (8, or 16 with a gated input;
+        // loads complete in order) are still out: the workgroup does not wait for everybody's first unit
+        if (my_u < u_end && request(g, my_u)) __builtin_amdgcn_s_waitcnt(SWIGLU ? 0x4F70 : 0x0F78);     // vmcnt(16) : vmcnt(8)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
         __syncthreads();                                    // all operands have landed
 
         while (my_u < u_end) {
