@@ -206,3 +206,38 @@ def test_quantised_cache_keeps_attention_scores(B, bits):
     assert rel < 5e-3, rel
     relq = np.linalg.norm(got - exact) / np.linalg.norm(exact)
     assert relq < (0.05 if fp8 else 0.35), relq
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_cache_shape_of_the_benchmark_on_sampled_rows(B, bits):
+    """The shapes bench.py times (cache of 32768 tokens x 1024 channels, query of 8192 x 4096): sampled rows of
+    the dequantised cache against the oracle's dequantisation of the same codes, sampled rows of the transform
+    against the oracle."""
+    import torch
+    rng = np.random.default_rng(40 + bits)
+    Mk, Kk = 32768, 1024
+    G, P, clip = bi.make_factors(Kk // 32, rng, rng, rng, 0.7)
+    t = B.Transform(Kk, G, P, clip)
+    X = torch.randn((Mk, Kk), device="cuda", generator=torch.Generator(device="cuda").manual_seed(bits)).to(torch.bfloat16)
+    codes, scales = B.batq_quantize_act_ex(t, X, act_bits=bits)
+    out = B.batq_dequantize(codes, scales, Mk, Kk, bits)
+    rm_codes = (B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor)(codes, Mk, Kk)
+    rm_scales = B.batq_scales_to_rowmajor(scales, Mk, Kk)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([rng.integers(0, Mk, 200), [0, 15, 16, 31, 32, Mk - 33, Mk - 1]]))
+    ref = (o.dequantize_fp8 if bits == 8 else o.dequantize)(rm_codes[rows].cpu().numpy(), rm_scales[rows].cpu().numpy())
+    assert np.array_equal(y_to_f32(out[rows]).astype(np.float64), ref)
+    if bits == 4:
+        Mq, Kq = 8192, 4096
+        Gq, Pq, _ = bi.make_factors(Kq // 32, rng, rng, rng, 0.7)
+        tq = B.Transform(Kq, Gq, Pq, None)
+        Q = torch.randn((Mq, Kq), device="cuda", generator=torch.Generator(device="cuda").manual_seed(9)).to(torch.bfloat16)
+        got = B.batq_transform_apply(tq, Q, B.APPLY_INVERSE_T, torch.float32)
+        torch.cuda.synchronize()
+        rq = np.unique(np.concatenate([rng.integers(0, Mq, 64), [0, 31, 32, Mq - 1]]))
+        Xf = Q[rq].float().cpu().numpy().astype(np.float64)
+        Mat = o.inverse_transpose_blocks(o.kron_blocks(Gq, Pq))
+        ref = o.apply_blocks(Xf, Mat)
+        absref = o.apply_blocks(np.abs(Xf), np.abs(Mat))
+        g = got[rq].cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(g - ref) <= 2.0 ** -24 * np.abs(ref) + 2.0 ** -20 * absref)
