@@ -591,6 +591,80 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
     }
 }
 
+// s_waitcnt lgkmcnt(0) only: the wave's LDS reads have delivered.
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// The same stage for tiles one or two strips wide.  Their 8 or 16 matrix instructions per stage are too few to
+// hide a barrier followed by the LDS reads of the next fragments in the last quarter of the stage, so here the
+// fragments run a whole stage ahead: on entry a/b hold both K steps of stage s, the barrier at the top makes
+// stage s+1 visible (and the slot of stage s, read a stage ago, free), and the reads of stage s+1 and the loads
+// of stage s+4 are spread under the stage's own matrix instructions.  Same WAIT / ISSUE / FIRST meaning and the
+// same load accounting as tiled_stage: no load of stage s+4 has been issued when stage s+1 is awaited.
+template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+__device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
+                                             uint4 (&b)[2][NJ], int (&sa)[4], int (&sb)[NJ]) {
+    static_assert(NJ <= 2, "narrow tiles only");
+    uint4 na[2][4], nb[2][NJ];
+    int sna[4], snb[NJ];
+    constexpr bool kNext = WAIT >= 0, kIssue = WAIT >= 0 && ISSUE;
+    if constexpr (kNext) {
+        wait_vmcnt<WAIT>();
+        wait_lds();                                         // this wave's fragments of stage s are in registers
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR, FIRST>(acc[i][j], a[0][i], b[0][j], sa[i], sb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i == 0) {
+            if constexpr (kNext) c.read_frags<NJ>(s + 1, 0, na[0], nb[0]);
+        } else if (i == 1) {
+            if constexpr (kIssue) issue_range<NJ, PAR == 0, 0, 2>(c, s + 4);
+        } else if (i == 2) {
+            if constexpr (kNext) c.read_frags<NJ>(s + 1, 1, na[1], nb[1]);
+        } else {
+            if constexpr (kIssue) issue_range<NJ, PAR == 0, 2, 4>(c, s + 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR + 1, false>(acc[i][j], a[1][i], b[1][j], sa[i], sb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i == 0) {
+            if constexpr (kNext && PAR == 1) c.read_scales<NJ>((s + 1) >> 1, sna, snb);
+        } else if (i == 1) {
+            if constexpr (kIssue) issue_range<NJ, PAR == 0, 4, 5 + NJ>(c, s + 4);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (kNext) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[h][i] = na[h][i];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) b[h][j] = nb[h][j];
+        }
+        if constexpr (PAR == 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sa[i] = sna[i];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) sb[j] = snb[j];
+        }
+    }
+}
+
+// Stage of a tile NJ strips wide: narrow tiles keep both K steps' fragments in `a`, `b`, wide ones the first.
+template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+__device__ __forceinline__ void any_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
+                                          uint4 (&b)[2][NJ], int (&sa)[4], int (&sb)[NJ]) {
+    if constexpr (NJ <= 2) narrow_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a, b, sa, sb);
+    else tiled_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a[0], b[0], sa, sb);
+}
+
 // Epilogue of a tile: 4 x NJ output tiles of 32 x 32 of this wave (rows m0 + wm*128.., columns n0 + wn*32*NJ..)
 // -> Y; value(i, j, e) = element e (accumulator register order) of output tile (i, j).
 // `ep_lds` is the wave's private 4 KiB LDS staging area.
@@ -732,7 +806,7 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     c.aim_reads(NJ, wm, wn, lane & 31);
 
     v16f acc[4][NJ];
-    uint4 fa[4], fb[NJ];
+    uint4 fa[2][4], fb[2][NJ];
     int sa[4], sb[NJ];
 
     // Loads per thread: 4 + NJ per stage, plus 4 for the scales of a K group issued with the
@@ -744,27 +818,28 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
     else wait_vmcnt<kOdd>();
     __syncthreads();
     c.read_scales<NJ>(0, sa, sb);
-    c.read_frags<NJ>(0, 0, fa, fb);
+    c.read_frags<NJ>(0, 0, fa[0], fb[0]);
+    if constexpr (NJ <= 2) c.read_frags<NJ>(0, 1, fa[1], fb[1]);
 
     // the first stage of a tile starts the accumulators from zero
     if (G >= 3) {
-        tiled_stage<NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
-        tiled_stage<NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
         for (int g = 1; g + 2 < G; ++g) {
-            tiled_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
-            tiled_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
+            any_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
+            any_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
         }
-        tiled_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);
-        tiled_stage<NJ, 1, kOdd, false, false>(c, T - 3, acc, fa, fb, sa, sb);
-        tiled_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);
+        any_stage<NJ, 1, kOdd, false, false>(c, T - 3, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
     } else if (G == 2) {
-        tiled_stage<NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
-        tiled_stage<NJ, 1, kOdd, false, false>(c, 1, acc, fa, fb, sa, sb);
-        tiled_stage<NJ, 0, 0, false, false>(c, 2, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<NJ, 1, kOdd, false, false>(c, 1, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, 0, false, false>(c, 2, acc, fa, fb, sa, sb);
     } else {
-        tiled_stage<NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
     }
-    tiled_stage<NJ, 1, -1, false, false>(c, T - 1, acc, fa, fb, sa, sb);
+    any_stage<NJ, 1, -1, false, false>(c, T - 1, acc, fa, fb, sa, sb);
 
     __syncthreads();                                      // every wave is done with the stage ring
     if (has_next) {
