@@ -15,6 +15,8 @@
 namespace batq {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // 2^(byte - 127) as fp32; byte 0 is the subnormal 2^-127, byte 255 (the format's NaN) gives NaN.
 __device__ __forceinline__ float e8m0_value(uint32_t byte) {
     if (byte == 0u) return __uint_as_float(0x00400000u);
@@ -118,7 +120,9 @@ dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sc
                     q.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 2));
                     q.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 3));
                 }
-                *reinterpret_cast<uint4*>(o) = q;
+                // streamed out (no reader in this kernel, nothing left dirty in the L2s at its end):
+                // 131072 x 1024 71 -> 53 us
+                __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(o));
             } else {
                 const float sc = e8m0_value(byte);
                 float v[8];
@@ -178,7 +182,6 @@ apply_kernel(const XT* __restrict__ X, int64_t ldx, int M, const double* __restr
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSplitBlock = 3 * 2 * 64 * 16;               // bytes of split operand per MX block (see split_operand)
 constexpr int kApplyWaves = 8;
