@@ -195,7 +195,9 @@ constexpr int kApplyLds = kApplyLdsT + kApplyWaves * 2 * kApplySlot;        // 1
 // a wave fetches its unit with LDS-direct loads (rows of 256 contiguous bytes, 16-byte chunk c of row r at
 // position (c & 8) | ((c ^ r) & 7)), prefetching the next unit into its second slot, and sends the results
 // back through the slot it has just emptied, so that the stores are rows of 256 contiguous bytes as well.
-template <typename OT>
+// NT: the output rows are stored non-temporally (faster up to ~150 MB of traffic, where the dirty lines a kernel
+// leaves in the L2s cost a write-back at its end; slower beyond: 268 MB 88 -> 101 us).
+template <typename OT, bool NT>
 __global__ void __launch_bounds__(kApplyWaves * 64)
 apply_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
            const uint4* __restrict__ split, OT* __restrict__ out, int64_t ldo) {
@@ -287,7 +289,11 @@ apply_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles
                 const int c = (pos & 8) | ((pos ^ r) & 7);
                 const uint4 q = *reinterpret_cast<const uint4*>(slot + r * 256 + pos * 16);
                 if (row0 + r < M && c < 4 * nreal)
-                    *reinterpret_cast<uint4*>(out + (size_t)(row0 + r) * ldo + (size_t)kb * 32 + c * 8) = q;
+                {
+                    uint4* dst = reinterpret_cast<uint4*>(out + (size_t)(row0 + r) * ldo + (size_t)kb * 32 + c * 8);
+                    if constexpr (NT) __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(dst));
+                    else *dst = q;
+                }
             }
         } else {
             // fp32 output: two blocks (256 bytes per row) at a time through the same slot
@@ -338,16 +344,24 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
         const bool fits = ((uintptr_t)X | (uintptr_t)out | (uintptr_t)(ldx * 2) | (uintptr_t)(ldo * (int64_t)sizeof(OT))) % 16 == 0 &&
                           ldx < (int64_t(1) << 25);
         if (sp && fits) {
-            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT>),
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT, false>),
                                                                hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
+            static const hipError_t attr_nt = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT, true>),
+                                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
             if (attr != hipSuccess) return attr;
+            if (attr_nt != hipSuccess) return attr_nt;
             const int units = (t->nb + 3) / 4, row_tiles = (M + 31) / 32;
             // about four workgroups per compute unit, at least 16 tiles each (the operands are fetched per workgroup)
             int tiles_per_wg = (int)(((int64_t)row_tiles * units + 1023) / 1024);
             if (tiles_per_wg < 16) tiles_per_wg = 16;
             const dim3 grid(units, (row_tiles + tiles_per_wg - 1) / tiles_per_wg), block(kApplyWaves * 64);
-            apply_mfma<OT><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
-                                                               reinterpret_cast<const uint4*>(sp), out, ldo);
+            const bool nt = sizeof(OT) == 2 && (size_t)M * t->K * 4 <= (size_t(150) << 20);
+            if (nt)
+                apply_mfma<OT, true><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
+                                                                         reinterpret_cast<const uint4*>(sp), out, ldo);
+            else
+                apply_mfma<OT, false><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
+                                                                          reinterpret_cast<const uint4*>(sp), out, ldo);
             return hipGetLastError();
         }
     }
