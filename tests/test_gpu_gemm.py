@@ -110,6 +110,30 @@ def test_tile_schedule_shapes(B, M, K, N):
     assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
 
 
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 14336), (300, 1536 + 32, 5000), (256, 768, 24000), (100, 512, 9000 + 24),
+                                   (512, 1024, 14336)])
+def test_narrow_tile_shapes(B, M, K, N):
+    """Few rows and many columns: every workgroup gets one or two strips, so all tiles are one or two strips wide
+    (their own stage schedule), with 4 to 16 K stages, ragged rows and a ragged last strip; every element."""
+    import torch
+    rng = np.random.default_rng(M * 7 + K + N)
+    xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
+    wc, ws, dwc, dws = _rand_q(rng, N, K, lo=122, hi=132)
+    wh = B.batq_weight_import(dwc, dws, K, N)
+    ref = o.gemm(xc, xs, wc, ws)
+    Y = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, M, torch.float32)
+    torch.cuda.synchronize()
+    tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
+    bad = np.argwhere(np.abs(y_to_f32(Y) - ref) > tol + 1e-30)
+    assert bad.size == 0, f"{len(bad)} wrong elements, first at {bad[0]}"
+    Yb = B.batq_gemm_mxfp4(_xc(xc), _xs(xs), wh, M, torch.bfloat16)
+    torch.cuda.synchronize()
+    refb = o.bf16_round(ref).astype(np.float64)
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+    bad = np.argwhere(np.abs(y_to_f32(Yb).astype(np.float64) - refb) > ulp * 1.0001 + tol)
+    assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
+
+
 @pytest.mark.parametrize("M,K,N", [(130, 8192, 320), (300, 8192 + 32, 200), (256, 8192 + 256, 1000), (97, 6144, 64),
                                    (65, 12288 + 64, 2100), (520, 16384, 136), (64, 12288 + 32, 2070), (7, 16384, 96)])
 def test_split_k_shapes(B, M, K, N):
