@@ -327,13 +327,29 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
  *   reference route: products and sums in fp64, one rounding to fp32.  bf16 output adds one rounding.  The
  *   query side of a transformed key cache takes INVERSE_T ((q T^-T)(k T)^T = q k^T), the attention output
  *   over a transformed value cache takes INVERSE (or folds T_v^-1 into the output projection).  X and out
- *   as for batq_quantize_act (DEVICE, row strides in elements); not in place (BATQ_ERR_SHAPE). */
+ *   as for batq_quantize_act (DEVICE, row strides in elements); not in place (BATQ_ERR_SHAPE).
+ *
+ * A cache that grows: batq_kv_append quantises M new token rows of X exactly as batq_quantize_act (act_bits 4) or
+ *   batq_quantize_act_mxfp8 (act_bits 8) would, but into rows row_offset .. row_offset + M - 1 of code and scale
+ *   arrays (DEVICE, caller-owned) that are laid out for capacity_rows rows: batq_code_bytes / batq_code8_bytes and
+ *   batq_scale_bytes of (capacity_rows, K).  Rows are independent, so a cache filled in any number of appends
+ *   holds what one call over all its rows would have written.  Appends that start on a multiple of 32 rows and
+ *   bring more than 128 rows take the matrix-core kernel, which writes whole 32-row tiles of codes: the code rows
+ *   after the appended block up to the next multiple of 32 (not yet part of the cache) are then overwritten with
+ *   unspecified values; other appends write their own rows only.  BATQ_ERR_SHAPE if the window does not fit.
+ *   batq_kv_dequantize reads rows row_offset .. row_offset + M - 1 of such arrays into out rows 0 .. M - 1
+ *   (otherwise as batq_dequantize).  Both are asynchronous on `stream` and allocate nothing. */
 typedef enum { BATQ_APPLY_FORWARD = 0, BATQ_APPLY_INVERSE = 1, BATQ_APPLY_INVERSE_T = 2 } batq_apply_mode;
 batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits,
                             void* out, batq_dtype odtype, int64_t ldo, void* stream);
 batq_status batq_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                  int64_t ldx, batq_apply_mode mode, void* out, batq_dtype odtype, int64_t ldo,
                                  void* stream);
+batq_status batq_kv_append(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K, int64_t ldx,
+                           int act_bits, uint8_t* codes, uint8_t* scales, int64_t row_offset, int64_t capacity_rows,
+                           void* stream);
+batq_status batq_kv_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t capacity_rows, int64_t row_offset,
+                               int M, int K, int bits, void* out, batq_dtype odtype, int64_t ldo, void* stream);
 
 /* ------------------------------------------------------------------------------------
  * Introspection (HOST only, no GPU needed): the work split of the tiled GEMM kernels for an M x K x N problem

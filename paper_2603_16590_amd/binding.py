@@ -67,6 +67,8 @@ SYMBOLS = {
     "batq_linear_glu": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_debug_tile_schedule": (_i, [_i, _i, _i, _i, _i, _i, _vp, _i]),
     "batq_dequantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _i, _i64, _vp]),
+    "batq_kv_append": (_i, [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _vp, _i64, _i64, _vp]),
+    "batq_kv_dequantize": (_i, [_vp, _vp, _i64, _i64, _i, _i, _i, _vp, _i, _i64, _vp]),
     "batq_transform_apply": (_i, [_vp, _vp, _i, _i, _i, _i64, _i, _vp, _i, _i64, _vp]),
 }
 
@@ -509,6 +511,28 @@ def batq_dequantize(codes, scales, M: int, K: int, bits: int = 4, out_dtype=None
         out = torch.empty((M, K), dtype=out_dtype or torch.bfloat16, device=codes.device)
     _check(lib.batq_dequantize(codes.data_ptr(), scales.data_ptr(), M, K, bits, out.data_ptr(), _dtype_code(out),
                                out.stride(0) if M > 1 else max(K, out.stride(0)), _stream()), "batq_dequantize")
+    return out
+
+
+def batq_kv_append(t: Transform, X, codes, scales, row_offset: int, capacity_rows: int, bits: int = 4):
+    """Quantise the rows of X into rows row_offset.. of a cache laid out for capacity_rows rows (codes, scales:
+    flat uint8 device tensors of batq_code_bytes / batq_code8_bytes and batq_scale_bytes of capacity_rows)."""
+    assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    _check(lib.batq_kv_append(t.handle, X.data_ptr(), _dtype_code(X), M, K,
+                              X.stride(0) if M > 1 else max(K, X.stride(0)), bits, codes.data_ptr(), scales.data_ptr(),
+                              row_offset, capacity_rows, _stream()), "batq_kv_append")
+
+
+def batq_kv_dequantize(codes, scales, capacity_rows: int, row_offset: int, M: int, K: int, bits: int = 4,
+                       out_dtype=None, out=None):
+    """Rows row_offset .. row_offset + M - 1 of a cache laid out for capacity_rows rows -> [M, K] tensor."""
+    import torch
+    if out is None:
+        out = torch.empty((M, K), dtype=out_dtype or torch.bfloat16, device=codes.device)
+    _check(lib.batq_kv_dequantize(codes.data_ptr(), scales.data_ptr(), capacity_rows, row_offset, M, K, bits,
+                                  out.data_ptr(), _dtype_code(out), out.stride(0) if M > 1 else max(K, out.stride(0)),
+                                  _stream()), "batq_kv_dequantize")
     return out
 
 

@@ -449,6 +449,9 @@ struct ActExtras {
     const float* row_scale = nullptr;
     const void* up = nullptr;
     int64_t ld_up = 0;
+    // destination window of a cache append: the arrays are laid out for `layout_rows` rows (0: for M) and the
+    // M rows go to rows row_offset .. row_offset + M - 1
+    int row_offset = 0, layout_rows = 0;
 };
 
 // Gated input: bf16 only (the rounding of silu(gate) * up is to bf16), up laid out like X.
@@ -475,7 +478,7 @@ batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdt
         return BATQ_ERR_SHAPE;
     if (batq_status st = check_extras(ex, xdtype, K); st != BATQ_OK) return st;
     if (batq::launch_quantize_act(t, X, xdtype, M, K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales, fp8,
-                                  static_cast<hipStream_t>(stream)) != hipSuccess) {
+                                  ex.row_offset, ex.layout_rows, static_cast<hipStream_t>(stream)) != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
@@ -525,7 +528,7 @@ batq_status linear_impl(const batq_transform* t, const batq_weight* w, const voi
     uint8_t* codes = static_cast<uint8_t*>(workspace);
     uint8_t* scales = codes + (a8 ? batq::code8_bytes_blocked(M, t->nb) : batq::code_bytes_blocked(M, t->nb));
     hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales,
-                                             a8, s);
+                                             a8, 0, 0, s);
     if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, glu, s);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -700,19 +703,43 @@ int batq_debug_tile_schedule(int M, int N, int K, int compute_units, int glu, in
     return batq::tile_schedule(M, N, K, compute_units, glu != 0, allow_ksplit != 0, tiles, capacity);
 }
 
-batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits, void* out,
-                            batq_dtype odtype, int64_t ldo, void* stream) {
+static batq_status dequantize_impl(const uint8_t* codes, const uint8_t* scales, int64_t layout_rows, int64_t row_offset,
+                                   int M, int K, int bits, void* out, batq_dtype odtype, int64_t ldo, void* stream) {
     if (bits != 4 && bits != 8) return BATQ_ERR_UNSUPPORTED;
     if (!dtype_ok(odtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || K <= 0 || K % 32 != 0 || ldo < K) return BATQ_ERR_SHAPE;
+    if (row_offset < 0 || layout_rows < row_offset + M || layout_rows > INT32_MAX) return BATQ_ERR_SHAPE;
     if (M == 0) return BATQ_OK;
     if (!codes || !scales || !out) return BATQ_ERR_NULL;
     if (!aligned16(codes) || !aligned16(out) || (ldo * (int64_t)dtype_size(odtype)) % 16 != 0) return BATQ_ERR_SHAPE;
     batq_status st = check_device();
     if (st != BATQ_OK) return st;
-    BATQ_HIP(batq::launch_dequantize(codes, scales, M, K / 32, bits == 8, out, odtype, ldo,
-                                     static_cast<hipStream_t>(stream)));
+    BATQ_HIP(batq::launch_dequantize(codes, scales, M, K / 32, bits == 8, out, odtype, ldo, (int)row_offset,
+                                     (int)layout_rows, static_cast<hipStream_t>(stream)));
     return BATQ_OK;
+}
+
+batq_status batq_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int K, int bits, void* out,
+                            batq_dtype odtype, int64_t ldo, void* stream) {
+    return dequantize_impl(codes, scales, M, 0, M, K, bits, out, odtype, ldo, stream);
+}
+
+batq_status batq_kv_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t capacity_rows, int64_t row_offset,
+                               int M, int K, int bits, void* out, batq_dtype odtype, int64_t ldo, void* stream) {
+    if (capacity_rows < 1) return BATQ_ERR_SHAPE;
+    return dequantize_impl(codes, scales, capacity_rows, row_offset, M, K, bits, out, odtype, ldo, stream);
+}
+
+batq_status batq_kv_append(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K, int64_t ldx,
+                           int act_bits, uint8_t* codes, uint8_t* scales, int64_t row_offset, int64_t capacity_rows,
+                           void* stream) {
+    if (act_bits != 4 && act_bits != 8) return BATQ_ERR_UNSUPPORTED;
+    if (M < 0 || capacity_rows < 1 || capacity_rows > INT32_MAX || row_offset < 0 || row_offset + M > capacity_rows)
+        return BATQ_ERR_SHAPE;
+    ActExtras ex;
+    ex.row_offset = (int)row_offset;
+    ex.layout_rows = (int)capacity_rows;
+    return quantize_impl(t, X, xdtype, M, K, ldx, ex, codes, scales, act_bits == 8, stream);
 }
 
 batq_status batq_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,

@@ -47,10 +47,10 @@ namespace batq {
 // U: DEVICE tensor like X (same dtype, row stride ldu) or null; with U the input is bf16(silu(X) * U).
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                int64_t ldx, const void* U, int64_t ldu, const float* row_scale, uint8_t* codes,
-                               uint8_t* scales, bool fp8, hipStream_t stream);
+                               uint8_t* scales, bool fp8, int row_offset, int layout_rows, hipStream_t stream);
 // Blocked codes (fp8: the 8-bit variant) + grouped scales -> row-major out (bf16 or fp32, row stride ldo).
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int nb, bool fp8, void* out,
-                             batq_dtype odtype, int64_t ldo, hipStream_t stream);
+                             batq_dtype odtype, int64_t ldo, int row_offset, int layout_rows, hipStream_t stream);
 // out = X T_k, X T_k^-1 or X T_k^-T block by block (mode = batq_apply_mode), no quantisation.
 hipError_t launch_transform_apply(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
                                   int mode, void* out, batq_dtype odtype, int64_t ldo, hipStream_t stream);

@@ -67,8 +67,8 @@ __device__ __forceinline__ void store8<uint16_t>(uint16_t* p, const float (&v)[8
 // code value x 2^(byte - 127), exact in fp32 (subnormals included; scale byte 255 and the E4M3 NaN codes give NaN).
 template <typename OT, bool FP8>
 __global__ void __launch_bounds__(256)
-dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int M, int nb,
-               OT* __restrict__ out, int64_t ldo) {
+dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int M, int nb, int row0,
+               int srows, OT* __restrict__ out, int64_t ldo) {
     constexpr int kPerRow = FP8 ? 4 : 2;                   // pieces of a K group per 16-row group
     constexpr int kPieces = 2 * kPerRow;
     constexpr int kSub = FP8 ? 2 : 4;                       // wave instructions per piece
@@ -77,8 +77,10 @@ dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sc
     const int lane = threadIdx.x & 63;
     const int groups = scale_groups(nb);
     const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int tile = (int)(unit / groups), g = (int)(unit - (int64_t)tile * groups);
-    if (tile >= (M + 31) >> 5) return;                      // wave-uniform
+    // rows row0 .. row0 + M - 1 of arrays laid out for srows rows -> out rows 0 .. M - 1
+    const int first_tile = row0 >> 5, last_tile = (row0 + M - 1) >> 5;
+    const int tile = first_tile + (int)(unit / groups), g = (int)(unit % groups);
+    if (tile > last_tile) return;                           // wave-uniform
     const size_t stages = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb));
     // this lane inside an instruction's rows: row, 16-byte slot of the row, 8-element part of the slot
     const int lr = FP8 ? lane >> 3 : lane >> 4;
@@ -102,9 +104,9 @@ dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sc
             const int slot = pos ^ ((r >> 2) & 3);          // undo the bank swizzle
             const int row = tile * 32 + (p / kPerRow) * 16 + r;
             const int k = g * 8 + (p % kPerRow) * (FP8 ? 2 : 4) + (FP8 ? slot >> 1 : slot);
-            if (row >= M || k >= nb) continue;
-            const uint32_t byte = scales[scale_index_internal(row, k, M)];
-            OT* o = out + (size_t)row * ldo + (size_t)k * 32 + (FP8 ? (slot & 1) * 16 + part * 8 : part * 8);
+            if (row < row0 || row >= row0 + M || k >= nb) continue;
+            const uint32_t byte = scales[scale_index_internal(row, k, srows)];
+            OT* o = out + (size_t)(row - row0) * ldo + (size_t)k * 32 + (FP8 ? (slot & 1) * 16 + part * 8 : part * 8);
             const uint2 d = w[p][i];
             if constexpr (kHw) {
                 const float sc = scale_operand(byte);
@@ -378,18 +380,19 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
 }  // namespace
 
 hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int M, int nb, bool fp8, void* out,
-                             batq_dtype odtype, int64_t ldo, hipStream_t stream) {
+                             batq_dtype odtype, int64_t ldo, int row_offset, int layout_rows, hipStream_t stream) {
     if (M == 0) return hipSuccess;
-    const int64_t units = (int64_t)((M + 31) >> 5) * scale_groups(nb);      // one wave each, four to a workgroup
+    const int tiles = ((row_offset + M - 1) >> 5) - (row_offset >> 5) + 1;
+    const int64_t units = (int64_t)tiles * scale_groups(nb);                // one wave each, four to a workgroup
     const dim3 grid((unsigned)((units + 3) / 4)), block(256);
     if (odtype == BATQ_BF16) {
         auto o = static_cast<uint16_t*>(out);
-        if (fp8) dequant_kernel<uint16_t, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, o, ldo);
-        else dequant_kernel<uint16_t, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, o, ldo);
+        if (fp8) dequant_kernel<uint16_t, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
+        else dequant_kernel<uint16_t, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
     } else {
         auto o = static_cast<float*>(out);
-        if (fp8) dequant_kernel<float, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, o, ldo);
-        else dequant_kernel<float, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, o, ldo);
+        if (fp8) dequant_kernel<float, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
+        else dequant_kernel<float, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
     }
     return hipGetLastError();
 }

@@ -99,7 +99,7 @@ __device__ __forceinline__ void swiglu8(float (&x)[8], const float (&u)[8]) {
 template <typename XT, int GO, bool TRANSFORM, bool FP8>
 __global__ void __launch_bounds__(256)
 quant_act_quad(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, int64_t ldu, int M, int nb,
-               int rows_per_wg,
+               int row0, int srows, int rows_per_wg,
                const float* __restrict__ G, int g_stride, const float* __restrict__ P, int p_stride,
                const float* __restrict__ clip, const float* __restrict__ clip_max,
                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
@@ -136,9 +136,9 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, 
     const float ck = clip[k];
     const float ck_max = clip_max ? clip_max[k] : 0.f;
 
-    const int row0 = blockIdx.y * rows_per_wg;
-    const int row1 = min(M, row0 + rows_per_wg);
-    for (int row = row0; row < row1; ++row) {
+    const int row_begin = blockIdx.y * rows_per_wg;
+    const int row_end = min(M, row_begin + rows_per_wg);
+    for (int row = row_begin; row < row_end; ++row) {
         float x[8], y[8];
         load8(X + (size_t)row * ldx + (size_t)k * 32 + q * 8, x);
         if (U) {
@@ -225,22 +225,22 @@ quant_act_quad(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, 
             const uint32_t s = e8m0_of_bound_fp8(bound);
             const uint2 packed = encode8_fp8(y, bound, s, scale_operand(s));
             if (live) {
-                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row, k, q >> 1, nb) + (q & 1) * 8) = packed;
-                if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row0 + row, k, q >> 1, nb) + (q & 1) * 8) = packed;
+                if (q == 0) scales[scale_index_internal(row0 + row, k, srows)] = (uint8_t)s;
             } else if (pad) {
-                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row, kpad, q >> 1, nb) + (q & 1) * 8) = uint2{0u, 0u};
-                if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+                *reinterpret_cast<uint2*>(codes + code8_slot_offset(row0 + row, kpad, q >> 1, nb) + (q & 1) * 8) = uint2{0u, 0u};
+                if (q == 0) scales[scale_index_internal(row0 + row, kpad, srows)] = (uint8_t)127;
             }
         } else {
             const uint32_t s = e8m0_of_bound(bound);
             const uint32_t packed = encode8(y, bound, scale_operand(s));
             if (live) {
-                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, k, nb) + q * 4) = packed;
-                if (q == 0) scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row0 + row, k, nb) + q * 4) = packed;
+                if (q == 0) scales[scale_index_internal(row0 + row, k, srows)] = (uint8_t)s;
             } else if (pad) {
                 // padding blocks up to the next multiple of 8: zero codes, neutral scale
-                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row, kpad, nb) + q * 4) = 0u;
-                if (q == 0) scales[scale_index_internal(row, kpad, M)] = (uint8_t)127;
+                *reinterpret_cast<uint32_t*>(codes + code_chunk_offset(row0 + row, kpad, nb) + q * 4) = 0u;
+                if (q == 0) scales[scale_index_internal(row0 + row, kpad, srows)] = (uint8_t)127;
             }
         }
     }
@@ -292,7 +292,7 @@ struct QuantPlan {
 template <bool MINMAX, bool FP8, bool SWIGLU>
 __global__ void __launch_bounds__((QuantPlan<FP8, SWIGLU>::kWaves * 64))
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ U, int64_t ldu, int M,
-               int nb, int wpg,
+               int nb, int srows, int wpg,
                const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     extern __shared__ __align__(16) uint8_t qlds[];
@@ -379,7 +379,7 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         // odd blocks at 4 + 2 half, 4 + 2 half + 1; lane kg writes pair kg
         const int row = tile * 32 + l32;
         if (row < M)
-            *reinterpret_cast<uint16_t*>(scales + ((size_t)pend_g * M + row) * 8 + 4 * kg + 2 * half) = (uint16_t)pend_sc;
+            *reinterpret_cast<uint16_t*>(scales + ((size_t)pend_g * srows + row) * 8 + 4 * kg + 2 * half) = (uint16_t)pend_sc;
         pend_u = -1;
     };
 
@@ -585,9 +585,15 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
     flush();
 }
 
+// Destination rows of a call: the code and scale arrays are laid out for `srows` rows, and the M rows of X go to
+// rows row0 .. row0 + M - 1 (a plain call: row0 = 0, srows = M).
+struct RowWindow {
+    int row0, srows;
+};
+
 template <bool MINMAX, bool FP8, bool SWIGLU>
 hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U,
-                          int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales, int cus,
+                          int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, int cus,
                           hipStream_t stream) {
     using Plan = QuantPlan<FP8, SWIGLU>;
     static bool attr_set = false;
@@ -602,15 +608,19 @@ hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int
     const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
     const int wpg = std::max(1, std::min(cus / groups, row_tiles));
     const int wgs = wpg * std::min(groups, cus);
+    // the window starts on a 32-row tile (the caller checks): whole 16-row code groups and 8-byte scale rows in
+    const size_t code_group = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb)) * 1024;
     quant_act_mfma<MINMAX, FP8, SWIGLU><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
-        X, ldx, U, ldu, M, nb, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
-        MINMAX ? t->d_clip_max : nullptr, row_scale, codes, scales);
+        X, ldx, U, ldu, M, nb, win.srows, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
+        MINMAX ? t->d_clip_max : nullptr, row_scale, codes + (size_t)(win.row0 >> 4) * code_group,
+        scales + (size_t)win.row0 * 8);
     return hipGetLastError();
 }
 
 template <bool SWIGLU>
 hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U, int64_t ldu,
-                       const float* row_scale, uint8_t* codes, uint8_t* scales, bool fp8, hipStream_t stream) {
+                       const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, bool fp8,
+                       hipStream_t stream) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0;
@@ -623,16 +633,16 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
     }
     if (fp8)
         return t->minmax
-                   ? launch_mfma_as<true, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream)
-                   : launch_mfma_as<false, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream);
+                   ? launch_mfma_as<true, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream)
+                   : launch_mfma_as<false, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream);
     return t->minmax
-               ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream)
-               : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, cus, stream);
+               ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream)
+               : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream);
 }
 
 template <typename XT, bool FP8>
 hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx, const XT* U, int64_t ldu,
-                       const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                       const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, hipStream_t stream) {
     const int nb = t->nb;
     const int gx = (scale_groups(nb) * 8 + 63) / 64;
     // aim at >= 4 workgroups per CU while keeping the per-lane factor loads amortised
@@ -642,14 +652,14 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
     const dim3 grid(gx, (M + rows_per_wg - 1) / rows_per_wg), block(256);
     const float* cmax = t->minmax ? t->d_clip_max : nullptr;
     if (!t->has_transform)
-        quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, nullptr, 0, nullptr,
+        quant_act_quad<XT, 4, false, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, win.row0, win.srows, rows_per_wg, nullptr, 0, nullptr,
                                                                        0, t->d_clip, cmax, row_scale, codes, scales);
     else if (t->g_outer == 4)
-        quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, t->d_outer,
+        quant_act_quad<XT, 4, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, win.row0, win.srows, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
                                                                       t->d_clip, cmax, row_scale, codes, scales);
     else
-        quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, rows_per_wg, t->d_outer,
+        quant_act_quad<XT, 8, true, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, win.row0, win.srows, rows_per_wg, t->d_outer,
                                                                       t->outer_stride, t->d_inner, t->inner_stride,
                                                                       t->d_clip, cmax, row_scale, codes, scales);
     return hipGetLastError();
@@ -662,7 +672,7 @@ hipError_t launch_quad(const batq_transform* t, const XT* X, int M, int64_t ldx,
 template <typename XT, bool FP8>
 __global__ void __launch_bounds__(256)
 quant_act_dense(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U, int64_t ldu, int M, int nb,
-                const float* __restrict__ T,
+                int row0, int srows, const float* __restrict__ T,
                 const float* __restrict__ clip, const float* __restrict__ clip_max,
                 const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     __shared__ float sT[32 * 32];
@@ -675,12 +685,12 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U,
     if (row >= M) return;
     if (!live) {
         if constexpr (FP8) {
-            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, 0, nb)) = uint4{0u, 0u, 0u, 0u};
-            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, 1, nb)) = uint4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row0 + row, k, 0, nb)) = uint4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row0 + row, k, 1, nb)) = uint4{0u, 0u, 0u, 0u};
         } else {
-            *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = uint4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4*>(codes + code_chunk_offset(row0 + row, k, nb)) = uint4{0u, 0u, 0u, 0u};
         }
-        scales[scale_index_internal(row, k, M)] = (uint8_t)127;
+        scales[scale_index_internal(row0 + row, k, srows)] = (uint8_t)127;
         return;
     }
     float x[32], y[32];
@@ -730,9 +740,9 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U,
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const uint2 a = encode8_fp8(y + 16 * h, bound, s, sc), b = encode8_fp8(y + 16 * h + 8, bound, s, sc);
-            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row, k, h, nb)) = uint4{a.x, a.y, b.x, b.y};
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(row0 + row, k, h, nb)) = uint4{a.x, a.y, b.x, b.y};
         }
-        scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+        scales[scale_index_internal(row0 + row, k, srows)] = (uint8_t)s;
     } else {
         const uint32_t s = e8m0_of_bound(bound);
         const float sc = scale_operand(s);
@@ -741,16 +751,16 @@ quant_act_dense(const XT* __restrict__ X, int64_t ldx, const XT* __restrict__ U,
         out.y = encode8(y + 8, bound, sc);
         out.z = encode8(y + 16, bound, sc);
         out.w = encode8(y + 24, bound, sc);
-        *reinterpret_cast<uint4*>(codes + code_chunk_offset(row, k, nb)) = out;
-        scales[scale_index_internal(row, k, M)] = (uint8_t)s;
+        *reinterpret_cast<uint4*>(codes + code_chunk_offset(row0 + row, k, nb)) = out;
+        scales[scale_index_internal(row0 + row, k, srows)] = (uint8_t)s;
     }
 }
 
 template <typename XT, bool FP8>
 hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx, const XT* U, int64_t ldu,
-                        const float* row_scale, uint8_t* codes, uint8_t* scales, hipStream_t stream) {
+                        const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, hipStream_t stream) {
     const dim3 grid(scale_groups(t->nb) * 8, (M + 255) / 256), block(256);
-    quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, t->nb, t->d_T, t->d_clip,
+    quant_act_dense<XT, FP8><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, t->nb, win.row0, win.srows, t->d_T, t->d_clip,
                                                           t->minmax ? t->d_clip_max : nullptr, row_scale, codes, scales);
     return hipGetLastError();
 }
@@ -760,7 +770,7 @@ constexpr int kQuadMaxRows = 128;
 template <bool FP8>
 hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
                               const void* U, int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales,
-                              hipStream_t stream) {
+                              RowWindow win, hipStream_t stream) {
     if (xdtype == BATQ_BF16) {
         auto Xp = static_cast<const uint16_t*>(X);
         auto Up = static_cast<const uint16_t*>(U);
@@ -768,19 +778,20 @@ hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype
         // rows (decode steps) the register-level kernel is the faster one for the Kronecker forms: it has no
         // 48 KiB of transform operands per K group to stage before the first row (2.4 us against 4.6 us at
         // 16 rows; the two meet at about 256 rows).
-        const bool few_rows = M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE;
+        // (and writes whole 32-row tiles of codes, so its window must start on one)
+        const bool few_rows = (M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE) || (win.row0 & 31) != 0;
         if (!few_rows && t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25))
-            return Up ? launch_mfma<true>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, FP8, stream)
-                      : launch_mfma<false>(t, Xp, M, ldx, nullptr, 0, row_scale, codes, scales, FP8, stream);
+            return Up ? launch_mfma<true>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, FP8, stream)
+                      : launch_mfma<false>(t, Xp, M, ldx, nullptr, 0, row_scale, codes, scales, win, FP8, stream);
         if (t->form == BATQ_FORM_DENSE)
-            return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
-        return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
+            return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);
+        return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);
     }
     auto Xp = static_cast<const float*>(X);
     auto Up = static_cast<const float*>(U);
     if (t->form == BATQ_FORM_DENSE)
-        return launch_dense<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
-    return launch_quad<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, stream);
+        return launch_dense<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);
+    return launch_quad<float, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);
 }
 
 // 1 / sqrt(mean_j x_j^2 + eps) per row (RMSNorm's row factor), one wave per row, fp32 accumulation.
@@ -806,11 +817,12 @@ row_rms_scale(const XT* __restrict__ X, int64_t ldx, int M, int K, float eps, fl
 
 hipError_t launch_quantize_act(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int K,
                                int64_t ldx, const void* U, int64_t ldu, const float* row_scale, uint8_t* codes,
-                               uint8_t* scales, bool fp8, hipStream_t stream) {
+                               uint8_t* scales, bool fp8, int row_offset, int layout_rows, hipStream_t stream) {
     (void)K;
     if (M == 0) return hipSuccess;
-    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, stream)
-               : launch_quantize_as<false>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, stream);
+    const RowWindow win{row_offset, layout_rows > 0 ? layout_rows : M};
+    return fp8 ? launch_quantize_as<true>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, win, stream)
+               : launch_quantize_as<false>(t, X, xdtype, M, ldx, U, ldu, row_scale, codes, scales, win, stream);
 }
 
 hipError_t launch_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, int64_t ldx, float eps, float* out,

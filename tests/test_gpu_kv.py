@@ -241,3 +241,57 @@ def test_cache_shape_of_the_benchmark_on_sampled_rows(B, bits):
         absref = o.apply_blocks(np.abs(Xf), np.abs(Mat))
         g = got[rq].cpu().numpy().astype(np.float64)
         assert np.all(np.abs(g - ref) <= 2.0 ** -24 * np.abs(ref) + 2.0 ** -20 * absref)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("form", ["kron", "dense"])
+def test_cache_filled_by_appends_equals_one_call(B, bits, form):
+    """A cache laid out for `cap` rows and filled by appends of many sizes (a prefill on the matrix cores from
+    row 0, single decode rows, unaligned and aligned chunks, a large aligned chunk in the middle) holds the codes
+    and scales one call over all rows writes; windows of it dequantise to the oracle's values bit for bit."""
+    import torch
+    cap, K = 600, 1024 + 32                                         # ragged last tile, ragged last K group
+    nb = K // 32
+    w = bi.make_small(cap, K, 8, seed=bits, dtype="bf16")
+    if form == "kron":
+        t = B.Transform(K, w.G, w.P, w.clip)
+    else:
+        t = B.Transform.general(K, dense=o.kron_blocks(w.G, w.P).astype(np.float32), clip=w.clip)
+    X = to_dev(w.X, "bf16")
+    c_ref, s_ref = B.batq_quantize_act_ex(t, X, act_bits=bits)
+    nbytes = B.batq_code8_bytes(cap, K) if bits == 8 else B.batq_code_bytes(cap, K)
+    codes = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")
+    scales = torch.full((B.batq_scale_bytes(cap, K),), 0x5A, dtype=torch.uint8, device="cuda")
+    at = 0
+    for m in (200, 1, 1, 22, 300, 3, 64, 9):                        # starts: 0, 200, 201, 202, 224, 524, 527, 591
+        B.batq_kv_append(t, X[at:at + m], codes, scales, at, cap, bits)
+        at += m
+    assert at == cap
+    torch.cuda.synchronize()
+    to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
+    assert torch.equal(to_rm(codes, cap, K), to_rm(c_ref, cap, K))
+    assert torch.equal(B.batq_scales_to_rowmajor(scales, cap, K), B.batq_scales_to_rowmajor(s_ref, cap, K))
+    # the padding blocks of the last K group carry zero codes and the neutral scale in every row
+    Kp = (nb + 7) // 8 * 256
+    rm_codes = to_rm(codes, cap, K).cpu().numpy()
+    rm_scales = B.batq_scales_to_rowmajor(scales, cap, K).cpu().numpy()
+    dq = o.dequantize_fp8 if bits == 8 else o.dequantize
+    for row0, m in ((0, cap), (37, 150), (31, 1), (599, 1), (224, 300)):
+        ref = dq(rm_codes[row0:row0 + m], rm_scales[row0:row0 + m])
+        got = B.batq_kv_dequantize(codes, scales, cap, row0, m, K, bits, torch.float32)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), ref), (row0, m)
+        gb = B.batq_kv_dequantize(codes, scales, cap, row0, m, K, bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(y_to_f32(gb).astype(np.float64), o.bf16_round(ref).astype(np.float64)), (row0, m)
+    assert Kp >= K
+    # windows that do not fit, and widths that do not exist
+    x1 = X[:4]
+    lib = B.lib
+    args = (t.handle, x1.data_ptr(), 1, 4, K, K)
+    assert lib.batq_kv_append(*args, bits, codes.data_ptr(), scales.data_ptr(), cap - 3, cap, None) == 2
+    assert lib.batq_kv_append(*args, bits, codes.data_ptr(), scales.data_ptr(), -1, cap, None) == 2
+    assert lib.batq_kv_append(*args, 5, codes.data_ptr(), scales.data_ptr(), 0, cap, None) == 4
+    outp = torch.zeros((4, K), device="cuda")
+    assert lib.batq_kv_dequantize(codes.data_ptr(), scales.data_ptr(), cap, cap - 3, 4, K, bits, outp.data_ptr(), 0, K,
+                                  None) == 2
