@@ -138,3 +138,34 @@ def test_gemm_option_combinations(B, case):
         assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol), (case, M, K, N, bits, glu)
     else:
         assert np.all(np.abs(got - ref) <= tol + 1e-30), (case, M, K, N, bits, glu)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_cache_append_chunkings(B, case):
+    """Random capacities, forms, widths and chunkings of the appends (fp32 and bf16 rows): the filled cache equals
+    the one-call result row for row."""
+    import torch
+    rng = np.random.default_rng(9000 + case)
+    K = 32 * int(rng.integers(1, 41))
+    cap = int(rng.integers(1, 700))
+    bits = int(rng.choice([4, 8]))
+    form = str(rng.choice(["identity", "gpk", "private_outer", "naive", "dense"]))
+    dtype = "bf16" if rng.integers(0, 3) else "f32"
+    _, kw = _transform(B, rng, K, form)
+    clip = rng.uniform(0.8, 1.0, K // 32).astype(np.float32)
+    t = B.Transform.general(K, clip=clip, **kw) if kw else B.Transform(K, None, None, clip)
+    w = bi.make_small(cap, K, 8, seed=case, dtype=dtype)
+    X = to_dev(w.X, dtype)
+    c_ref, s_ref = B.batq_quantize_act_ex(t, X, act_bits=bits)
+    nbytes = B.batq_code8_bytes(cap, K) if bits == 8 else B.batq_code_bytes(cap, K)
+    codes = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    scales = torch.full((B.batq_scale_bytes(cap, K),), 0xA5, dtype=torch.uint8, device="cuda")
+    at = 0
+    while at < cap:
+        m = int(min(cap - at, rng.choice([1, 1, 2, 7, 31, 32, 33, 129, 160, 300])))
+        B.batq_kv_append(t, X[at:at + m], codes, scales, at, cap, bits)
+        at += m
+    torch.cuda.synchronize()
+    to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
+    assert torch.equal(to_rm(codes, cap, K), to_rm(c_ref, cap, K)), (cap, K, bits, form, dtype)
+    assert torch.equal(B.batq_scales_to_rowmajor(scales, cap, K), B.batq_scales_to_rowmajor(s_ref, cap, K))
