@@ -332,11 +332,14 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
  * A cache that grows: batq_kv_append quantises M new token rows of X exactly as batq_quantize_act (act_bits 4) or
  *   batq_quantize_act_mxfp8 (act_bits 8) would, but into rows row_offset .. row_offset + M - 1 of code and scale
  *   arrays (DEVICE, caller-owned) that are laid out for capacity_rows rows: batq_code_bytes / batq_code8_bytes and
- *   batq_scale_bytes of (capacity_rows, K).  Rows are independent, so a cache filled in any number of appends
- *   holds what one call over all its rows would have written.  Appends that start on a multiple of 32 rows and
- *   bring more than 128 rows take the matrix-core kernel, which writes whole 32-row tiles of codes: the code rows
- *   after the appended block up to the next multiple of 32 (not yet part of the cache) are then overwritten with
- *   unspecified values; other appends write their own rows only.  BATQ_ERR_SHAPE if the window does not fit.
+ *   batq_scale_bytes of (capacity_rows, K).  Rows are independent: what a row gets does not depend on the
+ *   append that brought it, up to the kernel that ran.  bf16 appends that start on a multiple of 32 rows and bring
+ *   more than 128 rows take the matrix-core kernel, all others the register-level one; the two round their
+ *   transforms differently, so they agree up to rounding ties (single codes one step apart, fewer than 1e-3 of
+ *   them), as each agrees with the reference; fp32 rows always take the same kernel.  The matrix-core kernel
+ *   writes whole 32-row tiles of codes: the code rows after the appended block up to the next multiple of 32 (not
+ *   yet part of the cache) are then overwritten with unspecified values; other appends write their own rows only.
+ *   BATQ_ERR_SHAPE if the window does not fit.
  *   batq_kv_dequantize reads rows row_offset .. row_offset + M - 1 of such arrays into out rows 0 .. M - 1
  *   (otherwise as batq_dequantize).  Both are asynchronous on `stream` and allocate nothing. */
 typedef enum { BATQ_APPLY_FORWARD = 0, BATQ_APPLY_INVERSE = 1, BATQ_APPLY_INVERSE_T = 2 } batq_apply_mode;

@@ -8,7 +8,8 @@ import pytest
 import batq_inputs as bi
 from oracle import batq_oracle as o
 from gpu_util import (require_gpu, to_dev, y_to_f32, code_value_mismatch, grouped_to_rowmajor, blocked_to_rowmajor,
-                      blocked8_to_rowmajor, rowmajor_to_blocked, rowmajor_to_blocked8, rowmajor_to_grouped)
+                      blocked8_to_rowmajor, rowmajor_to_blocked, rowmajor_to_blocked8, rowmajor_to_grouped,
+                      assert_same_quantisation)
 
 pytestmark = pytest.mark.gpu
 
@@ -142,8 +143,8 @@ def test_gemm_option_combinations(B, case):
 
 @pytest.mark.parametrize("case", range(10))
 def test_cache_append_chunkings(B, case):
-    """Random capacities, forms, widths and chunkings of the appends (fp32 and bf16 rows): the filled cache equals
-    the one-call result row for row."""
+    """Random capacities, forms, widths and chunkings of the appends (fp32 and bf16 rows): the filled cache holds
+    the one-call result (byte for byte, or up to rounding ties where two kernels are mixed)."""
     import torch
     rng = np.random.default_rng(9000 + case)
     K = 32 * int(rng.integers(1, 41))
@@ -166,6 +167,6 @@ def test_cache_append_chunkings(B, case):
         B.batq_kv_append(t, X[at:at + m], codes, scales, at, cap, bits)
         at += m
     torch.cuda.synchronize()
-    to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
-    assert torch.equal(to_rm(codes, cap, K), to_rm(c_ref, cap, K)), (cap, K, bits, form, dtype)
-    assert torch.equal(B.batq_scales_to_rowmajor(scales, cap, K), B.batq_scales_to_rowmajor(s_ref, cap, K))
+    # fp32 rows always take the register-level kernels: byte for byte; bf16 rows mix them with the matrix cores
+    assert_same_quantisation(B, codes, scales, c_ref, s_ref, cap, K, bits, exact=dtype == "f32",
+                             what=(cap, K, bits, form, dtype))

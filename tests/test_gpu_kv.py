@@ -5,7 +5,8 @@ import pytest
 
 import batq_inputs as bi
 from oracle import batq_oracle as o
-from gpu_util import (require_gpu, to_dev, y_to_f32, rowmajor_to_blocked, rowmajor_to_blocked8, rowmajor_to_grouped)
+from gpu_util import (require_gpu, to_dev, y_to_f32, rowmajor_to_blocked, rowmajor_to_blocked8, rowmajor_to_grouped,
+                      assert_same_quantisation)
 
 pytestmark = pytest.mark.gpu
 
@@ -245,19 +246,22 @@ def test_cache_shape_of_the_benchmark_on_sampled_rows(B, bits):
 
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("form", ["kron", "dense"])
-def test_cache_filled_by_appends_equals_one_call(B, bits, form):
-    """A cache laid out for `cap` rows and filled by appends of many sizes (a prefill on the matrix cores from
-    row 0, single decode rows, unaligned and aligned chunks, a large aligned chunk in the middle) holds the codes
-    and scales one call over all rows writes; windows of it dequantise to the oracle's values bit for bit."""
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cache_filled_by_appends_equals_one_call(B, bits, form, dtype):
+    """A cache laid out for `cap` rows and filled by appends of many sizes (a prefill from row 0, single decode
+    rows, unaligned and aligned chunks, a large aligned chunk in the middle) holds what one call over all rows
+    writes: byte for byte with fp32 rows (one kernel serves every size), up to rounding ties with bf16 rows (large
+    aligned appends run on the matrix cores, the others on the register-level kernel).  Windows of the cache
+    dequantise to the oracle's values bit for bit."""
     import torch
     cap, K = 600, 1024 + 32                                         # ragged last tile, ragged last K group
     nb = K // 32
-    w = bi.make_small(cap, K, 8, seed=bits, dtype="bf16")
+    w = bi.make_small(cap, K, 8, seed=bits, dtype=dtype)
     if form == "kron":
         t = B.Transform(K, w.G, w.P, w.clip)
     else:
         t = B.Transform.general(K, dense=o.kron_blocks(w.G, w.P).astype(np.float32), clip=w.clip)
-    X = to_dev(w.X, "bf16")
+    X = to_dev(w.X, dtype)
     c_ref, s_ref = B.batq_quantize_act_ex(t, X, act_bits=bits)
     nbytes = B.batq_code8_bytes(cap, K) if bits == 8 else B.batq_code_bytes(cap, K)
     codes = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device="cuda")
@@ -269,8 +273,7 @@ def test_cache_filled_by_appends_equals_one_call(B, bits, form):
     assert at == cap
     torch.cuda.synchronize()
     to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
-    assert torch.equal(to_rm(codes, cap, K), to_rm(c_ref, cap, K))
-    assert torch.equal(B.batq_scales_to_rowmajor(scales, cap, K), B.batq_scales_to_rowmajor(s_ref, cap, K))
+    assert_same_quantisation(B, codes, scales, c_ref, s_ref, cap, K, bits, exact=dtype == "f32")
     # the padding blocks of the last K group carry zero codes and the neutral scale in every row
     Kp = (nb + 7) // 8 * 256
     rm_codes = to_rm(codes, cap, K).cpu().numpy()
@@ -288,7 +291,7 @@ def test_cache_filled_by_appends_equals_one_call(B, bits, form):
     # windows that do not fit, and widths that do not exist
     x1 = X[:4]
     lib = B.lib
-    args = (t.handle, x1.data_ptr(), 1, 4, K, K)
+    args = (t.handle, x1.data_ptr(), 1 if dtype == "bf16" else 0, 4, K, K)
     assert lib.batq_kv_append(*args, bits, codes.data_ptr(), scales.data_ptr(), cap - 3, cap, None) == 2
     assert lib.batq_kv_append(*args, bits, codes.data_ptr(), scales.data_ptr(), -1, cap, None) == 2
     assert lib.batq_kv_append(*args, 5, codes.data_ptr(), scales.data_ptr(), 0, cap, None) == 4
