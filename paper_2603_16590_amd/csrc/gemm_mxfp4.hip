@@ -723,11 +723,13 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
                         const int R = it * kRows + rl;
                         const int chunk = unit ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
                         const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
-                        // streamed out: nothing in this kernel reads Y, and it should not push operand lines
-                        // out of the L2 (cfg2 69.5 -> 67.5 us back to back)
+                        // written through the L2 (device scope): nothing in this kernel reads Y, and lines left
+                        // dirty in the eight L2s would be written back at the end of the kernel (cfg2 back to
+                        // back: plain stores 69.5 us, non-temporal 67.9, write-through 65.7)
                         if (lane_on && row < M) {
                             typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                            __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(yrow));
+                            const u32x4 vv{v.x, v.y, v.z, v.w};
+                            asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(yrow), "v"(vv) : "memory");
                         }
                         row += kRows;
                         yrow += ystep;

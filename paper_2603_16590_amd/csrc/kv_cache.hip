@@ -17,6 +17,13 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// 16-byte store written through the L2 (device scope): for output nobody reads in the same kernel.  Lines left
+// dirty in the eight L2s would be written back when the kernel ends.
+__device__ __forceinline__ void store16_through(void* p, const uint4& q) {
+    const u32x4 v{q.x, q.y, q.z, q.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(v) : "memory");
+}
+
 // 2^(byte - 127) as fp32; byte 0 is the subnormal 2^-127, byte 255 (the format's NaN) gives NaN.
 __device__ __forceinline__ float e8m0_value(uint32_t byte) {
     if (byte == 0u) return __uint_as_float(0x00400000u);
@@ -68,7 +75,7 @@ __device__ __forceinline__ void store8<uint16_t>(uint16_t* p, const float (&v)[8
 template <typename OT, bool FP8>
 __global__ void __launch_bounds__(256)
 dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ scales, int M, int nb, int row0,
-               int srows, OT* __restrict__ out, int64_t ldo) {
+               int srows, OT* __restrict__ out, int64_t ldo, bool big) {
     constexpr int kPerRow = FP8 ? 4 : 2;                   // pieces of a K group per 16-row group
     constexpr int kPieces = 2 * kPerRow;
     constexpr int kSub = FP8 ? 2 : 4;                       // wave instructions per piece
@@ -122,9 +129,11 @@ dequant_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sc
                     q.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 2));
                     q.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(d.x, sc, 3));
                 }
-                // streamed out (no reader in this kernel, nothing left dirty in the L2s at its end):
-                // 131072 x 1024 71 -> 53 us
-                __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(o));
+                // no reader in this kernel, and nothing should be left dirty in the L2s at its end: written
+                // through (32768 x 1024: plain stores 14.1 us, non-temporal 12.9, through 11.1), or, for outputs
+                // beyond the memory-side cache, non-temporal (131072 x 1024: 71 / 53 / 71 us)
+                if (big) __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(o));
+                else store16_through(o, q);
             } else {
                 const float sc = e8m0_value(byte);
                 float v[8];
@@ -197,9 +206,8 @@ constexpr int kApplyLds = kApplyLdsT + kApplyWaves * 2 * kApplySlot;        // 1
 // a wave fetches its unit with LDS-direct loads (rows of 256 contiguous bytes, 16-byte chunk c of row r at
 // position (c & 8) | ((c ^ r) & 7)), prefetching the next unit into its second slot, and sends the results
 // back through the slot it has just emptied, so that the stores are rows of 256 contiguous bytes as well.
-// NT: the output rows are stored non-temporally (faster up to ~150 MB of traffic, where the dirty lines a kernel
-// leaves in the L2s cost a write-back at its end; slower beyond: 268 MB 88 -> 101 us).
-template <typename OT, bool NT>
+// The output rows are written through the L2 (8192 x 4096: plain stores 28.9 us, through 25.8).
+template <typename OT>
 __global__ void __launch_bounds__(kApplyWaves * 64)
 apply_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles_per_wg,
            const uint4* __restrict__ split, OT* __restrict__ out, int64_t ldo) {
@@ -293,8 +301,7 @@ apply_mfma(const uint16_t* __restrict__ X, int64_t ldx, int M, int nb, int tiles
                 if (row0 + r < M && c < 4 * nreal)
                 {
                     uint4* dst = reinterpret_cast<uint4*>(out + (size_t)(row0 + r) * ldo + (size_t)kb * 32 + c * 8);
-                    if constexpr (NT) __builtin_nontemporal_store(u32x4{q.x, q.y, q.z, q.w}, reinterpret_cast<u32x4*>(dst));
-                    else *dst = q;
+                    store16_through(dst, q);
                 }
             }
         } else {
@@ -346,24 +353,16 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
         const bool fits = ((uintptr_t)X | (uintptr_t)out | (uintptr_t)(ldx * 2) | (uintptr_t)(ldo * (int64_t)sizeof(OT))) % 16 == 0 &&
                           ldx < (int64_t(1) << 25);
         if (sp && fits) {
-            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT, false>),
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT>),
                                                                hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
-            static const hipError_t attr_nt = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT, true>),
-                                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
             if (attr != hipSuccess) return attr;
-            if (attr_nt != hipSuccess) return attr_nt;
             const int units = (t->nb + 3) / 4, row_tiles = (M + 31) / 32;
             // about four workgroups per compute unit, at least 16 tiles each (the operands are fetched per workgroup)
             int tiles_per_wg = (int)(((int64_t)row_tiles * units + 1023) / 1024);
             if (tiles_per_wg < 16) tiles_per_wg = 16;
             const dim3 grid(units, (row_tiles + tiles_per_wg - 1) / tiles_per_wg), block(kApplyWaves * 64);
-            const bool nt = sizeof(OT) == 2 && (size_t)M * t->K * 4 <= (size_t(150) << 20);
-            if (nt)
-                apply_mfma<OT, true><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
-                                                                         reinterpret_cast<const uint4*>(sp), out, ldo);
-            else
-                apply_mfma<OT, false><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
-                                                                          reinterpret_cast<const uint4*>(sp), out, ldo);
+            apply_mfma<OT><<<grid, block, kApplyLds, stream>>>(X, ldx, M, t->nb, tiles_per_wg,
+                                                               reinterpret_cast<const uint4*>(sp), out, ldo);
             return hipGetLastError();
         }
     }
@@ -385,14 +384,15 @@ hipError_t launch_dequantize(const uint8_t* codes, const uint8_t* scales, int M,
     const int tiles = ((row_offset + M - 1) >> 5) - (row_offset >> 5) + 1;
     const int64_t units = (int64_t)tiles * scale_groups(nb);                // one wave each, four to a workgroup
     const dim3 grid((unsigned)((units + 3) / 4)), block(256);
+    const bool big = (size_t)M * nb * 32 * (odtype == BATQ_BF16 ? 2 : 4) > (size_t(128) << 20);
     if (odtype == BATQ_BF16) {
         auto o = static_cast<uint16_t*>(out);
-        if (fp8) dequant_kernel<uint16_t, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
-        else dequant_kernel<uint16_t, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
+        if (fp8) dequant_kernel<uint16_t, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo, big);
+        else dequant_kernel<uint16_t, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo, big);
     } else {
         auto o = static_cast<float*>(out);
-        if (fp8) dequant_kernel<float, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
-        else dequant_kernel<float, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo);
+        if (fp8) dequant_kernel<float, true><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo, big);
+        else dequant_kernel<float, false><<<grid, block, 0, stream>>>(codes, scales, M, nb, row_offset, layout_rows, o, ldo, big);
     }
     return hipGetLastError();
 }
