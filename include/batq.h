@@ -333,8 +333,8 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
  *   batq_quantize_act_mxfp8 (act_bits 8) would, but into rows row_offset .. row_offset + M - 1 of code and scale
  *   arrays (DEVICE, caller-owned) that are laid out for capacity_rows rows: batq_code_bytes / batq_code8_bytes and
  *   batq_scale_bytes of (capacity_rows, K).  Rows are independent: what a row gets does not depend on the
- *   append that brought it, up to the kernel that ran.  bf16 appends that start on a multiple of 32 rows and bring
- *   more than 128 rows take the matrix-core kernel, all others the register-level one; the two round their
+ *   append that brought it, up to the kernel that ran.  Of a bf16 append the rows from the first multiple of 32
+ *   on take the matrix-core kernel if they are more than 128, all other rows the register-level one; the two round their
  *   transforms differently, so they agree up to rounding ties (single codes one step apart, fewer than 1e-3 of
  *   them), as each agrees with the reference; fp32 rows always take the same kernel.  The matrix-core kernel
  *   writes whole 32-row tiles of codes: the code rows after the appended block up to the next multiple of 32 (not

@@ -778,9 +778,20 @@ hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype
         // rows (decode steps) the register-level kernel is the faster one for the Kronecker forms: it has no
         // 48 KiB of transform operands per K group to stage before the first row (2.4 us against 4.6 us at
         // 16 rows; the two meet at about 256 rows).
-        // (and writes whole 32-row tiles of codes, so its window must start on one)
-        const bool few_rows = (M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE) || (win.row0 & 31) != 0;
-        if (!few_rows && t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25))
+        // It writes whole 32-row tiles of codes, so its window must start on one: of a long window that does not,
+        // the rows up to the next tile go to the register-level kernel first.
+        const bool mfma_ok = t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25);
+        const int head = (32 - (win.row0 & 31)) & 31;
+        if (mfma_ok && head != 0 && M - head > kQuadMaxRows) {
+            hipError_t e = launch_quantize_as<FP8>(t, X, xdtype, head, ldx, U, ldu, row_scale, codes, scales, win, stream);
+            if (e != hipSuccess) return e;
+            return launch_quantize_as<FP8>(t, Xp + (size_t)head * ldx, xdtype, M - head, ldx,
+                                           Up ? Up + (size_t)head * ldu : nullptr, ldu,
+                                           row_scale ? row_scale + head : nullptr, codes, scales,
+                                           RowWindow{win.row0 + head, win.srows}, stream);
+        }
+        const bool few_rows = (M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE) || head != 0;
+        if (!few_rows && mfma_ok)
             return Up ? launch_mfma<true>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, FP8, stream)
                       : launch_mfma<false>(t, Xp, M, ldx, nullptr, 0, row_scale, codes, scales, win, FP8, stream);
         if (t->form == BATQ_FORM_DENSE)
