@@ -752,7 +752,15 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
                 if (row < M) {
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
-                        if (col0 + 32 * j < N) store_y<YT>(yp + 32 * j, value(i, j, 4 * q + r));
+                        if (col0 + 32 * j < N) {
+                            if constexpr (sizeof(YT) == 4) {
+                                // 32 lanes fill a 128-byte line: written through the L2 like the bf16 rows above
+                                const float fv = value(i, j, 4 * q + r);
+                                asm volatile("global_store_dword %0, %1, off sc1" :: "v"(yp + 32 * j), "v"(fv) : "memory");
+                            } else {
+                                store_y<YT>(yp + 32 * j, value(i, j, 4 * q + r));
+                            }
+                        }
                 }
                 ++row;
                 yp += ldy;
