@@ -76,6 +76,21 @@ def test_null_handles_are_rejected(B):
     assert lib.batq_weight_shape(None, C.byref(k), C.byref(n)) == 1
 
 
+def test_cache_window_arguments_are_checked_on_the_host(B):
+    lib = B.lib
+    # widths and windows are looked at before the handle or any pointer
+    assert lib.batq_kv_append(None, None, 1, 4, 64, 64, 5, None, None, 0, 16, None) == 4
+    assert lib.batq_kv_append(None, None, 1, 4, 64, 64, 4, None, None, 13, 16, None) == 2         # 13 + 4 > 16
+    assert lib.batq_kv_append(None, None, 1, 4, 64, 64, 8, None, None, -1, 16, None) == 2
+    assert lib.batq_kv_append(None, None, 1, 4, 64, 64, 8, None, None, 0, 0, None) == 2
+    assert lib.batq_kv_append(None, None, 1, 4, 64, 64, 8, None, None, 0, 16, None) == 1          # then the handle
+    assert lib.batq_kv_dequantize(None, None, 16, 13, 4, 64, 4, None, 1, 64, None) == 2
+    assert lib.batq_kv_dequantize(None, None, 0, 0, 0, 64, 4, None, 1, 64, None) == 2
+    assert lib.batq_kv_dequantize(None, None, 16, 0, 4, 64, 6, None, 1, 64, None) == 4
+    assert lib.batq_kv_dequantize(None, None, 16, 0, 4, 64, 4, None, 1, 64, None) == 1            # null arrays
+    assert lib.batq_kv_dequantize(None, None, 16, 16, 0, 64, 4, None, 1, 64, None) == 0           # empty window
+
+
 def test_workspace_size(B):
     assert B.batq_linear_workspace(2048, 4096) == 2048 * 2048 + 2048 * 128
     assert B.batq_linear_workspace(16, 4096) % 16 == 0
