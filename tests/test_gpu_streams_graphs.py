@@ -110,3 +110,46 @@ def test_split_k_gemm_in_graphs(B):
         assert float((outs[0] - ref).abs().max()) <= 1e-5 * scale
         if warm:
             assert torch.equal(outs[0], ref)
+
+
+def test_cache_calls_inside_a_captured_graph(B):
+    """A decode step on the cache (append one row, read the window back, transform the query) captured once and
+    replayed at a moving position is not possible (the position is a launch argument), so the graph holds the step
+    for one position and its replays must give the eager result every time, with eager appends in between."""
+    import torch
+    D, cap = 32 * 12, 200
+    w = bi.make_small(cap, D, 8, seed=4, dtype="bf16")
+    t = B.Transform(D, w.G, w.P, w.clip)
+    X = to_dev(w.X, "bf16")
+    codes = torch.zeros(B.batq_code8_bytes(cap, D), dtype=torch.uint8, device="cuda")
+    scales = torch.zeros(B.batq_scale_bytes(cap, D), dtype=torch.uint8, device="cuda")
+    B.batq_kv_append(t, X[:150], codes, scales, 0, cap, 8)          # prefill on the matrix cores
+    q = X[150:154]
+    # eager reference for the step at position 150
+    c_ref, s_ref = codes.clone(), scales.clone()
+    B.batq_kv_append(t, X[150:151], c_ref, s_ref, 150, cap, 8)
+    win_ref = B.batq_kv_dequantize(c_ref, s_ref, cap, 0, 151, D, 8)
+    q_ref = B.batq_transform_apply(t, q, B.APPLY_INVERSE_T)
+    torch.cuda.synchronize()
+    win = torch.empty_like(win_ref)
+    qt = torch.empty_like(q_ref)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                                    # first calls outside the capture
+        B.batq_kv_append(t, X[150:151], codes, scales, 150, cap, 8)
+        B.batq_kv_dequantize(codes, scales, cap, 0, 151, D, 8, out=win)
+        B.batq_transform_apply(t, q, B.APPLY_INVERSE_T, out=qt)
+    side.synchronize()
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr, stream=side):
+        B.batq_kv_append(t, X[150:151], codes, scales, 150, cap, 8)
+        B.batq_kv_dequantize(codes, scales, cap, 0, 151, D, 8, out=win)
+        B.batq_transform_apply(t, q, B.APPLY_INVERSE_T, out=qt)
+    for rep in range(3):
+        win.zero_()
+        qt.zero_()
+        B.batq_kv_append(t, X[160 + rep:161 + rep], codes, scales, 160 + rep, cap, 8)      # eager work in between
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(win, win_ref), rep
+        assert torch.equal(qt, q_ref), rep
