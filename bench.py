@@ -8,6 +8,14 @@ synthetic activations that is already resident in HBM.  Prints ONE JSON line.
 The timed loop rotates over enough distinct (X, workspace, Y) buffer sets that the
 footprint exceeds twice the 256 MB last-level cache, so the activation kernel is
 measured against HBM and not against the cache.
+
+Method: after the warm-up, the loop of --steps steps is timed --repeats times (each repeat
+bracketed by a device synchronisation); ms_per_step and value are the median repeat, the
+fastest and slowest are reported beside it.  Kernel durations come from HIP events on the
+launch stream around --steps launches of the kernel alone, again the median of the repeats.
+The shader clock and board power the tool `rocm-smi` shows while the step loop runs are
+recorded in `clock_state` (the matrix kernels run at the board's power limit, so the clock
+explains most of the spread between boxes and runs).
 """
 from __future__ import annotations
 
@@ -39,9 +47,11 @@ def main():
     ap.add_argument("--workload", type=int, default=2, choices=[0, 1, 2, 3, 4],
                     help="which synthetic configuration is the timed workload (default: 8B-class prefill up/gate)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--also", type=str, default="3", help="comma list of other configs to time briefly ('' = none)")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repeats of the --steps loop; the median is reported")
+    ap.add_argument("--also", type=str, default="0,1,3,4",
+                    help="comma list of other configs to time briefly ('' = none); all five are in the line by default")
+    ap.add_argument("--no-clock-state", action="store_true", help="do not call rocm-smi")
     ap.add_argument("--no-w4a8", action="store_true", help="skip the W4A8 side measurement")
-    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape side measurement (cfg1)")
     ap.add_argument("--no-two-streams", action="store_true",
                     help="skip the two-stream side measurement (its overlapping kernels distort a kernel trace)")
     ap.add_argument("--no-kv", action="store_true", help="skip the key/value-cache side measurement")
@@ -67,7 +77,7 @@ def main():
             return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).cuda()
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
-    def run_config(cfg: int, steps: int, warmup: int, a8: bool = False):
+    def run_config(cfg: int, steps: int, warmup: int, a8: bool = False, repeats: int = 5, rotate_weights: bool = True):
         # a8: the W4A8 variant of the same layer (MXFP8 activations, same MXFP4 weights)
         linear = B.batq_linear_a8w4 if a8 else B.batq_linear
         quantize = B.batq_quantize_act_mxfp8 if a8 else B.batq_quantize_act
@@ -78,7 +88,8 @@ def main():
         ydt = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
         xbytes = 2 if w.dtype == "bf16" else 4
         ybytes = 2 if w.out_dtype == "bf16" else 4
-        wsz = B.batq_linear_a8w4_workspace(w.M, w.K) if a8 else B.batq_linear_workspace(w.M, w.K)
+        # workspace of a step: codes, scales and (shapes that want them) the partial sums of the GEMM's K parts
+        wsz = B.batq_linear_workspace_for(wh, w.M, 8 if a8 else 4)
         per_set = w.M * w.K * xbytes + wsz + w.M * w.N * ybytes
         nsets = max(2, min(64, -(-(600 << 20) // per_set)))
         X0 = to_dev(w.X, w.dtype)
@@ -86,22 +97,30 @@ def main():
         Ws = [torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda") for _ in range(nsets)]
         Ys = [torch.empty((w.M, w.N), dtype=ydt, device="cuda") for _ in range(nsets)]
         cb = B.batq_code8_bytes(w.M, w.K) if a8 else B.batq_code_bytes(w.M, w.K)
+        sb = B.batq_scale_bytes(w.M, w.K)
+        parts_at = -(-(cb + sb) // 256) * 256
         codes = [wk[:cb] for wk in Ws]
-        scales = [wk[cb: wsz] for wk in Ws]
+        scales = [wk[cb: cb + sb] for wk in Ws]
 
         def step(i):
             j = i % nsets
             linear(t, wh, Xs[j], Y=Ys[j], workspace=Ws[j])
 
+        def median(v):
+            v = sorted(v)
+            return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
+
         for i in range(warmup):
             step(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            step(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_step = (t1 - t0) * 1e3 / steps
+        step_ms = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                step(i)
+            torch.cuda.synchronize()
+            step_ms.append((time.perf_counter() - t0) * 1e3 / steps)
+        ms_step = median(step_ms)
 
         # the same steps handed to two streams in turn (independent batches, as a server with more than one
         # request in flight would): the tail of one step's GEMM overlaps with the head of the next step
@@ -111,26 +130,32 @@ def main():
             for i in range(warmup):
                 with torch.cuda.stream(two[i & 1]):
                     step(i)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(steps):
-                with torch.cuda.stream(two[i & 1]):
-                    step(i)
-            torch.cuda.synchronize()
-            ms_step_two = (time.perf_counter() - t0) * 1e3 / steps
+            two_ms = []
+            for _ in range(repeats):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(steps):
+                    with torch.cuda.stream(two[i & 1]):
+                        step(i)
+                torch.cuda.synchronize()
+                two_ms.append((time.perf_counter() - t0) * 1e3 / steps)
+            ms_step_two = median(two_ms)
 
-        # per-kernel durations: HIP events on the stream the kernels are launched on
+        # per-kernel durations: HIP events on the stream the kernels are launched on, median of the repeats
         def timed(fn, n):
             for i in range(min(warmup, 10)):
                 fn(i)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            e0.record()
-            for i in range(n):
-                fn(i)
-            e1.record()
-            e1.synchronize()
-            return e0.elapsed_time(e1) / n
+            out = []
+            for _ in range(repeats):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                e1.synchronize()
+                out.append(e0.elapsed_time(e1) / n)
+            return median(out), min(out), max(out)
 
         # the quantiser alone touches only X and the codes: rotate over enough sets of those that their footprint
         # exceeds twice the 256 MB memory-side cache
@@ -139,27 +164,49 @@ def main():
             Xs.append(X0.clone())
             Ws.append(torch.empty(max(wsz, 16), dtype=torch.uint8, device="cuda"))
         qcodes = [wk[:cb] for wk in Ws]
-        qscales = [wk[cb: wsz] for wk in Ws]
-        ms_quant = timed(lambda i: quantize(t, Xs[i % nq], qcodes[i % nq], qscales[i % nq]), steps)
-        ms_gemm = timed(lambda i: gemm(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets]), steps)
-        ms_quant_warm = timed(lambda i: quantize(t, Xs[0], codes[0], scales[0]), steps)
+        qscales = [wk[cb: cb + sb] for wk in Ws]
+        parts = [wk[parts_at:] if wk.numel() > parts_at else None for wk in Ws]
+        ms_quant, ms_quant_min, ms_quant_max = timed(lambda i: quantize(t, Xs[i % nq], qcodes[i % nq], qscales[i % nq]), steps)
+        ms_gemm, ms_gemm_min, ms_gemm_max = timed(
+            lambda i: gemm(codes[i % nsets], scales[i % nsets], wh, w.M, Y=Ys[i % nsets], workspace=parts[i % nsets]), steps)
+        ms_quant_warm, _, _ = timed(lambda i: quantize(t, Xs[0], codes[0], scales[0]), steps)
+        # the GEMM with the weights coming from HBM: enough copies of the prepared weight taking turns that their
+        # footprint exceeds the 256 MB memory-side cache (the figure above re-reads one weight, which stays in it)
+        wbytes = w.K * w.N * (0.5 + 1.0 / 32)
+        nw = max(10, -(-(300 << 20) // int(wbytes))) if rotate_weights else 0
+        ms_gemm_rot = None
+        if nw:
+            wcodes, wscales = wh.export()
+            whs = [wh] + [B.batq_weight_import(wcodes, wscales, w.K, w.N) for _ in range(nw - 1)]
+            del wcodes, wscales
+            ms_gemm_rot, _, _ = timed(
+                lambda i: gemm(codes[i % nsets], scales[i % nsets], whs[i % nw], w.M, Y=Ys[i % nsets],
+                               workspace=parts[i % nsets]), steps)
+            del whs
 
         flops = 2.0 * w.M * w.K * w.N
         qbytes = w.M * w.K * (xbytes + (1.0 if a8 else 0.5) + 1.0 / 32)
         res = {
             "workload": f"cfg{cfg}:{w.name} M={w.M} K={w.K} N={w.N} x={w.dtype} y={w.out_dtype}",
-            "ms_per_step": ms_step,
+            "ms_per_step": ms_step, "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms),
+            "repeats": repeats, "steps_per_repeat": steps,
             "linear_tflops": flops / ms_step / 1e9,
             "ms_per_step_two_streams": ms_step_two,
             "linear_tflops_two_streams": flops / ms_step_two / 1e9 if ms_step_two else None,
             "quant_ms": ms_quant, "quant_gbs": qbytes / ms_quant / 1e6,
             "quant_gbs_cache_warm": qbytes / ms_quant_warm / 1e6,
-            "gemm_ms": ms_gemm, "gemm_tflops": flops / ms_gemm / 1e9,
+            "quant_ms_min": ms_quant_min, "quant_ms_max": ms_quant_max,
+            "gemm_ms": ms_gemm, "gemm_ms_min": ms_gemm_min, "gemm_ms_max": ms_gemm_max,
+            "gemm_tflops": flops / ms_gemm / 1e9,
+            "gemm_ms_rotating_weights": ms_gemm_rot, "weight_copies": nw,
+            "gemm_tflops_rotating_weights": flops / ms_gemm_rot / 1e9 if ms_gemm_rot else None,
+            "gemm_frac_of_fp4_peak": flops / ms_gemm / 1e9 / PEAK_FP4_TFLOPS,
+            "quant_frac_of_hbm_peak": qbytes / ms_quant / 1e6 / PEAK_HBM_GBS,
             "buffer_sets": nsets, "quant_buffer_sets": nq,
         }
         return w, t, wh, res, flops, qbytes
 
-    w, t, wh, res, flops, qbytes = run_config(args.workload, args.steps, args.warmup)
+    w, t, wh, res, flops, qbytes = run_config(args.workload, args.steps, args.warmup, repeats=args.repeats)
 
     # the dominant kernel of the step decides which roofline is reported first
     gemm_dominant = res["gemm_ms"] >= res["quant_ms"]
@@ -167,27 +214,133 @@ def main():
                  "unit": "TFLOP/s", "frac": res["gemm_tflops"] / PEAK_FP4_TFLOPS, "traffic": None}
     roof_quant = {"kernel": "quant_act_mfma", "bound": "hbm", "achieved": res["quant_gbs"], "peak": PEAK_HBM_GBS,
                   "unit": "GB/s", "frac": res["quant_gbs"] / PEAK_HBM_GBS, "traffic": None}
+    # HBM traffic per launch is not measured in this run: it comes from the stored rocprofv3 --pmc profile
+    # (FETCH_SIZE / WRITE_SIZE, calibrated on a copy kernel), whose file says which commit it was taken at
     traffic_file = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    traffic_source = None
     if os.path.exists(traffic_file):
         try:
-            tr = json.load(open(traffic_file)).get(f"cfg{args.workload}", {})
+            stored = json.load(open(traffic_file))
+            tr = stored.get(f"cfg{args.workload}", {})
             roof_gemm["traffic"] = tr.get("gemm_tiled")
             roof_quant["traffic"] = tr.get("quant_act_mfma")
+            traffic_source = {"file": "profiles/pmc_traffic.json", "kind": "stored rocprofv3 --pmc profile, not this run",
+                              "measured_at_commit": stored.get("measured_at_commit")}
         except Exception:
             pass
+    roof_gemm["traffic_source"] = roof_quant["traffic_source"] = traffic_source
+    roof_gemm.update({"ms": res["gemm_ms"], "ms_min": res["gemm_ms_min"], "ms_max": res["gemm_ms_max"],
+                      "achieved_rotating_weights": res["gemm_tflops_rotating_weights"]})
+    roof_quant.update({"ms": res["quant_ms"], "ms_min": res["quant_ms_min"], "ms_max": res["quant_ms_max"]})
+
+    # Shader clock and board power while the step loop runs (rocm-smi is slow, so half a second of steps is
+    # queued first); best effort: the headline numbers do not depend on it.
+    clock_state = None
+    if not args.no_clock_state:
+        import re
+        import shutil
+        import subprocess
+        smi = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+        try:
+            Xc = to_dev(w.X, w.dtype)
+            Yc = torch.empty((w.M, w.N), dtype=torch.bfloat16 if w.out_dtype == "bf16" else torch.float32, device="cuda")
+            wk = torch.empty(max(B.batq_linear_workspace_for(wh, w.M), 16), dtype=torch.uint8, device="cuda")
+            for _ in range(int(0.6 / max(res["ms_per_step"] * 1e-3, 1e-6))):
+                B.batq_linear(t, wh, Xc, Y=Yc, workspace=wk)
+            out = subprocess.run([smi, "-d", "0", "--showclocks", "--showpower", "--showmaxpower", "--showtemp"],
+                                 capture_output=True, text=True, timeout=30).stdout
+            torch.cuda.synchronize()
+            def grab(pat):
+                m = re.search(pat, out)
+                return m.group(1) if m else None
+            clock_state = {
+                "source": "rocm-smi while the step loop runs",
+                "sclk": grab(r"sclk clock level[^\n]*?\((\d+Mhz)\)"),
+                "mclk": grab(r"mclk clock level[^\n]*?\((\d+Mhz)\)"),
+                "power_w": grab(r"Graphics Package Power \(W\):\s*([\d.]+)") or grab(r"Power \(W\):\s*([\d.]+)"),
+                "power_cap_w": grab(r"Max Graphics Package Power \(W\):\s*([\d.]+)"),
+                "junction_temp_c": grab(r"Temperature \(Sensor junction\) \(C\):\s*([\d.]+)"),
+            }
+            del Xc, Yc, wk
+        except Exception as e:
+            clock_state = {"error": str(e)}
+
+    # Small-M shapes (cfg0: 64 tokens, cfg1: 16 tokens, the decode shape): the GEMM is one pass over the weight
+    # codes, so it is reported as a streaming rate over the weight's codes and scales, with enough copies of the
+    # weight taking turns to exceed the memory-side cache (at least 32).  The kernels take a few microseconds, less
+    # than a launch from Python, so they are timed as replays of a captured graph of one call per weight copy.
+    def small_config(cfg: int):
+        w1 = bi.make_workload(cfg)
+        t1_ = B.Transform(w1.K, w1.G, w1.P, w1.clip)
+        Wd1 = to_dev(w1.W, w1.dtype)
+        wbytes = w1.K * w1.N * (0.5 + 1.0 / 32)
+        ncopy = max(32, min(512, -(-(300 << 20) // int(wbytes))))
+        first = B.batq_prepare_weight(t1_, Wd1)
+        wcodes, wscales = first.export()
+        whs = [first] + [B.batq_weight_import(wcodes, wscales, w1.K, w1.N) for _ in range(ncopy - 1)]
+        X1 = to_dev(w1.X, w1.dtype)
+        ws1_ = torch.empty(max(B.batq_linear_workspace_for(first, w1.M), 16), dtype=torch.uint8, device="cuda")
+        cb1, sb1 = B.batq_code_bytes(w1.M, w1.K), B.batq_scale_bytes(w1.M, w1.K)
+        pa1 = -(-(cb1 + sb1) // 256) * 256
+        parts1 = ws1_[pa1:] if ws1_.numel() > pa1 else None
+        ydt = torch.bfloat16 if w1.out_dtype == "bf16" else torch.float32
+        Y1 = torch.empty((w1.M, w1.N), dtype=ydt, device="cuda")
+        side = torch.cuda.Stream()
+
+        def graph_us(fn):
+            with torch.cuda.stream(side):
+                for i in range(ncopy):
+                    fn(i)
+            side.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                for i in range(ncopy):
+                    fn(i)
+            gr.replay()
+            torch.cuda.synchronize()
+            out = []
+            for _ in range(args.repeats):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(4):
+                    gr.replay()
+                e1.record()
+                e1.synchronize()
+                out.append(e0.elapsed_time(e1) / (4 * ncopy) * 1e3)
+            return sorted(out)[len(out) // 2]
+
+        us_lin = graph_us(lambda i: B.batq_linear(t1_, whs[i], X1, Y=Y1, workspace=ws1_))
+        us_q = graph_us(lambda i: B.batq_quantize_act(t1_, X1, ws1_[:cb1], ws1_[cb1:cb1 + sb1]))
+        us_g = graph_us(lambda i: B.batq_gemm_mxfp4(ws1_[:cb1], ws1_[cb1:cb1 + sb1], whs[i], w1.M, Y=Y1, workspace=parts1))
+        xb = 2 if w1.dtype == "bf16" else 4
+        res1 = {"workload": f"cfg{cfg}:{w1.name} M={w1.M} K={w1.K} N={w1.N} x={w1.dtype} y={w1.out_dtype}",
+                "linear_us": us_lin, "linear_tflops": 2.0 * w1.M * w1.K * w1.N / us_lin / 1e6,
+                "quant_us": us_q, "quant_gbs": w1.M * w1.K * (xb + 0.5 + 1.0 / 32) / us_q / 1e3,
+                "gemm_us": us_g, "gemm_weight_stream_gbs": wbytes / us_g / 1e3,
+                "gemm_frac_of_hbm_peak": wbytes / us_g / 1e3 / PEAK_HBM_GBS, "weight_copies": ncopy,
+                "note": "graph replays of one call per weight copy (launch gaps between dependent kernels included), "
+                        "median of the repeats; the GEMM streams the weight once, so it is rated in GB/s over the "
+                        "weight codes and scales"}
+        del whs, Wd1, first, wcodes, wscales
+        torch.cuda.empty_cache()
+        return res1
 
     also = {}
     for c in [int(x) for x in args.also.split(",") if x.strip() != ""]:
         if c == args.workload:
             continue
-        _, _, _, r, _, _ = run_config(c, max(10, args.steps // 4), max(3, args.warmup // 4))
+        if c in (0, 1):
+            also[f"cfg{c}"] = small_config(c)
+            continue
+        _, _, _, r, _, _ = run_config(c, max(10, args.steps // 4), max(3, args.warmup // 4), repeats=args.repeats)
         also[f"cfg{c}"] = r
         torch.cuda.empty_cache()
 
     # the W4A8 variant of the same workload (MXFP8 activations): its matrix instructions run at the FP8 rate
     w4a8 = None
     if not args.no_w4a8:
-        _, _, _, r8, _, _ = run_config(args.workload, max(10, args.steps // 4), max(3, args.warmup // 4), a8=True)
+        _, _, _, r8, _, _ = run_config(args.workload, max(10, args.steps // 4), max(3, args.warmup // 4), a8=True,
+                                       repeats=args.repeats, rotate_weights=False)
         r8["gemm_frac_of_fp8_rate_peak"] = r8["gemm_tflops"] / PEAK_FP8_TFLOPS
         r8["quant_frac_of_hbm_peak"] = r8["quant_gbs"] / PEAK_HBM_GBS
         w4a8 = r8
@@ -218,8 +371,8 @@ def main():
         w_d = B.batq_prepare_weight(t_down, Wd)
         del Wg, Wu, Wd
         Xm = torch.randn((Mm, D), device="cuda", generator=gen).to(torch.bfloat16)
-        ws1 = torch.empty(B.batq_linear_workspace(Mm, D), dtype=torch.uint8, device="cuda")
-        ws2 = torch.empty(B.batq_linear_workspace(Mm, Fh), dtype=torch.uint8, device="cuda")
+        ws1 = torch.empty(B.batq_linear_workspace_for(w_gu, Mm), dtype=torch.uint8, device="cuda")
+        ws2 = torch.empty(B.batq_linear_workspace_for(w_d, Mm), dtype=torch.uint8, device="cuda")
         GU = torch.empty((Mm, 2 * Fh), dtype=torch.bfloat16, device="cuda")
         Hh = torch.empty((Mm, Fh), dtype=torch.bfloat16, device="cuda")
         Ym = torch.empty((Mm, D), dtype=torch.bfloat16, device="cuda")
@@ -252,51 +405,6 @@ def main():
                "ms_separate_activation_pass": ms_sep, "ms_gated_epilogue": ms_epi,
                "tflops_gated_epilogue": 6.0 * Mm * D * Fh / ms_epi / 1e9}
         del w_gu, w_d, GU, Hh, Ym, ws1, ws2, Xm
-        torch.cuda.empty_cache()
-
-    # Decode shape (cfg1: 16 tokens): the GEMM is one pass over the weight codes, so it is reported as a
-    # streaming rate over the weight's codes and scales, with 32 copies of the weight taking turns (285 MB, more
-    # than the memory-side cache).  The kernels take a few microseconds, less than a launch from Python, so
-    # they are timed as replays of a captured graph of 32 calls.
-    decode = None
-    if not args.no_decode:
-        w1 = bi.make_workload(1)
-        t1_ = B.Transform(w1.K, w1.G, w1.P, w1.clip)
-        Wd1 = to_dev(w1.W, w1.dtype)
-        whs = [B.batq_prepare_weight(t1_, Wd1) for _ in range(32)]
-        X1 = to_dev(w1.X, w1.dtype)
-        ws1_ = torch.empty(B.batq_linear_workspace(w1.M, w1.K), dtype=torch.uint8, device="cuda")
-        cb1 = B.batq_code_bytes(w1.M, w1.K)
-        Y1 = torch.empty((w1.M, w1.N), dtype=torch.bfloat16, device="cuda")
-        side = torch.cuda.Stream()
-
-        def graph_us(fn):
-            with torch.cuda.stream(side):
-                for i in range(32):
-                    fn(i)
-            side.synchronize()
-            gr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gr, stream=side):
-                for i in range(32):
-                    fn(i)
-            gr.replay()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                gr.replay()
-            e1.record()
-            e1.synchronize()
-            return e0.elapsed_time(e1) / (20 * 32) * 1e3
-
-        us_lin = graph_us(lambda i: B.batq_linear(t1_, whs[i], X1, Y=Y1, workspace=ws1_))
-        us_q = graph_us(lambda i: B.batq_quantize_act(t1_, X1, ws1_[:cb1], ws1_[cb1:]))
-        us_g = graph_us(lambda i: B.batq_gemm_mxfp4(ws1_[:cb1], ws1_[cb1:], whs[i], w1.M, Y=Y1))
-        wbytes = w1.K * w1.N * (0.5 + 1.0 / 32)
-        decode = {"workload": f"cfg1:{w1.name} M={w1.M} K={w1.K} N={w1.N}", "linear_us": us_lin, "quant_us": us_q,
-                  "gemm_us": us_g, "gemm_weight_stream_gbs": wbytes / us_g / 1e3,
-                  "note": "graph replays of 32 calls (launch gaps between dependent kernels included), 32 weight copies"}
-        del whs, Wd1
         torch.cuda.empty_cache()
 
     # Key/value-cache helpers (Sec. 3.2): a cache of 32768 tokens x 8 heads x 128 channels written by the
@@ -405,6 +513,9 @@ def main():
         "metric": "W4A4 MXFP4 linear TFLOP/s incl. online transform+quantize",
         "value": res["linear_tflops"], "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "repeats": args.repeats, "ms_per_step_min": res["ms_per_step_min"], "ms_per_step_max": res["ms_per_step_max"],
+        "timing": "median of `repeats` timed loops of `steps` steps each, synchronised on both sides",
+        "clock_state": clock_state,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "mxfp4 (e2m1 x e8m0), fp32 accumulate", "data": "synthetic",
         "config": {"workload": res["workload"], "block": 32, "gpk": "G4x4 (x) P8x8", "buffer_sets": res["buffer_sets"]},
@@ -412,6 +523,7 @@ def main():
                         "note": "same steps issued to two streams in turn; the headline value is the one-stream figure"},
         "quantize_gbs": res["quant_gbs"], "quantize_gbs_cache_warm": res["quant_gbs_cache_warm"],
         "gemm_tflops": res["gemm_tflops"], "quant_ms": res["quant_ms"], "gemm_ms": res["gemm_ms"],
+        "gemm_tflops_rotating_weights": res["gemm_tflops_rotating_weights"],
         "roofline": roof_gemm if gemm_dominant else roof_quant,
         "roofline_other": roof_quant if gemm_dominant else roof_gemm,
         "measured_ceilings": ceilings,
@@ -420,7 +532,6 @@ def main():
         "w4a8": w4a8,
         "mlp_block": mlp,
         "kv_cache": kv,
-        "decode": decode,
     }
     print(json.dumps(line))
 

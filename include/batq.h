@@ -51,11 +51,15 @@
  *     valid until the stream has passed the call.  The caller owns every tensor it
  *     passes; the library owns only what is inside its handles.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Online calls (batq_quantize_act, batq_gemm_mxfp4, batq_linear) only enqueue
- *     work: no host synchronisation and no allocation.
+ *     Online calls (batq_quantize_act*, batq_gemm_*, batq_linear*, the cache calls) only
+ *     enqueue kernels: no host synchronisation, no allocation, no state kept between
+ *     calls.  Which kernels run is a function of the call's arguments and the device
+ *     alone, so a call gives the same bits on any stream, eagerly or while the stream
+ *     is captured into a graph.  Scratch memory comes from the caller (`workspace`).
  *   - Argument errors are detected on the host before anything is launched and
  *     leave all outputs untouched.  Non-finite inputs are outside the contract.
- *   - Calls on distinct handles are thread-safe.
+ *   - Calls are thread-safe; a handle may be used by several threads at once (online
+ *     calls only read it), but not destroyed while in use.
  */
 #ifndef BATQ_H
 #define BATQ_H
@@ -208,12 +212,27 @@ batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* device_o
  * bf16 (round-to-nearest-even). */
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
                             int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+/* The same with scratch memory for K parts.  Shapes with few output tiles and a long K (down projections at a
+ * few hundred rows; at most 64 rows against a narrow N) are faster when K is cut into parts whose fp32 partial
+ * sums are added by a second kernel, in part order (deterministic).  batq_gemm_workspace(w, M, act_bits) is the
+ * number of bytes with which the GEMM of M rows against `w` uses all the parts it wants (0: the shape wants
+ * none; act_bits 4 or 0 for batq_gemm_mxfp4_ws, 8 for batq_gemm_a8w4_ws).  `workspace` is DEVICE memory, 256-byte
+ * aligned, or NULL with workspace_bytes 0; a smaller workspace gives fewer parts, none gives the plain call.
+ * The number of parts, and with it the fp32 rounding of Y, depends on (M, w, workspace_bytes, device) only. */
+size_t batq_gemm_workspace(const batq_weight* w, int M, int act_bits);
+batq_status batq_gemm_mxfp4_ws(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
+                               int M, void* Y, batq_dtype ydtype, int64_t ldy,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
- * `workspace` is DEVICE memory (16-byte aligned) of at least batq_linear_workspace(M, K)
+ * `workspace` is DEVICE memory (256-byte aligned) of at least batq_linear_workspace(M, K)
  * bytes (= batq_code_bytes(M, K) + batq_scale_bytes(M, K)).  It holds the activation codes
- * (at offset 0) followed by their scales, both in device order, between the two kernels. */
+ * (at offset 0) followed by their scales, both in device order, between the two kernels.
+ * What it holds beyond that (from the next 256-byte boundary on) serves the GEMM's K parts as in
+ * batq_gemm_mxfp4_ws: batq_linear_workspace_for(w, M, act_bits) is the size with which every call of
+ * the batq_linear family on M rows against `w` runs as fast as it can (>= batq_linear_workspace). */
 size_t batq_linear_workspace(int M, int K);
+size_t batq_linear_workspace_for(const batq_weight* w, int M, int act_bits);
 batq_status batq_linear(const batq_transform* t, const batq_weight* w,
                         const void* X, batq_dtype xdtype, int M, int64_t ldx,
                         void* Y, batq_dtype ydtype, int64_t ldy,
@@ -241,6 +260,9 @@ batq_status batq_codes8_from_rowmajor(const uint8_t* rowmajor, uint8_t* device_o
 /* Y[m][n] = sum_k 2^(xs[m][k]-127) 2^(ws[n][k]-127) sum_{j<32} e4m3(xq8[m][32k+j]) val(wq[n][32k+j]) */
 batq_status batq_gemm_a8w4(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w,
                            int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+batq_status batq_gemm_a8w4_ws(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w,
+                              int M, void* Y, batq_dtype ydtype, int64_t ldy,
+                              void* workspace, size_t workspace_bytes, void* stream);
 size_t batq_linear_a8w4_workspace(int M, int K);
 batq_status batq_linear_a8w4(const batq_transform* t, const batq_weight* w,
                              const void* X, batq_dtype xdtype, int M, int64_t ldx,
@@ -296,7 +318,7 @@ batq_status batq_row_rms_scale(const void* X, batq_dtype xdtype, int M, int K, i
  *   batq_gemm_a8w4 (act_bits 8) for the gate and up column of f; the product is formed in fp32 (about 2^-21
  *   relative) and rounded once to the output type.  H is M x N/2 (DEVICE, row stride ldh >= N/2 elements).  The
  *   weight's N must be a multiple of 64 (BATQ_ERR_SHAPE); with M > 64, operand code arrays of 2 GiB or more
- *   are not supported (BATQ_ERR_UNSUPPORTED).  K parts are not used, so nothing is allocated.
+ *   are not supported (BATQ_ERR_UNSUPPORTED).  K parts are not used.
  * batq_linear_glu: batq_linear_ex (same options and workspace) followed by the gated epilogue. */
 batq_status batq_prepare_weight_gate_up(batq_weight** out, const batq_transform* t, const void* W_gate,
                                         const void* W_up, batq_dtype wdtype, int K, int F, int64_t ldw,
@@ -353,16 +375,6 @@ batq_status batq_kv_append(const batq_transform* t, const void* X, batq_dtype xd
                            void* stream);
 batq_status batq_kv_dequantize(const uint8_t* codes, const uint8_t* scales, int64_t capacity_rows, int64_t row_offset,
                                int M, int K, int bits, void* out, batq_dtype odtype, int64_t ldo, void* stream);
-
-/* ------------------------------------------------------------------------------------
- * Introspection (HOST only, no GPU needed): the work split of the tiled GEMM kernels for an M x K x N problem
- * (M > 64) on a device with `compute_units` compute units, as the kernels would walk it.  Writes 7 ints per
- * tile to tiles[capacity * 7] (HOST): workgroup, first row, first column, width in 64-column strips, K part,
- * first K group (256 elements) and number of K groups; returns the number of tiles (also when capacity is
- * smaller; -1 for invalid arguments).  glu: the gated-output mode of batq_gemm_glu (N % 64 == 0);
- * allow_ksplit: K parts as chosen when the stream has partial-sum memory.  For tests of the schedule. */
-int batq_debug_tile_schedule(int M, int N, int K, int compute_units, int glu, int allow_ksplit,
-                             int* tiles, int capacity);
 
 #ifdef __cplusplus
 }

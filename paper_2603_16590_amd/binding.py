@@ -1,4 +1,4 @@
-"""ctypes binding of libbatq's C ABI (include/batq.h).
+"""ctypes binding of libbatq's C ABI (include/batq.h, include/batq_debug.h).
 
 Argument marshalling only: every step of the path runs inside the library's HIP
 kernels.  PyTorch tensors are used as device memory; the current torch stream is
@@ -24,7 +24,7 @@ STATUS_NAMES = {
     9: "BATQ_ERR_DEVICE", 10: "BATQ_ERR_MISMATCH",
 }
 
-# every symbol include/batq.h declares: (restype, argtypes)
+# every symbol the two headers declare: (restype, argtypes)
 _vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
 _fp = C.POINTER(C.c_float)
 SYMBOLS = {
@@ -49,7 +49,11 @@ SYMBOLS = {
     "batq_scales_to_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
     "batq_scales_from_rowmajor": (_i, [_vp, _vp, _i, _i, _vp]),
     "batq_gemm_mxfp4": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
+    "batq_gemm_workspace": (_sz, [_vp, _i, _i]),
+    "batq_gemm_mxfp4_ws": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_gemm_a8w4_ws": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_linear_workspace": (_sz, [_i, _i]),
+    "batq_linear_workspace_for": (_sz, [_vp, _i, _i]),
     "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_quantize_act_mxfp8": (_i, [_vp, _vp, _i, _i, _i, _i64, _vp, _vp, _vp]),
     "batq_code8_bytes": (_sz, [_i, _i]),
@@ -339,13 +343,24 @@ def batq_scales_from_rowmajor(rowmajor):
     return out
 
 
-def batq_gemm_mxfp4(xcodes, xscales, w: Weight, M: int, out_dtype=None, Y=None):
-    """GEMM on device-order activation codes and scales of M rows. Returns Y (M x N)."""
+def batq_gemm_workspace(w: Weight, M: int, act_bits: int = 4) -> int:
+    """Bytes of scratch with which the GEMM of M rows against w uses all the K parts it wants (0: none)."""
+    return int(lib.batq_gemm_workspace(w.handle, M, act_bits))
+
+
+def batq_gemm_mxfp4(xcodes, xscales, w: Weight, M: int, out_dtype=None, Y=None, workspace=None):
+    """GEMM on device-order activation codes and scales of M rows. Returns Y (M x N).
+    workspace: uint8 device tensor for the partial sums of K parts (batq_gemm_mxfp4_ws), or None (plain call)."""
     import torch
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes.device)
-    _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
-                               Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_mxfp4")
+    ldy = Y.stride(0) if M > 1 else max(w.N, Y.stride(0))
+    if workspace is None:
+        _check(lib.batq_gemm_mxfp4(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                                   ldy, _stream()), "batq_gemm_mxfp4")
+    else:
+        _check(lib.batq_gemm_mxfp4_ws(xcodes.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                                      ldy, workspace.data_ptr(), workspace.numel(), _stream()), "batq_gemm_mxfp4_ws")
     return Y
 
 
@@ -364,6 +379,11 @@ def batq_linear_workspace(M: int, K: int) -> int:
     return int(lib.batq_linear_workspace(M, K))
 
 
+def batq_linear_workspace_for(w: Weight, M: int, act_bits: int = 4) -> int:
+    """Workspace bytes with which the batq_linear family runs M rows against w as fast as it can."""
+    return int(lib.batq_linear_workspace_for(w.handle, M, act_bits))
+
+
 def batq_linear(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspace=None):
     """Y = Q(X P) Q(P^-1 W): fused transform+quantise kernel, then the MXFP4 GEMM."""
     import torch
@@ -371,9 +391,8 @@ def batq_linear(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspace=No
     M, K = X.shape
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
-    need = batq_linear_workspace(M, K)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+        workspace = torch.empty((max(batq_linear_workspace_for(w, M, 4), 16),), dtype=torch.uint8, device=X.device)
     _check(lib.batq_linear(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
                            X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
                            Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
@@ -420,12 +439,17 @@ def batq_codes8_from_rowmajor(rowmajor):
     return out
 
 
-def batq_gemm_a8w4(xcodes8, xscales, w: Weight, M: int, out_dtype=None, Y=None):
+def batq_gemm_a8w4(xcodes8, xscales, w: Weight, M: int, out_dtype=None, Y=None, workspace=None):
     import torch
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=xcodes8.device)
-    _check(lib.batq_gemm_a8w4(xcodes8.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
-                              Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), _stream()), "batq_gemm_a8w4")
+    ldy = Y.stride(0) if M > 1 else max(w.N, Y.stride(0))
+    if workspace is None:
+        _check(lib.batq_gemm_a8w4(xcodes8.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                                  ldy, _stream()), "batq_gemm_a8w4")
+    else:
+        _check(lib.batq_gemm_a8w4_ws(xcodes8.data_ptr(), xscales.data_ptr(), w.handle, M, Y.data_ptr(), _dtype_code(Y),
+                                     ldy, workspace.data_ptr(), workspace.numel(), _stream()), "batq_gemm_a8w4_ws")
     return Y
 
 
@@ -440,9 +464,8 @@ def batq_linear_a8w4(t: Transform, w: Weight, X, out_dtype=None, Y=None, workspa
     M, K = X.shape
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
-    need = batq_linear_a8w4_workspace(M, K)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+        workspace = torch.empty((max(batq_linear_workspace_for(w, M, 8), 16),), dtype=torch.uint8, device=X.device)
     _check(lib.batq_linear_a8w4(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
                                 X.stride(0) if M > 1 else max(K, X.stride(0)), Y.data_ptr(), _dtype_code(Y),
                                 Y.stride(0) if M > 1 else max(w.N, Y.stride(0)), workspace.data_ptr(),
@@ -490,9 +513,8 @@ def batq_linear_glu(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=Non
     F = w.N // 2
     if H is None:
         H = torch.empty((M, F), dtype=out_dtype or torch.bfloat16, device=X.device)
-    need = batq_linear_a8w4_workspace(M, K) if act_bits == 8 else batq_linear_workspace(M, K)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+        workspace = torch.empty((max(batq_linear_workspace_for(w, M, act_bits), 16),), dtype=torch.uint8, device=X.device)
     o = _opts(act_bits, row_scale, up, X)
     _check(lib.batq_linear_glu(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
                                X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), H.data_ptr(),
@@ -571,9 +593,8 @@ def batq_linear_ex(t: Transform, w: Weight, X, act_bits: int = 4, row_scale=None
     M, K = X.shape
     if Y is None:
         Y = torch.empty((M, w.N), dtype=out_dtype or torch.float32, device=X.device)
-    need = batq_linear_a8w4_workspace(M, K) if act_bits == 8 else batq_linear_workspace(M, K)
     if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=X.device)
+        workspace = torch.empty((max(batq_linear_workspace_for(w, M, act_bits), 16),), dtype=torch.uint8, device=X.device)
     o = _opts(act_bits, row_scale, up, X)
     _check(lib.batq_linear_ex(t.handle, w.handle, X.data_ptr(), _dtype_code(X), M,
                               X.stride(0) if M > 1 else max(K, X.stride(0)), C.byref(o), Y.data_ptr(),

@@ -1,5 +1,6 @@
 // C ABI of libbatq: argument validation, handle management, host-side fp64 inversion of
 // the Kronecker factors (Alg. 2 uses A^-1 and B_i^-1 for the weight side).
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -104,18 +105,26 @@ size_t dtype_size(batq_dtype d) { return d == BATQ_BF16 ? 2 : 4; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// BATQ_OK if the current device is a gfx950; looked up once per device.
 batq_status check_device() {
-    static int state = 0;   // 0 unknown, 1 ok, 2 bad
-    if (state == 0) {
-        int dev = 0;
+    static std::atomic<int> state[batq::kMaxDevices];   // 0 unknown, 1 ok, 2 bad
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    const bool cached = dev >= 0 && dev < batq::kMaxDevices;
+    int st = cached ? state[dev].load(std::memory_order_relaxed) : 0;
+    if (st == 0) {
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
             (void)hipGetLastError();
             return BATQ_ERR_DEVICE;
         }
-        state = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
+        st = std::strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 2;
+        if (cached) state[dev].store(st, std::memory_order_relaxed);
     }
-    return state == 1 ? BATQ_OK : BATQ_ERR_DEVICE;
+    return st == 1 ? BATQ_OK : BATQ_ERR_DEVICE;
 }
 
 template <typename T>
@@ -157,6 +166,16 @@ batq_status alloc_weight(batq_weight** out, int K, int N) {
     w->K = K;
     w->N = N;
     w->nb = K / 32;
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) w->cus = batq::device_compute_units(dev, &e);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            delete w;
+            return BATQ_ERR_DEVICE;
+        }
+    }
     if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), batq::code_bytes_blocked(N, K / 32)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void**>(&w->d_scales), batq::scale_bytes_internal(N, K / 32)) != hipSuccess) {
         (void)hipGetLastError();
@@ -485,9 +504,15 @@ batq_status quantize_impl(const batq_transform* t, const void* X, batq_dtype xdt
     return BATQ_OK;
 }
 
+// Partial sums of the GEMM's K parts start on a 256-byte boundary.
+constexpr size_t kPartsAlign = 256;
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
 // glu: Y = silu(gate) * up, M x N/2, for a weight prepared by batq_prepare_weight_gate_up
+// parts / parts_bytes: caller memory for the partial sums of K parts (null / 0: none, every tile runs over all of K)
 batq_status gemm_impl(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
-                      batq_dtype ydtype, int64_t ldy, bool a8, bool glu, void* stream) {
+                      batq_dtype ydtype, int64_t ldy, bool a8, bool glu, void* parts, size_t parts_bytes,
+                      void* stream) {
     if (!w) return BATQ_ERR_NULL;
     if (!dtype_ok(ydtype)) return BATQ_ERR_DTYPE;
     if (M < 0 || ldy < (glu ? w->N / 2 : w->N)) return BATQ_ERR_SHAPE;
@@ -495,8 +520,10 @@ batq_status gemm_impl(const uint8_t* xcodes, const uint8_t* xscales, const batq_
     if (M == 0) return BATQ_OK;
     if (!xcodes || !xscales || !Y) return BATQ_ERR_NULL;
     if (!aligned16(xcodes) || (reinterpret_cast<uintptr_t>(xscales) & 7u) != 0) return BATQ_ERR_SHAPE;
-    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, a8, glu, static_cast<hipStream_t>(stream)) !=
-        hipSuccess) {
+    if (parts_bytes > 0 && !parts) return BATQ_ERR_NULL;
+    if (parts && (reinterpret_cast<uintptr_t>(parts) & (kPartsAlign - 1)) != 0) return BATQ_ERR_SHAPE;
+    if (batq::launch_gemm_mxfp4(xcodes, xscales, w, M, Y, ydtype, ldy, a8, glu, parts, parts ? parts_bytes : 0,
+                                static_cast<hipStream_t>(stream)) != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
     }
@@ -521,15 +548,20 @@ batq_status linear_impl(const batq_transform* t, const batq_weight* w, const voi
     if (M == 0) return BATQ_OK;
     if (!X || !Y || !workspace) return BATQ_ERR_NULL;
     if (workspace_bytes < workspace_impl(M, t->K, a8)) return BATQ_ERR_WORKSPACE;
-    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 || !aligned16(workspace))
+    if (!aligned16(X) || (ldx * (int64_t)dtype_size(xdtype)) % 16 != 0 ||
+        (reinterpret_cast<uintptr_t>(workspace) & (kPartsAlign - 1)) != 0)
         return BATQ_ERR_SHAPE;
     if (batq_status st = check_extras(ex, xdtype, t->K); st != BATQ_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* codes = static_cast<uint8_t*>(workspace);
     uint8_t* scales = codes + (a8 ? batq::code8_bytes_blocked(M, t->nb) : batq::code_bytes_blocked(M, t->nb));
+    // what the workspace holds beyond the codes and scales serves the partial sums of the GEMM's K parts
+    const size_t parts_at = align_up(workspace_impl(M, t->K, a8), kPartsAlign);
+    uint8_t* parts = workspace_bytes > parts_at ? codes + parts_at : nullptr;
+    const size_t parts_bytes = parts ? workspace_bytes - parts_at : 0;
     hipError_t e = batq::launch_quantize_act(t, X, xdtype, M, t->K, ldx, ex.up, ex.ld_up, ex.row_scale, codes, scales,
                                              a8, 0, 0, s);
-    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, glu, s);
+    if (e == hipSuccess) e = batq::launch_gemm_mxfp4(codes, scales, w, M, Y, ydtype, ldy, a8, glu, parts, parts_bytes, s);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return BATQ_ERR_DEVICE;
@@ -626,16 +658,38 @@ batq_status batq_scales_from_rowmajor(const uint8_t* rowmajor, uint8_t* grouped,
 
 batq_status batq_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                             batq_dtype ydtype, int64_t ldy, void* stream) {
-    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, false, stream);
+    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, false, nullptr, 0, stream);
 }
 
 batq_status batq_gemm_a8w4(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                            batq_dtype ydtype, int64_t ldy, void* stream) {
-    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, false, stream);
+    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, false, nullptr, 0, stream);
+}
+
+size_t batq_gemm_workspace(const batq_weight* w, int M, int act_bits) {
+    if (!w || M <= 0 || (act_bits != 0 && act_bits != 4 && act_bits != 8)) return 0;
+    return batq::gemm_workspace_bytes(w, M, act_bits == 8, w->cus);
+}
+
+batq_status batq_gemm_mxfp4_ws(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
+                               batq_dtype ydtype, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, false, workspace, workspace_bytes, stream);
+}
+
+batq_status batq_gemm_a8w4_ws(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
+                              batq_dtype ydtype, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, false, workspace, workspace_bytes, stream);
 }
 
 size_t batq_linear_workspace(int M, int K) { return workspace_impl(M, K, false); }
 size_t batq_linear_a8w4_workspace(int M, int K) { return workspace_impl(M, K, true); }
+
+size_t batq_linear_workspace_for(const batq_weight* w, int M, int act_bits) {
+    if (!w || M <= 0 || (act_bits != 0 && act_bits != 4 && act_bits != 8)) return 0;
+    const size_t base = workspace_impl(M, w->K, act_bits == 8);
+    const size_t parts = batq::gemm_workspace_bytes(w, M, act_bits == 8, w->cus);
+    return parts ? align_up(base, kPartsAlign) + parts : base;
+}
 
 batq_status batq_linear(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,
                         int64_t ldx, void* Y, batq_dtype ydtype, int64_t ldy, void* workspace,
@@ -683,7 +737,7 @@ batq_status batq_linear_ex(const batq_transform* t, const batq_weight* w, const 
 batq_status batq_gemm_glu(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M, int act_bits,
                           void* H, batq_dtype hdtype, int64_t ldh, void* stream) {
     if (act_bits != 0 && act_bits != 4 && act_bits != 8) return BATQ_ERR_UNSUPPORTED;
-    return gemm_impl(xcodes, xscales, w, M, H, hdtype, ldh, act_bits == 8, true, stream);
+    return gemm_impl(xcodes, xscales, w, M, H, hdtype, ldh, act_bits == 8, true, nullptr, 0, stream);
 }
 
 batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const void* X, batq_dtype xdtype, int M,

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <atomic>
 #include "../../include/batq.h"
 
 namespace batq {
@@ -34,11 +36,41 @@ struct batq_transform {
 // Prepared (inverse-transformed, quantised) weights.
 struct batq_weight {
     int K = 0, N = 0, nb = 0;
+    int cus = 0;                  // compute units of the device the weight lives on
     uint8_t* d_codes = nullptr;   // blocked code layout (code_layout.h), rows and K zero-padded
     uint8_t* d_scales = nullptr;  // internal group-major layout (scale_layout.h), padded groups
 };
 
 namespace batq {
+
+// Per-device facts the launch code needs, looked up once per device and safe to use from several host threads
+// (the values are idempotent, so a race between two first calls only repeats the lookup).
+constexpr int kMaxDevices = 64;
+
+// Compute units of `dev` (hipDeviceAttributeMultiprocessorCount); 0 with *err set on failure.
+inline int device_compute_units(int dev, hipError_t* err) {
+    static std::atomic<int> cus[kMaxDevices];
+    *err = hipSuccess;
+    const bool cached = dev >= 0 && dev < kMaxDevices;
+    int n = cached ? cus[dev].load(std::memory_order_relaxed) : 0;
+    if (n > 0) return n;
+    *err = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (*err != hipSuccess) return 0;
+    if (cached) cus[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
+// Raises the dynamic-LDS limit of `Kernel` to `bytes` on the current device, once per device and kernel.
+template <auto Kernel>
+inline hipError_t ensure_dynamic_lds(int dev, int bytes) {
+    static std::atomic<bool> done[kMaxDevices];
+    const bool cached = dev >= 0 && dev < kMaxDevices;
+    if (cached && done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    const hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && cached) done[dev].store(true, std::memory_order_release);
+    return e;
+}
 
 // Each launcher validates nothing: callers (the C ABI) have checked shapes already.
 // Codes are written in the blocked layout of code_layout.h (fp8: MXFP8 codes in its 8-bit variant),
@@ -66,8 +98,13 @@ hipError_t launch_prepare_weight(const batq_transform* t, const void* W, batq_dt
 // xscales_internal: activation scales in the grouped layout.
 // glu: gated output, Y = silu(gate) * up is M x N/2 for a weight with interleaved gate / up columns
 // (gemm_glu_supported says whether the shapes allow it).
+// parts / parts_bytes: DEVICE memory (256-byte aligned) for the partial sums of K parts, or null / 0; how many
+// K parts run depends on the shape, the device and parts_bytes only (never on the stream or on earlier calls).
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, hipStream_t stream);
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, void* parts,
+                             size_t parts_bytes, hipStream_t stream);
+// Partial-sum bytes with which the GEMM of M rows against `w` runs all the K parts it wants (0: it wants none).
+size_t gemm_workspace_bytes(const batq_weight* w, int M, bool a8, int compute_units);
 bool gemm_glu_supported(const batq_weight* w, int M, bool a8);
 // Host replay of the tiled kernels' work split: 7 ints per tile (workgroup, first row, first column, strips, K part,
 // first K group, K groups) into out[capacity * 7]; returns the number of tiles.

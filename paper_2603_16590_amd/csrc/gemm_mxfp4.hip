@@ -17,10 +17,7 @@
 //   gemm_direct - one wave per 32x32 tile with operands straight from global memory; only for
 //                 operand arrays of 2 GiB or more (the tiled kernel uses 32-bit load offsets).
 #include <algorithm>
-#include <map>
-#include <mutex>
 #include <type_traits>
-#include <utility>
 
 #include "batq_internal.h"
 #include "code_layout.h"
@@ -1263,133 +1260,120 @@ splitk_reduce_rows(const float* __restrict__ P, int parts, int M, int N, YT* __r
     store_y<YT>(Y + (int64_t)m * ldy + n, acc);
 }
 
-// Partial-sum memory of the K-split launches: one buffer per (device, stream), created at the first launch
-// that needs it and kept until the process ends.  Kernels of one stream run in order, so the launches of a
-// stream can share it; launches on different streams never do.  While a stream is being captured into a graph
-// no memory is allocated: a stream without a buffer then gets none (the caller falls back to the unsplit kernel).
-constexpr size_t kSplitScratchBytes = size_t(32) << 20;
-float* splitk_scratch(int dev, hipStream_t stream) {
-    static std::mutex mu;
-    static std::map<std::pair<int, hipStream_t>, float*> buffers;
-    std::lock_guard<std::mutex> lock(mu);
-    auto it = buffers.find({dev, stream});
-    if (it != buffers.end()) return it->second;
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &cap) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
+// A8: the activation codes are MXFP8 in the blocked 8-bit layout.  GLU: gated output (Y is M x N/2, N % 64 == 0).
+// Partial sums of the K parts live in caller memory: `parts` (256-byte aligned, `parts_bytes` bytes; null: none).
+// How many K parts a launch uses is a function of the shape, the device's compute units and parts_bytes only
+// (gemm_plan), so the same call gives the same bits on every stream, eagerly or captured.
+struct GemmPlan {
+    TilePlan tiled;             // M > 64: the tiled kernels' plan, ksplit set
+    size_t part_floats = 0;     // floats of one K part's partial sums
+    int col_blocks = 0;         // 32-column blocks of the padded output (tiled kernels)
+    int ksplit = 1;             // K parts used
+    int want = 1;               // K parts the shape would like (workspace permitting)
+    bool skinny = false, wide = false;
+    int cols = 0;               // skinny: workgroups along N
+};
+
+inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size_t parts_bytes) {
+    GemmPlan g;
+    if (M > 64) {
+        g.tiled = make_plan(M, N, nb, cus, glu);
+        if (!glu) {
+            g.col_blocks = 2 * g.tiled.strips_n;
+            g.part_floats = (size_t)g.tiled.tiles_m * 8 * g.col_blocks * kPartialBlockFloats;
+            g.want = choose_ksplit(g.tiled, 0, 0);
+            g.ksplit = g.want > 1 ? choose_ksplit(g.tiled, g.part_floats * sizeof(float), parts_bytes) : 1;
+        }
+        g.tiled.ksplit = g.ksplit;
+        return g;
     }
-    if (cap != hipStreamCaptureStatusNone) return nullptr;
-    void* p = nullptr;
-    if (hipMalloc(&p, kSplitScratchBytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    buffers[{dev, stream}] = static_cast<float*>(p);
-    return static_cast<float*>(p);
+    g.skinny = true;
+    // 64 columns per workgroup pay with two row tiles (the X codes are the larger share of a workgroup's
+    // loads then) when they make one full round of workgroups: between three quarters of and all the compute
+    // units (64 x 4096 x 14336: 15.4 -> 12.9 us; with one row tile, or a second partial round, it loses).  Not
+    // for the 8-bit kernel, which would not fit its registers.
+    const int cols64 = (N + 63) / 64;
+    g.wide = !glu && !a8 && M > 32 && cols64 <= cus && 4 * cols64 >= 3 * cus;
+    g.cols = (glu || g.wide) ? cols64 : (N + 31) / 32;
+    // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two
+    // workgroup rows then take half of K each (64 x 14336 x 4096: 15.8 -> 12.0 us).  More parts, or shorter
+    // K, lose more to the second kernel than they gain.
+    g.part_floats = (size_t)M * N;
+    g.want = (!glu && !g.wide && 2 * g.cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
+    g.ksplit = (g.want > 1 && (size_t)g.want * g.part_floats * sizeof(float) <= parts_bytes) ? g.want : 1;
+    return g;
 }
 
-// A8: the activation codes are MXFP8 in the blocked 8-bit layout.  GLU: gated output (Y is M x N/2, N % 64 == 0).
 template <typename YT, bool A8, bool GLU>
 hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight* w, int M, YT* Y, int64_t ldy,
-                        hipStream_t stream) {
+                        float* parts, size_t parts_bytes, hipStream_t stream) {
     const int N = w->N, nb = w->nb;
     const size_t xbytes = A8 ? code8_bytes_blocked(M, nb) : code_bytes_blocked(M, nb);
     const bool fits32 = xbytes < (1ull << 31) && code_bytes_blocked(N, nb) < (1ull << 31);
-    if (M > 64 && fits32) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<YT, GLU>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
-                              : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<YT, GLU>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        int dev = 0, cus = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        TilePlan pl = make_plan(M, N, nb, cus, GLU);
-        float* parts = nullptr;
-        int ksplit = 1, col_blocks = 0;
-        size_t part_floats = 0;
-        if constexpr (!GLU) {
-            // K parts for few-strip, long-K shapes (choose_ksplit), if the stream has partial-sum memory
-            col_blocks = 2 * pl.strips_n;
-            part_floats = (size_t)pl.tiles_m * 8 * col_blocks * kPartialBlockFloats;
-            ksplit = choose_ksplit(pl, part_floats * sizeof(float), kSplitScratchBytes);
-            parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
-        }
-        if (parts) {
-            static bool attr_f32_set = false;
-            if (!attr_f32_set) {
-                e = A8 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_a8<partial_f32, false>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kA8Lds)
-                       : hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled<partial_f32, false>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kTiledLds);
-                if (e != hipSuccess) return e;
-                attr_f32_set = true;
-            }
-            pl.ksplit = ksplit;
-            if constexpr (A8)
-                gemm_tiled_a8<partial_f32, false><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
-                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
-                    (int64_t)col_blocks, (int64_t)part_floats);
-            else
-                gemm_tiled<partial_f32, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
-                    xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
-                    (int64_t)col_blocks, (int64_t)part_floats);
-            splitk_reduce<YT><<<dim3(col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
-                parts, ksplit, (int64_t)part_floats, col_blocks, M, N, Y, ldy);
-        } else if constexpr (A8) {
-            gemm_tiled_a8<YT, GLU><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales,
-                                                                                     M, N, nb, pl, Y, ldy, 0);
-        } else {
-            gemm_tiled<YT, GLU><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
-                                                                                     N, nb, pl, Y, ldy, 0);
-        }
-    } else if (M <= 64) {
-        // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two
-        // workgroup rows then take half of K each (64 x 14336 x 4096: 15.8 -> 12.0 us).  More parts, or shorter
-        // K, lose more to the second kernel than they gain.
-        int dev = 0, cus = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        // 64 columns per workgroup pay with two row tiles (the X codes are the larger share of a workgroup's
-        // loads then) when they make one full round of workgroups: between three quarters of and all the compute
-        // units (64 x 4096 x 14336: 15.4 -> 12.9 us; with one row tile, or a second partial round, it loses).  Not
-        // for the 8-bit kernel, which would not fit its registers.
-        const int cols64 = (N + 63) / 64;
-        const bool wide = !GLU && !A8 && M > 32 && cols64 <= cus && 4 * cols64 >= 3 * cus;
-        const int cols = (GLU || wide) ? (N + 63) / 64 : (N + 31) / 32;
-        int ksplit = (!GLU && !wide && 2 * cols <= cus && scale_groups(nb) >= 48) ? 2 : 1;
-        float* parts = ksplit > 1 ? splitk_scratch(dev, stream) : nullptr;
-        if (!parts || (size_t)ksplit * M * N * sizeof(float) > kSplitScratchBytes) ksplit = 1;
-        const dim3 grid(cols, ksplit), block(kSkinnyWaves * 64);
-        if constexpr (GLU) {
-            if (M <= 32)
-                gemm_skinny<YT, 1, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-            else
-                gemm_skinny<YT, 2, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-        } else if (wide) {
-            if constexpr (!A8)
-                gemm_skinny<YT, 2, false, false, true><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-        } else {
-            if (M <= 32)
-                gemm_skinny<YT, 1, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-            else
-                gemm_skinny<YT, 2, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, parts);
-        }
-        if (ksplit > 1) {
-            const int64_t total = (int64_t)M * N;
-            splitk_reduce_rows<YT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(parts, ksplit, M, N, Y, ldy);
-        }
-    } else {
+    if (M > 64 && !fits32) {
         if constexpr (GLU) return hipErrorNotSupported;       // callers check gemm_glu_supported first
         const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
         gemm_direct<YT, A8><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy);
+        return hipGetLastError();
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const int cus = device_compute_units(dev, &e);
+    if (e != hipSuccess) return e;
+    const GemmPlan g = gemm_plan(M, N, nb, cus, A8, GLU, parts ? parts_bytes : 0);
+    if (!g.skinny) {
+        const TilePlan& pl = g.tiled;
+        if (g.ksplit > 1) {
+            if constexpr (!GLU) {
+                if constexpr (A8) {
+                    e = ensure_dynamic_lds<&gemm_tiled_a8<partial_f32, false>>(dev, kA8Lds);
+                    if (e != hipSuccess) return e;
+                    gemm_tiled_a8<partial_f32, false><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(
+                        xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
+                        (int64_t)g.col_blocks, (int64_t)g.part_floats);
+                } else {
+                    e = ensure_dynamic_lds<&gemm_tiled<partial_f32, false>>(dev, kTiledLds);
+                    if (e != hipSuccess) return e;
+                    gemm_tiled<partial_f32, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
+                        xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
+                        (int64_t)g.col_blocks, (int64_t)g.part_floats);
+                }
+                splitk_reduce<YT><<<dim3(g.col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
+                    parts, g.ksplit, (int64_t)g.part_floats, g.col_blocks, M, N, Y, ldy);
+            }
+        } else if constexpr (A8) {
+            e = ensure_dynamic_lds<&gemm_tiled_a8<YT, GLU>>(dev, kA8Lds);
+            if (e != hipSuccess) return e;
+            gemm_tiled_a8<YT, GLU><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales,
+                                                                                     M, N, nb, pl, Y, ldy, 0);
+        } else {
+            e = ensure_dynamic_lds<&gemm_tiled<YT, GLU>>(dev, kTiledLds);
+            if (e != hipSuccess) return e;
+            gemm_tiled<YT, GLU><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
+                                                                                     N, nb, pl, Y, ldy, 0);
+        }
+    } else {
+        const dim3 grid(g.cols, g.ksplit), block(kSkinnyWaves * 64);
+        float* pp = g.ksplit > 1 ? parts : nullptr;
+        if constexpr (GLU) {
+            if (M <= 32)
+                gemm_skinny<YT, 1, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+            else
+                gemm_skinny<YT, 2, A8, true, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+        } else if (g.wide) {
+            if constexpr (!A8)
+                gemm_skinny<YT, 2, false, false, true><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+        } else {
+            if (M <= 32)
+                gemm_skinny<YT, 1, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+            else
+                gemm_skinny<YT, 2, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+        }
+        if (g.ksplit > 1) {
+            const int64_t total = (int64_t)M * N;
+            splitk_reduce_rows<YT><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(parts, g.ksplit, M, N, Y, ldy);
+        }
     }
     return hipGetLastError();
 }
@@ -1440,11 +1424,8 @@ hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, 
 
 int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_ksplit, int* out, int capacity) {
     const int nb = K / 32;
-    TilePlan pl = make_plan(M, N, nb, compute_units, glu);
-    if (allow_ksplit && !glu) {
-        const size_t part_bytes = (size_t)pl.tiles_m * 8 * 2 * pl.strips_n * kPartialBlockFloats * sizeof(float);
-        pl.ksplit = choose_ksplit(pl, part_bytes, kSplitScratchBytes);
-    }
+    const GemmPlan g = gemm_plan(M, N, nb, compute_units, false, glu, allow_ksplit ? ~size_t(0) : 0);
+    const TilePlan& pl = g.tiled;
     int n = 0;
     for (int b = 0; b < pl.workers; ++b) {
         int cur, end;
@@ -1461,6 +1442,14 @@ int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_k
     return n;
 }
 
+size_t gemm_workspace_bytes(const batq_weight* w, int M, bool a8, int cus) {
+    if (M <= 0) return 0;
+    const size_t xbytes = a8 ? code8_bytes_blocked(M, w->nb) : code_bytes_blocked(M, w->nb);
+    if (M > 64 && !(xbytes < (1ull << 31) && code_bytes_blocked(w->N, w->nb) < (1ull << 31))) return 0;
+    const GemmPlan g = gemm_plan(M, w->N, w->nb, cus, a8, false, 0);
+    return g.want > 1 ? (size_t)g.want * g.part_floats * sizeof(float) : 0;
+}
+
 bool gemm_glu_supported(const batq_weight* w, int M, bool a8) {
     if (w->N % 64 != 0) return false;
     if (M <= 64) return true;
@@ -1470,22 +1459,25 @@ bool gemm_glu_supported(const batq_weight* w, int M, bool a8) {
 
 template <bool GLU>
 static hipError_t launch_gemm_as(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                                 void* Y, batq_dtype ydtype, int64_t ldy, bool a8, hipStream_t stream) {
+                                 void* Y, batq_dtype ydtype, int64_t ldy, bool a8, float* parts, size_t parts_bytes,
+                                 hipStream_t stream) {
     if (ydtype == BATQ_BF16) {
         uint16_t* Yp = static_cast<uint16_t*>(Y);
-        return a8 ? launch_typed<uint16_t, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
-                  : launch_typed<uint16_t, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+        return a8 ? launch_typed<uint16_t, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, parts, parts_bytes, stream)
+                  : launch_typed<uint16_t, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, parts, parts_bytes, stream);
     }
     float* Yp = static_cast<float*>(Y);
-    return a8 ? launch_typed<float, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream)
-              : launch_typed<float, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, stream);
+    return a8 ? launch_typed<float, true, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, parts, parts_bytes, stream)
+              : launch_typed<float, false, GLU>(xcodes, xscales_internal, w, M, Yp, ldy, parts, parts_bytes, stream);
 }
 
 hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_internal, const batq_weight* w, int M,
-                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, hipStream_t stream) {
+                             void* Y, batq_dtype ydtype, int64_t ldy, bool a8, bool glu, void* parts,
+                             size_t parts_bytes, hipStream_t stream) {
     if (M == 0) return hipSuccess;
-    return glu ? launch_gemm_as<true>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, stream)
-               : launch_gemm_as<false>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, stream);
+    float* pf = static_cast<float*>(parts);
+    return glu ? launch_gemm_as<true>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, nullptr, 0, stream)
+               : launch_gemm_as<false>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, pf, parts_bytes, stream);
 }
 
 }  // namespace batq

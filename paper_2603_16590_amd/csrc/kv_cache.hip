@@ -353,9 +353,9 @@ hipError_t apply_typed(const batq_transform* t, const XT* X, int M, int64_t ldx,
         const bool fits = ((uintptr_t)X | (uintptr_t)out | (uintptr_t)(ldx * 2) | (uintptr_t)(ldo * (int64_t)sizeof(OT))) % 16 == 0 &&
                           ldx < (int64_t(1) << 25);
         if (sp && fits) {
-            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma<OT>),
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
-            if (attr != hipSuccess) return attr;
+            int dev = 0;
+            if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+            if (hipError_t e = ensure_dynamic_lds<&apply_mfma<OT>>(dev, kApplyLds); e != hipSuccess) return e;
             const int units = (t->nb + 3) / 4, row_tiles = (M + 31) / 32;
             // about four workgroups per compute unit, at least 16 tiles each (the operands are fetched per workgroup)
             int tiles_per_wg = (int)(((int64_t)row_tiles * units + 1023) / 1024);

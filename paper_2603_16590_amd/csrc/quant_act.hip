@@ -593,16 +593,10 @@ struct RowWindow {
 
 template <bool MINMAX, bool FP8, bool SWIGLU>
 hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U,
-                          int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, int cus,
-                          hipStream_t stream) {
+                          int64_t ldu, const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, int dev,
+                          int cus, hipStream_t stream) {
     using Plan = QuantPlan<FP8, SWIGLU>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_act_mfma<MINMAX, FP8, SWIGLU>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Plan::kLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (hipError_t e = ensure_dynamic_lds<&quant_act_mfma<MINMAX, FP8, SWIGLU>>(dev, Plan::kLds); e != hipSuccess) return e;
     // whole K groups per workgroup set: floor(compute units / groups) workgroups share a group
     const int nb = t->nb;
     const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
@@ -621,23 +615,18 @@ template <bool SWIGLU>
 hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U, int64_t ldu,
                        const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, bool fp8,
                        hipStream_t stream) {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) {
-            cus = 0;
-            return e;
-        }
-    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const int cus = device_compute_units(dev, &e);
+    if (e != hipSuccess) return e;
     if (fp8)
         return t->minmax
-                   ? launch_mfma_as<true, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream)
-                   : launch_mfma_as<false, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream);
+                   ? launch_mfma_as<true, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream)
+                   : launch_mfma_as<false, true, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream);
     return t->minmax
-               ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream)
-               : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, cus, stream);
+               ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream)
+               : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream);
 }
 
 template <typename XT, bool FP8>

@@ -83,11 +83,9 @@ def test_small_shapes_random_codes(B, M, K, N):
     assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol)
 
 
-@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
-def test_tile_schedule_shapes(B, M, K, N):
-    """Shapes that give the persistent workgroups of the tiled kernel several tiles each, of every
-    width (64 .. 256 columns), with ragged last row panels and column strips, 2 to 10 K stages and
-    every column-band count; every output element is checked."""
+def _check_every_element(B, M, K, N, workspace_fraction=None):
+    """Random codes, every output element against the oracle, fp32 and bf16 output.  workspace_fraction: None for
+    the plain call, else the share of batq_gemm_workspace() handed to the call with a workspace."""
     import torch
     rng = np.random.default_rng(M + K + N)
     xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
@@ -95,19 +93,33 @@ def test_tile_schedule_shapes(B, M, K, N):
     wh = B.batq_weight_import(dwc, dws, K, N)
     ref = o.gemm(xc, xs, wc, ws)
     dxc_b, dxs_g = _xc(xc), _xs(xs)
-    Y = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
+    work = None
+    if workspace_fraction is not None:
+        need = B.batq_gemm_workspace(wh, M)
+        assert need > 0, "the shape was chosen to want K parts"
+        work = torch.empty(max(256, int(need * workspace_fraction)), dtype=torch.uint8, device="cuda")
+    Y = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32, workspace=work)
     torch.cuda.synchronize()
     got = y_to_f32(Y)
     tol = 1e-6 * (np.abs(o.dequantize(xc, xs)) @ np.abs(o.dequantize(wc, ws)).T)
     bad = np.argwhere(np.abs(got - ref) > tol + 1e-30)
     assert bad.size == 0, f"{len(bad)} wrong elements, first at {bad[0]}"
-    Yb = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.bfloat16)
+    Yb = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.bfloat16, workspace=work)
     torch.cuda.synchronize()
     refb = o.bf16_round(ref).astype(np.float64)
     gotb = y_to_f32(Yb).astype(np.float64)
     ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
     bad = np.argwhere(np.abs(gotb - refb) > ulp * 1.0001 + tol)
     assert bad.size == 0, f"{len(bad)} wrong bf16 elements, first at {bad[0]}"
+    return wh, dxc_b, dxs_g, Y
+
+
+@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
+def test_tile_schedule_shapes(B, M, K, N):
+    """Shapes that give the persistent workgroups of the tiled kernel several tiles each, of every
+    width (64 .. 256 columns), with ragged last row panels and column strips, 2 to 10 K stages and
+    every column-band count; every output element is checked."""
+    _check_every_element(B, M, K, N)
 
 
 @pytest.mark.parametrize("M,K,N", [(200, 2048, 14336), (300, 1536 + 32, 5000), (256, 768, 24000), (100, 512, 9000 + 24),
@@ -137,25 +149,49 @@ def test_narrow_tile_shapes(B, M, K, N):
 @pytest.mark.parametrize("M,K,N", [(130, 8192, 320), (300, 8192 + 32, 200), (256, 8192 + 256, 1000), (97, 6144, 64),
                                    (65, 12288 + 64, 2100), (520, 16384, 136), (64, 12288 + 32, 2070), (7, 16384, 96)])
 def test_split_k_shapes(B, M, K, N):
-    """Few strips and a long K: the tiled kernel cuts K into 2 to 8 parts (partial tiles summed in a second
-    kernel), with ragged panels, strips and part lengths; every output element is checked, on the current
-    stream and on a side stream (each stream has its own partial-sum memory)."""
+    """Few strips and a long K: with a workspace the kernels cut K into 2 to 8 parts (partial tiles summed in a
+    second kernel), with ragged panels, strips and part lengths.  Every output element is checked for the plain
+    call, the full workspace and a third of it (fewer parts); the result is a function of the arguments: the same
+    bits on the current stream, on a side stream and from launches that overlap (each with its own workspace)."""
     import torch
-    test_tile_schedule_shapes(B, M, K, N)
-    rng = np.random.default_rng(M + K + N)
-    xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
-    wc, ws, dwc, dws = _rand_q(rng, N, K, lo=122, hi=132)
-    wh = B.batq_weight_import(dwc, dws, K, N)
-    dxc_b, dxs_g = _xc(xc), _xs(xs)
-    Y0 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
-    torch.cuda.synchronize()
+    _check_every_element(B, M, K, N)
+    _check_every_element(B, M, K, N, workspace_fraction=0.34)
+    wh, dxc_b, dxs_g, Y0 = _check_every_element(B, M, K, N, workspace_fraction=1.0)
+    need = B.batq_gemm_workspace(wh, M)
+    works = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(3)]
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        Y1 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
-        Y2 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)
-    Y3 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32)      # overlaps with the side stream's launches
+        Y1 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32, workspace=works[0])
+        Y2 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32, workspace=works[1])
+    Y3 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32, workspace=works[2])   # overlaps with the side stream
     torch.cuda.synchronize()
     assert torch.equal(Y0, Y1) and torch.equal(Y0, Y2) and torch.equal(Y0, Y3)
+    # a larger workspace than asked for changes nothing
+    big = torch.empty(2 * need + 4096, dtype=torch.uint8, device="cuda")
+    Y4 = B.batq_gemm_mxfp4(dxc_b, dxs_g, wh, M, torch.float32, workspace=big)
+    torch.cuda.synchronize()
+    assert torch.equal(Y0, Y4)
+
+
+def test_gemm_workspace_arguments(B):
+    import torch
+    rng = np.random.default_rng(12)
+    xc, xs, dxc, dxs = _rand_q(rng, 130, 8192)
+    wc, ws, dwc, dws = _rand_q(rng, 320, 8192)
+    wh = B.batq_weight_import(dwc, dws, 8192, 320)
+    assert B.batq_gemm_workspace(wh, 130) > 0 and B.batq_gemm_workspace(wh, 130) % 256 == 0
+    assert B.batq_gemm_workspace(wh, 0) == 0 and B.batq_gemm_workspace(wh, 130, 5) == 0
+    assert B.batq_linear_workspace_for(wh, 130) > B.batq_linear_workspace(130, 8192)
+    wide = B.batq_weight_import(torch.zeros((9000, 64), dtype=torch.uint8, device="cuda"),
+                                torch.full((9000, 4), 127, dtype=torch.uint8, device="cuda"), 128, 9000)
+    assert B.batq_gemm_workspace(wide, 130) == 0
+    assert B.batq_linear_workspace_for(wide, 130) == B.batq_linear_workspace(130, 128)
+    Y = torch.empty((130, 320), device="cuda")
+    work = torch.empty(B.batq_gemm_workspace(wh, 130) + 256, dtype=torch.uint8, device="cuda")
+    args = (_xc(xc).data_ptr(), _xs(xs).data_ptr(), wh.handle, 130, Y.data_ptr(), B.F32, 320)
+    assert B.lib.batq_gemm_mxfp4_ws(*args, None, 1024, None) == 1                    # bytes without memory
+    assert B.lib.batq_gemm_mxfp4_ws(*args, work.data_ptr() + 16, 1024, None) == 2    # not 256-byte aligned
+    assert B.lib.batq_gemm_mxfp4_ws(*args, None, 0, None) == 0                       # the plain call
 
 
 def test_extreme_scales(B):
@@ -187,8 +223,8 @@ def test_strided_output_and_empty(B):
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
 def test_linear_all_configs(B, cfg):
-    """batq_linear at full size; checked on sampled rows x sampled columns against the oracle GEMM
-    of the operands the GPU produced, and end to end against the pure-oracle layer."""
+    """batq_linear at full size: every output element against the oracle GEMM of the operands the GPU
+    produced, and sampled rows and columns end to end against the pure-oracle layer."""
     import torch
     w = bi.make_workload(cfg)
     t = B.Transform(w.K, w.G, w.P, w.clip)
@@ -196,7 +232,8 @@ def test_linear_all_configs(B, cfg):
     X = to_dev(w.X, w.dtype)
     ws_bytes = B.batq_linear_workspace(w.M, w.K)
     assert ws_bytes == B.batq_code_bytes(w.M, w.K) + B.batq_scale_bytes(w.M, w.K)
-    work = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    assert B.batq_linear_workspace_for(wh, w.M) >= ws_bytes
+    work = torch.empty(B.batq_linear_workspace_for(wh, w.M), dtype=torch.uint8, device="cuda")
     out_dtype = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
     Y = B.batq_linear(t, wh, X, out_dtype, workspace=work)
     Y32 = B.batq_linear(t, wh, X, torch.float32, workspace=work)
@@ -208,31 +245,50 @@ def test_linear_all_configs(B, cfg):
     # same codes in the workspace (rows past M of the last 32-row tile are unspecified)
     assert np.array_equal(blocked_to_rowmajor(work[: xc_d.numel()].cpu().numpy(), w.M, w.K // 32),
                           blocked_to_rowmajor(xc_d.cpu().numpy(), w.M, w.K // 32))
-    rows = sample_rows(w.M, 96, seed=cfg)
-    cols = sample_rows(w.N, 768, seed=cfg + 10)
-    xcodes = blocked_to_rowmajor(xc_d.cpu().numpy(), w.M, w.K // 32)[rows]
-    xscales = grouped_to_rowmajor(xs_d.cpu().numpy(), w.M, w.K // 32)[rows]
+    # every element of Y (config 4: the first and last 512 rows, all columns) against the oracle's fp64 product
+    # of the operands the GPU produced, 512 rows at a time
+    xcodes = blocked_to_rowmajor(xc_d.cpu().numpy(), w.M, w.K // 32)
+    xscales = grouped_to_rowmajor(xs_d.cpu().numpy(), w.M, w.K // 32)
     wc, wsc = wh.export()
     torch.cuda.synchronize()
-    wc, wsc = wc[torch.from_numpy(cols).cuda()].cpu().numpy(), wsc[torch.from_numpy(cols).cuda()].cpu().numpy()
-    ref = o.gemm(xcodes, xscales, wc, wsc)
-    sub = lambda T: T[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].float().cpu().numpy()
-    e32 = _relfro(sub(Y32), ref)
+    wc, wsc = wc.cpu().numpy(), wsc.cpu().numpy()
+    Wdq = o.dequantize(wc, wsc)
+    chunks = [(at, min(at + 512, w.M)) for at in range(0, w.M, 512)]
+    if cfg == 4:
+        chunks = [chunks[0], chunks[-1]]
+    num = den = numb = denb = 0.0
+    for r0, r1 in chunks:
+        Xdq = o.dequantize(xcodes[r0:r1], xscales[r0:r1])
+        ref = Xdq @ Wdq.T                                        # = o.gemm on these rows
+        tol = 1e-6 * (np.abs(Xdq) @ np.abs(Wdq).T)
+        got = Y32[r0:r1].cpu().numpy().astype(np.float64)
+        bad = np.argwhere(np.abs(got - ref) > tol + 1e-30)
+        assert bad.size == 0, f"rows {r0}..{r1}: {len(bad)} wrong fp32 elements, first at {bad[0]}"
+        num += float(np.sum((got - ref) ** 2))
+        den += float(np.sum(ref ** 2))
+        if w.out_dtype == "bf16":
+            refb = o.bf16_round(ref).astype(np.float64)
+            gotb = Y[r0:r1].float().cpu().numpy().astype(np.float64)
+            ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+            bad = np.argwhere(np.abs(gotb - refb) > ulp * 1.0001 + tol)
+            assert bad.size == 0, f"rows {r0}..{r1}: {len(bad)} wrong bf16 elements, first at {bad[0]}"
+            numb += float(np.sum((gotb - refb) ** 2))
+            denb += float(np.sum(refb ** 2))
+    e32 = float(np.sqrt(num / den))
     assert e32 <= 1e-3 and e32 <= 1e-5, e32
     if w.out_dtype == "bf16":
-        refb = o.bf16_round(ref).astype(np.float64)
-        got = sub(Y).astype(np.float64)
-        eb = _relfro(got, refb)
-        assert eb <= 1e-3, eb
-        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
-        tol = 1e-6 * (np.abs(o.dequantize(xcodes, xscales)) @ np.abs(o.dequantize(wc, wsc)).T)
-        assert np.all(np.abs(got - refb) <= ulp * 1.0001 + tol)
-    # end to end: the oracle quantises the same rows itself; only tie-level code differences remain
+        assert float(np.sqrt(numb / denb)) <= 1e-3
+    del Wdq
+    # end to end on sampled rows and columns: the oracle quantises the same rows and columns itself; only
+    # tie-level code differences remain
+    rows = sample_rows(w.M, 96, seed=cfg)
+    cols = sample_rows(w.N, 768, seed=cfg + 10)
+    sub = lambda T: T[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].float().cpu().numpy()
     oxc, oxs = o.quantize_act(w.X_f32()[rows], w.G, w.P, w.clip)
     owc, ows = o.prepare_weight(w.W_f32()[:, cols], w.G, w.P)
     ref_e2e = o.gemm(oxc, oxs, owc, ows)
     e2e = _relfro(sub(Y32), ref_e2e)
-    print(f"cfg {cfg}: fp32-out err {e32:.2e}, end-to-end err {e2e:.2e}")
+    print(f"cfg {cfg}: fp32-out err {e32:.2e} over {sum(b - a for a, b in chunks)} rows x {w.N} columns, end-to-end err {e2e:.2e}")
     assert e2e <= 2e-3, e2e
 
 

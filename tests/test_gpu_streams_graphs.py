@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 import batq_inputs as bi
+from oracle import batq_oracle as o
 from gpu_util import require_gpu, to_dev
 
 pytestmark = pytest.mark.gpu
@@ -32,7 +33,7 @@ def test_linear_on_a_side_stream(B, M):
     ref8 = B.batq_linear_a8w4(t, wh, X, torch.bfloat16)
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
-    work = torch.empty(B.batq_linear_a8w4_workspace(M, w.K), dtype=torch.uint8, device="cuda")
+    work = torch.empty(B.batq_linear_workspace_for(wh, M, 8), dtype=torch.uint8, device="cuda")
     Y = torch.empty_like(ref)
     Y8 = torch.empty_like(ref)
     with torch.cuda.stream(side):
@@ -69,47 +70,88 @@ def test_linear_inside_a_captured_graph(B, M):
         assert bool(torch.isfinite(junk))
 
 
-def test_split_k_gemm_in_graphs(B):
-    """A long-K, few-strip GEMM cuts K into parts and keeps partial sums in memory owned by the stream.  A
-    capture on a stream that has none yet must not allocate (the unsplit kernel is recorded instead); a
-    capture on a stream that has run the shape before records the split kernels.  Both replay correctly."""
+def _split_k_problem(B, seed=5):
     import torch
     M, K, N = 130, 8192, 320
-    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    g = torch.Generator(device="cuda"); g.manual_seed(seed)
     wc = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda", generator=g)
     ws = torch.randint(122, 132, (N, K // 32), dtype=torch.uint8, device="cuda", generator=g)
     wh = B.batq_weight_import(wc, ws, K, N)
-    xs = B.batq_scales_from_rowmajor(torch.randint(122, 132, (M, K // 32), dtype=torch.uint8, device="cuda", generator=g))
+    xsr = torch.randint(122, 132, (M, K // 32), dtype=torch.uint8, device="cuda", generator=g)
     xr = torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device="cuda", generator=g)
-    xc = B.batq_codes_from_rowmajor(xr)
-    ref = B.batq_gemm_mxfp4(xc, xs, wh, M, torch.float32)            # eager, current stream: split
+    ref = o.gemm(xr.cpu().numpy(), xsr.cpu().numpy(), wc.cpu().numpy(), ws.cpu().numpy())
+    tol = 1e-6 * (np.abs(o.dequantize(xr.cpu().numpy(), xsr.cpu().numpy())) @
+                  np.abs(o.dequantize(wc.cpu().numpy(), ws.cpu().numpy())).T)
+    return M, wh, B.batq_codes_from_rowmajor(xr), B.batq_scales_from_rowmajor(xsr), ref, tol
+
+
+def test_split_k_gemm_in_graphs(B):
+    """A long-K, few-strip GEMM with a workspace cuts K into parts.  The kernels a call enqueues depend on its
+    arguments only, so a capture records the same kernels as an eager call, on a stream that has never run the
+    shape as on one that has, and every replay gives the eager bits."""
+    import torch
+    M, wh, xc, xs, ref64, tol = _split_k_problem(B)
+    need = B.batq_gemm_workspace(wh, M)
+    assert need > 0
+    work = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ref = B.batq_gemm_mxfp4(xc, xs, wh, M, torch.float32, workspace=work)       # eager, current stream
     torch.cuda.synchronize()
-    scale = float(ref.abs().max())
+    assert np.all(np.abs(ref.cpu().numpy().astype(np.float64) - ref64) <= tol + 1e-30)
     for warm in (False, True):
         st = torch.cuda.Stream()
         Y = torch.zeros_like(ref)
         if warm:
             with torch.cuda.stream(st):
-                B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y)
+                B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y, workspace=work)
             st.synchronize()
             assert torch.equal(Y, ref)
         gr = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gr, stream=st):
-            B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y)
-        outs = []
+            B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Y, workspace=work)
         for rep in range(3):
             Y.zero_()
             junk = torch.randn(300, 300, device="cuda") @ torch.randn(300, 300, device="cuda")
             torch.cuda.synchronize()
             gr.replay()
             torch.cuda.synchronize()
-            outs.append(Y.clone())
+            assert torch.equal(Y, ref), (warm, rep)
             assert bool(torch.isfinite(junk).all())
-        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
-        # split and unsplit kernels differ only in the order of fp32 additions
-        assert float((outs[0] - ref).abs().max()) <= 1e-5 * scale
-        if warm:
-            assert torch.equal(outs[0], ref)
+
+
+def test_split_k_graph_replay_beside_eager_launches(B):
+    """A graph captured on stream A, replayed on stream B while eager K-part GEMMs run on A: each call owns the
+    workspace it was given, so nothing is shared between the two and both give the reference bits."""
+    import torch
+    M, wh, xc, xs, ref64, tol = _split_k_problem(B, seed=6)
+    need = B.batq_gemm_workspace(wh, M)
+    work_g = torch.empty(need, dtype=torch.uint8, device="cuda")
+    work_e = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ref = B.batq_gemm_mxfp4(xc, xs, wh, M, torch.float32, workspace=work_e)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(ref.cpu().numpy().astype(np.float64) - ref64) <= tol + 1e-30)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    Yg = torch.zeros_like(ref)
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr, stream=sa):
+        B.batq_gemm_mxfp4(xc, xs, wh, M, Y=Yg, workspace=work_g)
+    Ye = [torch.zeros_like(ref) for _ in range(6)]
+    for rep in range(3):
+        Yg.zero_()
+        for y in Ye:
+            y.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sa):
+            for y in Ye[:3]:
+                B.batq_gemm_mxfp4(xc, xs, wh, M, Y=y, workspace=work_e)
+        with torch.cuda.stream(sb):
+            gr.replay()
+        with torch.cuda.stream(sa):
+            for y in Ye[3:]:
+                B.batq_gemm_mxfp4(xc, xs, wh, M, Y=y, workspace=work_e)
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, ref), rep
+        for y in Ye:
+            assert torch.equal(y, ref), rep
 
 
 def test_cache_calls_inside_a_captured_graph(B):

@@ -17,9 +17,12 @@ def B():
 
 
 def _header_functions():
-    text = open(os.path.join(ROOT, "include", "batq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(batq_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("batq.h", "batq_debug.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(batq_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(B):
