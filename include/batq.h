@@ -224,6 +224,17 @@ batq_status batq_gemm_mxfp4_ws(const uint8_t* xcodes, const uint8_t* xscales, co
                                int M, void* Y, batq_dtype ydtype, int64_t ldy,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that can neither pass a workspace nor let the library allocate (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): batq_gemm_mxfp4_ws with the K-part sums in a 16 MiB array that
+ * is part of the library's device code (one copy per GPU that runs the library, held until the process ends).
+ * Same result, bit for bit, as batq_gemm_mxfp4_ws with a workspace of batq_gemm_workspace(w, M, 4) bytes.
+ * BATQ_ERR_WORKSPACE if the shape asks for more than 16 MiB (no shape does on 256 compute units: the K parts
+ * ask for at most 64 KiB per compute unit).  Calls no allocating routine.  All calls on one GPU share that
+ * GPU's array, which keeps the last call's contents (nothing in it needs clearing): calls that overlap on one GPU
+ * - different streams, or graphs replayed side by side - race on it and must be serialised by the caller. */
+batq_status batq_gemm_mxfp4_noalloc(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w,
+                                    int M, void* Y, batq_dtype ydtype, int64_t ldy, void* stream);
+
 /* Online steps 1+2: Y = Q(X P) Q(P^-1 W) (the objective of Sec. 3.1).
  * `workspace` is DEVICE memory (256-byte aligned) of at least batq_linear_workspace(M, K)
  * bytes (= batq_code_bytes(M, K) + batq_scale_bytes(M, K)).  It holds the activation codes

@@ -52,6 +52,7 @@ SYMBOLS = {
     "batq_gemm_workspace": (_sz, [_vp, _i, _i]),
     "batq_gemm_mxfp4_ws": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp, _sz, _vp]),
     "batq_gemm_a8w4_ws": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp, _sz, _vp]),
+    "batq_gemm_mxfp4_noalloc": (_i, [_vp, _vp, _vp, _i, _vp, _i, _i64, _vp]),
     "batq_linear_workspace": (_sz, [_i, _i]),
     "batq_linear_workspace_for": (_sz, [_vp, _i, _i]),
     "batq_linear": (_i, [_vp, _vp, _vp, _i, _i, _i64, _vp, _i, _i64, _vp, _sz, _vp]),

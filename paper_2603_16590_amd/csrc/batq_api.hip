@@ -176,6 +176,10 @@ batq_status alloc_weight(batq_weight** out, int K, int N) {
             return BATQ_ERR_DEVICE;
         }
     }
+    {
+        void* unused = nullptr;                             // first use of the device: resolve the static scratch array
+        if (batq::static_scratch(&unused) != hipSuccess) (void)hipGetLastError();
+    }
     if (hipMalloc(reinterpret_cast<void**>(&w->d_codes), batq::code_bytes_blocked(N, K / 32)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void**>(&w->d_scales), batq::scale_bytes_internal(N, K / 32)) != hipSuccess) {
         (void)hipGetLastError();
@@ -679,6 +683,19 @@ batq_status batq_gemm_mxfp4_ws(const uint8_t* xcodes, const uint8_t* xscales, co
 batq_status batq_gemm_a8w4_ws(const uint8_t* xcodes8, const uint8_t* xscales, const batq_weight* w, int M, void* Y,
                               batq_dtype ydtype, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
     return gemm_impl(xcodes8, xscales, w, M, Y, ydtype, ldy, true, false, workspace, workspace_bytes, stream);
+}
+
+batq_status batq_gemm_mxfp4_noalloc(const uint8_t* xcodes, const uint8_t* xscales, const batq_weight* w, int M,
+                                    void* Y, batq_dtype ydtype, int64_t ldy, void* stream) {
+    if (!w) return BATQ_ERR_NULL;
+    const size_t need = M > 0 ? batq::gemm_workspace_bytes(w, M, false, w->cus) : 0;
+    if (need > batq::kStaticScratchBytes) return BATQ_ERR_WORKSPACE;
+    void* parts = nullptr;
+    if (need > 0 && batq::static_scratch(&parts) != hipSuccess) {
+        (void)hipGetLastError();
+        return BATQ_ERR_DEVICE;
+    }
+    return gemm_impl(xcodes, xscales, w, M, Y, ydtype, ldy, false, false, parts, need, stream);
 }
 
 size_t batq_linear_workspace(int M, int K) { return workspace_impl(M, K, false); }

@@ -105,6 +105,11 @@ hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_inter
                              size_t parts_bytes, hipStream_t stream);
 // Partial-sum bytes with which the GEMM of M rows against `w` runs all the K parts it wants (0: it wants none).
 size_t gemm_workspace_bytes(const batq_weight* w, int M, bool a8, int compute_units);
+// The per-device partial-sum array of the allocation-free entry point (kStaticScratchBytes bytes, 256-byte
+// aligned) on the current device; its address is looked up once per device.  64 KiB per compute unit is the
+// most a GEMM's K parts ask for, so 16 MiB serves every shape on 256 compute units.
+constexpr size_t kStaticScratchBytes = size_t(16) << 20;
+hipError_t static_scratch(void** ptr);
 bool gemm_glu_supported(const batq_weight* w, int M, bool a8);
 // Host replay of the tiled kernels' work split: 7 ints per tile (workgroup, first row, first column, strips, K part,
 // first K group, K groups) into out[capacity * 7]; returns the number of tiles.

@@ -1480,4 +1480,27 @@ hipError_t launch_gemm_mxfp4(const uint8_t* xcodes, const uint8_t* xscales_inter
                : launch_gemm_as<false>(xcodes, xscales_internal, w, M, Y, ydtype, ldy, a8, pf, parts_bytes, stream);
 }
 
+// Partial-sum memory for callers that can pass no workspace and must not allocate: one array per device, part of
+// the loaded code object (each device that runs the library holds its own copy until the process ends).  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+// Nothing in it has to start at zero: every K part writes all the blocks the reduction reads.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void** ptr) {
+    static std::atomic<void*> address[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool cached = dev >= 0 && dev < kMaxDevices;
+    void* p = cached ? address[dev].load(std::memory_order_acquire) : nullptr;
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        if (cached) address[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
+}
+
 }  // namespace batq
