@@ -365,13 +365,12 @@ batq_status batq_linear_glu(const batq_transform* t, const batq_weight* w, const
  * A cache that grows: batq_kv_append quantises M new token rows of X exactly as batq_quantize_act (act_bits 4) or
  *   batq_quantize_act_mxfp8 (act_bits 8) would, but into rows row_offset .. row_offset + M - 1 of code and scale
  *   arrays (DEVICE, caller-owned) that are laid out for capacity_rows rows: batq_code_bytes / batq_code8_bytes and
- *   batq_scale_bytes of (capacity_rows, K).  Rows are independent: what a row gets does not depend on the
- *   append that brought it, up to the kernel that ran.  Of a bf16 append the rows from the first multiple of 32
- *   on take the matrix-core kernel if they are more than 128, all other rows the register-level one; the two round their
- *   transforms differently, so they agree up to rounding ties (single codes one step apart, fewer than 1e-3 of
- *   them), as each agrees with the reference; fp32 rows always take the same kernel.  The matrix-core kernel
- *   writes whole 32-row tiles of codes: the code rows after the appended block up to the next multiple of 32 (not
- *   yet part of the cache) are then overwritten with unspecified values; other appends write their own rows only.
+ *   batq_scale_bytes of (capacity_rows, K).  Rows are independent, and a row's codes and scale do not depend on
+ *   the append that brought it: any sequence of appends leaves exactly the bytes one call over all rows writes
+ *   (bf16 rows always take the matrix-core arithmetic, fp32 rows the register-level kernel).  Of a bf16 append of
+ *   more than 2^22 / K rows the part from the first multiple of 32 on is written in whole 32-row tiles of codes: the
+ *   code rows after the appended block up to the next multiple of 32 (not yet part of the cache) then hold
+ *   unspecified values; other appends write their own rows only.
  *   BATQ_ERR_SHAPE if the window does not fit.
  *   batq_kv_dequantize reads rows row_offset .. row_offset + M - 1 of such arrays into out rows 0 .. M - 1
  *   (otherwise as batq_dequantize).  Both are asynchronous on `stream` and allocate nothing. */

@@ -585,6 +585,120 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
     flush();
 }
 
+// The same arithmetic for few rows, and for rows that do not start on a 32-row tile of the destination (cache
+// appends): one wave per (32-row tile of the call, MX block), operands straight from global memory into registers
+// (no workgroup set-up, no LDS staging: with few rows that would cost more than the rows), codes and scale bytes
+// stored row by row at any destination row.  Every floating-point step - the six matrix instructions of a block
+// in the same order on the same pre-split operand, the row factor, the block extrema, the bound, the clamp and the
+// convert - is the one quant_act_mfma takes, so a row gets the same codes and scale whichever of the two kernels
+// quantises it, in whatever batch it arrives.
+template <bool MINMAX, bool FP8, bool SWIGLU>
+__global__ void __launch_bounds__(256)
+quant_act_mfma_rows(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ U, int64_t ldu, int M,
+                    int nb, int row0, int srows, const uint4* __restrict__ Tsplit, const float* __restrict__ clip,
+                    const float* __restrict__ clip_max, const float* __restrict__ row_scale,
+                    uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int nbp = scale_groups(nb) * 8;                   // blocks of a row, the padding of the last K group included
+    const int tiles = (M + 31) >> 5;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= tiles * nbp) return;                        // wave-uniform
+    const int tile = unit / nbp, k = unit - tile * nbp;
+    const int row = tile * 32 + l32;
+    const bool live = row < M;
+    const int drow = row0 + row;                            // destination row in arrays laid out for srows rows
+    if (k >= nb) {
+        // padding block: zero codes, neutral scale
+        if (live) {
+            if constexpr (FP8)
+                *reinterpret_cast<uint4*>(codes + code8_slot_offset(drow, k, kg, nb)) = uint4{0u, 0u, 0u, 0u};
+            else
+                *reinterpret_cast<uint2*>(codes + code_chunk_offset(drow, k, nb) + 8 * kg) = uint2{0u, 0u};
+            if (kg == 0) scales[scale_index_internal(drow, k, srows)] = (uint8_t)127;
+        }
+        return;
+    }
+    const int rr = min(row, M - 1);                         // rows past the end repeat the last one: computed, not stored
+    // this lane's operand: elements 16 kg + 8 h .. + 7 of block k of its row
+    const uint16_t* xp = X + (size_t)rr * ldx + (size_t)k * 32 + 16 * kg;
+    u32x4 x[2], up[2] = {};
+    x[0] = *reinterpret_cast<const u32x4*>(xp);
+    x[1] = *reinterpret_cast<const u32x4*>(xp + 8);
+    if constexpr (SWIGLU) {
+        const uint16_t* upp = U + (size_t)rr * ldu + (size_t)k * 32 + 16 * kg;
+        up[0] = *reinterpret_cast<const u32x4*>(upp);
+        up[1] = *reinterpret_cast<const u32x4*>(upp + 8);
+    }
+    const uint4* tf = Tsplit + (size_t)k * (kTsplitBlock / 16) + lane;
+    uint4 tfr[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) tfr[i] = tf[i * 64];
+    const float rs = row_scale ? row_scale[rr] : 1.0f;
+    if constexpr (SWIGLU) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[h][i] = swiglu_pair(x[h][i], up[h][i]);
+    }
+    v16f acc = {};
+#pragma unroll
+    for (int t = 2; t >= 0; --t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, tfr[t * 2 + h]),
+                                                          __builtin_bit_cast(bf16x8, x[h]), acc, 0, 0, 0);
+    float y[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) y[r] = acc[r];
+    if (row_scale) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] *= rs;
+    }
+    auto other_half = [&](float v) -> float {
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, v)));
+    };
+    float bound;
+    if constexpr (MINMAX) {
+        float mn = y[0], mx = y[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) {
+            mn = __builtin_fminf(mn, y[r]);
+            mx = __builtin_fmaxf(mx, y[r]);
+        }
+        mn = __builtin_fminf(mn, other_half(mn));
+        mx = __builtin_fmaxf(mx, other_half(mx));
+        const float lo = clip[k] * mn, hi = clip_max[k] * mx;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] = clamp_lo_hi(y[r], lo, hi);
+        bound = __builtin_fmaxf(__builtin_fabsf(clamp_lo_hi(mn, lo, hi)), __builtin_fabsf(clamp_lo_hi(mx, lo, hi)));
+    } else {
+        float a = __builtin_fabsf(y[0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) a = __builtin_fmaxf(a, __builtin_fabsf(y[r]));
+        bound = clip[k] * __builtin_fmaxf(a, other_half(a));    // one fp32 multiply
+    }
+    if constexpr (FP8) {
+        const uint32_t sb = e8m0_of_bound_fp8(bound);
+        const float sc = scale_operand(sb);
+        const uint2 o0 = encode8_fp8(y, bound, sb, sc), o1 = encode8_fp8(y + 8, bound, sb, sc);
+        if (live) {
+            *reinterpret_cast<uint4*>(codes + code8_slot_offset(drow, k, kg, nb)) = uint4{o0.x, o0.y, o1.x, o1.y};
+            if (kg == 0) scales[scale_index_internal(drow, k, srows)] = (uint8_t)sb;
+        }
+    } else {
+        const uint32_t sb = e8m0_of_bound(bound);
+        const float sc = scale_operand(sb);
+        uint2 out;
+        out.x = encode8(y, bound, sc);
+        out.y = encode8(y + 8, bound, sc);
+        if (live) {
+            *reinterpret_cast<uint2*>(codes + code_chunk_offset(drow, k, nb) + 8 * kg) = out;
+            if (kg == 0) scales[scale_index_internal(drow, k, srows)] = (uint8_t)sb;
+        }
+    }
+}
+
 // Destination rows of a call: the code and scale arrays are laid out for `srows` rows, and the M rows of X go to
 // rows row0 .. row0 + M - 1 (a plain call: row0 = 0, srows = M).
 struct RowWindow {
@@ -627,6 +741,29 @@ hipError_t launch_mfma(const batq_transform* t, const uint16_t* X, int M, int64_
     return t->minmax
                ? launch_mfma_as<true, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream)
                : launch_mfma_as<false, false, SWIGLU>(t, X, M, ldx, U, ldu, row_scale, codes, scales, win, dev, cus, stream);
+}
+
+template <bool SWIGLU>
+hipError_t launch_mfma_rows(const batq_transform* t, const uint16_t* X, int M, int64_t ldx, const uint16_t* U, int64_t ldu,
+                            const float* row_scale, uint8_t* codes, uint8_t* scales, RowWindow win, bool fp8,
+                            hipStream_t stream) {
+    const int nb = t->nb;
+    const int64_t units = (int64_t)((M + 31) / 32) * scale_groups(nb) * 8;
+    const dim3 grid((unsigned)((units + 3) / 4)), block(256);
+    const uint4* ts = reinterpret_cast<const uint4*>(t->d_Tsplit);
+    const float* cmax = t->minmax ? t->d_clip_max : nullptr;
+#define BATQ_ROWS(MM, F8)                                                                                              \
+    quant_act_mfma_rows<MM, F8, SWIGLU><<<grid, block, 0, stream>>>(X, ldx, U, ldu, M, nb, win.row0, win.srows, ts,    \
+                                                                     t->d_clip, cmax, row_scale, codes, scales)
+    if (fp8) {
+        if (t->minmax) BATQ_ROWS(true, true);
+        else BATQ_ROWS(false, true);
+    } else {
+        if (t->minmax) BATQ_ROWS(true, false);
+        else BATQ_ROWS(false, false);
+    }
+#undef BATQ_ROWS
+    return hipGetLastError();
 }
 
 template <typename XT, bool FP8>
@@ -754,7 +891,12 @@ hipError_t launch_dense(const batq_transform* t, const XT* X, int M, int64_t ldx
     return hipGetLastError();
 }
 
-constexpr int kQuadMaxRows = 128;
+// bf16 rows with a transform always go through the matrix cores, with one arithmetic (see quant_act_mfma_rows).
+// Which of the two kernels serves a row only changes the speed: the row-by-row kernel has no set-up but fetches
+// 6 KiB of transform operand per 2 KiB of X, so it wins while the call is small (graph-replayed, rows x K:
+// 16 x 4096 2.4 us against 4.6 us, 1024 x 4096 5.0 against 5.7, 384 x 14336 6.4 against 6.5, 2048 x 4096 7.7 against
+// 7.3): it takes calls of up to 2^22 elements, and the rows in front of the first 32-row tile of a longer window.
+constexpr int64_t kRowsKernelMaxElements = int64_t(1) << 22;
 
 template <bool FP8>
 hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype xdtype, int M, int64_t ldx,
@@ -763,26 +905,24 @@ hipError_t launch_quantize_as(const batq_transform* t, const void* X, batq_dtype
     if (xdtype == BATQ_BF16) {
         auto Xp = static_cast<const uint16_t*>(X);
         auto Up = static_cast<const uint16_t*>(U);
-        // the matrix-core kernel (any form of T_k) addresses a 32-row tile with 32-bit byte offsets.  With few
-        // rows (decode steps) the register-level kernel is the faster one for the Kronecker forms: it has no
-        // 48 KiB of transform operands per K group to stage before the first row (2.4 us against 4.6 us at
-        // 16 rows; the two meet at about 256 rows).
-        // It writes whole 32-row tiles of codes, so its window must start on one: of a long window that does not,
-        // the rows up to the next tile go to the register-level kernel first.
-        const bool mfma_ok = t->has_transform && t->d_Tsplit && ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25);
-        const int head = (32 - (win.row0 & 31)) & 31;
-        if (mfma_ok && head != 0 && M - head > kQuadMaxRows) {
-            hipError_t e = launch_quantize_as<FP8>(t, X, xdtype, head, ldx, U, ldu, row_scale, codes, scales, win, stream);
-            if (e != hipSuccess) return e;
-            return launch_quantize_as<FP8>(t, Xp + (size_t)head * ldx, xdtype, M - head, ldx,
-                                           Up ? Up + (size_t)head * ldu : nullptr, ldu,
-                                           row_scale ? row_scale + head : nullptr, codes, scales,
-                                           RowWindow{win.row0 + head, win.srows}, stream);
+        if (t->has_transform && t->d_Tsplit) {
+            // the persistent kernel addresses a 32-row tile with 32-bit byte offsets and writes whole 32-row tiles of
+            // codes, so its window must start on one
+            const bool wide_ok = ldx < (int64_t(1) << 25) && ldu < (int64_t(1) << 25);
+            const int head = std::min(M, (32 - (win.row0 & 31)) & 31);
+            const int rest = M - head;
+            const int by_rows = (!wide_ok || (int64_t)rest * t->K <= kRowsKernelMaxElements) ? M : head;
+            if (by_rows > 0) {
+                hipError_t e = Up ? launch_mfma_rows<true>(t, Xp, by_rows, ldx, Up, ldu, row_scale, codes, scales, win, FP8, stream)
+                                  : launch_mfma_rows<false>(t, Xp, by_rows, ldx, nullptr, 0, row_scale, codes, scales, win, FP8, stream);
+                if (e != hipSuccess || by_rows == M) return e;
+            }
+            const RowWindow tail{win.row0 + by_rows, win.srows};
+            const uint16_t* Xt = Xp + (size_t)by_rows * ldx;
+            const float* rst = row_scale ? row_scale + by_rows : nullptr;
+            return Up ? launch_mfma<true>(t, Xt, M - by_rows, ldx, Up + (size_t)by_rows * ldu, ldu, rst, codes, scales, tail, FP8, stream)
+                      : launch_mfma<false>(t, Xt, M - by_rows, ldx, nullptr, 0, rst, codes, scales, tail, FP8, stream);
         }
-        const bool few_rows = (M <= kQuadMaxRows && t->form != BATQ_FORM_DENSE) || head != 0;
-        if (!few_rows && mfma_ok)
-            return Up ? launch_mfma<true>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, FP8, stream)
-                      : launch_mfma<false>(t, Xp, M, ldx, nullptr, 0, row_scale, codes, scales, win, FP8, stream);
         if (t->form == BATQ_FORM_DENSE)
             return launch_dense<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);
         return launch_quad<uint16_t, FP8>(t, Xp, M, ldx, Up, ldu, row_scale, codes, scales, win, stream);

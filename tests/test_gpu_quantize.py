@@ -267,8 +267,9 @@ def test_argument_errors_leave_outputs_untouched(B):
 
 
 def test_row_stride_beyond_the_matrix_core_kernels_offsets(B):
-    """A bf16 input whose row stride is 2^25 elements or more cannot be addressed with the matrix-core kernel's
-    32-bit tile offsets: such calls take the register-level or the dense kernel.  Same bar as elsewhere."""
+    """A bf16 input whose row stride is 2^25 elements or more cannot be addressed with the persistent matrix-core
+    kernel's 32-bit tile offsets: such calls take the row-by-row matrix-core kernel (64-bit addresses) whatever the
+    row count, with the same arithmetic - the codes of the contiguous call, byte for byte."""
     import torch
     M, K, ld = 5, 32 * 9, 1 << 25
     w = bi.make_small(M, K, 8, seed=77, dtype="bf16")
@@ -283,6 +284,47 @@ def test_row_stride_beyond_the_matrix_core_kernels_offsets(B):
         gs = grouped_to_rowmajor(s.cpu().numpy(), M, K // 32)
         oc, os_ = o.quantize_act_blocks(w.X_f32(), T, w.clip)
         assert np.mean(gs != os_) <= 0.01 and np.mean(code_value_mismatch(gc, oc)) <= 1e-3
-        # and the same codes as the contiguous call wherever the two kernels agree on ties
+        # and the same codes and scales as the contiguous call
         g0 = blocked_to_rowmajor(c0.cpu().numpy(), M, K // 32)
-        assert np.mean(code_value_mismatch(gc, g0)) <= 1e-3
+        assert np.array_equal(gc, g0) and torch.equal(s, s0)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_a_rows_codes_do_not_depend_on_the_batch(B, bits):
+    """Sec. 3.2 writes the key/value cache token by token and evaluates whole sequences: the same bf16 row must get
+    the same codes and scale in a 1-row, a 16-row, a 129-row and a 2100-row call.  The whole call (more than 2^22
+    elements) runs on the persistent matrix-core kernel, the small ones on the row-by-row kernel; the two share one
+    arithmetic.  Checked with every option of the online call, and for an append whose window starts off a 32-row
+    tile (its first rows take the row-by-row kernel, the rest the persistent one)."""
+    import torch
+    M, K = 2100, 32 * 65
+    assert M * K > 1 << 22
+    w = bi.make_small(M, K, 8, seed=31 + bits, dtype="bf16")
+    rng = np.random.default_rng(bits)
+    rs = torch.from_numpy(rng.uniform(0.5, 2.0, M).astype(np.float32)).cuda()
+    X = to_dev(w.X, "bf16")
+    Uup = to_dev(bi.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)), "bf16")
+    to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
+    transforms = [B.Transform(K, w.G, w.P, w.clip),
+                  B.Transform.general(K, dense=o.kron_blocks(w.G, w.P).astype(np.float32),
+                                      clip_min=w.clip, clip_max=np.minimum(1.0, w.clip + 0.05).astype(np.float32))]
+    for t in transforms:
+        for opts in ({}, {"row_scale": rs}, {"up": Uup}):
+            def run(r0, r1):
+                kw = {k: v[r0:r1] for k, v in opts.items()}
+                c, s = B.batq_quantize_act_ex(t, X[r0:r1], act_bits=bits, **kw)
+                return to_rm(c, r1 - r0, K), B.batq_scales_to_rowmajor(s, r1 - r0, K)
+            c_all, s_all = run(0, M)
+            for r0, r1 in ((0, 1), (2099, 2100), (3, 19), (64, 193), (130, 131), (500, 628), (200, 1000)):
+                c, s = run(r0, r1)
+                torch.cuda.synchronize()
+                assert torch.equal(c, c_all[r0:r1]) and torch.equal(s, s_all[r0:r1]), (bits, list(opts), r0, r1)
+        # one long append at row 7 of a cache laid out for more rows
+        cap = M + 40
+        codes = torch.zeros(B.batq_code8_bytes(cap, K) if bits == 8 else B.batq_code_bytes(cap, K), dtype=torch.uint8, device="cuda")
+        scales = torch.zeros(B.batq_scale_bytes(cap, K), dtype=torch.uint8, device="cuda")
+        B.batq_kv_append(t, X, codes, scales, 7, cap, bits)
+        c_ref, s_ref = B.batq_quantize_act_ex(t, X, act_bits=bits)
+        torch.cuda.synchronize()
+        assert torch.equal(to_rm(codes, cap, K)[7:7 + M], to_rm(c_ref, M, K))
+        assert torch.equal(B.batq_scales_to_rowmajor(scales, cap, K)[7:7 + M], B.batq_scales_to_rowmajor(s_ref, M, K))
