@@ -382,6 +382,9 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// s_waitcnt lgkmcnt(0) only: the wave's LDS reads have delivered.
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 // One matrix instruction of the grid of 32x32 tiles a wave owns; ZERO starts the accumulation.
 template <int KK, bool ZERO>
 __device__ __forceinline__ void mfma_one(v16f& acc, const uint4& a, const uint4& b, int sa, int sb) {
@@ -390,11 +393,6 @@ __device__ __forceinline__ void mfma_one(v16f& acc, const uint4& a, const uint4&
     else
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, KK, sa, KK, sb);
 }
-
-// Scheduling hints: keep the instruction order written below (the wave runs alone on its
-// SIMD, so LDS latency is hidden only by what the wave itself has queued on the matrix pipe).
-#define BATQ_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, (n), 0)
-#define BATQ_SCHED_DSRD(n) __builtin_amdgcn_sched_group_barrier(0x100, (n), 0)
 
 struct TiledCtx {
     // global -> LDS
@@ -490,6 +488,14 @@ struct TiledCtx {
 #pragma unroll
         for (int i = 1; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
     }
+    // fragment IDX of that order alone
+    template <int NJ, int IDX>
+    __device__ __forceinline__ void read_frag_one(int s, int half, uint4 (&fa)[4], uint4 (&fb)[NJ]) const {
+        const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
+        if constexpr (IDX == 0) fa[0] = *reinterpret_cast<const uint4*>(base + a_rd);
+        else if constexpr (IDX <= NJ) fb[IDX - 1] = *reinterpret_cast<const uint4*>(base + b_rd + (IDX - 1) * 32 * kStageBytes);
+        else fa[IDX - NJ] = *reinterpret_cast<const uint4*>(base + a_rd + (IDX - NJ) * 32 * kStageBytes);
+    }
     template <int NJ>
     __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[NJ]) const {
         const uint8_t* sp = smem + kRing * kStageLds + (g & 1) * kScaleGroupLds;
@@ -510,75 +516,65 @@ __device__ __forceinline__ void issue_range(const TiledCtx& c, int s) {
     }
 }
 
-// Matrix instructions Q .. 2 NJ - 1 of the last quarter of a stage (tile rows 2 and 3 of the second
-// K step), each followed by its share of the 5 + NJ load parts of stage s+4.
-template <int NJ, int PAR, bool DO_ISSUE, int Q>
-__device__ __forceinline__ void stage_part_two(const TiledCtx& c, int s, v16f (&acc)[4][NJ], const uint4 (&a1)[4],
-                                               const uint4 (&b1)[NJ], const int (&sa)[4], const int (&sb)[NJ]) {
-    if constexpr (Q < 2 * NJ) {
-        constexpr int i = 2 + Q / NJ, j = Q % NJ;
-        constexpr int kParts = 5 + NJ, kSlots = 2 * NJ;
-        mfma_one<2 * PAR + 1, false>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
-        if constexpr (DO_ISSUE) {
-            __builtin_amdgcn_sched_barrier(0);
-            issue_range<NJ, PAR == 0, Q * kParts / kSlots, (Q + 1) * kParts / kSlots>(c, s + 4);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        stage_part_two<NJ, PAR, DO_ISSUE, Q + 1>(c, s, acc, a1, b1, sa, sb);
+// One K step of a stage for tiles three or four strips wide: its 4 NJ matrix instructions in row-major tile order,
+// and after each of them at most one LDS fragment read and its share of a set of load parts, so that neither the
+// LDS pipe nor the vector-memory address path sees a burst (a wave that blocks on either cannot issue its next
+// matrix instruction: measured on cfg3, bunched reads and loads cost 360 of 1490 cycles per stage).
+//   KK      scale byte of the K step (op_sel); ZERO: the K step starts the accumulators
+//   RD      read the fragments of (rd_stage, rd_half) into ra / rb, one per matrix instruction, in the order the
+//           next K step consumes them (a0, b0.., a1..a3)
+//   TE      the stage `st` whose load parts [P0, P1) are issued here is even (its last part = the scales of a K group)
+template <int NJ, int KK, bool ZERO, bool RD, bool TE, int P0, int P1, int M>
+__device__ __forceinline__ void wide_k_step(const TiledCtx& c, v16f (&acc)[4][NJ], const uint4 (&a)[4],
+                                            const uint4 (&b)[NJ], const int (&sa)[4], const int (&sb)[NJ], int rd_stage,
+                                            int rd_half, uint4 (&ra)[4], uint4 (&rb)[NJ], int st) {
+    constexpr int NM = 4 * NJ;
+    if constexpr (M < NM) {
+        constexpr int i = M / NJ, j = M % NJ;
+        mfma_one<KK, ZERO>(acc[i][j], a[i], b[j], sa[i], sb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (RD && M < 4 + NJ) c.read_frag_one<NJ, M>(rd_stage, rd_half, ra, rb);
+        constexpr int np = P1 - P0;
+        issue_range<NJ, TE, P0 + M * np / NM, P0 + (M + 1) * np / NM>(c, st);
+        __builtin_amdgcn_sched_barrier(0);
+        wide_k_step<NJ, KK, ZERO, RD, TE, P0, P1, M + 1>(c, acc, a, b, sa, sb, rd_stage, rd_half, ra, rb, st);
     }
 }
 
-// One K stage (two matrix-instruction K steps) of the software pipeline.
-//   NJ     32-column matrix tiles per wave
-//   PAR    parity of the stage inside its K group (selects the scale bytes: op_sel 2 PAR, 2 PAR + 1)
-//   WAIT   loads that may stay in flight once stage s+1 has landed (-1: there is no stage s+1)
-//   ISSUE  start the loads of stage s+4 into the ring slot this stage frees
-//   FIRST  first stage of a tile: its first K step starts the accumulators from zero
-// On entry a0/b0 hold the fragments of (s, first half); on exit those of (s+1, first half).
-template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+// One K stage (two matrix-instruction K steps) of the software pipeline, tiles three or four strips wide.
+//   NJ       32-column matrix tiles per wave
+//   PAR      parity of the stage inside its K group (selects the scale bytes: op_sel 2 PAR, 2 PAR + 1)
+//   WAIT     loads that may stay in flight once stage s+1 has landed (-1: there is no stage s+1)
+//   ISSUE_A  start the loads of stage s+4 (the first half of its parts) after the barrier, into the ring slot this
+//            stage frees there
+//   ISSUE_B  finish the loads of stage s+3 (the second half of its parts; the slot was freed by the barrier of
+//            stage s-1) during the first K step
+//   FIRST    first stage of a tile: its first K step starts the accumulators from zero
+// On entry a0/b0 hold the fragments of (s, first half); on exit those of (s+1, first half).  The barrier sits
+// between the two K steps: by then every wave has stage s completely in registers (the second half's fragments are
+// read under the first K step), and once all have also seen stage s+1 land, its fragments are read under the second
+// K step.  The loads of a stage are thus issued one by one over a whole stage length, from the middle of stage s-4
+// to the middle of stage s-3, and have two to three stages to land.  When stage s+1 is awaited, stages s+2 and s+3
+// have been issued completely and stage s+4 not at all.
+template <int NJ, int PAR, int WAIT, bool ISSUE_A, bool ISSUE_B, bool FIRST>
 __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a0)[4],
                                             uint4 (&b0)[NJ], int (&sa)[4], int (&sb)[NJ]) {
+    constexpr int kParts = 5 + NJ, kA = (kParts + 1) / 2;
     uint4 a1[4], b1[NJ];
-    // first half: fetch the second half's fragments underneath its matrix instructions
-    c.read_frags<NJ>(s, 1, a1, b1);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR, FIRST>(acc[i][j], a0[i], b0[j], sa[i], sb[j]);
-    if constexpr (NJ == 4) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            BATQ_SCHED_DSRD(1);
-            BATQ_SCHED_MFMA(2);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4 + NJ; ++i) {
-            BATQ_SCHED_DSRD(1);
-            BATQ_SCHED_MFMA(1);
-        }
-        if constexpr (4 * NJ > 4 + NJ) BATQ_SCHED_MFMA(4 * NJ - (4 + NJ));
-    }
-    // second half, part one
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) mfma_one<2 * PAR + 1, false>(acc[i][j], a1[i], b1[j], sa[i], sb[j]);
-    BATQ_SCHED_MFMA(2 * NJ);
-    __builtin_amdgcn_sched_barrier(0);
+    // first K step: the second half's fragments, and the rest of stage s+3's loads (stage s+3 has the other parity)
+    wide_k_step<NJ, 2 * PAR, FIRST, true, PAR == 1, (ISSUE_B ? kA : 0), (ISSUE_B ? kParts : 0), 0>(
+        c, acc, a0, b0, sa, sb, s, 1, a1, b1, s + 3);
     int sna[4], snb[NJ];
     if constexpr (WAIT >= 0) {
-        // every wave has read stage s completely (its last fragments are in registers); once all
-        // have also seen stage s+1 land, the slot of stage s can be refilled
         wait_vmcnt<WAIT>();
+        wait_lds();                                         // this wave's fragments of stage s are in registers
         __syncthreads();
-        c.read_frags<NJ>(s + 1, 0, a0, b0);
         if constexpr (PAR == 1) c.read_scales<NJ>((s + 1) >> 1, sna, snb);
     }
     __builtin_amdgcn_sched_barrier(0);
-    // second half, part two: covers the latency of the reads just issued; the loads of stage s+4
-    // are issued between the matrix instructions, so the matrix pipe never waits for them
-    stage_part_two<NJ, PAR, (WAIT >= 0 && ISSUE), 0>(c, s, acc, a1, b1, sa, sb);
+    // second K step: the next stage's first fragments, and the first loads of stage s+4 (same parity as s)
+    wide_k_step<NJ, 2 * PAR + 1, false, (WAIT >= 0), PAR == 0, 0, ((WAIT >= 0 && ISSUE_A) ? kA : 0), 0>(
+        c, acc, a1, b1, sa, sb, s + 1, 0, a0, b0, s + 4);
     if constexpr (WAIT >= 0 && PAR == 1) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -587,9 +583,6 @@ __device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc
         for (int j = 0; j < NJ; ++j) sb[j] = snb[j];
     }
 }
-
-// s_waitcnt lgkmcnt(0) only: the wave's LDS reads have delivered.
-__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // The same stage for tiles one or two strips wide.  Their 8 or 16 matrix instructions per stage are too few to
 // hide a barrier followed by the LDS reads of the next fragments in the last quarter of the stage, so here the
@@ -655,11 +648,13 @@ __device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&ac
 }
 
 // Stage of a tile NJ strips wide: narrow tiles keep both K steps' fragments in `a`, `b`, wide ones the first.
-template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
+// ISSUE: stage s+4 exists and is loaded into the slot this stage frees; PREV: the same was true of stage s-1 (wide
+// tiles issue a stage's loads in two halves, the second half during the following stage).
+template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST, bool PREV = true>
 __device__ __forceinline__ void any_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
                                           uint4 (&b)[2][NJ], int (&sa)[4], int (&sb)[NJ]) {
     if constexpr (NJ <= 2) narrow_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a, b, sa, sb);
-    else tiled_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a[0], b[0], sa, sb);
+    else tiled_stage<NJ, PAR, WAIT, ISSUE, (PREV && !FIRST), FIRST>(c, s, acc, a[0], b[0], sa, sb);
 }
 
 // Epilogue of a tile: 4 x NJ output tiles of 32 x 32 of this wave (rows m0 + wm*128.., columns n0 + wn*32*NJ..)
@@ -841,17 +836,17 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
             any_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
             any_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
         }
-        any_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);
-        any_stage<NJ, 1, kOdd, false, false>(c, T - 3, acc, fa, fb, sa, sb);
-        any_stage<NJ, 0, 0, false, false>(c, T - 2, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);            // finishes the loads of stage T-1
+        any_stage<NJ, 1, kOdd, false, false, false>(c, T - 3, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, 0, false, false, false>(c, T - 2, acc, fa, fb, sa, sb);
     } else if (G == 2) {
         any_stage<NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
-        any_stage<NJ, 1, kOdd, false, false>(c, 1, acc, fa, fb, sa, sb);
-        any_stage<NJ, 0, 0, false, false>(c, 2, acc, fa, fb, sa, sb);
+        any_stage<NJ, 1, kOdd, false, false, false>(c, 1, acc, fa, fb, sa, sb);
+        any_stage<NJ, 0, 0, false, false, false>(c, 2, acc, fa, fb, sa, sb);
     } else {
         any_stage<NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
     }
-    any_stage<NJ, 1, -1, false, false>(c, T - 1, acc, fa, fb, sa, sb);
+    any_stage<NJ, 1, -1, false, false, false>(c, T - 1, acc, fa, fb, sa, sb);
 
     __syncthreads();                                      // every wave is done with the stage ring
     if (has_next) {
