@@ -17,11 +17,8 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// 16-byte store written through the L2 (device scope): for output nobody reads in the same kernel.  Lines left
-// dirty in the eight L2s would be written back when the kernel ends.
 __device__ __forceinline__ void store16_through(void* p, const uint4& q) {
-    const u32x4 v{q.x, q.y, q.z, q.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(v) : "memory");
+    batq::store16_through(p, batq_u32x4{q.x, q.y, q.z, q.w});
 }
 
 // 2^(byte - 127) as fp32; byte 0 is the subnormal 2^-127, byte 255 (the format's NaN) gives NaN.

@@ -76,6 +76,15 @@ __device__ __forceinline__ float swiglu_f32(float g, float u) {
     return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
 }
 
+// 16-byte store written through the L2 (device scope), for output that nobody reads in the same kernel: lines left
+// dirty in the eight L2s would be written back when the kernel ends.  A store of more than 8 bytes reads its data
+// registers after it has issued; the compiler keeps the next instructions from overwriting them for its own
+// stores but cannot see inside an asm statement, so the two wait states are part of it.
+typedef uint32_t batq_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_through(void* p, const batq_u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" :: "v"(p), "v"(v) : "memory");
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs).
