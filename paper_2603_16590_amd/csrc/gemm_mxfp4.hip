@@ -339,9 +339,11 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 }
 
 // ------------------------------------------------------------------------------------------
-// Tiled kernel.  Persistent workgroups of 4 waves, one per compute unit.  An output tile is
-// 256 rows by 64 NJ columns (NJ = 1..4 "strips" of 64 columns); the waves sit 2x2 on it, each
-// holding 4 x NJ matrix tiles (128 x 32 NJ outputs) in up to 256 accumulator registers.
+// Tiled kernel.  Persistent workgroups, one per compute unit.  An output tile is 256 rows by 64 NJ
+// columns (NJ = 1..4 "strips" of 64 columns); the waves sit (8 / RT) x 2 on it, each holding RT x NJ
+// matrix tiles (32 RT x 32 NJ outputs) in up to 64 RT accumulator registers.  RT = 4: 4 waves, one per
+// SIMD (the 8-bit kernel); RT = 2: 8 waves, two per SIMD, 128 accumulator and 128 other registers each:
+// while one wave of a SIMD converts and stores its outputs or waits for LDS, the other one issues.
 // K advances in stages of 128 elements (64 code bytes per row).  Codes and scales go
 // global -> LDS with LDS-direct loads (no VGPR staging, no ds_write): a ring of 4 stage
 // buffers keeps three stages in flight.  Scales of a whole 256-element K group (two stages)
@@ -357,9 +359,12 @@ constexpr int kOperandStage = kTile * kStageBytes;        // 16 KiB per operand 
 constexpr int kStageLds = 2 * kOperandStage;               // A then B
 constexpr int kRing = 4;                   // stage buffers
 constexpr int kScaleGroupLds = 2 * kTile * 8;              // A then B scale bytes of one K group (4 KiB)
-constexpr int kEpilogueWaveLds = 16 * 256;                 // per wave: 16 output rows x 256 bytes
+constexpr int kEpilogueWaveLds = 16 * 256;                 // per wave of 4: 16 output rows x 256 bytes
 constexpr int kEpilogueLds0 = kRing * kStageLds + 2 * kScaleGroupLds;
 constexpr int kTiledLds = kEpilogueLds0 + 4 * kEpilogueWaveLds;     // 152 KiB
+// rows of a wave's staged output block and the bytes of its staging area: 16 KiB per workgroup either way
+template <int RT> constexpr int kEpilogueBlockRows = RT == 4 ? 16 : 8;
+template <int RT> constexpr int kEpilogueWaveBytes = kEpilogueBlockRows<RT> * 256;
 
 // 16-byte slot swizzle inside a 64-byte LDS row: the 32 rows a fragment read touches, and the
 // 16 rows x 4 slots an LDS-direct load writes, both spread over all banks.
@@ -394,10 +399,19 @@ __device__ __forceinline__ void mfma_one(v16f& acc, const uint4& a, const uint4&
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(a), frag(b), acc, 4, 4, KK, sa, KK, sb);
 }
 
+template <int RT>
 struct TiledCtx {
+    static_assert(RT == 4 || RT == 2, "4 or 8 waves");
+    static constexpr int kWaves = 16 / RT;          // 2 columns of 8 / RT waves
+    static constexpr int kPA = RT;                  // 1 KiB pieces of A per wave and stage (16 in all)
+    static constexpr int kPBMax = RT;               // most pieces of B per wave and stage
+    static constexpr int kSc = RT / 2;              // scale loads per wave, operand and K group (64 dwords each)
+    // pieces of B per wave and stage for a tile nj strips wide (4 nj in all; with 8 waves the last ones may
+    // fall beyond the tile: they are loaded like the others, into the unused rest of the stage buffer)
+    static constexpr __device__ __host__ int pb(int nj) { return (4 * nj + kWaves - 1) / kWaves; }
     // global -> LDS
     const uint8_t* xc; const uint8_t* wc; const uint8_t* xs; const uint8_t* ws;
-    uint32_t aoff[4], boff[4], sao[2], sbo[2];
+    uint32_t aoff[kPA], boff[kPBMax], sao[kSc], sbo[kSc];
     uint32_t lds0, lds_sc, row_group_bytes;   // bytes of one 16-row group of a code array (all of K)
     int M, N, wave, lane;
     int T, s0;        // stages of the aimed tile and the first of them (stage = 128 K elements; K parts start on K groups)
@@ -406,8 +420,8 @@ struct TiledCtx {
     int a_rd, b_rd, sc_a_rd, sc_b_rd, kg, fsw;
 
     // Per-lane load offsets of a tile.  Wave w, load j copies the 1 KiB piece of row group
-    // (tile row / 16 + 4 w + j) of A, and (tile column / 16 + nj w + j) of B, into LDS rows
-    // 16 (4 w + j) .. + 15 (16 (nj w + j) ..) of a stage buffer; the blocked code layout already is
+    // (tile row / 16 + kPA w + j) of A, and (tile column / 16 + pb w + j) of B, into LDS rows
+    // 16 (kPA w + j) .. + 15 (16 (pb w + j) ..) of a stage buffer; the blocked code layout already is
     // the swizzled LDS image, so lane i just moves bytes 16 i .. 16 i + 15.  Row groups past the
     // edge are clamped to the last one (their results are never stored).
     __device__ __forceinline__ void aim(const Tile& t) {
@@ -416,132 +430,152 @@ struct TiledCtx {
         asm volatile("" : "+v"(lane));      // recompute the lane terms per tile instead of keeping them in registers
         T = 2 * t.ng;
         s0 = 2 * t.g0;
+        const int npb = pb(t.nj);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            aoff[j] = (uint32_t)min((t.m0 >> 4) + 4 * wave + j, rgA - 1) * row_group_bytes + lane * 16;
-            boff[j] = (uint32_t)min((t.n0 >> 4) + t.nj * wave + j, rgB - 1) * row_group_bytes + lane * 16;
-        }
-        // scales: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords 128 w .. 128 w + 127
-        // of each (two pieces of 64).  B rows beyond the tile's 64 nj are fetched and not used.
+        for (int j = 0; j < kPA; ++j)
+            aoff[j] = (uint32_t)min((t.m0 >> 4) + kPA * wave + j, rgA - 1) * row_group_bytes + lane * 16;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int d = 128 * wave + 64 * j + lane;
+        for (int j = 0; j < kPBMax; ++j)
+            boff[j] = (uint32_t)min((t.n0 >> 4) + npb * wave + j, rgB - 1) * row_group_bytes + lane * 16;
+        // scales: per K group, A and B each 256 rows x 2 dwords; wave w loads dwords 64 kSc w .. + 64 kSc - 1
+        // of each (pieces of 64).  B rows beyond the tile's 64 nj are fetched and not used.
+#pragma unroll
+        for (int j = 0; j < kSc; ++j) {
+            const int d = 64 * kSc * wave + 64 * j + lane;
             sao[j] = ((uint32_t)min(t.m0 + (d >> 1), M - 1) * 2 + (d & 1)) * 4;
             sbo[j] = ((uint32_t)min(t.n0 + (d >> 1), N - 1) * 2 + (d & 1)) * 4;
         }
     }
-    // The loads of one stage, in a fixed order: parts 0..3 = this wave's 4 A pieces, parts 4..4+nj-1
-    // its nj B pieces, part 4+nj = the scales of the K group an even stage opens (4 dword loads).
+    // The loads of one stage, in a fixed order: parts 0..kPA-1 = this wave's A pieces, parts kPA..kPA+pb-1
+    // its B pieces, part kPA+pb = the scales of the K group an even stage opens (2 kSc dword loads).
     // Completion is counted per thread in this order.
     __device__ __forceinline__ void issue_scales(int s) const {
         const int g = s >> 1;
-        const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * 512;
+        const uint32_t sbuf = lds_sc + (uint32_t)(g & 1) * kScaleGroupLds + (uint32_t)wave * (256 * kSc);
         const uint8_t* sag = xs + (size_t)(g + (s0 >> 1)) * M * 8;
         const uint8_t* sbg = ws + (size_t)(g + (s0 >> 1)) * N * 8;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) dma4(sag, sao[j], sbuf + j * 256);
+        for (int j = 0; j < kSc; ++j) dma4(sag, sao[j], sbuf + j * 256);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
+        for (int j = 0; j < kSc; ++j) dma4(sbg, sbo[j], sbuf + kTile * 8 + j * 256);
     }
     template <int PART>
     __device__ __forceinline__ void issue_part(int s, int nj, bool even) const {
         const uint32_t buf = lds0 + (uint32_t)(s & (kRing - 1)) * kStageLds;
-        if constexpr (PART < 4) {
-            dma16(xc + (size_t)(s + s0) * 1024, aoff[PART], buf + (uint32_t)(4 * wave + PART) * 1024);
+        if constexpr (PART < kPA) {
+            dma16(xc + (size_t)(s + s0) * 1024, aoff[PART], buf + (uint32_t)(kPA * wave + PART) * 1024);
         } else {
-            if (PART < 4 + nj)
-                dma16(wc + (size_t)(s + s0) * 1024, boff[(PART - 4) & 3], buf + kOperandStage + (uint32_t)(nj * wave + PART - 4) * 1024);
-            else if (PART == 4 + nj && even)
+            const int npb = pb(nj);
+            if (PART < kPA + npb)
+                dma16(wc + (size_t)(s + s0) * 1024, boff[(PART - kPA) & (kPBMax - 1)],
+                      buf + kOperandStage + (uint32_t)(npb * wave + PART - kPA) * 1024);
+            else if (PART == kPA + npb && even)
                 issue_scales(s);
         }
     }
-    // First stages of a tile (all ring slots must be free): 4 + nj loads each, 4 more on even stages.
+    // First stages of a tile (all ring slots must be free): kPA + pb loads each, 2 kSc more on even stages.
     __device__ __forceinline__ void issue_prologue(int nj) const {
         const int n = T < kRing ? T : kRing;
+        const int npb = pb(nj);
         for (int s = 0; s < n; ++s) {
             issue_part<0>(s, nj, false);
             issue_part<1>(s, nj, false);
-            issue_part<2>(s, nj, false);
-            issue_part<3>(s, nj, false);
-            issue_part<4>(s, nj, false);
-            if (nj > 1) issue_part<5>(s, nj, false);
-            if (nj > 2) issue_part<6>(s, nj, false);
-            if (nj > 3) issue_part<7>(s, nj, false);
+            if constexpr (kPA == 4) {
+                issue_part<2>(s, nj, false);
+                issue_part<3>(s, nj, false);
+            }
+            issue_part<kPA>(s, nj, false);
+            if (npb > 1) issue_part<kPA + 1>(s, nj, false);
+            if constexpr (kPBMax == 4) {
+                if (npb > 2) issue_part<kPA + 2>(s, nj, false);
+                if (npb > 3) issue_part<kPA + 3>(s, nj, false);
+            }
             if ((s & 1) == 0) issue_scales(s);
         }
     }
     // Where this lane reads its fragments and scales from: row (wave row base + 32 i + l32),
     // slot ((2 half + kg) ^ f(row)).
     __device__ __forceinline__ void aim_reads(int nj, int wm, int wn, int l32) {
-        a_rd = (wm * 128 + l32) * kStageBytes;
+        a_rd = (wm * 32 * RT + l32) * kStageBytes;
         b_rd = kOperandStage + (wn * 32 * nj + l32) * kStageBytes;
-        sc_a_rd = ((wm * 128 + l32) * 2 + kg) * 4;
+        sc_a_rd = ((wm * 32 * RT + l32) * 2 + kg) * 4;
         sc_b_rd = kTile * 8 + ((wn * 32 * nj + l32) * 2 + kg) * 4;
     }
-    // in the order the matrix instructions consume them: a0, b0.., a1..a3
+    // in the order the matrix instructions consume them: a0, b0.., a1..
     template <int NJ>
-    __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[4], uint4 (&fb)[NJ]) const {
+    __device__ __forceinline__ void read_frags(int s, int half, uint4 (&fa)[RT], uint4 (&fb)[NJ]) const {
         const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
         fa[0] = *reinterpret_cast<const uint4*>(base + a_rd);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) fb[j] = *reinterpret_cast<const uint4*>(base + b_rd + j * 32 * kStageBytes);
 #pragma unroll
-        for (int i = 1; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
+        for (int i = 1; i < RT; ++i) fa[i] = *reinterpret_cast<const uint4*>(base + a_rd + i * 32 * kStageBytes);
     }
     // fragment IDX of that order alone
     template <int NJ, int IDX>
-    __device__ __forceinline__ void read_frag_one(int s, int half, uint4 (&fa)[4], uint4 (&fb)[NJ]) const {
+    __device__ __forceinline__ void read_frag_one(int s, int half, uint4 (&fa)[RT], uint4 (&fb)[NJ]) const {
         const uint8_t* base = smem + (s & (kRing - 1)) * kStageLds + (((2 * half + kg) ^ fsw) << 4);
         if constexpr (IDX == 0) fa[0] = *reinterpret_cast<const uint4*>(base + a_rd);
         else if constexpr (IDX <= NJ) fb[IDX - 1] = *reinterpret_cast<const uint4*>(base + b_rd + (IDX - 1) * 32 * kStageBytes);
         else fa[IDX - NJ] = *reinterpret_cast<const uint4*>(base + a_rd + (IDX - NJ) * 32 * kStageBytes);
     }
     template <int NJ>
-    __device__ __forceinline__ void read_scales(int g, int (&sa)[4], int (&sb)[NJ]) const {
+    __device__ __forceinline__ void read_scales(int g, int (&sa)[RT], int (&sb)[NJ]) const {
         const uint8_t* sp = smem + kRing * kStageLds + (g & 1) * kScaleGroupLds;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
+        for (int i = 0; i < RT; ++i) sa[i] = *reinterpret_cast<const int*>(sp + sc_a_rd + i * 256);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) sb[j] = *reinterpret_cast<const int*>(sp + sc_b_rd + j * 256);
     }
 };
 
 // Loads [P0, P1) of stage s, in the fixed order (NJ static).
-template <int NJ, bool EVEN, int P0, int P1>
-__device__ __forceinline__ void issue_range(const TiledCtx& c, int s) {
+template <int RT, int NJ, bool EVEN, int P0, int P1>
+__device__ __forceinline__ void issue_range(const TiledCtx<RT>& c, int s) {
     if constexpr (P0 < P1) {
-        if constexpr (P0 < 4 + NJ) c.issue_part<P0>(s, NJ, false);
+        if constexpr (P0 < TiledCtx<RT>::kPA + TiledCtx<RT>::pb(NJ)) c.template issue_part<P0>(s, NJ, false);
         else if constexpr (EVEN) c.issue_scales(s);
-        issue_range<NJ, EVEN, P0 + 1, P1>(c, s);
+        issue_range<RT, NJ, EVEN, P0 + 1, P1>(c, s);
+    }
+}
+// Fragments [R0, R1) of the consumption order.
+template <int RT, int NJ, int R0, int R1>
+__device__ __forceinline__ void read_frag_range(const TiledCtx<RT>& c, int s, int half, uint4 (&fa)[RT], uint4 (&fb)[NJ]) {
+    if constexpr (R0 < R1) {
+        c.template read_frag_one<NJ, R0>(s, half, fa, fb);
+        read_frag_range<RT, NJ, R0 + 1, R1>(c, s, half, fa, fb);
     }
 }
 
-// One K step of a stage for tiles three or four strips wide: its 4 NJ matrix instructions in row-major tile order,
-// and after each of them at most one LDS fragment read and its share of a set of load parts, so that neither the
+// One K step of a stage: its RT x NJ matrix instructions in row-major tile order, and after each of them one LDS
+// fragment read (two where a K step has fewer instructions than fragments) and its share of a set of load parts, so that neither the
 // LDS pipe nor the vector-memory address path sees a burst (a wave that blocks on either cannot issue its next
 // matrix instruction: measured on cfg3, bunched reads and loads cost 360 of 1490 cycles per stage).
 //   KK      scale byte of the K step (op_sel); ZERO: the K step starts the accumulators
 //   RD      read the fragments of (rd_stage, rd_half) into ra / rb, one per matrix instruction, in the order the
-//           next K step consumes them (a0, b0.., a1..a3)
+//           next K step consumes them (a0, b0.., a1..)
 //   TE      the stage `st` whose load parts [P0, P1) are issued here is even (its last part = the scales of a K group)
-template <int NJ, int KK, bool ZERO, bool RD, bool TE, int P0, int P1, int M>
-__device__ __forceinline__ void wide_k_step(const TiledCtx& c, v16f (&acc)[4][NJ], const uint4 (&a)[4],
-                                            const uint4 (&b)[NJ], const int (&sa)[4], const int (&sb)[NJ], int rd_stage,
-                                            int rd_half, uint4 (&ra)[4], uint4 (&rb)[NJ], int st) {
-    constexpr int NM = 4 * NJ;
+template <int RT, int NJ, int KK, bool ZERO, bool RD, bool TE, int P0, int P1, int M>
+__device__ __forceinline__ void wide_k_step(const TiledCtx<RT>& c, v16f (&acc)[RT][NJ], const uint4 (&a)[RT],
+                                            const uint4 (&b)[NJ], const int (&sa)[RT], const int (&sb)[NJ], int rd_stage,
+                                            int rd_half, uint4 (&ra)[RT], uint4 (&rb)[NJ], int st) {
+    constexpr int NM = RT * NJ, NR = RT + NJ, kPer = (NR + NM - 1) / NM;
     if constexpr (M < NM) {
         constexpr int i = M / NJ, j = M % NJ;
         mfma_one<KK, ZERO>(acc[i][j], a[i], b[j], sa[i], sb[j]);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (RD && M < 4 + NJ) c.read_frag_one<NJ, M>(rd_stage, rd_half, ra, rb);
+        if constexpr (RD)
+            read_frag_range<RT, NJ, (M * kPer < NR ? M * kPer : NR), ((M + 1) * kPer < NR ? (M + 1) * kPer : NR)>(
+                c, rd_stage, rd_half, ra, rb);
         constexpr int np = P1 - P0;
-        issue_range<NJ, TE, P0 + M * np / NM, P0 + (M + 1) * np / NM>(c, st);
+        issue_range<RT, NJ, TE, P0 + M * np / NM, P0 + (M + 1) * np / NM>(c, st);
         __builtin_amdgcn_sched_barrier(0);
-        wide_k_step<NJ, KK, ZERO, RD, TE, P0, P1, M + 1>(c, acc, a, b, sa, sb, rd_stage, rd_half, ra, rb, st);
+        wide_k_step<RT, NJ, KK, ZERO, RD, TE, P0, P1, M + 1>(c, acc, a, b, sa, sb, rd_stage, rd_half, ra, rb, st);
     }
 }
 
-// One K stage (two matrix-instruction K steps) of the software pipeline, tiles three or four strips wide.
+// One K stage (two matrix-instruction K steps) of the software pipeline (with 4 waves: tiles three or four strips
+// wide).
 //   NJ       32-column matrix tiles per wave
 //   PAR      parity of the stage inside its K group (selects the scale bytes: op_sel 2 PAR, 2 PAR + 1)
 //   WAIT     loads that may stay in flight once stage s+1 has landed (-1: there is no stage s+1)
@@ -556,42 +590,42 @@ __device__ __forceinline__ void wide_k_step(const TiledCtx& c, v16f (&acc)[4][NJ
 // K step.  The loads of a stage are thus issued one by one over a whole stage length, from the middle of stage s-4
 // to the middle of stage s-3, and have two to three stages to land.  When stage s+1 is awaited, stages s+2 and s+3
 // have been issued completely and stage s+4 not at all.
-template <int NJ, int PAR, int WAIT, bool ISSUE_A, bool ISSUE_B, bool FIRST>
-__device__ __forceinline__ void tiled_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a0)[4],
-                                            uint4 (&b0)[NJ], int (&sa)[4], int (&sb)[NJ]) {
-    constexpr int kParts = 5 + NJ, kA = (kParts + 1) / 2;
-    uint4 a1[4], b1[NJ];
+template <int RT, int NJ, int PAR, int WAIT, bool ISSUE_A, bool ISSUE_B, bool FIRST>
+__device__ __forceinline__ void tiled_stage(const TiledCtx<RT>& c, int s, v16f (&acc)[RT][NJ], uint4 (&a0)[RT],
+                                            uint4 (&b0)[NJ], int (&sa)[RT], int (&sb)[NJ]) {
+    constexpr int kParts = TiledCtx<RT>::kPA + TiledCtx<RT>::pb(NJ) + 1, kA = (kParts + 1) / 2;
+    uint4 a1[RT], b1[NJ];
     // first K step: the second half's fragments, and the rest of stage s+3's loads (stage s+3 has the other parity)
-    wide_k_step<NJ, 2 * PAR, FIRST, true, PAR == 1, (ISSUE_B ? kA : 0), (ISSUE_B ? kParts : 0), 0>(
+    wide_k_step<RT, NJ, 2 * PAR, FIRST, true, PAR == 1, (ISSUE_B ? kA : 0), (ISSUE_B ? kParts : 0), 0>(
         c, acc, a0, b0, sa, sb, s, 1, a1, b1, s + 3);
-    int sna[4], snb[NJ];
+    int sna[RT], snb[NJ];
     if constexpr (WAIT >= 0) {
         wait_vmcnt<WAIT>();
         wait_lds();                                         // this wave's fragments of stage s are in registers
         __syncthreads();
-        if constexpr (PAR == 1) c.read_scales<NJ>((s + 1) >> 1, sna, snb);
+        if constexpr (PAR == 1) c.template read_scales<NJ>((s + 1) >> 1, sna, snb);
     }
     __builtin_amdgcn_sched_barrier(0);
     // second K step: the next stage's first fragments, and the first loads of stage s+4 (same parity as s)
-    wide_k_step<NJ, 2 * PAR + 1, false, (WAIT >= 0), PAR == 0, 0, ((WAIT >= 0 && ISSUE_A) ? kA : 0), 0>(
+    wide_k_step<RT, NJ, 2 * PAR + 1, false, (WAIT >= 0), PAR == 0, 0, ((WAIT >= 0 && ISSUE_A) ? kA : 0), 0>(
         c, acc, a1, b1, sa, sb, s + 1, 0, a0, b0, s + 4);
     if constexpr (WAIT >= 0 && PAR == 1) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sa[i] = sna[i];
+        for (int i = 0; i < RT; ++i) sa[i] = sna[i];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) sb[j] = snb[j];
     }
 }
 
-// The same stage for tiles one or two strips wide.  Their 8 or 16 matrix instructions per stage are too few to
+// The same stage for tiles one or two strips wide, 4 waves.  Their 8 or 16 matrix instructions per stage are too few to
 // hide a barrier followed by the LDS reads of the next fragments in the last quarter of the stage, so here the
 // fragments run a whole stage ahead: on entry a/b hold both K steps of stage s, the barrier at the top makes
 // stage s+1 visible (and the slot of stage s, read a stage ago, free), and the reads of stage s+1 and the loads
 // of stage s+4 are spread under the stage's own matrix instructions.  Same WAIT / ISSUE / FIRST meaning and the
 // same load accounting as tiled_stage: no load of stage s+4 has been issued when stage s+1 is awaited.
 template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST>
-__device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
+__device__ __forceinline__ void narrow_stage(const TiledCtx<4>& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
                                              uint4 (&b)[2][NJ], int (&sa)[4], int (&sb)[NJ]) {
     static_assert(NJ <= 2, "narrow tiles only");
     uint4 na[2][4], nb[2][NJ];
@@ -610,11 +644,11 @@ __device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&ac
         if (i == 0) {
             if constexpr (kNext) c.read_frags<NJ>(s + 1, 0, na[0], nb[0]);
         } else if (i == 1) {
-            if constexpr (kIssue) issue_range<NJ, PAR == 0, 0, 2>(c, s + 4);
+            if constexpr (kIssue) issue_range<4, NJ, PAR == 0, 0, 2>(c, s + 4);
         } else if (i == 2) {
             if constexpr (kNext) c.read_frags<NJ>(s + 1, 1, na[1], nb[1]);
         } else {
-            if constexpr (kIssue) issue_range<NJ, PAR == 0, 2, 4>(c, s + 4);
+            if constexpr (kIssue) issue_range<4, NJ, PAR == 0, 2, 4>(c, s + 4);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -626,7 +660,7 @@ __device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&ac
         if (i == 0) {
             if constexpr (kNext && PAR == 1) c.read_scales<NJ>((s + 1) >> 1, sna, snb);
         } else if (i == 1) {
-            if constexpr (kIssue) issue_range<NJ, PAR == 0, 4, 5 + NJ>(c, s + 4);
+            if constexpr (kIssue) issue_range<4, NJ, PAR == 0, 4, 5 + NJ>(c, s + 4);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -647,20 +681,22 @@ __device__ __forceinline__ void narrow_stage(const TiledCtx& c, int s, v16f (&ac
     }
 }
 
-// Stage of a tile NJ strips wide: narrow tiles keep both K steps' fragments in `a`, `b`, wide ones the first.
+// Stage of a tile NJ strips wide: with 4 waves, narrow tiles keep both K steps' fragments in `a`, `b`; all others
+// the first K step's.
 // ISSUE: stage s+4 exists and is loaded into the slot this stage frees; PREV: the same was true of stage s-1 (wide
 // tiles issue a stage's loads in two halves, the second half during the following stage).
-template <int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST, bool PREV = true>
-__device__ __forceinline__ void any_stage(const TiledCtx& c, int s, v16f (&acc)[4][NJ], uint4 (&a)[2][4],
-                                          uint4 (&b)[2][NJ], int (&sa)[4], int (&sb)[NJ]) {
-    if constexpr (NJ <= 2) narrow_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a, b, sa, sb);
-    else tiled_stage<NJ, PAR, WAIT, ISSUE, (PREV && !FIRST), FIRST>(c, s, acc, a[0], b[0], sa, sb);
+template <int RT, int NJ> constexpr bool kNarrowStages = RT == 4 && NJ <= 2;
+template <int RT, int NJ, int PAR, int WAIT, bool ISSUE, bool FIRST, bool PREV = true>
+__device__ __forceinline__ void any_stage(const TiledCtx<RT>& c, int s, v16f (&acc)[RT][NJ], uint4 (&a)[2][RT],
+                                          uint4 (&b)[2][NJ], int (&sa)[RT], int (&sb)[NJ]) {
+    if constexpr (kNarrowStages<RT, NJ>) narrow_stage<NJ, PAR, WAIT, ISSUE, FIRST>(c, s, acc, a, b, sa, sb);
+    else tiled_stage<RT, NJ, PAR, WAIT, ISSUE, (PREV && !FIRST), FIRST>(c, s, acc, a[0], b[0], sa, sb);
 }
 
-// Epilogue of a tile: 4 x NJ output tiles of 32 x 32 of this wave (rows m0 + wm*128.., columns n0 + wn*32*NJ..)
+// Epilogue of a tile: RT x NJ output tiles of 32 x 32 of this wave (rows m0 + wm*32*RT.., columns n0 + wn*32*NJ..)
 // -> Y; value(i, j, e) = element e (accumulator register order) of output tile (i, j).
-// `ep_lds` is the wave's private 4 KiB LDS staging area.
-template <int NJ, typename YT, typename F>
+// `ep_lds` is the wave's private LDS staging area (kEpilogueWaveBytes<RT>).
+template <int NJ, typename YT, int RT, typename F>
 __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int lane, int wm, int wn, int m0, int n0,
                                                 int M, int N, YT* __restrict__ Y, int64_t ldy) {
     // ---- epilogue: accumulators -> Y
@@ -672,12 +708,14 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
         // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
         const bool fast = n0 + kStrip * NJ <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
         if (fast) {
-            uint8_t* ep = ep_lds;   // [16 rows][256 bytes]
+            constexpr int BR = kEpilogueBlockRows<RT>;      // rows staged at a time
+            uint8_t* ep = ep_lds;   // [BR rows][256 bytes]
             const int odd = lane_e & 1, l32 = lane_e & 31, kg = lane_e >> 5;
             // Lanes pair up: from its two packed values (rows r, r+1 of its column) and the neighbour's,
             // the even lane assembles row r and the odd lane row r+1 of the column pair.
             const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
-            // Value pair (j, u) of a 16-row block goes to block row 8 (u / 2) + 2 (u % 2) + (4 kg + odd) and
+            // Value pair (j, u) of a block (16 rows = accumulator registers 8 h .. 8 h + 7, or 8 rows = registers
+            // 4 h .. 4 h + 3) goes to block row 8 (u / 2) + 2 (u % 2) + (4 kg + odd) and
             // 16-byte chunk (4 j + l32 / 8) ^ swizzle(row); the swizzle only depends on the lane
             // (row & 1 = odd, (row >> 2) & 1 = kg), so it folds into per-lane base pointers, one per j.
             uint8_t* pj[NJ];
@@ -686,24 +724,24 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
                 pj[j] = ep + (4 * kg + odd) * 256 + ((4 * (j ^ (odd | (kg << 1))) + (l32 >> 3)) << 4) + ((l32 >> 1) & 3) * 4;
             // read-back: one instruction covers kRows rows of 4 NJ 16-byte units (NJ = 3 leaves lanes
             // 48..63 idle); row pointers advance by additions only
-            constexpr int kUnits = 4 * NJ, kRows = NJ == 3 ? 4 : 64 / kUnits;
+            constexpr int kUnits = 4 * NJ, kRows = NJ == 3 ? 4 : (64 / kUnits < BR ? 64 / kUnits : BR);
             const int rl = lane_e / kUnits, unit = lane_e % kUnits;
-            const bool lane_on = NJ != 3 || lane_e < 48;
-            int row = m0 + wm * 128 + rl;
+            const bool lane_on = kRows * kUnits == 64 || lane_e < kRows * kUnits;
+            int row = m0 + wm * 32 * RT + rl;
             YT* yrow = Y + (size_t)row * ldy + n0 + wn * 32 * NJ + unit * 8;
             const int64_t ystep = (int64_t)kRows * ldy;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    __builtin_amdgcn_sched_barrier(0);      // one 16-row block at a time: keeps register use flat
+                for (int h = 0; h < 32 / BR; ++h) {
+                    __builtin_amdgcn_sched_barrier(0);      // one block at a time: keeps register use flat
 #pragma unroll
                     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
+                        for (int u = 0; u < BR / 4; ++u) {
                             f32x2 pr;
-                            pr.x = value(i, j, 8 * h + 2 * u);
-                            pr.y = value(i, j, 8 * h + 2 * u + 1);
+                            pr.x = value(i, j, (BR / 2) * h + 2 * u);
+                            pr.y = value(i, j, (BR / 2) * h + 2 * u + 1);
                             const int mine = __builtin_bit_cast(int, __builtin_convertvector(pr, bf16x2));
                             const int theirs = __builtin_amdgcn_mov_dpp(mine, 0xB1, 0xF, 0xF, true);
                             *reinterpret_cast<uint32_t*>(pj[j] + (8 * (u >> 1) + 2 * (u & 1)) * 256) =
@@ -711,7 +749,7 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
                         }
                     // wave-private buffer: the wave's own LDS operations complete in order
 #pragma unroll
-                    for (int it = 0; it < 16 / kRows; ++it) {
+                    for (int it = 0; it < BR / kRows; ++it) {
                         const int R = it * kRows + rl;
                         const int chunk = unit ^ (((R & 1) << 2) | (((R >> 2) & 1) << 3));
                         const uint4 v = *reinterpret_cast<const uint4*>(ep + R * 256 + chunk * 16);
@@ -728,10 +766,10 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
     }
     // general path: element-wise stores with edge checks; rows visited in increasing order per lane
     const int col0 = n0 + wn * 32 * NJ + (lane_e & 31);
-    int row = m0 + wm * 128 + 4 * (lane_e >> 5);
+    int row = m0 + wm * 32 * RT + 4 * (lane_e >> 5);
     YT* yp = Y + (size_t)row * ldy + col0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             __builtin_amdgcn_sched_barrier(0);
@@ -762,29 +800,29 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
 // 32 p .., 64 p + 32 .. 64 p + 63 = the matching up columns), so matrix tiles 2 j and 2 j + 1 of a wave hold
 // gate and up of the same outputs in the same lanes and registers; what is stored is silu(gate) * up, to the
 // M x N/2 array Y (N here = its column count).  NJ must be even.
-template <int NJ, typename YT, bool GLU>
-__device__ __forceinline__ void store_tile(v16f (&acc_in)[4][NJ], uint8_t* ep_lds, int lane, int wm, int wn,
+template <int NJ, typename YT, bool GLU, int RT = 4>
+__device__ __forceinline__ void store_tile(v16f (&acc_in)[RT][NJ], uint8_t* ep_lds, int lane, int wm, int wn,
                                            const Tile& t, int M, int N, YT* __restrict__ Y, int64_t ldy) {
     static_assert(!GLU || NJ % 2 == 0, "gated output needs gate/up tile pairs");
     auto value = [&](int i, int j, int e) -> float {
         if constexpr (GLU) return swiglu_f32(acc_in[i][2 * j][e], acc_in[i][2 * j + 1][e]);
         else return acc_in[i][j][e];
     };
-    store_tile_impl<(GLU ? NJ / 2 : NJ), YT>(value, ep_lds, lane, wm, wn, t.m0, GLU ? t.n0 / 2 : t.n0, M, N, Y, ldy);
+    store_tile_impl<(GLU ? NJ / 2 : NJ), YT, RT>(value, ep_lds, lane, wm, wn, t.m0, GLU ? t.n0 / 2 : t.n0, M, N, Y, ldy);
 }
 
 // Partial sums of a K part, in the order the accumulators hold them: 32x32 blocks, block (rb, cb) of the
 // padded output as 4 pieces of 64 lanes x 4 floats; piece q of lane (l32, kg) = rows 32 rb + 8 q + 4 kg .. + 3
 // of column 32 cb + l32.  Every store instruction writes 1 KiB of consecutive memory.
 constexpr int kPartialBlockFloats = 32 * 32;
-template <int NJ>
-__device__ __forceinline__ void store_partial(v16f (&acc)[4][NJ], float* __restrict__ P, int lane, int wm, int wn,
+template <int NJ, int RT = 4>
+__device__ __forceinline__ void store_partial(v16f (&acc)[RT][NJ], float* __restrict__ P, int lane, int wm, int wn,
                                               const Tile& t, int col_blocks) {
     int lane_e = lane;
     asm volatile("" : "+v"(lane_e));
-    const int rb0 = (t.m0 >> 5) + 4 * wm, cb0 = (t.n0 >> 5) + NJ * wn;
+    const int rb0 = (t.m0 >> 5) + RT * wm, cb0 = (t.n0 >> 5) + NJ * wn;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             float* blk = P + ((size_t)(rb0 + i) * col_blocks + cb0 + j) * kPartialBlockFloats + lane_e * 4;
@@ -800,49 +838,52 @@ __device__ __forceinline__ void store_partial(v16f (&acc)[4][NJ], float* __restr
 // the epilogue the loads of the next tile's first stages are started, so they run underneath it.
 // YT = partial_f32 (K parts): Y is the partial-sum array in accumulator order (store_partial), `ldy` its number
 // of 32-column blocks and `part_stride` the floats of one part; for every other YT part_stride is unused.
-template <int NJ, typename YT, bool GLU>
-__device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_next, const Tile& next,
+template <int RT, int NJ, typename YT, bool GLU>
+__device__ __forceinline__ void run_tile(TiledCtx<RT>& c, const Tile& t, bool has_next, const Tile& next,
                                          YT* __restrict__ Y, int64_t ldy, int64_t part_stride) {
     const int lane = c.lane, wave = c.wave;
     const int wm = wave >> 1, wn = wave & 1;
     const int T = c.T, G = T >> 1;
     c.aim_reads(NJ, wm, wn, lane & 31);
+    // tile-variant as far as the compiler can tell: addresses derived from them for all four tile widths would
+    // otherwise be kept in registers across the whole kernel
+    asm volatile("" : "+v"(c.a_rd), "+v"(c.b_rd), "+v"(c.sc_a_rd), "+v"(c.sc_b_rd));
 
-    v16f acc[4][NJ];
-    uint4 fa[2][4], fb[2][NJ];
-    int sa[4], sb[NJ];
+    v16f acc[RT][NJ];
+    uint4 fa[2][RT], fb[2][NJ];
+    int sa[RT], sb[NJ];
 
-    // Loads per thread: 4 + NJ per stage, plus 4 for the scales of a K group issued with the
-    // group's even stage; they complete in issue order.  In steady state stages s+2 and s+3
-    // (12 + 2 NJ loads) stay in flight while stage s+1 is awaited.  Stores of the previous tile
-    // that are still pending only make a wait longer than needed.
-    constexpr int kOdd = 4 + NJ, kSteady = 12 + 2 * NJ;
+    // Loads per thread: kPA + pb per stage (4 + NJ with 4 waves), plus 2 kSc for the scales of a K group
+    // issued with the group's even stage; they complete in issue order.  In steady state stages s+2 and s+3
+    // stay in flight while stage s+1 is awaited.  Stores of the previous tile that are still pending only make
+    // a wait longer than needed.
+    constexpr int kOdd = TiledCtx<RT>::kPA + TiledCtx<RT>::pb(NJ), kSteady = 2 * kOdd + 2 * TiledCtx<RT>::kSc;
     if (T >= 4) wait_vmcnt<kSteady + kOdd>();
     else wait_vmcnt<kOdd>();
     __syncthreads();
-    c.read_scales<NJ>(0, sa, sb);
-    c.read_frags<NJ>(0, 0, fa[0], fb[0]);
-    if constexpr (NJ <= 2) c.read_frags<NJ>(0, 1, fa[1], fb[1]);
+    c.template read_scales<NJ>(0, sa, sb);
+    c.template read_frags<NJ>(0, 0, fa[0], fb[0]);
+    if constexpr (kNarrowStages<RT, NJ>) c.template read_frags<NJ>(0, 1, fa[1], fb[1]);
 
     // the first stage of a tile starts the accumulators from zero
     if (G >= 3) {
-        any_stage<NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
-        any_stage<NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, kSteady, true, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 1, kSteady, true, false>(c, 1, acc, fa, fb, sa, sb);
         for (int g = 1; g + 2 < G; ++g) {
-            any_stage<NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
-            any_stage<NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
+            any_stage<RT, NJ, 0, kSteady, true, false>(c, 2 * g, acc, fa, fb, sa, sb);
+            any_stage<RT, NJ, 1, kSteady, true, false>(c, 2 * g + 1, acc, fa, fb, sa, sb);
         }
-        any_stage<NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);            // finishes the loads of stage T-1
-        any_stage<NJ, 1, kOdd, false, false, false>(c, T - 3, acc, fa, fb, sa, sb);
-        any_stage<NJ, 0, 0, false, false, false>(c, T - 2, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, kSteady, false, false>(c, T - 4, acc, fa, fb, sa, sb);            // finishes the loads of stage T-1
+        any_stage<RT, NJ, 1, kOdd, false, false, false>(c, T - 3, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, 0, false, false, false>(c, T - 2, acc, fa, fb, sa, sb);
     } else if (G == 2) {
-        any_stage<NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
-        any_stage<NJ, 1, kOdd, false, false, false>(c, 1, acc, fa, fb, sa, sb);
-        any_stage<NJ, 0, 0, false, false, false>(c, 2, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, kSteady, false, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 1, kOdd, false, false, false>(c, 1, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, 0, false, false, false>(c, 2, acc, fa, fb, sa, sb);
     } else {
-        any_stage<NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
+        any_stage<RT, NJ, 0, 0, false, true>(c, 0, acc, fa, fb, sa, sb);
     }
-    any_stage<NJ, 1, -1, false, false, false>(c, T - 1, acc, fa, fb, sa, sb);
+    any_stage<RT, NJ, 1, -1, false, false, false>(c, T - 1, acc, fa, fb, sa, sb);
 
     __syncthreads();                                      // every wave is done with the stage ring
     if (has_next) {
@@ -852,10 +893,10 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
 
     // ---- epilogue: accumulators -> Y
     if constexpr (std::is_same_v<YT, partial_f32>) {
-        store_partial<NJ>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
+        store_partial<NJ, RT>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wm, wn, t, (int)ldy);
     } else {
-        store_tile<NJ, YT, GLU>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveLds, lane, wm,
-                                wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
+        store_tile<NJ, YT, GLU, RT>(acc, const_cast<uint8_t*>(c.smem) + kEpilogueLds0 + wave * kEpilogueWaveBytes<RT>,
+                                    lane, wm, wn, t, c.M, GLU ? c.N / 2 : c.N, Y, ldy);
     }
 }
 
@@ -863,8 +904,8 @@ __device__ __forceinline__ void run_tile(TiledCtx& c, const Tile& t, bool has_ne
 // pl.ksplit > 1: tiles cover one K part each and store their partial sums to Y + part * part_stride
 // (fp32, summed by splitk_reduce); used when there are fewer strips than workgroups.
 // GLU: gated output (see store_tile); the plan then hands out tiles 2 or 4 strips wide, and Y is M x N/2.
-template <typename YT, bool GLU>
-__global__ void __launch_bounds__(256, 1)
+template <typename YT, bool GLU, int RT>
+__global__ void __launch_bounds__(1024 / RT, 1)
 gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
            const uint8_t* __restrict__ ws, int M, int N, int nb, TilePlan pl, YT* __restrict__ Y, int64_t ldy,
            int64_t part_stride) {
@@ -879,7 +920,7 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
 
     const int lane = threadIdx.x & 63;
-    TiledCtx c;
+    TiledCtx<RT> c;
     c.xc = xc; c.wc = wc; c.xs = xs; c.ws = ws;
     c.M = M; c.N = N; c.smem = smem;
     c.row_group_bytes = (uint32_t)(2 * ((nb + 7) >> 3)) * 1024u;   // stages of 128 K elements (K zero-padded to 256)
@@ -895,14 +936,14 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     for (;;) {
         const bool has_next = next_tile(pl, cur, end, next);
         if constexpr (GLU) {
-            if (t.nj == 4) run_tile<4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
-            else run_tile<2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+            if (t.nj == 4) run_tile<RT, 4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
+            else run_tile<RT, 2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
         } else {
             switch (t.nj) {
-                case 4: run_tile<4, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
-                case 3: run_tile<3, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
-                case 2: run_tile<2, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
-                default: run_tile<1, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 4: run_tile<RT, 4, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 3: run_tile<RT, 3, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                case 2: run_tile<RT, 2, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
+                default: run_tile<RT, 1, YT, false>(c, t, has_next, next, Y, ldy, part_stride); break;
             }
         }
         if (!has_next) break;
@@ -1104,6 +1145,7 @@ __device__ __forceinline__ void a8_run_tile(A8Ctx& c, const Tile& t, bool has_ne
     const int wm = wave >> 1, wn = wave & 1;
     const int T = c.T, G = T >> 2;
     c.aim_reads(NJ, wm, wn, lane & 31);
+    asm volatile("" : "+v"(c.a_rd), "+v"(c.b_rd), "+v"(c.sc_a_rd), "+v"(c.sc_b_rd));      // see run_tile
 
     v16f acc[4][NJ];
     uint4 a0[4][2], a1[4][2], b0[NJ], b1[NJ];
@@ -1261,6 +1303,7 @@ struct GemmPlan {
     int col_blocks = 0;         // 32-column blocks of the padded output (tiled kernels)
     int ksplit = 1;             // K parts used
     int want = 1;               // K parts the shape would like (workspace permitting)
+    int rt = 4;                 // 4-bit tiled kernel: 32-row matrix tiles per wave (4: 4 waves, 2: 8 waves)
     bool skinny = false, wide = false;
     int cols = 0;               // skinny: workgroups along N
 };
@@ -1276,6 +1319,14 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
             g.ksplit = g.want > 1 ? choose_ksplit(g.tiled, g.part_floats * sizeof(float), parts_bytes) : 1;
         }
         g.tiled.ksplit = g.ksplit;
+        // Eight waves where the workgroups get tiles three or four strips wide: their epilogues and LDS waits then
+        // overlap with the other wave's matrix instructions (2048 x 4096 x 14336: 67.8 -> 64.5 us,
+        // 8192 x 3584 x 18944: 345 -> 328, 1024 x 4096 x 14336: 38.7 -> 36.3).  Narrow tiles stay with four waves
+        // (one strip per workgroup, 256 x 14336 x 4096: 40.0 us against 46.5 with eight waves, which then fetch
+        // more of B than they use and read each A fragment for fewer instructions).
+        const long units = (long)g.tiled.tiles_m * g.tiled.strips_n;
+        const long per_worker = (units + g.tiled.workers - 1) / g.tiled.workers;
+        g.rt = (!a8 && g.ksplit == 1 && per_worker * g.tiled.pair >= 3) ? 2 : 4;
         return g;
     }
     g.skinny = true;
@@ -1324,9 +1375,9 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
                         xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
                         (int64_t)g.col_blocks, (int64_t)g.part_floats);
                 } else {
-                    e = ensure_dynamic_lds<&gemm_tiled<partial_f32, false>>(dev, kTiledLds);
+                    e = ensure_dynamic_lds<&gemm_tiled<partial_f32, false, 4>>(dev, kTiledLds);
                     if (e != hipSuccess) return e;
-                    gemm_tiled<partial_f32, false><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
+                    gemm_tiled<partial_f32, false, 4><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(
                         xc, xs, w->d_codes, w->d_scales, M, N, nb, pl, reinterpret_cast<partial_f32*>(parts),
                         (int64_t)g.col_blocks, (int64_t)g.part_floats);
                 }
@@ -1338,11 +1389,16 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
             if (e != hipSuccess) return e;
             gemm_tiled_a8<YT, GLU><<<dim3(pl.workers), dim3(256), kA8Lds, stream>>>(xc, xs, w->d_codes, w->d_scales,
                                                                                      M, N, nb, pl, Y, ldy, 0);
-        } else {
-            e = ensure_dynamic_lds<&gemm_tiled<YT, GLU>>(dev, kTiledLds);
+        } else if (g.rt == 2) {
+            e = ensure_dynamic_lds<&gemm_tiled<YT, GLU, 2>>(dev, kTiledLds);
             if (e != hipSuccess) return e;
-            gemm_tiled<YT, GLU><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
-                                                                                     N, nb, pl, Y, ldy, 0);
+            gemm_tiled<YT, GLU, 2><<<dim3(pl.workers), dim3(512), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
+                                                                                        N, nb, pl, Y, ldy, 0);
+        } else {
+            e = ensure_dynamic_lds<&gemm_tiled<YT, GLU, 4>>(dev, kTiledLds);
+            if (e != hipSuccess) return e;
+            gemm_tiled<YT, GLU, 4><<<dim3(pl.workers), dim3(256), kTiledLds, stream>>>(xc, xs, w->d_codes, w->d_scales, M,
+                                                                                        N, nb, pl, Y, ldy, 0);
         }
     } else {
         const dim3 grid(g.cols, g.ksplit), block(kSkinnyWaves * 64);

@@ -114,11 +114,12 @@ def _check_every_element(B, M, K, N, workspace_fraction=None):
     return wh, dxc_b, dxs_g, Y
 
 
-@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000)])
+@pytest.mark.parametrize("M,K,N", [(768, 512, 30000), (4096, 256, 2098), (1500, 768, 9000), (2100, 1024 + 32, 7000),
+                                   (520, 2048 + 96, 16000)])
 def test_tile_schedule_shapes(B, M, K, N):
-    """Shapes that give the persistent workgroups of the tiled kernel several tiles each, of every
-    width (64 .. 256 columns), with ragged last row panels and column strips, 2 to 10 K stages and
-    every column-band count; every output element is checked."""
+    """Shapes that give the persistent workgroups of the tiled kernel three or more strips each (the eight-wave
+    kernel), in several tiles of every width (64 .. 256 columns), with ragged last row panels and column strips,
+    2 to 18 K stages and every column-band count; every output element is checked."""
     _check_every_element(B, M, K, N)
 
 

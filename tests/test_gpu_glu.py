@@ -60,7 +60,7 @@ def _rand_codes(rng, R, K, bits):
 
 
 @pytest.mark.parametrize("M,K,F", [(1, 64, 32), (20, 96, 64), (33, 1024, 96), (64, 12288 + 32, 160), (65, 160, 32),
-                                   (300, 2048 + 64, 288), (700, 512, 1440)])
+                                   (300, 2048 + 64, 288), (700, 512, 1440), (520, 512, 5632), (300, 768, 8192 + 96)])
 @pytest.mark.parametrize("bits", [4, 8])
 def test_gemm_glu_random_codes(B, M, K, F, bits):
     import torch
