@@ -7,15 +7,17 @@
 // one operand fragment.  Accumulator register r of lane l is element
 // (8*(r/4) + 4*(l/32) + r%4, l % 32) of the 32x32 tile.
 //
-// Three kernels:
+// Kernels:
 //   gemm_skinny - M <= 64: 32 output columns per workgroup, K split over its 8 waves.
-//   gemm_tiled  - persistent workgroups of 4 waves, output tiles of 256 rows x 64..256 columns
-//                 (each wave 128 x 32..128 = 4 x 1..4 matrix tiles in up to 256 accumulator
-//                 registers); codes and scales stream global -> LDS with LDS-direct loads through
-//                 a 4-stage ring (XOR-swizzled 16-byte slots); every workgroup takes an equal
-//                 share of the output, and the shares of one XCD form a compact block for its L2.
+//   gemm_tiled  - persistent workgroups of 4 or 8 waves, output tiles of 256 rows x 64..256 columns;
+//                 codes and scales stream global -> LDS with LDS-direct loads through a 4-stage ring
+//                 (XOR-swizzled 16-byte slots); every workgroup takes an equal share of the output,
+//                 and the shares of one XCD form a compact block for its L2.  8 waves (two per SIMD)
+//                 where the tiles are three or four strips wide.
+//   gemm_mid    - few rows and strips: one 128 x 64 tile (and K part) per workgroup, at most one
+//                 workgroup per compute unit; X fragments straight from the L2 to registers.
 //   gemm_direct - one wave per 32x32 tile with operands straight from global memory; only for
-//                 operand arrays of 2 GiB or more (the tiled kernel uses 32-bit load offsets).
+//                 operand arrays of 2 GiB or more (the other kernels use 32-bit load offsets).
 #include <algorithm>
 #include <type_traits>
 
@@ -43,6 +45,7 @@ __device__ __forceinline__ void store_y<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_y<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)float_to_bf16_bits(v); }
 
+__device__ __forceinline__ uint4 as_uint4(const batq_u32x4 v) { return uint4{v.x, v.y, v.z, v.w}; }
 __device__ __forceinline__ v8i frag(const uint4 v) {
     return v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
 }
@@ -380,6 +383,17 @@ __device__ __forceinline__ void dma4(const void* gbase, uint32_t voff, uint32_t 
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :: "v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
 }
+// Loads to registers whose completion the caller awaits itself (wait_vmcnt, in issue order with the LDS-direct
+// loads): the compiler sees no memory access, so it neither adds waits of its own nor knows that the result is
+// late - every use must follow the wait and a ready() on the register.
+__device__ __forceinline__ void load16_async(batq_u32x4& dst, const void* gbase, uint32_t voff) {
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(gbase) : "memory");
+}
+__device__ __forceinline__ void load4_async(int& dst, const void* gbase, uint32_t voff) {
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(gbase) : "memory");
+}
+template <typename V>
+__device__ __forceinline__ void ready(V& v) { asm volatile("; landed: %0" : "+v"(v)); }
 // s_waitcnt vmcnt(N) only (expcnt and lgkmcnt left at their maxima), gfx9 encoding.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -952,6 +966,237 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
 }
 
 // ------------------------------------------------------------------------------------------
+// Kernel for shapes with so few rows and strips that 128-row panels x strips (x K parts) give at most one
+// workgroup per compute unit, where the tiled kernel's 256-row tiles leave compute units idle or half empty.
+// A workgroup of 4 waves computes 128 RT rows x 64 columns (RT = 1 is what the launch code uses), wave w the rows
+// 32 RT w .. + 32 RT - 1 of all 64 columns: the rows of X a wave multiplies belong to it alone, so their
+// fragments go from global memory (the L2) straight to registers, D - 2 stages ahead, and only the weight strip
+// (4 KiB per stage, read by all four waves) goes through LDS, each wave fetching one of its four 1 KiB pieces:
+// per stage 12 KiB enter the compute unit and 8 KiB of fragments are read from LDS, against 20 KiB and 40 KiB
+// for a 256 x 64 tile of the tiled kernel.
+//
+// Loads of a wave complete in the order it issued them.  Stage q's are: the strip piece, 2 RT fragments of X
+// and, for even q, RT + 2 scale dwords (those of the K group q opens); stages are issued in order.  At the top
+// of stage s a wave waits until only loads of the stages after s + 1 can be outstanding, then meets the others at
+// the barrier: the whole strip stage s + 1 is in LDS and is read to registers under the matrix instructions of
+// stage s, and every wave is done with stage s - 1, whose LDS slot and registers the loads of stage s + D - 1
+// then overwrite (issued after the stage's own matrix instructions, which still read the scale registers of the
+// K group they complete).
+constexpr int kMidStageLds = 64 * kStageBytes;      // 4 KiB; D of them: the LDS slots of the weight strip (a wave
+                                                    // works D - 2 stages ahead); the epilogue's staging reuses them
+
+template <int RT, int D>
+struct MidCtx {
+    static_assert(D % 2 == 0 && D >= 4, "stages come in K groups of two");
+    uint32_t aoff[RT][2], boff, sao[RT], sbo[2], lds0;
+    int wave, T;
+    // the next stage to load: its index, where its codes and the scales of its K group start
+    int q;
+    const uint8_t* xq; const uint8_t* wq; const uint8_t* sag; const uint8_t* sbg;
+    size_t sa_step, sb_step;                    // bytes of one K group of scales (rows x 8)
+
+    // The loads of the next stage, in the counted order, into LDS slot `slot` and the given registers.  Every
+    // stage index gets the same number of loads, so that the waits are the same everywhere and no load is
+    // conditional (a register an asynchronous load writes must not meet another value at a control-flow join:
+    // the compiler would copy it while it is still in flight).  Past the K part's T stages all lanes fetch the
+    // first 16 bytes of the last stage instead: one cache line per instruction, into a free LDS slot and dead
+    // registers.
+    template <bool EVEN>
+    __device__ __forceinline__ void issue(int slot, batq_u32x4 (&a)[RT][2], int (&sa)[RT], int (&sb)[2]) {
+        const uint32_t m = q < T ? ~0u : 0u;
+        dma16(wq, boff & m, lds0 + (uint32_t)slot * kMidStageLds + (uint32_t)wave * 1024);
+#pragma unroll
+        for (int i = 0; i < RT; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) load16_async(a[i][h], xq, aoff[i][h] & m);
+        if constexpr (EVEN) {
+#pragma unroll
+            for (int i = 0; i < RT; ++i) load4_async(sa[i], sag, sao[i] & m);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) load4_async(sb[j], sbg, sbo[j] & m);
+        }
+        ++q;
+        const bool more = q < T;                      // uniform; the pointers stay on the last stage otherwise
+        xq += more ? 1024 : 0;
+        wq += more ? 1024 : 0;
+        if constexpr (!EVEN) {
+            sag += more ? sa_step : 0;
+            sbg += more ? sb_step : 0;
+        }
+    }
+    // loads a wave issues for a stage of parity p
+    static constexpr __device__ int count(int p) { return 1 + 2 * RT + ((p & 1) == 0 ? RT + 2 : 0); }
+};
+
+// Loads of stage indices Q .. D - 2, before the first stage is multiplied.
+template <int RT, int D, int Q>
+__device__ __forceinline__ void mid_prologue(MidCtx<RT, D>& c, batq_u32x4 (&a)[D][RT][2], int (&sa)[D / 2][RT], int (&sb)[D / 2][2]) {
+    if constexpr (Q < D - 1) {
+        c.template issue<(Q & 1) == 0>(Q, a[Q], sa[Q >> 1], sb[Q >> 1]);
+        mid_prologue<RT, D, Q + 1>(c, a, sa, sb);
+    }
+}
+
+// Stages base + U .. base + D - 1 of a K part (base a multiple of D, so stage base + U lives in LDS
+// slot and register slot U and has parity U % 2).  ALL: all of them exist.  On entry b[U % 2] holds the strip
+// fragments of stage base + U; those of the next stage are read under its matrix instructions.
+template <int RT, int D, int U, bool ALL>
+__device__ __forceinline__ void mid_steps(MidCtx<RT, D>& c, int base, const uint8_t* smem, int b_rd0, int b_rd1,
+                                          v16f (&acc)[RT][2], batq_u32x4 (&a)[D][RT][2],
+                                          int (&sa)[D / 2][RT], int (&sb)[D / 2][2], uint4 (&b)[2][2][2]) {
+    if constexpr (U < D) {
+        const int s = base + U;
+        // stage s + 1 has landed (this wave's loads; the barrier adds the other waves' strip pieces): only the
+        // loads of stage indices s + 2 .. s + D - 2 can be outstanding
+        wait_vmcnt<(D - 4) / 2 * (MidCtx<RT, D>::count(0) + MidCtx<RT, D>::count(1)) + MidCtx<RT, D>::count(U)>();
+        wait_lds();                                                // the fragments of stage s are in registers
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        constexpr int u1 = (U + 1) % D;
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+            ready(a[u1][i][0]);
+            ready(a[u1][i][1]);
+            if constexpr ((u1 & 1) == 0) ready(sa[u1 >> 1][i]);
+        }
+        if constexpr ((u1 & 1) == 0) {
+            ready(sb[u1 >> 1][0]);
+            ready(sb[u1 >> 1][1]);
+        }
+        const uint8_t* bs = smem + u1 * kMidStageLds;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            b[u1 & 1][j][0] = *reinterpret_cast<const uint4*>(bs + b_rd0 + j * 32 * kStageBytes);
+            b[u1 & 1][j][1] = *reinterpret_cast<const uint4*>(bs + b_rd1 + j * 32 * kStageBytes);
+        }
+        if (ALL || s < c.T) {                                      // workgroup-uniform
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    mfma_one<2 * (U & 1), false>(acc[i][j], as_uint4(a[U][i][0]), b[U & 1][j][0], sa[U >> 1][i], sb[U >> 1][j]);
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    mfma_one<2 * (U & 1) + 1, false>(acc[i][j], as_uint4(a[U][i][1]), b[U & 1][j][1], sa[U >> 1][i], sb[U >> 1][j]);
+        }
+        // Every wave has read the fragments of stage s - 1 and finished its matrix instructions on them: the LDS
+        // slot and registers of stage s - 1 take stage s + D - 1.  (After this stage's matrix instructions: for odd
+        // s they still read the scale registers that the K group of stage s + D - 1 takes over.)
+        constexpr int un = (U + D - 1) % D;
+        c.template issue<(un & 1) == 0>(un, a[un], sa[un >> 1], sb[un >> 1]);
+        mid_steps<RT, D, U + 1, ALL>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+    }
+}
+
+// Requires operand code arrays below 2 GiB (32-bit load offsets).  Grid: (strips, row panels of 128 RT, K parts);
+// YT = partial_f32: partial sums of K part blockIdx.z in store_partial order (ldy = 32-column blocks of the padded
+// output, part_stride = floats of a part).
+template <typename YT, int RT, int D>
+__global__ void __launch_bounds__(256, 2)
+gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
+         const uint8_t* __restrict__ ws, int M, int N, int nb, int ksplit, YT* __restrict__ Y, int64_t ldy,
+         int64_t part_stride) {
+    __shared__ __align__(16) uint8_t smem[D * kMidStageLds];
+    typedef __attribute__((address_space(3))) uint8_t lds_byte;
+    const int lane = threadIdx.x & 63, l32 = lane & 31, kg = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int groups = (nb + 7) >> 3;
+    Tile t;
+    t.n0 = blockIdx.x * kStrip;
+    t.m0 = blockIdx.y * (128 * RT);
+    t.nj = 1;
+    t.part = blockIdx.z;
+    t.g0 = groups * t.part / ksplit;
+    t.ng = groups * (t.part + 1) / ksplit - t.g0;
+    const int T = 2 * t.ng;                                     // stages of 128 K elements
+
+    MidCtx<RT, D> c;
+    c.wave = wave;
+    c.T = T;
+    c.q = 0;
+    c.xq = xc + (size_t)(2 * t.g0) * 1024;
+    c.wq = wc + (size_t)(2 * t.g0) * 1024;
+    c.sa_step = (size_t)M * 8;
+    c.sb_step = (size_t)N * 8;
+    c.sag = xs + t.g0 * c.sa_step;
+    c.sbg = ws + t.g0 * c.sb_step;
+    c.lds0 = (uint32_t)(uintptr_t)(lds_byte*)smem;
+    const uint32_t row_group_bytes = (uint32_t)(2 * groups) * 1024u;
+    const int rgA = (M + 15) >> 4, rgB = (N + 15) >> 4;
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        // row groups past the edge are clamped to the last one (their results are never stored)
+        const int R = t.m0 + 32 * RT * wave + 32 * i + l32, r = R & 15;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            c.aoff[i][h] = (uint32_t)min(R >> 4, rgA - 1) * row_group_bytes + r * 64 + (((2 * h + kg) ^ slot_swizzle(r)) << 4);
+        c.sao[i] = (uint32_t)(min(R, M - 1) * 2 + kg) * 4;
+    }
+    c.boff = (uint32_t)min((t.n0 >> 4) + wave, rgB - 1) * row_group_bytes + lane * 16;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) c.sbo[j] = (uint32_t)(min(t.n0 + 32 * j + l32, N - 1) * 2 + kg) * 4;
+    // this lane's fragment of strip row (32 j + l32), K step h: slot (2 h + kg) ^ swizzle(row)
+    const int b_rd0 = l32 * kStageBytes + ((kg ^ slot_swizzle(l32)) << 4);
+    const int b_rd1 = l32 * kStageBytes + (((2 + kg) ^ slot_swizzle(l32)) << 4);
+
+    v16f acc[RT][2];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = v16f{};
+    batq_u32x4 a[D][RT][2];
+    int sa[D / 2][RT], sb[D / 2][2];
+
+    uint4 b[2][2][2];
+    mid_prologue<RT, D, 0>(c, a, sa, sb);
+    // stage 0 has landed: stage indices 1 .. D - 2 may be outstanding
+    wait_vmcnt<(D - 2) / 2 * (MidCtx<RT, D>::count(1) + MidCtx<RT, D>::count(0))>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < RT; ++i) {
+        ready(a[0][i][0]);
+        ready(a[0][i][1]);
+        ready(sa[0][i]);
+    }
+    ready(sb[0][0]);
+    ready(sb[0][1]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        b[0][j][0] = *reinterpret_cast<const uint4*>(smem + b_rd0 + j * 32 * kStageBytes);
+        b[0][j][1] = *reinterpret_cast<const uint4*>(smem + b_rd1 + j * 32 * kStageBytes);
+    }
+
+    int base = 0;
+    for (; base + D <= T; base += D) mid_steps<RT, D, 0, true>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+    if (base < T) mid_steps<RT, D, 0, false>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+    wait_vmcnt<0>();                                            // the loads past the last stage have landed, too
+    // their destinations count as in use until here: a register the compiler took for something else would be
+    // overwritten when the load lands
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+            ready(a[d][i][0]);
+            ready(a[d][i][1]);
+            ready(sa[d >> 1][i]);
+        }
+        ready(sb[d >> 1][0]);
+        ready(sb[d >> 1][1]);
+    }
+    wait_lds();
+    __builtin_amdgcn_s_barrier();                               // every wave is done with the strip ring
+    asm volatile("" ::: "memory");
+    if constexpr (std::is_same_v<YT, partial_f32>) {
+        store_partial<2, RT>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wave, 0, t, (int)ldy);
+    } else {
+        store_tile<2, YT, false, RT>(acc, smem + wave * kEpilogueWaveBytes<RT>, lane, wave, 0, t, M, N, Y, ldy);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Tiled kernel for MXFP8 activations (W4A8).  Same persistent work split, tile shapes, LDS-direct
 // loads and epilogue as gemm_tiled; what differs follows from the 8-bit A operand: a matrix
 // instruction takes twice as long (the pipe runs at the FP8 rate), so a stage is one K step of 64
@@ -1297,6 +1542,11 @@ splitk_reduce_rows(const float* __restrict__ P, int parts, int M, int N, YT* __r
 // Partial sums of the K parts live in caller memory: `parts` (256-byte aligned, `parts_bytes` bytes; null: none).
 // How many K parts a launch uses is a function of the shape, the device's compute units and parts_bytes only
 // (gemm_plan), so the same call gives the same bits on every stream, eagerly or captured.
+#ifndef BATQ_MID
+#define BATQ_MID 1
+#endif
+// LDS slots of gemm_mid's weight strip (10: slower on every shape tried, 128 x 4096 x 14336 12.0 -> 12.8 us)
+constexpr int kMidDepth = 6;
 struct GemmPlan {
     TilePlan tiled;             // M > 64: the tiled kernels' plan, ksplit set
     size_t part_floats = 0;     // floats of one K part's partial sums
@@ -1304,6 +1554,7 @@ struct GemmPlan {
     int ksplit = 1;             // K parts used
     int want = 1;               // K parts the shape would like (workspace permitting)
     int rt = 4;                 // 4-bit tiled kernel: 32-row matrix tiles per wave (4: 4 waves, 2: 8 waves)
+    bool mid = false;           // 4-bit, plain output, at most one 128 x 64 tile (and K part) per compute unit: gemm_mid
     bool skinny = false, wide = false;
     int cols = 0;               // skinny: workgroups along N
 };
@@ -1327,6 +1578,14 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
         const long units = (long)g.tiled.tiles_m * g.tiled.strips_n;
         const long per_worker = (units + g.tiled.workers - 1) / g.tiled.workers;
         g.rt = (!a8 && g.ksplit == 1 && per_worker * g.tiled.pair >= 3) ? 2 : 4;
+        // gemm_mid where all its workgroups (128-row panels x strips x K parts) run at once.  Graph-replayed, weights
+        // in HBM, tiled kernel -> gemm_mid: 128 x 4096 x 14336 14.9 -> 12.0 us, 300 x 4096 x 4096 12.8 -> 9.9,
+        // 2048 x 4096 x 1024 12.5 -> 10.5, 256 x 14336 x 4096 without K parts 39.1 -> 29.0, 128 x 14336 x 4096 with
+        // 4 K parts 19.8 -> 15.5, 256 x 8192 x 4096 with 2 K parts 19.9 -> 17.0.  With more workgroups than compute
+        // units it loses (256 x 4096 x 14336: 16.6 -> 19.4, 512 x 14336 x 4096 with 4 K parts 30.7 -> 36.7); two
+        // 32-row tiles per wave (256-row panels) lose everywhere (256 x 4096 x 14336: 18.1).
+        g.mid = BATQ_MID && !a8 && !glu && g.rt == 4 &&
+                (long)((M + 127) / 128) * g.tiled.strips_n * g.ksplit <= g.tiled.workers;
         return g;
     }
     g.skinny = true;
@@ -1366,7 +1625,20 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
     const GemmPlan g = gemm_plan(M, N, nb, cus, A8, GLU, parts ? parts_bytes : 0);
     if (!g.skinny) {
         const TilePlan& pl = g.tiled;
-        if (g.ksplit > 1) {
+        if (g.mid) {
+            if constexpr (!A8 && !GLU) {
+                const dim3 grid(pl.strips_n, (M + 127) / 128, g.ksplit), block(256);
+                if (g.ksplit > 1) {
+                    gemm_mid<partial_f32, 1, kMidDepth><<<grid, block, 0, stream>>>(
+                        xc, xs, w->d_codes, w->d_scales, M, N, nb, g.ksplit, reinterpret_cast<partial_f32*>(parts),
+                        (int64_t)g.col_blocks, (int64_t)g.part_floats);
+                    splitk_reduce<YT><<<dim3(g.col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
+                        parts, g.ksplit, (int64_t)g.part_floats, g.col_blocks, M, N, Y, ldy);
+                } else {
+                    gemm_mid<YT, 1, kMidDepth><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, 1, Y, ldy, 0);
+                }
+            }
+        } else if (g.ksplit > 1) {
             if constexpr (!GLU) {
                 if constexpr (A8) {
                     e = ensure_dynamic_lds<&gemm_tiled_a8<partial_f32, false>>(dev, kA8Lds);

@@ -126,8 +126,10 @@ def test_tile_schedule_shapes(B, M, K, N):
 @pytest.mark.parametrize("M,K,N", [(200, 2048, 14336), (300, 1536 + 32, 5000), (256, 768, 24000), (100, 512, 9000 + 24),
                                    (512, 1024, 14336)])
 def test_narrow_tile_shapes(B, M, K, N):
-    """Few rows and many columns: every workgroup gets one or two strips, so all tiles are one or two strips wide
-    (their own stage schedule), with 4 to 16 K stages, ragged rows and a ragged last strip; every element."""
+    """Few rows and many columns: every workgroup gets one or two strips.  Up to 128 rows that is one 128 x 64 tile
+    per compute unit (the kernel that loads X fragments straight to registers), above it tiles of the four-wave
+    tiled kernel one or two strips wide (their own stage schedule); 4 to 16 K stages, ragged rows and a ragged last
+    strip; every element."""
     import torch
     rng = np.random.default_rng(M * 7 + K + N)
     xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
