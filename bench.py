@@ -56,6 +56,8 @@ def main():
                     help="skip the two-stream side measurement (its overlapping kernels distort a kernel trace)")
     ap.add_argument("--no-kv", action="store_true", help="skip the key/value-cache side measurement")
     ap.add_argument("--no-mlp", action="store_true", help="skip the MLP-block side measurement (gate/up, SwiGLU, down)")
+    ap.add_argument("--no-gemm-over-m", action="store_true",
+                    help="skip the GEMM-time-over-token-count table (16 to 1024 rows on the two headline weight shapes)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling tool (register-only MFMA "
                     "loop, streaming HBM kernels)")
     args = ap.parse_args()
@@ -462,6 +464,59 @@ def main():
         del Xk, Xq, Ok, Oq
         torch.cuda.empty_cache()
 
+    # GEMM time over the token count M on the two headline weight shapes, weights in HBM: 20 copies of the weight
+    # take turns, the 20 calls are replayed as one captured graph (so the gaps between dependent launches are in the
+    # figure), each call with the workspace batq_gemm_workspace() asks for.  One pass over the weight's codes and
+    # scales at the measured read ceiling is the floor for small M.
+    over_m = None
+    if not args.no_gemm_over_m:
+        over_m = {"note": "us per GEMM call, graph replays of 20 calls over 20 weight copies, median of the repeats; "
+                          "weight_stream_us = weight codes and scales / 5.5 TB/s", "shapes": {}}
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(11)
+        side = torch.cuda.Stream()
+        for Kw, Nw in ((4096, 14336), (14336, 4096)):
+            nbw = Kw // 32
+            rw = np.random.default_rng(Kw)
+            Gw, Pw, cw = bi.make_factors(nbw, rw, rw, rw, 0.85)
+            tw = B.Transform(Kw, Gw, Pw, cw)
+            first = B.batq_prepare_weight(tw, (torch.randn((Kw, Nw), device="cuda", generator=gen) * 0.02).to(torch.bfloat16))
+            wcodes, wscales = first.export()
+            whs = [first] + [B.batq_weight_import(wcodes, wscales, Kw, Nw) for _ in range(19)]
+            row = {}
+            for Mw in (16, 64, 128, 256, 512, 1024):
+                Xw = torch.randn((Mw, Kw), device="cuda", generator=gen).to(torch.bfloat16)
+                xc_ = torch.empty(B.batq_code_bytes(Mw, Kw), dtype=torch.uint8, device="cuda")
+                xs_ = torch.empty(B.batq_scale_bytes(Mw, Kw), dtype=torch.uint8, device="cuda")
+                B.batq_quantize_act(tw, Xw, xc_, xs_)
+                need = B.batq_gemm_workspace(first, Mw)
+                work = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
+                Yw = torch.empty((Mw, Nw), dtype=torch.bfloat16, device="cuda")
+                with torch.cuda.stream(side):
+                    for i in range(20):
+                        B.batq_gemm_mxfp4(xc_, xs_, whs[i], Mw, Y=Yw, workspace=work)
+                side.synchronize()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=side):
+                    for i in range(20):
+                        B.batq_gemm_mxfp4(xc_, xs_, whs[i], Mw, Y=Yw, workspace=work)
+                gr.replay()
+                torch.cuda.synchronize()
+                out = []
+                for _ in range(args.repeats):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(10):
+                        gr.replay()
+                    e1.record()
+                    e1.synchronize()
+                    out.append(e0.elapsed_time(e1) / 200 * 1e3)
+                row[str(Mw)] = sorted(out)[len(out) // 2]
+                del gr
+            over_m["shapes"][f"K={Kw} N={Nw}"] = {"us": row, "weight_stream_us": Kw * Nw * (0.5 + 1.0 / 32) / 5.5e6}
+            del whs, first, wcodes, wscales
+            torch.cuda.empty_cache()
+
     ceilings = None
     tool = os.path.join(ROOT, "paper_2603_16590_amd", "batq_ceilings")
     if not args.no_ceilings and os.path.exists(tool):
@@ -531,6 +586,7 @@ def main():
         "also": also,
         "w4a8": w4a8,
         "mlp_block": mlp,
+        "gemm_over_m": over_m,
         "kv_cache": kv,
     }
     print(json.dumps(line))

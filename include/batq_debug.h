@@ -13,7 +13,8 @@ extern "C" {
 
 /* ------------------------------------------------------------------------------------
  * Introspection (HOST only, no GPU needed): the work split of the tiled GEMM kernels for an M x K x N problem
- * (M > 64) on a device with `compute_units` compute units, as the kernels would walk it.  Writes 7 ints per
+ * (M > 64; 0 tiles below) on a device with `compute_units` compute units, as the kernels would walk it (shapes
+ * with at most one 128 x 64 tile per compute unit go to another kernel, one tile per workgroup).  Writes 7 ints per
  * tile to tiles[capacity * 7] (HOST): workgroup, first row, first column, width in 64-column strips, K part,
  * first K group (256 elements) and number of K groups; returns the number of tiles (also when capacity is
  * smaller; -1 for invalid arguments).  glu: the gated-output mode of batq_gemm_glu (N % 64 == 0);

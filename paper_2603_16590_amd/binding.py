@@ -100,6 +100,13 @@ def _load() -> C.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2603_16590_amd.build` "
             "(there is no fallback path)")
+    # The tensors this binding is handed live in torch's HIP runtime, and torch ships its own copy of it: that copy
+    # has to be in the process before the library's dependency on the HIP runtime is resolved, or the library gets
+    # a second runtime that knows none of torch's allocations (its first call then fails with BATQ_ERR_DEVICE).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     l = C.CDLL(LIB_PATH)
     for name, (res, args) in SYMBOLS.items():
         fn = getattr(l, name)            # AttributeError if the library does not export it

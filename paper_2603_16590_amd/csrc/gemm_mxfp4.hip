@@ -1559,9 +1559,11 @@ struct GemmPlan {
     int cols = 0;               // skinny: workgroups along N
 };
 
-inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size_t parts_bytes) {
+// fits32: both code arrays are below 2 GiB (the tiled kernels and gemm_mid use 32-bit load offsets; M > 64 without
+// it is the caller's case for gemm_direct).
+inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size_t parts_bytes, bool fits32 = true) {
     GemmPlan g;
-    if (M > 64) {
+    if (M > 32) {
         g.tiled = make_plan(M, N, nb, cus, glu);
         if (!glu) {
             g.col_blocks = 2 * g.tiled.strips_n;
@@ -1584,9 +1586,11 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
         // 4 K parts 19.8 -> 15.5, 256 x 8192 x 4096 with 2 K parts 19.9 -> 17.0.  With more workgroups than compute
         // units it loses (256 x 4096 x 14336: 16.6 -> 19.4, 512 x 14336 x 4096 with 4 K parts 30.7 -> 36.7); two
         // 32-row tiles per wave (256-row panels) lose everywhere (256 x 4096 x 14336: 18.1).
-        g.mid = BATQ_MID && !a8 && !glu && g.rt == 4 &&
+        // From 33 rows on it also beats the small-M kernel (64 x 4096 x 14336: 12.9 -> 11.0 us).
+        g.mid = BATQ_MID && !a8 && !glu && fits32 && g.rt == 4 &&
                 (long)((M + 127) / 128) * g.tiled.strips_n * g.ksplit <= g.tiled.workers;
-        return g;
+        if (M > 64 || g.mid) return g;
+        g = GemmPlan();
     }
     g.skinny = true;
     // 64 columns per workgroup pay with two row tiles (the X codes are the larger share of a workgroup's
@@ -1622,7 +1626,7 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
     if (e != hipSuccess) return e;
     const int cus = device_compute_units(dev, &e);
     if (e != hipSuccess) return e;
-    const GemmPlan g = gemm_plan(M, N, nb, cus, A8, GLU, parts ? parts_bytes : 0);
+    const GemmPlan g = gemm_plan(M, N, nb, cus, A8, GLU, parts ? parts_bytes : 0, fits32);
     if (!g.skinny) {
         const TilePlan& pl = g.tiled;
         if (g.mid) {
@@ -1743,6 +1747,7 @@ hipError_t launch_codes8_to_rowmajor(const uint8_t* blocked, uint8_t* rowmajor, 
 
 int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_ksplit, int* out, int capacity) {
     const int nb = K / 32;
+    if (M <= 64) return 0;                                      // the small-M kernels have no tile schedule
     const GemmPlan g = gemm_plan(M, N, nb, compute_units, false, glu, allow_ksplit ? ~size_t(0) : 0);
     const TilePlan& pl = g.tiled;
     int n = 0;
@@ -1764,8 +1769,9 @@ int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_k
 size_t gemm_workspace_bytes(const batq_weight* w, int M, bool a8, int cus) {
     if (M <= 0) return 0;
     const size_t xbytes = a8 ? code8_bytes_blocked(M, w->nb) : code_bytes_blocked(M, w->nb);
-    if (M > 64 && !(xbytes < (1ull << 31) && code_bytes_blocked(w->N, w->nb) < (1ull << 31))) return 0;
-    const GemmPlan g = gemm_plan(M, w->N, w->nb, cus, a8, false, 0);
+    const bool fits32 = xbytes < (1ull << 31) && code_bytes_blocked(w->N, w->nb) < (1ull << 31);
+    if (M > 64 && !fits32) return 0;
+    const GemmPlan g = gemm_plan(M, w->N, w->nb, cus, a8, false, 0, fits32);
     return g.want > 1 ? (size_t)g.want * g.part_floats * sizeof(float) : 0;
 }
 

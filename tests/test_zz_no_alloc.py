@@ -37,8 +37,8 @@ def _noalloc(B, xc, xs, wh, M, Y):
 
 def test_noalloc_gemm_equals_the_workspace_entry_point(B):
     import torch
-    # (M, K, N): K parts in the tiled kernel (16 MiB, the most any shape asks for), fewer rows and columns,
-    # two K parts in the small-M kernel, and a shape without K parts
+    # (M, K, N): K parts at 16 MiB, the most any shape asks for; fewer rows and columns; 40 rows (K parts in the
+    # one-tile-per-workgroup kernel) followed by 31 (two K parts in the small-M kernel); a shape without K parts
     cases = [(300, 14336, 4096), (130, 8192, 320), (40, 16384, 96), (200, 512, 3000)]
     for n, (M, K, N) in enumerate(cases):
         wh, xc, xs = _problem(B, M, K, N, seed=20 + n)
@@ -67,7 +67,10 @@ def test_noalloc_gemm_equals_the_workspace_entry_point(B):
             torch.cuda.synchronize()
             assert torch.equal(Y1, ref), (M, K, N, dt)
             assert torch.equal(Y2, ref2), (M2, K, N, dt)
-            assert torch.equal(Y2, ref[:M2]), "rows are independent"
+            # (the smaller call may run on another kernel with another summation order: compared with the first
+            # call's rows only to rounding)
+            assert torch.allclose(Y2.float(), ref[:M2].float(), rtol=2e-2 if dt == torch.bfloat16 else 1e-4,
+                                  atol=1e-2 * float(ref.float().abs().max()) if dt == torch.bfloat16 else 1e-4 * float(ref.abs().max()))
 
 
 def test_noalloc_gemm_argument_errors(B):
