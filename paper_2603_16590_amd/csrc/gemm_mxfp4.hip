@@ -1584,8 +1584,8 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
         // in HBM, tiled kernel -> gemm_mid: 128 x 4096 x 14336 14.9 -> 12.0 us, 300 x 4096 x 4096 12.8 -> 9.9,
         // 2048 x 4096 x 1024 12.5 -> 10.5, 256 x 14336 x 4096 without K parts 39.1 -> 29.0, 128 x 14336 x 4096 with
         // 4 K parts 19.8 -> 15.5, 256 x 8192 x 4096 with 2 K parts 19.9 -> 17.0.  With more workgroups than compute
-        // units it loses (256 x 4096 x 14336: 16.6 -> 19.4, 512 x 14336 x 4096 with 4 K parts 30.7 -> 36.7); two
-        // 32-row tiles per wave (256-row panels) lose everywhere (256 x 4096 x 14336: 18.1).
+        // units it loses (256 x 4096 x 14336: 16.6 -> 19.4, 512 x 14336 x 4096 with 4 K parts 30.7 -> 36.7); 256-row
+        // panels, with two 32-row tiles per wave or with eight waves, lose everywhere (256 x 4096 x 14336: 18.1, 18.7).
         // From 33 rows on it also beats the small-M kernel (64 x 4096 x 14336: 12.9 -> 11.0 us).
         g.mid = BATQ_MID && !a8 && !glu && fits32 && g.rt == 4 &&
                 (long)((M + 127) / 128) * g.tiled.strips_n * g.ksplit <= g.tiled.workers;
