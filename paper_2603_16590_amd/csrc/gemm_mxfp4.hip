@@ -719,8 +719,8 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
     asm volatile("" : "+v"(lane_e));
     if constexpr (sizeof(YT) == 2) {
         // bf16: transpose through a wave-private LDS buffer so that every lane stores 16 contiguous
-        // bytes.  Needs the whole tile width inside N and 16-byte aligned rows (workgroup-uniform).
-        const bool fast = n0 + kStrip * NJ <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+        // bytes.  Needs the wave's whole width inside N and 16-byte aligned rows (wave-uniform).
+        const bool fast = n0 + (wn + 1) * 32 * NJ <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
         if (fast) {
             constexpr int BR = kEpilogueBlockRows<RT>;      // rows staged at a time
             uint8_t* ep = ep_lds;   // [BR rows][256 bytes]
