@@ -141,6 +141,50 @@ def test_gemm_option_combinations(B, case):
         assert np.all(np.abs(got - ref) <= tol + 1e-30), (case, M, K, N, bits, glu)
 
 
+@pytest.mark.parametrize("case", range(17))
+def test_gemm_kernel_choice_combinations(B, case):
+    """Random (M, K, N, workspace) over the ranges in which the library switches between its 4-bit GEMM kernels (small-M,
+    one tile per workgroup, tiled with four or eight waves, with and without K parts): every element against the
+    oracle, and the same bits when the call is repeated."""
+    import torch
+    rng = np.random.default_rng(7700 + case)
+    M = int(rng.choice([20, 33, 48, 64, 65, 100, 128, 129, 200, 300, 520, 700]))
+    K = 32 * int(rng.integers(4, 130)) if case % 3 else 256 * int(rng.integers(24, 60))
+    N = int(rng.integers(60, 16000)) if case % 2 else 64 * int(rng.integers(1, 120))
+    if case >= 14:                                     # many strips per workgroup: the eight-wave tiled kernel
+        M, K, N = int(rng.integers(520, 1100)), 32 * int(rng.integers(4, 40)), int(rng.integers(14000, 26000))
+    if M * N * K > 2.5e10:
+        N = max(64, int(2.5e10 / (M * K)))
+    out_bf16 = bool(rng.integers(0, 2))
+    wc = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    ws = rng.integers(124, 130, size=(N, K // 32), dtype=np.uint8)
+    xc = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    xs = rng.integers(124, 130, size=(M, K // 32), dtype=np.uint8)
+    wh = B.batq_weight_import(torch.from_numpy(wc).cuda(), torch.from_numpy(ws).cuda(), K, N)
+    dxc = torch.from_numpy(rowmajor_to_blocked(xc)).cuda()
+    dxs = torch.from_numpy(rowmajor_to_grouped(xs)).cuda()
+    dq_x, dq_w = o.dequantize(xc, xs), o.dequantize(wc, ws)
+    ref = dq_x @ dq_w.T
+    tol = 2e-6 * (np.abs(dq_x) @ np.abs(dq_w).T)
+    need = B.batq_gemm_workspace(wh, M)
+    frac = [0.0, 0.4, 1.0][int(rng.integers(0, 3))]
+    work = torch.empty(max(256, int(need * frac)), dtype=torch.uint8, device="cuda") if need and frac > 0 else None
+    odt = torch.bfloat16 if out_bf16 else torch.float32
+    Y = B.batq_gemm_mxfp4(dxc, dxs, wh, M, odt, workspace=work)
+    Y2 = B.batq_gemm_mxfp4(dxc, dxs, wh, M, odt, workspace=work)
+    torch.cuda.synchronize()
+    what = (case, M, K, N, need, frac, out_bf16)
+    assert torch.equal(Y, Y2), what
+    got = y_to_f32(Y).astype(np.float64)
+    if out_bf16:
+        refb = o.bf16_round(ref).astype(np.float64)
+        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(refb), 1e-300))) - 7)
+        bad = np.argwhere(np.abs(got - refb) > ulp * 1.0001 + tol)
+    else:
+        bad = np.argwhere(np.abs(got - ref) > tol + 1e-30)
+    assert bad.size == 0, (what, len(bad), bad[:3].tolist())
+
+
 @pytest.mark.parametrize("case", range(10))
 def test_cache_append_chunkings(B, case):
     """Random capacities, forms, widths and chunkings of the appends (fp32 and bf16 rows): the filled cache holds
