@@ -68,6 +68,21 @@ def test_headline_shapes(lib):
     assert sorted(set(t[:, 3])) == [2, 4]
 
 
+def test_column_bands_follow_the_tile_rounds(lib):
+    """The workgroups of one XCD (workgroup index mod 8) own a compact block of the output.  Its A rows are streamed
+    once per tile round, so many rounds call for few bands (a tall-narrow block would re-read much of A every round):
+    cfg4's ten rounds give every XCD 1024 rows and all columns; cfg3's single round the 1024 x 2048 blocks that
+    minimise rows + columns; cfg2's two rounds 1024 x 3584."""
+    for (M, K, N), rows, cols in (((8192, 3584, 18944), 1024, 18944), ((4096, 14336, 4096), 1024, 2048),
+                                  ((2048, 4096, 14336), 1024, 3584)):
+        t = _check(lib, M, N, K, 256, False, False)
+        for x in range(8):
+            mine = t[t[:, 0] % 8 == x]
+            r = mine[:, 1].max() + 256 - mine[:, 1].min()
+            c = (mine[:, 2] + 64 * mine[:, 3]).max() - mine[:, 2].min()
+            assert (r, c) == (rows, cols), ((M, K, N), x, r, c)
+
+
 def test_random_shapes(lib):
     rng = np.random.default_rng(0)
     for _ in range(300):
