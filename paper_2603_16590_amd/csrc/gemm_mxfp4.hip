@@ -929,9 +929,11 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     // this workgroup's share of the linear strip order
     int cur, end;
     worker_share(pl, blockIdx.x, cur, end);
+    TileWalk walk;
+    walk_begin(pl, cur, end, walk);
 
     Tile t, next;
-    if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
+    if (!next_tile(pl, walk, t)) return;                  // workgroup-uniform
 
     const int lane = threadIdx.x & 63;
     TiledCtx<RT> c;
@@ -948,7 +950,7 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     c.aim(t);
     c.issue_prologue(t.nj);
     for (;;) {
-        const bool has_next = next_tile(pl, cur, end, next);
+        const bool has_next = next_tile(pl, walk, next);
         if constexpr (GLU) {
             if (t.nj == 4) run_tile<RT, 4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
             else run_tile<RT, 2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
@@ -1450,9 +1452,11 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
 
     int cur, end;
     worker_share(pl, blockIdx.x, cur, end);
+    TileWalk walk;
+    walk_begin(pl, cur, end, walk);
 
     Tile t, next;
-    if (!next_tile(pl, cur, end, t)) return;              // workgroup-uniform
+    if (!next_tile(pl, walk, t)) return;                  // workgroup-uniform
 
     const int lane = threadIdx.x & 63;
     A8Ctx c;
@@ -1471,7 +1475,7 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     c.issue_stage<2>(2);
     c.issue_stage<3>(3);
     for (;;) {
-        const bool has_next = next_tile(pl, cur, end, next);
+        const bool has_next = next_tile(pl, walk, next);
         if constexpr (GLU) {
             if (t.nj == 4) a8_run_tile<4, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
             else a8_run_tile<2, YT, true>(c, t, has_next, next, Y, ldy, part_stride);
@@ -1754,8 +1758,10 @@ int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_k
     for (int b = 0; b < pl.workers; ++b) {
         int cur, end;
         worker_share(pl, b, cur, end);
+        TileWalk walk;
+        walk_begin(pl, cur, end, walk);
         Tile t;
-        while (next_tile(pl, cur, end, t)) {
+        while (next_tile(pl, walk, t)) {
             if (n < capacity) {
                 int* o = out + (size_t)n * 7;
                 o[0] = b; o[1] = t.m0; o[2] = t.n0; o[3] = t.nj; o[4] = t.part; o[5] = t.g0; o[6] = t.ng;

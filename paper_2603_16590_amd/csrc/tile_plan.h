@@ -26,34 +26,76 @@ struct Tile {
     int part, g0, ng;   // K part, its first K group and its number of K groups
 };
 
-// Takes the next tile off the share [cur, end) of the linear order: K part by K part, inside a part the
-// strip order (column bands -> row panels -> strips).
-__host__ __device__ inline bool next_tile(const TilePlan& pl, int& cur, int end, Tile& t) {
-    if (cur >= end) return false;
-    int part = 0, at = cur, stop = end;
-    if (pl.ksplit > 1) {
-        const int per_part = pl.tiles_m * pl.strips_n;
-        part = cur / per_part;
-        at = cur - part * per_part;
-        stop = (end - part * per_part) < per_part ? (end - part * per_part) : per_part;      // a tile does not reach into the next K part
-    }
-    int b = 0;
-    while (b + 1 < pl.bands && at >= pl.tiles_m * ((b + 1) * pl.strips_n / pl.bands)) ++b;
-    const int bs = b * pl.strips_n / pl.bands, be = (b + 1) * pl.strips_n / pl.bands;
-    const int width = be - bs;
-    const int local = at - pl.tiles_m * bs;
-    const int p = local / width, sl = local - p * width;
-    const int run = (stop - at) < (width - sl) ? (stop - at) : (width - sl);           // units left in this row panel of the band
-    const int most = 4 / pl.pair;                         // units per tile at most (a tile is at most 4 strips wide)
-    const int nt = (run + most - 1) / most;               // tiles the run is cut into, near-equal widths
-    const int units = (run + nt - 1) / nt;
+// A workgroup's walk through its share [cur, end) of the linear order: K part by K part, inside a part the strip
+// order (column bands -> row panels -> strips).  The position is decoded once (divisions) and then advanced tile by
+// tile with additions and compares only: the kernels take the next tile between an epilogue and the next main loop,
+// where every instruction is on the critical path (the same walk decoded from scratch for every tile cost ~900 cycles
+// per tile).
+struct TileWalk {
+    int cur, end;            // position and end of the share, in scheduling units over all K parts
+    int part, at;            // K part of `cur` and position inside it
+    int b, bs, width;        // column band of `cur`: index, first unit, units
+    int p, sl;               // row panel and unit inside the band's panel row
+    int g0, ng;              // K groups of `part`
+};
+
+__host__ __device__ inline void walk_set_band(const TilePlan& pl, TileWalk& w) {
+    w.bs = w.b * pl.strips_n / pl.bands;
+    w.width = (w.b + 1) * pl.strips_n / pl.bands - w.bs;
+}
+__host__ __device__ inline void walk_set_part(const TilePlan& pl, TileWalk& w) {
+    w.g0 = pl.groups * w.part / pl.ksplit;
+    w.ng = pl.groups * (w.part + 1) / pl.ksplit - w.g0;
+}
+// Start of the walk over [cur, end).
+__host__ __device__ inline void walk_begin(const TilePlan& pl, int cur, int end, TileWalk& w) {
+    w.cur = cur;
+    w.end = end;
+    const int per_part = pl.tiles_m * pl.strips_n;
+    w.part = pl.ksplit > 1 ? cur / per_part : 0;
+    w.at = cur - w.part * per_part;
+    w.b = 0;
+    while (w.b + 1 < pl.bands && w.at >= pl.tiles_m * ((w.b + 1) * pl.strips_n / pl.bands)) ++w.b;
+    walk_set_band(pl, w);
+    const int local = w.at - pl.tiles_m * w.bs;
+    w.p = local / w.width;
+    w.sl = local - w.p * w.width;
+    walk_set_part(pl, w);
+}
+// Takes the next tile off the walk: at most 4 strips of what is left of the share in this row panel of the band (a
+// tile does not reach into the next panel, band or K part), the run cut into tiles of near-equal width.
+__host__ __device__ inline bool next_tile(const TilePlan& pl, TileWalk& w, Tile& t) {
+    if (w.cur >= w.end) return false;
+    const int per_part = pl.tiles_m * pl.strips_n;
+    int run = w.end - w.cur;
+    if (per_part - w.at < run) run = per_part - w.at;
+    if (w.width - w.sl < run) run = w.width - w.sl;       // units left in this row panel of the band
+    const int shift = pl.pair == 2 ? 1 : 2;               // at most 4 strips = 4 / pair units per tile
+    const int nt = (run + (1 << shift) - 1) >> shift;     // tiles the run is cut into, near-equal widths
+    int units = nt == 1 ? run : (run + nt - 1) / nt;
     t.nj = units * pl.pair;
-    t.m0 = p * kTile;
-    t.n0 = (bs + sl) * kStrip * pl.pair;
-    t.part = part;
-    t.g0 = pl.groups * part / pl.ksplit;
-    t.ng = pl.groups * (part + 1) / pl.ksplit - t.g0;
-    cur += units;
+    t.m0 = w.p * kTile;
+    t.n0 = (w.bs + w.sl) * kStrip * pl.pair;
+    t.part = w.part;
+    t.g0 = w.g0;
+    t.ng = w.ng;
+    // advance
+    w.cur += units;
+    w.at += units;
+    w.sl += units;
+    if (w.sl == w.width) {
+        w.sl = 0;
+        if (++w.p == pl.tiles_m) {
+            w.p = 0;
+            if (++w.b == pl.bands) {                      // the part is done (at == per_part)
+                w.b = 0;
+                w.at = 0;
+                ++w.part;
+                if (w.cur < w.end) walk_set_part(pl, w);
+            }
+            if (w.cur < w.end) walk_set_band(pl, w);
+        }
+    }
     return true;
 }
 
