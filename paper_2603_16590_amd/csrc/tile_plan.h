@@ -130,6 +130,12 @@ __host__ __device__ inline void worker_share(const TilePlan& pl, int block, int&
     const int per_xcd = pl.workers >> 3;
     const int share = (block & 7) * per_xcd + (block >> 3);
     const int64_t total = (int64_t)pl.tiles_m * pl.strips_n * pl.ksplit;
+    if (total < (1 << 20)) {                    // the usual case: 32-bit products and divisions (workers <= 2^11)
+        const uint32_t t32 = (uint32_t)total, wk = (uint32_t)pl.workers;
+        cur = (int)(t32 * (uint32_t)share / wk);
+        end = (int)(t32 * (uint32_t)(share + 1) / wk);
+        return;
+    }
     cur = (int)(total * share / pl.workers);
     end = (int)(total * (share + 1) / pl.workers);
 }
