@@ -1110,8 +1110,12 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
     t.m0 = blockIdx.y * (128 * RT);
     t.nj = 1;
     t.part = blockIdx.z;
-    t.g0 = groups * t.part / ksplit;
-    t.ng = groups * (t.part + 1) / ksplit - t.g0;
+    t.g0 = 0;
+    t.ng = groups;
+    if (ksplit > 1) {                                           // (divisions only where there are K parts)
+        t.g0 = groups * t.part / ksplit;
+        t.ng = groups * (t.part + 1) / ksplit - t.g0;
+    }
     const int T = 2 * t.ng;                                     // stages of 128 K elements
 
     MidCtx<RT, D> c;
