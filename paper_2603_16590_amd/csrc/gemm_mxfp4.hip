@@ -930,7 +930,7 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
     int cur, end;
     worker_share(pl, blockIdx.x, cur, end);
     TileWalk walk;
-    walk_begin(pl, cur, end, walk);
+    walk_begin(pl, blockIdx.x, cur, end, walk);
 
     Tile t, next;
     if (!next_tile(pl, walk, t)) return;                  // workgroup-uniform
@@ -1457,7 +1457,7 @@ gemm_tiled_a8(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, co
     int cur, end;
     worker_share(pl, blockIdx.x, cur, end);
     TileWalk walk;
-    walk_begin(pl, cur, end, walk);
+    walk_begin(pl, blockIdx.x, cur, end, walk);
 
     Tile t, next;
     if (!next_tile(pl, walk, t)) return;                  // workgroup-uniform
@@ -1763,7 +1763,7 @@ int tile_schedule(int M, int N, int K, int compute_units, bool glu, bool allow_k
         int cur, end;
         worker_share(pl, b, cur, end);
         TileWalk walk;
-        walk_begin(pl, cur, end, walk);
+        walk_begin(pl, b, cur, end, walk);
         Tile t;
         while (next_tile(pl, walk, t)) {
             if (n < capacity) {

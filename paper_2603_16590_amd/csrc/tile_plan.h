@@ -37,6 +37,7 @@ struct TileWalk {
     int b, bs, width;        // column band of `cur`: index, first unit, units
     int p, sl;               // row panel and unit inside the band's panel row
     int g0, ng;              // K groups of `part`
+    int lead;                // narrower tiles still to be put in front of the wider ones (see walk_begin)
 };
 
 __host__ __device__ inline void walk_set_band(const TilePlan& pl, TileWalk& w) {
@@ -47,8 +48,19 @@ __host__ __device__ inline void walk_set_part(const TilePlan& pl, TileWalk& w) {
     w.g0 = pl.groups * w.part / pl.ksplit;
     w.ng = pl.groups * (w.part + 1) / pl.ksplit - w.g0;
 }
-// Start of the walk over [cur, end).
-__host__ __device__ inline void walk_begin(const TilePlan& pl, int cur, int end, TileWalk& w) {
+// Tiles a run of `run` units is cut into: at most 4 strips = 4 / pair units each.
+__host__ __device__ inline int run_tiles(const TilePlan& pl, int run) {
+    const int shift = pl.pair == 2 ? 1 : 2;
+    return (run + (1 << shift) - 1) >> shift;
+}
+// Start of the walk over [cur, end) by workgroup `block`.
+// A run of units is cut into tiles of near-equal width, i.e. of two widths one unit apart.  Workgroups whose shares
+// are alike would all reach their epilogues at the same moments, and the whole chip would then write its output
+// in bursts (the write path, not the compute units, sets the length of such an epilogue) and not at all in
+// between.  So the workgroups of an XCD take turns in how many of the narrower tiles of their first run they put in
+// front of the wider ones: with 3 narrow tiles of 10 the four classes run a quarter of a tile apart.  Workgroups that
+// stream the same weight columns (same place in their row panel, 8 apart inside the XCD) are in the same class.
+__host__ __device__ inline void walk_begin(const TilePlan& pl, int block, int cur, int end, TileWalk& w) {
     w.cur = cur;
     w.end = end;
     const int per_part = pl.tiles_m * pl.strips_n;
@@ -61,6 +73,17 @@ __host__ __device__ inline void walk_begin(const TilePlan& pl, int cur, int end,
     w.p = local / w.width;
     w.sl = local - w.p * w.width;
     walk_set_part(pl, w);
+    int run = end - cur;
+    if (per_part - w.at < run) run = per_part - w.at;
+    if (w.width - w.sl < run) run = w.width - w.sl;
+    w.lead = 0;
+    if (run > 0) {
+        const int nt = run_tiles(pl, run);
+        const int wide = nt == 1 ? run : (run + nt - 1) / nt;
+        const int narrow = nt * wide - run;                 // tiles of width wide - 1 in the run
+        w.lead = (block >> 3) & 3;
+        while (w.lead > narrow) w.lead -= narrow + 1;
+    }
 }
 // Takes the next tile off the walk: at most 4 strips of what is left of the share in this row panel of the band (a
 // tile does not reach into the next panel, band or K part), the run cut into tiles of near-equal width.
@@ -70,9 +93,12 @@ __host__ __device__ inline bool next_tile(const TilePlan& pl, TileWalk& w, Tile&
     int run = w.end - w.cur;
     if (per_part - w.at < run) run = per_part - w.at;
     if (w.width - w.sl < run) run = w.width - w.sl;       // units left in this row panel of the band
-    const int shift = pl.pair == 2 ? 1 : 2;               // at most 4 strips = 4 / pair units per tile
-    const int nt = (run + (1 << shift) - 1) >> shift;     // tiles the run is cut into, near-equal widths
+    const int nt = run_tiles(pl, run);                    // tiles the run is cut into, near-equal widths
     int units = nt == 1 ? run : (run + nt - 1) / nt;
+    if (w.lead > 0 && units * nt != run) {                // a narrower tile first
+        --units;
+        --w.lead;
+    }
     t.nj = units * pl.pair;
     t.m0 = w.p * kTile;
     t.n0 = (w.bs + w.sl) * kStrip * pl.pair;

@@ -83,6 +83,30 @@ def test_column_bands_follow_the_tile_rounds(lib):
             assert (r, c) == (rows, cols), ((M, K, N), x, r, c)
 
 
+def test_workgroups_of_an_xcd_take_turns_with_the_narrow_tiles(lib):
+    """A run of strips is cut into tiles of two widths one strip apart.  If every workgroup put the wide ones first,
+    all would reach their epilogues together and the chip would write its output in bursts; so workgroup i of an XCD
+    puts i % (number of narrow tiles + 1), at most 3, narrow tiles in front.  Workgroups 8 apart inside an XCD stream
+    the same weight columns and must stay in step."""
+    def widths(t, b):
+        return [int(x[3]) for x in t if x[0] == b]
+    t = _check(lib, 8192, 18944, 3584, 256, False, False)       # cfg4: 37 strips per workgroup = 7 x 4 + 3 x 3
+    for x in (0, 5):
+        assert widths(t, x) == [4] * 7 + [3] * 3
+        assert widths(t, x + 8) == [3] + [4] * 7 + [3] * 2
+        assert widths(t, x + 16) == [3] * 2 + [4] * 7 + [3]
+        assert widths(t, x + 24) == [3] * 3 + [4] * 7
+        assert widths(t, x + 32) == widths(t, x)
+    for b in range(256):                                       # same columns (8 workgroups apart in the XCD): same order
+        i = b >> 3
+        if i + 8 < 32:
+            assert widths(t, b) == widths(t, b + 64)
+    t = _check(lib, 2048, 14336, 4096, 256, False, False)       # cfg2: 7 strips = 4 + 3
+    assert widths(t, 0) == [4, 3] and widths(t, 8) == [3, 4] and widths(t, 16) == [4, 3] and widths(t, 24) == [3, 4]
+    t = _check(lib, 4096, 4096, 14336, 256, False, False)       # cfg3: one tile each, nothing to reorder
+    assert all(widths(t, b) == [4] for b in range(256))
+
+
 def test_random_shapes(lib):
     rng = np.random.default_rng(0)
     for _ in range(300):
