@@ -839,6 +839,7 @@ __device__ __forceinline__ void store_partial(v16f (&acc)[RT][NJ], float* __rest
     for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
+            if (cb0 + j >= col_blocks) continue;            // (a workgroup of two strips whose second does not exist)
             float* blk = P + ((size_t)(rb0 + i) * col_blocks + cb0 + j) * kPartialBlockFloats + lane_e * 4;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -970,27 +971,30 @@ gemm_tiled(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const
 // ------------------------------------------------------------------------------------------
 // Kernel for shapes with so few rows and strips that 128-row panels x strips (x K parts) give at most one
 // workgroup per compute unit, where the tiled kernel's 256-row tiles leave compute units idle or half empty.
-// A workgroup of 4 waves computes 128 RT rows x 64 columns (RT = 1 is what the launch code uses), wave w the rows
-// 32 RT w .. + 32 RT - 1 of all 64 columns: the rows of X a wave multiplies belong to it alone, so their
-// fragments go from global memory (the L2) straight to registers, D - 2 stages ahead, and only the weight strip
-// (4 KiB per stage, read by all four waves) goes through LDS, each wave fetching one of its four 1 KiB pieces:
-// per stage 12 KiB enter the compute unit and 8 KiB of fragments are read from LDS, against 20 KiB and 40 KiB
-// for a 256 x 64 tile of the tiled kernel.
+// A workgroup of 4 waves computes 128 RT rows x 64 NS columns (RT = 1 is what the launch code uses; NS = 1 strip,
+// or 2 where only pairs of strips give at most one workgroup per compute unit), wave w the rows
+// 32 RT w .. + 32 RT - 1 of all its columns: the rows of X a wave multiplies belong to it alone, so their
+// fragments go from global memory (the L2) straight to registers, D - 2 stages ahead, and only the weight strips
+// (4 KiB per strip and stage, read by all four waves) go through LDS, each wave fetching one of a strip's four
+// 1 KiB pieces: with one strip, per stage 12 KiB enter the compute unit and 8 KiB of fragments are read from LDS,
+// against 20 KiB and 40 KiB for a 256 x 64 tile of the tiled kernel.
 //
-// Loads of a wave complete in the order it issued them.  Stage q's are: the strip piece, 2 RT fragments of X
-// and, for even q, RT + 2 scale dwords (those of the K group q opens); stages are issued in order.  At the top
+// Loads of a wave complete in the order it issued them.  Stage q's are: NS strip pieces, 2 RT fragments of X
+// and, for even q, RT + 2 NS scale dwords (those of the K group q opens); stages are issued in order.  At the top
 // of stage s a wave waits until only loads of the stages after s + 1 can be outstanding, then meets the others at
 // the barrier: the whole strip stage s + 1 is in LDS and is read to registers under the matrix instructions of
 // stage s, and every wave is done with stage s - 1, whose LDS slot and registers the loads of stage s + D - 1
 // then overwrite (issued after the stage's own matrix instructions, which still read the scale registers of the
 // K group they complete).
-constexpr int kMidStageLds = 64 * kStageBytes;      // 4 KiB; D of them: the LDS slots of the weight strip (a wave
-                                                    // works D - 2 stages ahead); the epilogue's staging reuses them
+constexpr int kMidStripLds = 64 * kStageBytes;      // 4 KiB: one stage of one 64-column strip.  A workgroup keeps D
+                                                    // stages of its NS strips in LDS (a wave works D - 2 stages
+                                                    // ahead); the epilogue's staging reuses them
 
-template <int RT, int D>
+template <int RT, int D, int NS>
 struct MidCtx {
     static_assert(D % 2 == 0 && D >= 4, "stages come in K groups of two");
-    uint32_t aoff[RT][2], boff, sao[RT], sbo[2], lds0;
+    static constexpr int NJ = 2 * NS;           // 32-column matrix tiles of a wave
+    uint32_t aoff[RT][2], boff[NS], sao[RT], sbo[NJ], lds0;
     int wave, T;
     // the next stage to load: its index, where its codes and the scales of its K group start
     int q;
@@ -1004,9 +1008,11 @@ struct MidCtx {
     // first 16 bytes of the last stage instead: one cache line per instruction, into a free LDS slot and dead
     // registers.
     template <bool EVEN>
-    __device__ __forceinline__ void issue(int slot, batq_u32x4 (&a)[RT][2], int (&sa)[RT], int (&sb)[2]) {
+    __device__ __forceinline__ void issue(int slot, batq_u32x4 (&a)[RT][2], int (&sa)[RT], int (&sb)[NJ]) {
         const uint32_t m = q < T ? ~0u : 0u;
-        dma16(wq, boff & m, lds0 + (uint32_t)slot * kMidStageLds + (uint32_t)wave * 1024);
+#pragma unroll
+        for (int n = 0; n < NS; ++n)
+            dma16(wq, boff[n] & m, lds0 + (uint32_t)(slot * NS + n) * kMidStripLds + (uint32_t)wave * 1024);
 #pragma unroll
         for (int i = 0; i < RT; ++i)
 #pragma unroll
@@ -1015,7 +1021,7 @@ struct MidCtx {
 #pragma unroll
             for (int i = 0; i < RT; ++i) load4_async(sa[i], sag, sao[i] & m);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) load4_async(sb[j], sbg, sbo[j] & m);
+            for (int j = 0; j < NJ; ++j) load4_async(sb[j], sbg, sbo[j] & m);
         }
         ++q;
         const bool more = q < T;                      // uniform; the pointers stay on the last stage otherwise
@@ -1027,30 +1033,44 @@ struct MidCtx {
         }
     }
     // loads a wave issues for a stage of parity p
-    static constexpr __device__ int count(int p) { return 1 + 2 * RT + ((p & 1) == 0 ? RT + 2 : 0); }
+    static constexpr __device__ int count(int p) { return NS + 2 * RT + ((p & 1) == 0 ? RT + NJ : 0); }
 };
 
 // Loads of stage indices Q .. D - 2, before the first stage is multiplied.
-template <int RT, int D, int Q>
-__device__ __forceinline__ void mid_prologue(MidCtx<RT, D>& c, batq_u32x4 (&a)[D][RT][2], int (&sa)[D / 2][RT], int (&sb)[D / 2][2]) {
+template <int RT, int D, int NS, int Q>
+__device__ __forceinline__ void mid_prologue(MidCtx<RT, D, NS>& c, batq_u32x4 (&a)[D][RT][2], int (&sa)[D / 2][RT],
+                                             int (&sb)[D / 2][2 * NS]) {
     if constexpr (Q < D - 1) {
         c.template issue<(Q & 1) == 0>(Q, a[Q], sa[Q >> 1], sb[Q >> 1]);
-        mid_prologue<RT, D, Q + 1>(c, a, sa, sb);
+        mid_prologue<RT, D, NS, Q + 1>(c, a, sa, sb);
+    }
+}
+
+// This lane's fragments of the strips' stage in LDS slot `slot`: matrix tile j = 32 columns, K steps 0 and 1.
+template <int D, int NS>
+__device__ __forceinline__ void mid_read_strips(const uint8_t* smem, int slot, int b_rd0, int b_rd1, uint4 (&b)[2 * NS][2]) {
+    const uint8_t* bs = smem + slot * NS * kMidStripLds;
+#pragma unroll
+    for (int j = 0; j < 2 * NS; ++j) {
+        b[j][0] = *reinterpret_cast<const uint4*>(bs + b_rd0 + j * 32 * kStageBytes);
+        b[j][1] = *reinterpret_cast<const uint4*>(bs + b_rd1 + j * 32 * kStageBytes);
     }
 }
 
 // Stages base + U .. base + D - 1 of a K part (base a multiple of D, so stage base + U lives in LDS
 // slot and register slot U and has parity U % 2).  ALL: all of them exist.  On entry b[U % 2] holds the strip
 // fragments of stage base + U; those of the next stage are read under its matrix instructions.
-template <int RT, int D, int U, bool ALL>
-__device__ __forceinline__ void mid_steps(MidCtx<RT, D>& c, int base, const uint8_t* smem, int b_rd0, int b_rd1,
-                                          v16f (&acc)[RT][2], batq_u32x4 (&a)[D][RT][2],
-                                          int (&sa)[D / 2][RT], int (&sb)[D / 2][2], uint4 (&b)[2][2][2]) {
+template <int RT, int D, int NS, int U, bool ALL>
+__device__ __forceinline__ void mid_steps(MidCtx<RT, D, NS>& c, int base, const uint8_t* smem, int b_rd0, int b_rd1,
+                                          v16f (&acc)[RT][2 * NS], batq_u32x4 (&a)[D][RT][2],
+                                          int (&sa)[D / 2][RT], int (&sb)[D / 2][2 * NS], uint4 (&b)[2][2 * NS][2]) {
+    using Ctx = MidCtx<RT, D, NS>;
+    constexpr int NJ = 2 * NS;
     if constexpr (U < D) {
         const int s = base + U;
         // stage s + 1 has landed (this wave's loads; the barrier adds the other waves' strip pieces): only the
         // loads of stage indices s + 2 .. s + D - 2 can be outstanding
-        wait_vmcnt<(D - 4) / 2 * (MidCtx<RT, D>::count(0) + MidCtx<RT, D>::count(1)) + MidCtx<RT, D>::count(U)>();
+        wait_vmcnt<(D - 4) / 2 * (Ctx::count(0) + Ctx::count(1)) + Ctx::count(U)>();
         wait_lds();                                                // the fragments of stage s are in registers
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -1062,25 +1082,20 @@ __device__ __forceinline__ void mid_steps(MidCtx<RT, D>& c, int base, const uint
             if constexpr ((u1 & 1) == 0) ready(sa[u1 >> 1][i]);
         }
         if constexpr ((u1 & 1) == 0) {
-            ready(sb[u1 >> 1][0]);
-            ready(sb[u1 >> 1][1]);
-        }
-        const uint8_t* bs = smem + u1 * kMidStageLds;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            b[u1 & 1][j][0] = *reinterpret_cast<const uint4*>(bs + b_rd0 + j * 32 * kStageBytes);
-            b[u1 & 1][j][1] = *reinterpret_cast<const uint4*>(bs + b_rd1 + j * 32 * kStageBytes);
+            for (int j = 0; j < NJ; ++j) ready(sb[u1 >> 1][j]);
         }
+        mid_read_strips<D, NS>(smem, u1, b_rd0, b_rd1, b[u1 & 1]);
         if (ALL || s < c.T) {                                      // workgroup-uniform
 #pragma unroll
             for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NJ; ++j)
                     mfma_one<2 * (U & 1), false>(acc[i][j], as_uint4(a[U][i][0]), b[U & 1][j][0], sa[U >> 1][i], sb[U >> 1][j]);
 #pragma unroll
             for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NJ; ++j)
                     mfma_one<2 * (U & 1) + 1, false>(acc[i][j], as_uint4(a[U][i][1]), b[U & 1][j][1], sa[U >> 1][i], sb[U >> 1][j]);
         }
         // Every wave has read the fragments of stage s - 1 and finished its matrix instructions on them: the LDS
@@ -1088,27 +1103,28 @@ __device__ __forceinline__ void mid_steps(MidCtx<RT, D>& c, int base, const uint
         // s they still read the scale registers that the K group of stage s + D - 1 takes over.)
         constexpr int un = (U + D - 1) % D;
         c.template issue<(un & 1) == 0>(un, a[un], sa[un >> 1], sb[un >> 1]);
-        mid_steps<RT, D, U + 1, ALL>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+        mid_steps<RT, D, NS, U + 1, ALL>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     }
 }
 
-// Requires operand code arrays below 2 GiB (32-bit load offsets).  Grid: (strips, row panels of 128 RT, K parts);
-// YT = partial_f32: partial sums of K part blockIdx.z in store_partial order (ldy = 32-column blocks of the padded
-// output, part_stride = floats of a part).
-template <typename YT, int RT, int D>
+// Requires operand code arrays below 2 GiB (32-bit load offsets).  Grid: (groups of NS strips, row panels of 128 RT,
+// K parts); YT = partial_f32: partial sums of K part blockIdx.z in store_partial order (ldy = 32-column blocks of the
+// padded output, part_stride = floats of a part).
+template <typename YT, int RT, int D, int NS>
 __global__ void __launch_bounds__(256, 2)
 gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
          const uint8_t* __restrict__ ws, int M, int N, int nb, int ksplit, YT* __restrict__ Y, int64_t ldy,
          int64_t part_stride) {
-    __shared__ __align__(16) uint8_t smem[D * kMidStageLds];
+    constexpr int NJ = 2 * NS;
+    __shared__ __align__(16) uint8_t smem[D * NS * kMidStripLds];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
     const int lane = threadIdx.x & 63, l32 = lane & 31, kg = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int groups = (nb + 7) >> 3;
     Tile t;
-    t.n0 = blockIdx.x * kStrip;
+    t.n0 = blockIdx.x * (kStrip * NS);
     t.m0 = blockIdx.y * (128 * RT);
-    t.nj = 1;
+    t.nj = NS;
     t.part = blockIdx.z;
     t.g0 = 0;
     t.ng = groups;
@@ -1118,7 +1134,7 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
     }
     const int T = 2 * t.ng;                                     // stages of 128 K elements
 
-    MidCtx<RT, D> c;
+    MidCtx<RT, D, NS> c;
     c.wave = wave;
     c.T = T;
     c.q = 0;
@@ -1140,25 +1156,28 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
             c.aoff[i][h] = (uint32_t)min(R >> 4, rgA - 1) * row_group_bytes + r * 64 + (((2 * h + kg) ^ slot_swizzle(r)) << 4);
         c.sao[i] = (uint32_t)(min(R, M - 1) * 2 + kg) * 4;
     }
-    c.boff = (uint32_t)min((t.n0 >> 4) + wave, rgB - 1) * row_group_bytes + lane * 16;
+    // wave w fetches the 16-column piece w of each of the workgroup's strips
 #pragma unroll
-    for (int j = 0; j < 2; ++j) c.sbo[j] = (uint32_t)(min(t.n0 + 32 * j + l32, N - 1) * 2 + kg) * 4;
+    for (int n = 0; n < NS; ++n)
+        c.boff[n] = (uint32_t)min((t.n0 >> 4) + 4 * n + wave, rgB - 1) * row_group_bytes + lane * 16;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) c.sbo[j] = (uint32_t)(min(t.n0 + 32 * j + l32, N - 1) * 2 + kg) * 4;
     // this lane's fragment of strip row (32 j + l32), K step h: slot (2 h + kg) ^ swizzle(row)
     const int b_rd0 = l32 * kStageBytes + ((kg ^ slot_swizzle(l32)) << 4);
     const int b_rd1 = l32 * kStageBytes + (((2 + kg) ^ slot_swizzle(l32)) << 4);
 
-    v16f acc[RT][2];
+    v16f acc[RT][NJ];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = v16f{};
+        for (int j = 0; j < NJ; ++j) acc[i][j] = v16f{};
     batq_u32x4 a[D][RT][2];
-    int sa[D / 2][RT], sb[D / 2][2];
+    int sa[D / 2][RT], sb[D / 2][NJ];
 
-    uint4 b[2][2][2];
-    mid_prologue<RT, D, 0>(c, a, sa, sb);
+    uint4 b[2][NJ][2];
+    mid_prologue<RT, D, NS, 0>(c, a, sa, sb);
     // stage 0 has landed: stage indices 1 .. D - 2 may be outstanding
-    wait_vmcnt<(D - 2) / 2 * (MidCtx<RT, D>::count(1) + MidCtx<RT, D>::count(0))>();
+    wait_vmcnt<(D - 2) / 2 * (MidCtx<RT, D, NS>::count(1) + MidCtx<RT, D, NS>::count(0))>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -1167,17 +1186,13 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
         ready(a[0][i][1]);
         ready(sa[0][i]);
     }
-    ready(sb[0][0]);
-    ready(sb[0][1]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        b[0][j][0] = *reinterpret_cast<const uint4*>(smem + b_rd0 + j * 32 * kStageBytes);
-        b[0][j][1] = *reinterpret_cast<const uint4*>(smem + b_rd1 + j * 32 * kStageBytes);
-    }
+    for (int j = 0; j < NJ; ++j) ready(sb[0][j]);
+    mid_read_strips<D, NS>(smem, 0, b_rd0, b_rd1, b[0]);
 
     int base = 0;
-    for (; base + D <= T; base += D) mid_steps<RT, D, 0, true>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
-    if (base < T) mid_steps<RT, D, 0, false>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+    for (; base + D <= T; base += D) mid_steps<RT, D, NS, 0, true>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+    if (base < T) mid_steps<RT, D, NS, 0, false>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     wait_vmcnt<0>();                                            // the loads past the last stage have landed, too
     // their destinations count as in use until here: a register the compiler took for something else would be
     // overwritten when the load lands
@@ -1189,16 +1204,16 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
             ready(a[d][i][1]);
             ready(sa[d >> 1][i]);
         }
-        ready(sb[d >> 1][0]);
-        ready(sb[d >> 1][1]);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) ready(sb[d >> 1][j]);
     }
     wait_lds();
     __builtin_amdgcn_s_barrier();                               // every wave is done with the strip ring
     asm volatile("" ::: "memory");
     if constexpr (std::is_same_v<YT, partial_f32>) {
-        store_partial<2, RT>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wave, 0, t, (int)ldy);
+        store_partial<NJ, RT>(acc, reinterpret_cast<float*>(Y) + t.part * part_stride, lane, wave, 0, t, (int)ldy);
     } else {
-        store_tile<2, YT, false, RT>(acc, smem + wave * kEpilogueWaveBytes<RT>, lane, wave, 0, t, M, N, Y, ldy);
+        store_tile<NJ, YT, false, RT>(acc, smem + wave * kEpilogueWaveBytes<RT>, lane, wave, 0, t, M, N, Y, ldy);
     }
 }
 
@@ -1562,7 +1577,8 @@ struct GemmPlan {
     int ksplit = 1;             // K parts used
     int want = 1;               // K parts the shape would like (workspace permitting)
     int rt = 4;                 // 4-bit tiled kernel: 32-row matrix tiles per wave (4: 4 waves, 2: 8 waves)
-    bool mid = false;           // 4-bit, plain output, at most one 128 x 64 tile (and K part) per compute unit: gemm_mid
+    bool mid = false;           // 4-bit, plain output, at most one gemm_mid workgroup per compute unit
+    int mid_strips = 1;         // strips of a gemm_mid workgroup (tile of 128 rows x 64 or 128 columns)
     bool skinny = false, wide = false;
     int cols = 0;               // skinny: workgroups along N
 };
@@ -1594,9 +1610,17 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
         // 4 K parts 19.8 -> 15.5, 256 x 8192 x 4096 with 2 K parts 19.9 -> 17.0.  With more workgroups than compute
         // units it loses (256 x 4096 x 14336: 16.6 -> 19.4, 512 x 14336 x 4096 with 4 K parts 30.7 -> 36.7); 256-row
         // panels, with two 32-row tiles per wave or with eight waves, lose everywhere (256 x 4096 x 14336: 18.1, 18.7).
-        // From 33 rows on it also beats the small-M kernel (64 x 4096 x 14336: 12.9 -> 11.0 us).
-        g.mid = BATQ_MID && !a8 && !glu && fits32 && g.rt == 4 &&
-                (long)((M + 127) / 128) * g.tiled.strips_n * g.ksplit <= g.tiled.workers;
+        // From 33 rows on it also beats the small-M kernel (64 x 4096 x 14336: 12.9 -> 11.0 us).  Where single strips
+        // are too many but pairs of strips fit, a workgroup takes two (tiled kernel -> that: 256 x 4096 x 14336
+        // 17.1 -> 16.3 us, 200 rows 15.9 -> 15.4); where single strips fit they are the faster choice (128 x 4096 x
+        // 14336: 12.0 us against 16.1 with pairs on half the compute units).
+        if (BATQ_MID && !a8 && !glu && fits32 && g.rt == 4) {
+            const long panels = (M + 127) / 128, strips = g.tiled.strips_n;
+            const bool one = panels * strips * g.ksplit <= g.tiled.workers;
+            const bool two = panels * ((strips + 1) / 2) * g.ksplit <= g.tiled.workers;
+            g.mid = one || two;
+            g.mid_strips = one ? 1 : 2;
+        }
         if (M > 64 || g.mid) return g;
         g = GemmPlan();
     }
@@ -1639,15 +1663,22 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         const TilePlan& pl = g.tiled;
         if (g.mid) {
             if constexpr (!A8 && !GLU) {
-                const dim3 grid(pl.strips_n, (M + 127) / 128, g.ksplit), block(256);
+                const int ns = g.mid_strips;
+                const dim3 grid((pl.strips_n + ns - 1) / ns, (M + 127) / 128, g.ksplit), block(256);
                 if (g.ksplit > 1) {
-                    gemm_mid<partial_f32, 1, kMidDepth><<<grid, block, 0, stream>>>(
-                        xc, xs, w->d_codes, w->d_scales, M, N, nb, g.ksplit, reinterpret_cast<partial_f32*>(parts),
-                        (int64_t)g.col_blocks, (int64_t)g.part_floats);
+                    partial_f32* const P = reinterpret_cast<partial_f32*>(parts);
+                    if (ns == 2)
+                        gemm_mid<partial_f32, 1, kMidDepth, 2><<<grid, block, 0, stream>>>(
+                            xc, xs, w->d_codes, w->d_scales, M, N, nb, g.ksplit, P, (int64_t)g.col_blocks, (int64_t)g.part_floats);
+                    else
+                        gemm_mid<partial_f32, 1, kMidDepth, 1><<<grid, block, 0, stream>>>(
+                            xc, xs, w->d_codes, w->d_scales, M, N, nb, g.ksplit, P, (int64_t)g.col_blocks, (int64_t)g.part_floats);
                     splitk_reduce<YT><<<dim3(g.col_blocks, (M + 31) / 32), dim3(256), 0, stream>>>(
                         parts, g.ksplit, (int64_t)g.part_floats, g.col_blocks, M, N, Y, ldy);
+                } else if (ns == 2) {
+                    gemm_mid<YT, 1, kMidDepth, 2><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, 1, Y, ldy, 0);
                 } else {
-                    gemm_mid<YT, 1, kMidDepth><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, 1, Y, ldy, 0);
+                    gemm_mid<YT, 1, kMidDepth, 1><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, 1, Y, ldy, 0);
                 }
             }
         } else if (g.ksplit > 1) {

@@ -124,12 +124,13 @@ def test_tile_schedule_shapes(B, M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", [(200, 2048, 14336), (300, 1536 + 32, 5000), (256, 768, 24000), (100, 512, 9000 + 24),
-                                   (512, 1024, 14336)])
+                                   (512, 1024, 14336), (256, 512, 12840), (130, 640, 16320)])
 def test_narrow_tile_shapes(B, M, K, N):
-    """Few rows and many columns: every workgroup gets one or two strips.  Up to 128 rows that is one 128 x 64 tile
-    per compute unit (the kernel that loads X fragments straight to registers), above it tiles of the four-wave
-    tiled kernel one or two strips wide (their own stage schedule); 4 to 16 K stages, ragged rows and a ragged last
-    strip; every element."""
+    """Few rows and many columns: every workgroup gets one or two strips.  Where 128-row panels x strips, or x pairs
+    of strips (200 x 14336, 256 x 12840 with its odd, ragged last strip, 130 x 16320 = exactly one workgroup per
+    compute unit), fit the compute units that is one 128 x 64 or 128 x 128 tile each (the kernel that loads X
+    fragments straight to registers), otherwise tiles of the four-wave tiled kernel one or two strips wide (their own
+    stage schedule); 4 to 16 K stages, ragged rows and a ragged last strip; every element."""
     import torch
     rng = np.random.default_rng(M * 7 + K + N)
     xc, xs, dxc, dxs = _rand_q(rng, M, K, lo=122, hi=132)
@@ -150,10 +151,12 @@ def test_narrow_tile_shapes(B, M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", [(130, 8192, 320), (300, 8192 + 32, 200), (256, 8192 + 256, 1000), (97, 6144, 64),
-                                   (65, 12288 + 64, 2100), (520, 16384, 136), (64, 12288 + 32, 2070), (7, 16384, 96)])
+                                   (65, 12288 + 64, 2100), (520, 16384, 136), (64, 12288 + 32, 2070), (7, 16384, 96),
+                                   (384, 8192 + 256, 3264 + 30)])
 def test_split_k_shapes(B, M, K, N):
     """Few strips and a long K: with a workspace the kernels cut K into 2 to 8 parts (partial tiles summed in a
-    second kernel), with ragged panels, strips and part lengths.  Every output element is checked for the plain
+    second kernel), with ragged panels, strips and part lengths (the last shape: two K parts of the kernel with one
+    128 x 128 tile per workgroup, whose last workgroup has a single, ragged strip).  Every output element is checked for the plain
     call, the full workspace and a third of it (fewer parts); the result is a function of the arguments: the same
     bits on the current stream, on a side stream and from launches that overlap (each with its own workspace)."""
     import torch
