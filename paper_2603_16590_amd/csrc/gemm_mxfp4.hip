@@ -1007,8 +1007,34 @@ struct MidCtx {
     // the compiler would copy it while it is still in flight).  Past the K part's T stages all lanes fetch the
     // first 16 bytes of the last stage instead: one cache line per instruction, into a free LDS slot and dead
     // registers.
-    template <bool EVEN>
+    // LIVE: the caller knows that the stage exists (q < T) and that it is not the last one either, so the masks
+    // and the clamped pointer steps (a dozen scalar and vector instructions per stage, in a loop whose pace is set by
+    // the instructions a wave issues) are left out.
+    template <bool EVEN, bool LIVE = false>
     __device__ __forceinline__ void issue(int slot, batq_u32x4 (&a)[RT][2], int (&sa)[RT], int (&sb)[NJ]) {
+        if constexpr (LIVE) {
+#pragma unroll
+            for (int n = 0; n < NS; ++n)
+                dma16(wq, boff[n], lds0 + (uint32_t)(slot * NS + n) * kMidStripLds + (uint32_t)wave * 1024);
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) load16_async(a[i][h], xq, aoff[i][h]);
+            if constexpr (EVEN) {
+#pragma unroll
+                for (int i = 0; i < RT; ++i) load4_async(sa[i], sag, sao[i]);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) load4_async(sb[j], sbg, sbo[j]);
+            }
+            ++q;
+            xq += 1024;
+            wq += 1024;
+            if constexpr (!EVEN) {
+                sag += sa_step;
+                sbg += sb_step;
+            }
+            return;
+        }
         const uint32_t m = q < T ? ~0u : 0u;
 #pragma unroll
         for (int n = 0; n < NS; ++n)
@@ -1060,7 +1086,8 @@ __device__ __forceinline__ void mid_read_strips(const uint8_t* smem, int slot, i
 // Stages base + U .. base + D - 1 of a K part (base a multiple of D, so stage base + U lives in LDS
 // slot and register slot U and has parity U % 2).  ALL: all of them exist.  On entry b[U % 2] holds the strip
 // fragments of stage base + U; those of the next stage are read under its matrix instructions.
-template <int RT, int D, int NS, int U, bool ALL>
+// LIVE: the stages base + D - 1 .. base + 2 D - 2 whose loads are issued here exist and are not the last one.
+template <int RT, int D, int NS, int U, bool ALL, bool LIVE = false>
 __device__ __forceinline__ void mid_steps(MidCtx<RT, D, NS>& c, int base, const uint8_t* smem, int b_rd0, int b_rd1,
                                           v16f (&acc)[RT][2 * NS], batq_u32x4 (&a)[D][RT][2],
                                           int (&sa)[D / 2][RT], int (&sb)[D / 2][2 * NS], uint4 (&b)[2][2 * NS][2]) {
@@ -1086,6 +1113,10 @@ __device__ __forceinline__ void mid_steps(MidCtx<RT, D, NS>& c, int base, const 
             for (int j = 0; j < NJ; ++j) ready(sb[u1 >> 1][j]);
         }
         mid_read_strips<D, NS>(smem, u1, b_rd0, b_rd1, b[u1 & 1]);
+        // the reads go out first and are not waited for here: this stage's matrix instructions take the fragments
+        // read a stage ago (left alone, the compiler moves matrix instructions across the stage boundary and then
+        // waits for a read it has just issued)
+        __builtin_amdgcn_sched_barrier(0);
         if (ALL || s < c.T) {                                      // workgroup-uniform
 #pragma unroll
             for (int i = 0; i < RT; ++i)
@@ -1102,8 +1133,9 @@ __device__ __forceinline__ void mid_steps(MidCtx<RT, D, NS>& c, int base, const 
         // slot and registers of stage s - 1 take stage s + D - 1.  (After this stage's matrix instructions: for odd
         // s they still read the scale registers that the K group of stage s + D - 1 takes over.)
         constexpr int un = (U + D - 1) % D;
-        c.template issue<(un & 1) == 0>(un, a[un], sa[un >> 1], sb[un >> 1]);
-        mid_steps<RT, D, NS, U + 1, ALL>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
+        c.template issue<(un & 1) == 0, LIVE>(un, a[un], sa[un >> 1], sb[un >> 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mid_steps<RT, D, NS, U + 1, ALL, LIVE>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     }
 }
 
@@ -1191,6 +1223,7 @@ gemm_mid(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const u
     mid_read_strips<D, NS>(smem, 0, b_rd0, b_rd1, b[0]);
 
     int base = 0;
+    for (; base + 2 * D <= T; base += D) mid_steps<RT, D, NS, 0, true, true>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     for (; base + D <= T; base += D) mid_steps<RT, D, NS, 0, true>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     if (base < T) mid_steps<RT, D, NS, 0, false>(c, base, smem, b_rd0, b_rd1, acc, a, sa, sb, b);
     wait_vmcnt<0>();                                            // the loads past the last stage have landed, too
