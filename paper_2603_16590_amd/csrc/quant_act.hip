@@ -293,7 +293,9 @@ template <bool MINMAX, bool FP8, bool SWIGLU>
 __global__ void __launch_bounds__((QuantPlan<FP8, SWIGLU>::kWaves * 64))
 quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __restrict__ U, int64_t ldu, int M,
                int nb, int srows, int wpg,
-               const uint4* __restrict__ Tsplit, const float* __restrict__ clip, const float* __restrict__ clip_max,
+               const uint4* __restrict__ Tsplit, const float* __restrict__ outer, int outer_stride,
+               const float* __restrict__ inner, int inner_stride, int gshift,
+               const float* __restrict__ clip, const float* __restrict__ clip_max,
                const float* __restrict__ row_scale, uint8_t* __restrict__ codes, uint8_t* __restrict__ scales) {
     extern __shared__ __align__(16) uint8_t qlds[];
     typedef __attribute__((address_space(3))) uint8_t lds_byte;
@@ -388,7 +390,22 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         const int nblk = min(8, nb - k0);                   // real blocks in this group
         __syncthreads();                                    // every wave is done with the previous group's operands
         if (tid == 0) *counter = (uint32_t)(2 * t_begin);
-        {
+        if (gshift) {
+            // Kronecker form: only the factors are fetched (outer and inner factor of block k0 + kb, 320 bytes, by
+            // wave kb % waves into its code staging area, which the flush leaves free), and the workgroup forms the
+            // blocks' split operands itself below
+            flush();
+            const int go = 32 >> gshift, gi = 1 << gshift;
+            for (int kb = wave; kb < nblk; kb += kQuantWaves) {
+                const uint32_t dst = lds_base + Plan::kLdsStage + wave * Plan::kCodeStage + (kb / kQuantWaves) * 512;
+                const float* ob = outer + (size_t)(k0 + kb) * outer_stride;
+                const float* ib = inner + (size_t)(k0 + kb) * inner_stride;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                             :: "v"((uint32_t)min(lane, go * go - 1) * 4u), "s"(ob), "s"(dst) : "memory");
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                             :: "v"((uint32_t)min(lane, gi * gi - 1) * 4u), "s"(ib), "s"(dst + 256) : "memory");
+            }
+        } else {
             // the group's transform operands go global -> LDS with LDS-direct loads (1 KiB per wave
             // instruction, lane i -> LDS base + 16 i)
             const uint8_t* src = reinterpret_cast<const uint8_t*>(Tsplit) + (size_t)k0 * kTsplitBlock;
@@ -404,6 +421,51 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         if (my_u < u_end && request(g, my_u)) __builtin_amdgcn_s_waitcnt(SWIGLU ? 0x4F70 : 0x0F78);     // vmcnt(16) : vmcnt(8)
         else __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
         __syncthreads();                                    // all operands have landed
+        if (gshift) {
+            // T_k = outer (x) inner, element by element the exact product of the two fp32 factors, split into three
+            // bf16 terms (each the remainder rounded to fp32, then to bf16, nearest even) in the operand's lane order:
+            // bit for bit what the host writes into the pre-split array (from the fp64 product), at 320 instead of
+            // 6144 bytes fetched per block, while the first units' rows are on their way
+            const int go = 32 >> gshift, gi = 1 << gshift;
+            for (int item = tid; item < nblk * 128; item += kQuantWaves * 64) {
+                const int kb = item >> 7, hf = (item >> 6) & 1, ln = item & 63;
+                const float* fo = reinterpret_cast<const float*>(qlds + Plan::kLdsStage + (kb % kQuantWaves) * Plan::kCodeStage +
+                                                                 (kb / kQuantWaves) * 512);
+                const float* fi = fo + 64;
+                const int m = ln & 31;
+                const int oc = 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3);
+                const int a2 = oc >> gshift, c2 = oc & (gi - 1);
+                const int in0 = 16 * (ln >> 5) + 8 * hf;
+                uint32_t w[3][4];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int ic = in0 + e, a = ic >> gshift, c = ic & (gi - 1);
+                    // p = o * i exactly = h + l (h the rounded product, l its error, from a fused multiply-add); the
+                    // terms are b0 = bf16(h), b1 = bf16(fl(p - b0)), b2 = bf16(fl(p - b0 - b1)), where h - b0 and
+                    // (h - b0) - b1 are exact in fp32 and one addition of l rounds each remainder correctly
+                    const float o = fo[a * go + a2], iv = fi[c * gi + c2];
+                    float h = o * iv;
+                    asm volatile("" : "+v"(h));             // the rounded product itself: not to be fused into what follows
+                    const float l = __builtin_fmaf(o, iv, -h);
+                    uint32_t b[3];
+                    b[0] = float_to_bf16_bits(h);
+                    const float d0 = h - bf16_bits_to_float(b[0]);
+                    b[1] = float_to_bf16_bits(d0 + l);
+                    const float d1 = d0 - bf16_bits_to_float(b[1]);
+                    b[2] = float_to_bf16_bits(d1 + l);
+#pragma unroll
+                    for (int term = 0; term < 3; ++term) {
+                        if (e & 1) w[term][e >> 1] |= b[term] << 16;
+                        else w[term][e >> 1] = b[term];
+                    }
+                }
+#pragma unroll
+                for (int term = 0; term < 3; ++term)
+                    *reinterpret_cast<uint4*>(tlds + kb * kTsplitBlock + ((term * 2 + hf) * 64 + ln) * 16) =
+                        uint4{w[term][0], w[term][1], w[term][2], w[term][3]};
+            }
+            __syncthreads();                                // the operands are complete, the staging areas free again
+        }
 
         while (my_u < u_end) {
             const int u = my_u;
@@ -716,10 +778,19 @@ hipError_t launch_mfma_as(const batq_transform* t, const uint16_t* X, int M, int
     const int groups = scale_groups(nb), row_tiles = (M + 31) / 32;
     const int wpg = std::max(1, std::min(cus / groups, row_tiles));
     const int wgs = wpg * std::min(groups, cus);
+    // Kronecker forms: a workgroup can form the split operands of its K group from the factors (320 bytes fetched per
+    // block) instead of fetching them (6 KiB per block, which every XCD pulls into its L2 once and every workgroup
+    // into its LDS).  Forming them takes a workgroup ~1 us before its first unit, so it pays where a wave has three
+    // or more units to work through (kernel trace, fetching -> forming: 4096 x 14336 28-33 -> 29 us and 128.7 ->
+    // 118.2 MB fetched for 117.4 MB of input, 8192 x 3584 18.8 -> 18.0 us; 2048 x 4096, one unit per wave: 8.0 -> 9.1 us,
+    // so that shape keeps fetching).  The bits of the operands, and so of the output, are the same either way.
+    const int units_per_wg = 2 * ((row_tiles + wpg - 1) / wpg);
+    const bool build_operands = t->form == BATQ_FORM_KRON && units_per_wg >= 3 * Plan::kWaves;
     // the window starts on a 32-row tile (the caller checks): whole 16-row code groups and 8-byte scale rows in
     const size_t code_group = (size_t)(FP8 ? code8_stages(nb) : code_stages(nb)) * 1024;
     quant_act_mfma<MINMAX, FP8, SWIGLU><<<dim3(wgs), dim3(Plan::kWaves * 64), Plan::kLds, stream>>>(
-        X, ldx, U, ldu, M, nb, win.srows, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_clip,
+        X, ldx, U, ldu, M, nb, win.srows, wpg, reinterpret_cast<const uint4*>(t->d_Tsplit), t->d_outer, t->outer_stride,
+        t->d_inner, t->inner_stride, build_operands ? (t->g_inner == 8 ? 3 : 2) : 0, t->d_clip,
         MINMAX ? t->d_clip_max : nullptr, row_scale, codes + (size_t)(win.row0 >> 4) * code_group,
         scales + (size_t)win.row0 * 8);
     return hipGetLastError();

@@ -113,6 +113,45 @@ def test_forms_and_clip_modes(B, form, dtype, clipmode):
     print(f"{form} {dtype} {clipmode}: mismatch fraction {frac:.2e}")
 
 
+@pytest.mark.parametrize("form,bits,gated", [("gpk48", 4, False), ("gpk84", 4, False), ("paper_order", 4, False),
+                                              ("paper_order84", 8, False), ("naive", 4, True), ("gpk48", 8, True)])
+def test_operands_formed_in_the_kernel_give_the_same_bits(B, form, bits, gated):
+    """A bf16 call large enough that a wave of the persistent kernel works through three or more units (here 400 rows
+    of K = 32 x 2085: more K groups than compute units, so a workgroup also takes a second group, and a last group of
+    5 blocks) forms the split operands of T_k = outer (x) inner in the kernel from the factors; a call of 32 rows
+    takes the row-by-row kernel, which reads the operands the host split.  Both must give every row the same code and
+    scale bytes, for every Kronecker form, for MXFP4 and MXFP8 output, with and without a gated input: the in-kernel
+    products and three-term splits are bit for bit the host's."""
+    import torch
+    rng = np.random.default_rng(zlib.crc32(f"formed/{form}/{bits}/{gated}".encode()))
+    M, K = 400, 32 * 2085
+    nb = K // 32
+    if form == "gpk48":                 # the default: global 4x4 outer, private 8x8 inner
+        f = lambda g, per_block: (np.eye(g) + 0.05 * rng.standard_normal((nb, g, g) if per_block else (g, g))).astype(np.float32)
+        kw = dict(outer=f(4, False), inner=f(8, True))
+    else:
+        kw, _ = _factors(rng, form, nb)
+    kw["clip"] = rng.uniform(0.8, 1.0, nb).astype(np.float32)
+    t = B.Transform.general(K, **kw)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(int(rng.integers(1 << 30)))
+    X = (torch.randn((M, K), device="cuda", generator=g) * 1.5).to(torch.bfloat16)
+    U = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16) if gated else None
+    rs = torch.rand((M,), device="cuda", generator=g) + 0.5
+    call = lambda x, u, r: B.batq_quantize_act_ex(t, x, bits, row_scale=r, up=u)
+    c_all, s_all = call(X, U, rs)
+    torch.cuda.synchronize()
+    to_rm = B.batq_codes8_to_rowmajor if bits == 8 else B.batq_codes_to_rowmajor
+    ca, sa = to_rm(c_all, M, K), B.batq_scales_to_rowmajor(s_all, M, K)
+    for r0, r1 in ((0, 32), (192, 224), (368, 400)):
+        c, sc = call(X[r0:r1], None if U is None else U[r0:r1], rs[r0:r1])
+        torch.cuda.synchronize()
+        assert torch.equal(B.batq_scales_to_rowmajor(sc, r1 - r0, K), sa[r0:r1]), (form, bits, gated, r0)
+        assert torch.equal(to_rm(c, r1 - r0, K), ca[r0:r1]), (form, bits, gated, r0)
+    # and not trivially: the codes are not all zero, the scales not all alike
+    assert int((ca != 0).sum()) > ca.numel() // 2 and len(torch.unique(sa)) > 3
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_minmax_quantiser_bit_exact_without_transform(B, dtype):
     # the quantiser alone (identity transform), fed the same tensor as the oracle: bit-exact
