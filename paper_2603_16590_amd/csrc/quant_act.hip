@@ -389,7 +389,9 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
         const int k0 = g * 8;
         const int nblk = min(8, nb - k0);                   // real blocks in this group
         __syncthreads();                                    // every wave is done with the previous group's operands
-        if (tid == 0) *counter = (uint32_t)(2 * t_begin);
+        // the first units go to the waves by number (no barrier and no draw in front of a launch's first request: they
+        // cost 0.5 us), the rest are drawn from the counter, which is set by the barrier below
+        if (tid == 0) *counter = (uint32_t)(2 * t_begin + kQuantWaves);
         if (gshift) {
             // Kronecker form: only the factors are fetched (outer and inner factor of block k0 + kb, 320 bytes, by
             // wave kb % waves into its code staging area, which the flush leaves free), and the workgroup forms the
@@ -414,13 +416,12 @@ quant_act_mfma(const uint16_t* __restrict__ X, int64_t ldx, const uint16_t* __re
                 asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                              :: "v"((uint32_t)(p * 1024 + lane * 16)), "s"(src), "s"(lds_base + (uint32_t)p * 1024) : "memory");
         }
-        __syncthreads();                                    // the counter is set
-        int my_u = grab();
+        int my_u = 2 * t_begin + wave;
         // this wave's share of the operands has landed once only the unit's loads (8, or 16 with a gated input;
         // loads complete in order) are still out: the workgroup does not wait for everybody's first unit
         if (my_u < u_end && request(g, my_u)) __builtin_amdgcn_s_waitcnt(SWIGLU ? 0x4F70 : 0x0F78);     // vmcnt(16) : vmcnt(8)
         else __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
-        __syncthreads();                                    // all operands have landed
+        __syncthreads();                                    // all operands have landed, the counter is set
         if (gshift) {
             // T_k = outer (x) inner, element by element the exact product of the two fp32 factors, split into three
             // bf16 terms (each the remainder rounded to fp32, then to bf16, nearest even) in the operand's lane order:
