@@ -722,6 +722,7 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
         // bytes.  Needs the wave's whole width inside N and 16-byte aligned rows (wave-uniform).
         const bool fast = n0 + (wn + 1) * 32 * NJ <= N && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
         if (fast) {
+            const bool big = (size_t)M * (size_t)N * sizeof(YT) > (size_t(128) << 20);     // kernel-uniform
             constexpr int BR = kEpilogueBlockRows<RT>;      // rows staged at a time
             uint8_t* ep = ep_lds;   // [BR rows][256 bytes]
             const int odd = lane_e & 1, l32 = lane_e & 31, kg = lane_e >> 5;
@@ -770,7 +771,12 @@ __device__ __forceinline__ void store_tile_impl(F value, uint8_t* ep_lds, int la
                         // written through the L2 (device scope): nothing in this kernel reads Y, and lines left
                         // dirty in the eight L2s would be written back at the end of the kernel (cfg2 back to
                         // back: plain stores 69.5 us, non-temporal 67.9, write-through 65.7)
-                        if (lane_on && row < M) store16_through(yrow, batq_u32x4{v.x, v.y, v.z, v.w});
+                        // (an output beyond 128 MB also non-temporally: 8192 x 18944 bf16, 310 MB, 274.8 -> 262.0 us;
+                        // 2048 x 14336, 59 MB, no difference either way)
+                        if (lane_on && row < M) {
+                            if (big) store16_through_nt(yrow, batq_u32x4{v.x, v.y, v.z, v.w});
+                            else store16_through(yrow, batq_u32x4{v.x, v.y, v.z, v.w});
+                        }
                         row += kRows;
                         yrow += ystep;
                     }

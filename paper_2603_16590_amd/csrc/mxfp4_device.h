@@ -85,6 +85,12 @@ __device__ __forceinline__ void store16_through(void* p, const batq_u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" :: "v"(p), "v"(v) : "memory");
 }
 
+// The same for an output larger than the memory-side cache can hold for whoever reads it next: also non-temporal,
+// so that it does not push the operands out of that cache on its way.
+__device__ __forceinline__ void store16_through_nt(void* p, const batq_u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(p), "v"(v) : "memory");
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs).
