@@ -197,16 +197,20 @@ constexpr int kSkinnyWaves = 8;
 // 64-column group of the interleaved weight (sharing the loads of X), and stores silu(gate) * up to M x N/2.
 // WIDE (not with GLU): a workgroup owns 64 output columns instead of 32, which halves how often the X codes
 // are read; used when N is large enough that 64-column workgroups still fill the chip.
-template <typename YT, int RT, bool A8, bool GLU, bool WIDE>
+// NARROW (not with GLU or WIDE): a workgroup owns 16 output columns, for N so small that 32-column workgroups would
+// leave half the compute units without one: lanes 16-31 of each half wave load what lanes 0-15 load (the same cache
+// lines) and their columns of the matrix instructions' results are dropped.
+template <typename YT, int RT, bool A8, bool GLU, bool WIDE, bool NARROW = false>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, const uint8_t* __restrict__ wc,
             const uint8_t* __restrict__ ws, int M, int N, int nb, YT* __restrict__ Y, int64_t ldy,
             float* __restrict__ partial) {
     static_assert(!(GLU && WIDE), "the gated kernel already takes two column groups");
+    static_assert(!(NARROW && (GLU || WIDE)), "16 columns only for the plain kernel");
     constexpr int NG = (GLU || WIDE) ? 2 : 1;               // 32-column groups of the weight per workgroup
     __shared__ float part[kSkinnyWaves][16][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n0 = blockIdx.x * 32 * NG;                    // first weight column
+    const int n0 = blockIdx.x * (NARROW ? 16 : 32 * NG);    // first weight column
     const int i = lane & 31, kg = lane >> 5;
     const int groups = scale_groups(nb);
     // gridDim.y > 1: the K groups are first cut into gridDim.y parts, one per workgroup row, whose sums go
@@ -218,7 +222,7 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
     const uint8_t* pb[NG];
 #pragma unroll
     for (int c = 0; c < NG; ++c) {
-        bn[c] = min(n0 + 32 * c + i, N - 1);                // rows and columns past the edge are computed, not stored
+        bn[c] = min(n0 + 32 * c + (NARROW ? (i & 15) : i), N - 1);   // rows and columns past the edge are computed, not stored
         const int rb = bn[c] & 15;
         pb[c] = wc + (size_t)(bn[c] >> 4) * code_stages(nb) * 1024 + rb * 64;
         swb[c] = (rb >> 2) & 3;
@@ -331,7 +335,7 @@ gemm_skinny(const uint8_t* __restrict__ xc, const uint8_t* __restrict__ xs, cons
 #pragma unroll
                 for (int c = 0; c < NG; ++c) {
                     const int col = n0 + 32 * c + (l & 31);
-                    if (row < M && col < N) {
+                    if (row < M && col < N && (!NARROW || (l & 31) < 16)) {
                         if (gridDim.y > 1) partial[((size_t)blockIdx.y * M + row) * N + col] = v[c][h];
                         else store_y<YT>(Y + (size_t)row * ldy + col, v[c][h]);
                     }
@@ -1618,7 +1622,7 @@ struct GemmPlan {
     int rt = 4;                 // 4-bit tiled kernel: 32-row matrix tiles per wave (4: 4 waves, 2: 8 waves)
     bool mid = false;           // 4-bit, plain output, at most one gemm_mid workgroup per compute unit
     int mid_strips = 1;         // strips of a gemm_mid workgroup (tile of 128 rows x 64 or 128 columns)
-    bool skinny = false, wide = false;
+    bool skinny = false, wide = false, narrow = false;
     int cols = 0;               // skinny: workgroups along N
 };
 
@@ -1670,7 +1674,13 @@ inline GemmPlan gemm_plan(int M, int N, int nb, int cus, bool a8, bool glu, size
     // for the 8-bit kernel, which would not fit its registers.
     const int cols64 = (N + 63) / 64;
     g.wide = !glu && !a8 && M > 32 && cols64 <= cus && 4 * cols64 >= 3 * cus;
-    g.cols = (glu || g.wide) ? cols64 : (N + 31) / 32;
+    // 16 columns per workgroup where 32 would give at most half the compute units a workgroup (decode shapes with
+    // N <= 4096 on 256 compute units; graph-replayed, 20 weight copies taking turns: 16 x 4096 x 4096 4.7 -> 4.5 us,
+    // 16 x 14336 x 4096 11.2 -> 10.2 us, where it also replaces two K parts and their second kernel,
+    // 32 x 8192 x 2048 7.0 -> 6.8).  (Four instead of two K groups in flight per wave, with a ring of register sets:
+    // 16 x 14336 x 4096 back to 11.2 us; not in.)
+    g.narrow = !glu && !g.wide && M <= 32 && 2 * ((N + 31) / 32) <= cus;
+    g.cols = (glu || g.wide) ? cols64 : g.narrow ? (N + 15) / 16 : (N + 31) / 32;
     // Narrow N with a long K leaves half the compute units idle while every workgroup reads all of A: two
     // workgroup rows then take half of K each (64 x 14336 x 4096: 15.8 -> 12.0 us).  More parts, or shorter
     // K, lose more to the second kernel than they gain.
@@ -1765,6 +1775,8 @@ hipError_t launch_typed(const uint8_t* xc, const uint8_t* xs, const batq_weight*
         } else if (g.wide) {
             if constexpr (!A8)
                 gemm_skinny<YT, 2, false, false, true><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
+        } else if (g.narrow) {
+            gemm_skinny<YT, 1, A8, false, false, true><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);
         } else {
             if (M <= 32)
                 gemm_skinny<YT, 1, A8, false, false><<<grid, block, 0, stream>>>(xc, xs, w->d_codes, w->d_scales, M, N, nb, Y, ldy, pp);

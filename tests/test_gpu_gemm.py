@@ -59,8 +59,11 @@ def test_single_block_is_exact(B):
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 64, 1), (37, 96, 70), (64, 128, 64), (65, 160, 129), (130, 1024, 96),
-                                   (16, 4096, 256), (300, 2048 + 64, 520), (257, 256, 300), (513, 96, 257), (700, 32, 70)])
+                                   (16, 4096, 256), (300, 2048 + 64, 520), (257, 256, 300), (513, 96, 257), (700, 32, 70),
+                                   (16, 512, 1000), (32, 768, 4096), (5, 256, 17), (20, 1024 + 96, 4090)])
 def test_small_shapes_random_codes(B, M, K, N):
+    """(The last four: up to 32 rows and at most 4096 columns, where a workgroup of the small-M kernel takes 16 instead
+    of 32 columns: N a multiple of 16 but not of 32, the full 4096, fewer than 32, and a ragged last group of 10.)"""
     import torch
     rng = np.random.default_rng(M * 7 + K + N)
     xc, xs, dxc, dxs = _rand_q(rng, M, K)

@@ -161,7 +161,8 @@ def _rand_q8(rng, R, K):
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 64, 1), (37, 96, 70), (64, 128, 64), (65, 160, 129), (16, 4096, 256),
-                                   (300, 2048 + 64, 520), (513, 96, 257), (768, 512, 3000), (40, 12288 + 32, 300)])
+                                   (300, 2048 + 64, 520), (513, 96, 257), (768, 512, 3000), (40, 12288 + 32, 300),
+                                   (16, 512, 1000), (20, 1024 + 96, 4090)])
 def test_a8w4_gemm_random_codes(B, M, K, N):
     import torch
     rng = np.random.default_rng(M * 7 + K + N)
